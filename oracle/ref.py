@@ -119,3 +119,147 @@ def dequantize(packed, gmin, gscale, rows, dim, bits, group):
                                        _p(gscale, C.c_float), rows, dim, bits, group,
                                        _p(out, C.c_float)), "dequantize")
     return out
+
+
+# ------------------------------------------------ attentive aggregation ------
+def _declare_agg(L):
+    i32p, f32p, f64p, u8p = (C.POINTER(C.c_int32), C.POINTER(C.c_float), C.POINTER(C.c_double),
+                             C.POINTER(C.c_uint8))
+    L.tinykg_ref_kg_aggregate_fwd_f64.argtypes = [
+        C.c_int64, C.c_int, C.c_int64, i32p, i32p, i32p, f64p, f64p, f64p, f64p, C.c_int, C.c_int,
+        C.c_int, C.c_double, C.c_int, f64p, f64p, f64p, f64p]
+    L.tinykg_ref_kg_aggregate_bwd_f64.argtypes = [
+        C.c_int64, C.c_int, C.c_int64, i32p, i32p, i32p, f64p, f64p, u8p, f64p, f64p, f64p,
+        C.c_int, C.c_int, C.c_int, C.c_double, f64p, C.c_int, f64p, f64p, f64p, f64p]
+    L.tinykg_ref_kg_aggregate_fwd.argtypes = [
+        C.c_int64, C.c_int, C.c_int64, i32p, i32p, i32p, f32p, f32p, f32p, f32p, C.c_int, C.c_int,
+        C.c_int, C.c_float, C.c_int, f32p, f32p, u8p]
+    L.tinykg_ref_kg_aggregate_bwd.argtypes = [
+        C.c_int64, C.c_int, C.c_int64, i32p, i32p, i32p, f32p, f32p, u8p, f32p, f32p, f32p,
+        C.c_int, C.c_int, C.c_int, C.c_float, f32p, C.c_int, f32p, f32p, f32p, f32p]
+
+
+_agg_declared = False
+
+
+def _agg():
+    global _agg_declared
+    L = lib()
+    if not _agg_declared:
+        _declare_agg(L)
+        _agg_declared = True
+    return L
+
+
+def _coo(head, rel, tail):
+    head = np.ascontiguousarray(head, dtype=np.int32)
+    rel = np.ascontiguousarray(rel, dtype=np.int32)
+    tail = np.ascontiguousarray(tail, dtype=np.int32)
+    assert head.shape == rel.shape == tail.shape and head.ndim == 1
+    return head, rel, tail
+
+
+def default_threads():
+    return max(1, min(16, os.cpu_count() or 1))
+
+
+def aggregate_fwd_f64(n_nodes, head, rel, tail, E, Wr, er, W, slope, threads=1):
+    """Double-precision layer forward.  Returns E_out, H, J, pi (per triplet)."""
+    head, rel, tail = _coo(head, rel, tail)
+    E, Wr, er, W = (np.ascontiguousarray(a, dtype=np.float64) for a in (E, Wr, er, W))
+    R, k, d = Wr.shape
+    dout = W.shape[0]
+    assert E.shape == (n_nodes, d) and er.shape == (R, k) and W.shape == (dout, d)
+    Eout = np.empty((n_nodes, dout)); H = np.empty((n_nodes, d)); J = np.empty((n_nodes, dout))
+    pi = np.empty(head.size)
+    D = C.c_double
+    _check(_agg().tinykg_ref_kg_aggregate_fwd_f64(
+        n_nodes, R, head.size, _p(head, C.c_int32), _p(rel, C.c_int32), _p(tail, C.c_int32),
+        _p(E, D), _p(Wr, D), _p(er, D), _p(W, D), d, k, dout, float(slope), threads,
+        _p(Eout, D), _p(H, D), _p(J, D), _p(pi, D)), "aggregate_fwd_f64")
+    return Eout, H, J, pi
+
+
+def aggregate_bwd_f64(n_nodes, head, rel, tail, Ehat, Hhat, mask, Wr, er, W, slope, gEout,
+                      threads=1):
+    """Double-precision layer backward at the given saved tensors.
+    mask: [n_nodes, d_out] array, nonzero where J > 0.  Returns gE, gWr, ger, gW."""
+    head, rel, tail = _coo(head, rel, tail)
+    Ehat, Hhat, Wr, er, W, gEout = (np.ascontiguousarray(a, dtype=np.float64)
+                                    for a in (Ehat, Hhat, Wr, er, W, gEout))
+    mask = np.ascontiguousarray(mask, dtype=np.uint8)
+    R, k, d = Wr.shape
+    dout = W.shape[0]
+    assert Ehat.shape == (n_nodes, d) == Hhat.shape and mask.shape == (n_nodes, dout) == gEout.shape
+    gE = np.empty((n_nodes, d)); gWr = np.empty((R, k, d)); ger = np.empty((R, k))
+    gW = np.empty((dout, d))
+    D = C.c_double
+    _check(_agg().tinykg_ref_kg_aggregate_bwd_f64(
+        n_nodes, R, head.size, _p(head, C.c_int32), _p(rel, C.c_int32), _p(tail, C.c_int32),
+        _p(Ehat, D), _p(Hhat, D), _p(mask, C.c_uint8), _p(Wr, D), _p(er, D), _p(W, D), d, k, dout,
+        float(slope), _p(gEout, D), threads, _p(gE, D), _p(gWr, D), _p(ger, D), _p(gW, D)),
+        "aggregate_bwd_f64")
+    return gE, gWr, ger, gW
+
+
+def aggregate_fwd(n_nodes, head, rel, tail, E, Wr, er, W, slope, threads=1):
+    """fp32-in / fp32-out layer forward.  Returns E_out, H (fp32) and the boolean
+    mask J > 0 as uint8 [n_nodes, d_out]."""
+    head, rel, tail = _coo(head, rel, tail)
+    E, Wr, er, W = (np.ascontiguousarray(a, dtype=np.float32) for a in (E, Wr, er, W))
+    R, k, d = Wr.shape
+    dout = W.shape[0]
+    assert E.shape == (n_nodes, d) and er.shape == (R, k) and W.shape == (dout, d)
+    Eout = np.empty((n_nodes, dout), np.float32); H = np.empty((n_nodes, d), np.float32)
+    mask = np.empty((n_nodes, dout), np.uint8)
+    F = C.c_float
+    _check(_agg().tinykg_ref_kg_aggregate_fwd(
+        n_nodes, R, head.size, _p(head, C.c_int32), _p(rel, C.c_int32), _p(tail, C.c_int32),
+        _p(E, F), _p(Wr, F), _p(er, F), _p(W, F), d, k, dout, float(slope), threads,
+        _p(Eout, F), _p(H, F), _p(mask, C.c_uint8)), "aggregate_fwd")
+    return Eout, H, mask
+
+
+def aggregate_bwd(n_nodes, head, rel, tail, Ehat, Hhat, mask, Wr, er, W, slope, gEout, threads=1):
+    """fp32-in / fp32-out layer backward at the given saved tensors."""
+    head, rel, tail = _coo(head, rel, tail)
+    Ehat, Hhat, Wr, er, W, gEout = (np.ascontiguousarray(a, dtype=np.float32)
+                                    for a in (Ehat, Hhat, Wr, er, W, gEout))
+    mask = np.ascontiguousarray(mask, dtype=np.uint8)
+    R, k, d = Wr.shape
+    dout = W.shape[0]
+    assert Ehat.shape == (n_nodes, d) == Hhat.shape and mask.shape == (n_nodes, dout) == gEout.shape
+    gE = np.empty((n_nodes, d), np.float32); gWr = np.empty((R, k, d), np.float32)
+    ger = np.empty((R, k), np.float32); gW = np.empty((dout, d), np.float32)
+    F = C.c_float
+    _check(_agg().tinykg_ref_kg_aggregate_bwd(
+        n_nodes, R, head.size, _p(head, C.c_int32), _p(rel, C.c_int32), _p(tail, C.c_int32),
+        _p(Ehat, F), _p(Hhat, F), _p(mask, C.c_uint8), _p(Wr, F), _p(er, F), _p(W, F), d, k, dout,
+        float(slope), _p(gEout, F), threads, _p(gE, F), _p(gWr, F), _p(ger, F), _p(gW, F)),
+        "aggregate_bwd")
+    return gE, gWr, ger, gW
+
+
+# ---- the saved context of one layer (Fig. 1): Q(E; seed), Q(H; seed+1), 1-bit mask
+def save_context(E, H, mask, bits, group, seed):
+    """Compress what the backward pass needs.  bits == 32 keeps fp32 copies."""
+    E = np.ascontiguousarray(E, dtype=np.float32)
+    H = np.ascontiguousarray(H, dtype=np.float32)
+    mask_bits = pack((np.ascontiguousarray(mask) != 0).astype(np.uint8), 1)
+    if bits == 32:
+        return {"bits": 32, "E": E.copy(), "H": H.copy(), "mask": mask_bits}
+    pE, mnE, scE = quantize(E, bits, group, seed)
+    pH, mnH, scH = quantize(H, bits, group, (seed + 1) & (2 ** 64 - 1))
+    return {"bits": bits, "group": group, "packed_E": pE, "gmin_E": mnE, "gscale_E": scE,
+            "packed_H": pH, "gmin_H": mnH, "gscale_H": scH, "mask": mask_bits}
+
+
+def restore_context(ctx, n_nodes, d_in, d_out):
+    """E_hat, H_hat (fp32) and the unpacked mask [n_nodes, d_out]."""
+    mask = unpack(ctx["mask"], n_nodes * d_out, 1).reshape(n_nodes, d_out)
+    if ctx["bits"] == 32:
+        return ctx["E"], ctx["H"], mask
+    b, g = ctx["bits"], ctx["group"]
+    Eh = dequantize(ctx["packed_E"], ctx["gmin_E"], ctx["gscale_E"], n_nodes, d_in, b, g)
+    Hh = dequantize(ctx["packed_H"], ctx["gmin_H"], ctx["gscale_H"], n_nodes, d_in, b, g)
+    return Eh, Hh, mask

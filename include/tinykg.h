@@ -1,0 +1,162 @@
+/*
+ * tinykg.h -- C ABI of the MI355X (gfx950) implementation of TinyKG's activation
+ * compressor and of the attentive knowledge-graph aggregation layer whose saved
+ * activations it compresses.
+ *
+ * General conventions
+ *   - Every tensor pointer is a DEVICE pointer owned by the caller, 16-byte
+ *     aligned, dense, row-major, unless a parameter says "host".
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     Calls enqueue work on it and return without synchronising; the caller
+ *     keeps inputs, outputs and workspace alive until the stream has drained.
+ *   - Outputs are fully overwritten (gradients are assigned, not accumulated).
+ *   - No entry point allocates or frees device memory except
+ *     tinykg_graph_create / tinykg_graph_destroy.
+ *   - Errors are returned as tinykg_status; nothing is written when a call
+ *     returns TINYKG_ERR_INVALID_ARG / _SHAPE / _UNSUPPORTED / _WORKSPACE.
+ *     TINYKG_ERR_DEVICE reports a failed HIP call (launch, copy, allocation).
+ *   - Inputs must be finite; behaviour for NaN/Inf activations is unspecified.
+ */
+#ifndef TINYKG_H
+#define TINYKG_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  TINYKG_OK = 0,
+  TINYKG_ERR_INVALID_ARG = 1, /* null pointer, misaligned pointer, bad bits/group/rounding */
+  TINYKG_ERR_SHAPE = 2,       /* negative size, rows*dim not a multiple of group, ... */
+  TINYKG_ERR_UNSUPPORTED = 3, /* a size the kernels are not built for */
+  TINYKG_ERR_WORKSPACE = 4,   /* workspace missing or too small */
+  TINYKG_ERR_DEVICE = 5       /* a HIP runtime call failed */
+} tinykg_status;
+
+typedef enum { TINYKG_ROUND_STOCHASTIC = 0, TINYKG_ROUND_NEAREST = 1 } tinykg_rounding;
+
+const char* tinykg_status_string(tinykg_status s);
+
+/* Size helpers (host arithmetic only).  Sec. 3.2 "Memory Analysis": an N x d
+ * activation map costs rows*dim*bits/8 bytes of codes plus one (min, scale)
+ * fp32 pair per group, i.e. bits/8 + 8/group bytes per element. */
+size_t  tinykg_packed_bytes(int64_t rows, int64_t dim, int bits); /* rows*dim*bits/8 */
+int64_t tinykg_num_groups(int64_t rows, int64_t dim, int group);  /* rows*dim/group  */
+
+/* Quant of Sec. 3.3, Eq. (3), fused with the bit-stream conversion of Sec. 4.1.4.
+ *
+ * The row-major flattening of act[rows, dim] is cut into groups of `group`
+ * consecutive elements.  Per group: Z = min, R = max - Z, B = 2^bits - 1;
+ * gmin = Z (a minimum of -0 is stored as +0), gscale = R / B.  Per element
+ * code = SR((e - Z) * (B / R)) clamped to [0, B], where SR rounds up with
+ * probability equal to the fractional part; the group maximum always gets code
+ * B and a constant group gets all-zero codes and gscale = 0.  The rounding
+ * noise is 16 bits per element from Philox4x32-10 with key = seed and counter =
+ * (flat element index) / 8: element i uses the low (i even) or high (i odd) half
+ * of output word (i / 2) mod 4, so the result depends only on (act, seed) and
+ * never on the launch geometry.  Codes are packed LSB-first: element i occupies
+ * bits [(i*bits) mod 8, +bits) of byte (i*bits) / 8.
+ *
+ *   act    in   [rows, dim] fp32
+ *   bits        1, 2, 4 or 8
+ *   group       32, 64, 128 or 256; rows*dim must be a multiple (else ERR_SHAPE)
+ *   packed out  tinykg_packed_bytes(rows, dim, bits) bytes
+ *   gmin   out  tinykg_num_groups(...) fp32
+ *   gscale out  tinykg_num_groups(...) fp32
+ * rows*dim == 0 returns TINYKG_OK and writes nothing. */
+tinykg_status tinykg_quantize(const float* act, int64_t rows, int64_t dim, int bits, int group,
+                              uint64_t seed, uint8_t* packed, float* gmin, float* gscale,
+                              void* stream);
+
+/* As tinykg_quantize, with two more controls:
+ *   first_index  flat index of act[0] inside a larger tensor (multiple of
+ *                `group`); the noise counter starts there, so quantising a slice
+ *                yields the bytes the whole tensor's run would produce for it.
+ *   rounding     TINYKG_ROUND_STOCHASTIC, or TINYKG_ROUND_NEAREST (the ablation
+ *                of Sec. 4.4, Table 6: code = floor(x + 1/2), seed unused). */
+tinykg_status tinykg_quantize_ex(const float* act, int64_t rows, int64_t dim, int bits, int group,
+                                 uint64_t seed, uint64_t first_index, int rounding,
+                                 uint8_t* packed, float* gmin, float* gscale, void* stream);
+
+/* Dequant of Sec. 3.3, Eq. (4): out[i] = fma(code_i, gscale[i/group], gmin[i/group])
+ * (R * code / B + Z with scale = R / B, one rounding).  Arguments as above;
+ * out is [rows, dim] fp32. */
+tinykg_status tinykg_dequantize(const uint8_t* packed, const float* gmin, const float* gscale,
+                                int64_t rows, int64_t dim, int bits, int group, float* out,
+                                void* stream);
+
+/* ------------------------------------------------------------------------- *
+ * Attentive aggregation layer (the KG-Layer of Sec. 3.2, Eq. (1), in the
+ * three-stage form of Eq. (2), with KGAT's attention as the sparse operator):
+ *   a_j = W_r e_t,  b_j = W_r e_h + e_r,  s_j = a_j . tanh(b_j)      per triplet j = (h, r, t)
+ *   pi_j = softmax of s_j over the triplets that share the head h
+ *   H_h = e_h + sum_j pi_j e_t ;  J_h = W H_h ;  E'_h = J_h > 0 ? J_h : slope * J_h
+ * A head without triplets has H_h = e_h.  Repeated triplets and self-loops are
+ * separate edges.
+ * ------------------------------------------------------------------------- */
+
+/* Opaque, immutable graph: triplets grouped by head (CSR), plus the orderings
+ * the kernels need.  Built once, shared by every layer and step (Sec. 3.2: the
+ * adjacency is kept once for all layers). */
+typedef struct tinykg_graph tinykg_graph;
+
+/* head/rel/tail: DEVICE int32 arrays of n_edges entries, any order; ids must lie
+ * in [0, n_nodes) and [0, n_rel) (else ERR_INVALID_ARG).  Synchronises `stream`,
+ * allocates device memory owned by the graph.  *out is set only on TINYKG_OK. */
+tinykg_status tinykg_graph_create(int64_t n_nodes, int32_t n_rel, int64_t n_edges,
+                                  const int32_t* head, const int32_t* rel, const int32_t* tail,
+                                  void* stream, tinykg_graph** out);
+void tinykg_graph_destroy(tinykg_graph* g);
+int64_t tinykg_graph_num_nodes(const tinykg_graph* g);
+int64_t tinykg_graph_num_edges(const tinykg_graph* g);
+
+/* The saved context of one layer (Fig. 1; Sec. 3.2: the inputs of the spmm and mm
+ * stages, and one bit per element for the ReLU-type stage, Sec. 4.1.4).
+ * Caller-allocated device buffers in exactly tinykg_quantize's output layout.
+ * With bits == 32 nothing is compressed: packed_E / packed_H hold the fp32
+ * tensors themselves (n_nodes*d_in*4 bytes each) and gmin / gscale are unused
+ * (may be NULL). */
+typedef struct {
+  uint8_t* packed_E; float* gmin_E; float* gscale_E; /* Q(E; seed),     n = n_nodes*d_in */
+  uint8_t* packed_H; float* gmin_H; float* gscale_H; /* Q(H; seed + 1), n = n_nodes*d_in */
+  uint8_t* mask_J; /* [J > 0], n_nodes*d_out bits, LSB-first, ceil(n_nodes*d_out/8) bytes */
+} tinykg_saved;
+
+/* Scratch bytes the forward (is_bwd == 0) or backward (is_bwd != 0) call needs. */
+size_t tinykg_kg_aggregate_workspace_bytes(const tinykg_graph* g, int d_in, int d_rel, int d_out,
+                                           int is_bwd);
+
+/* Forward pass; exact (compression never changes E_out -- Fig. 1), and saves the
+ * context compressed: Q(E; seed), Q(H; seed+1) with `bits`/`group` as in
+ * tinykg_quantize (or fp32 copies when bits == 32), and the sign mask of J.
+ *   E [n_nodes, d_in], Wr [n_rel, d_rel, d_in], er [n_rel, d_rel], W [d_out, d_in]
+ *   E_out [n_nodes, d_out]
+ * d_in == d_rel in {32, 64, 128}; d_out a multiple of 16 up to 128; n_nodes*d_in
+ * a multiple of `group` (else ERR_UNSUPPORTED / ERR_SHAPE). */
+tinykg_status tinykg_kg_aggregate_fwd(const tinykg_graph* g, const float* E, const float* Wr,
+                                      const float* er, const float* W, int d_in, int d_rel,
+                                      int d_out, float leaky_slope, int bits, int group,
+                                      uint64_t seed, float* E_out, const tinykg_saved* saved,
+                                      void* workspace, size_t workspace_bytes, void* stream);
+
+/* Backward pass: the vector-Jacobian product of the layer evaluated at the saved
+ * context (Sec. 3.3: gradients are computed from the dequantised activations;
+ * Eq. (2): grad_J = ctx(J, grad_E'), (grad_H, grad_W) = ctx(H, W, grad_J),
+ * grad_E = ctx(A, grad_H)).  Projections, scores and attention are recomputed
+ * from E_hat = Dequant(Q(E)); dequantisation is fused into the gathers.
+ *   grad_E_out [n_nodes, d_out]  ->  grad_E [n_nodes, d_in], grad_Wr [n_rel, d_rel, d_in],
+ *   grad_er [n_rel, d_rel], grad_W [d_out, d_in] */
+tinykg_status tinykg_kg_aggregate_bwd(const tinykg_graph* g, const tinykg_saved* saved,
+                                      const float* Wr, const float* er, const float* W, int d_in,
+                                      int d_rel, int d_out, float leaky_slope, int bits, int group,
+                                      const float* grad_E_out, float* grad_E, float* grad_Wr,
+                                      float* grad_er, float* grad_W, void* workspace,
+                                      size_t workspace_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TINYKG_H */

@@ -126,7 +126,9 @@ int tinykg_ref_quantize_codes(const float* act, int64_t n, int bits, int group, 
       if (x[j] < mn) mn = x[j];
       if (x[j] > mx) mx = x[j];
     }
-    mn = mn + 0.0f;  // reading: a minimum of -0 is stored as +0
+    mn = mn + 0.0f;  // reading: a minimum of -0 is stored as +0 ...
+    mx = mx + 0.0f;  // ... and likewise the maximum, so R and R/B of an all-zero
+                     // group are +0 whatever the order of its +0 / -0 elements
     const float range = mx - mn;       // R, rounded once
     const float scale = range / Bf;    // R / B, correctly rounded
     // B / R, correctly rounded.  Reading: when R is so small that B/R is not

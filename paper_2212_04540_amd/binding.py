@@ -1,0 +1,222 @@
+"""Thin ctypes binding of libtinykg.so (the C ABI declared in include/tinykg.h).
+
+Argument marshalling only: every step of the path runs inside the HIP library.
+torch is used for device memory and for the current stream; tensors are never
+touched by torch arithmetic here.  There is no CPU fallback: if the library is
+missing or a call fails, an exception is raised.
+"""
+import ctypes as C
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libtinykg.so")
+_lib = None
+
+ROUND_STOCHASTIC = 0
+ROUND_NEAREST = 1
+
+EXPORTS = [
+    "tinykg_status_string", "tinykg_packed_bytes", "tinykg_num_groups", "tinykg_quantize",
+    "tinykg_quantize_ex", "tinykg_dequantize", "tinykg_graph_create", "tinykg_graph_destroy",
+    "tinykg_graph_num_nodes", "tinykg_graph_num_edges", "tinykg_kg_aggregate_workspace_bytes",
+    "tinykg_kg_aggregate_fwd", "tinykg_kg_aggregate_bwd",
+]
+
+
+class TinyKGError(RuntimeError):
+    def __init__(self, status, what):
+        self.status = int(status)
+        msg = lib().tinykg_status_string(int(status)).decode()
+        super().__init__(f"{what}: {msg} (status {int(status)})")
+
+
+class Saved(C.Structure):
+    """tinykg_saved: device pointers of one layer's saved context."""
+    _fields_ = [("packed_E", C.c_void_p), ("gmin_E", C.c_void_p), ("gscale_E", C.c_void_p),
+                ("packed_H", C.c_void_p), ("gmin_H", C.c_void_p), ("gscale_H", C.c_void_p),
+                ("mask_J", C.c_void_p)]
+
+
+def lib():
+    """Load libtinykg.so (built in-tree by paper_2212_04540_amd/build.py)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            raise RuntimeError(f"{_LIB_PATH} is missing: build it with "
+                               "`python -m paper_2212_04540_amd.build` (hipcc, gfx950)")
+        L = C.CDLL(_LIB_PATH)
+        vp, i64, u64, i32, f32, sz = C.c_void_p, C.c_int64, C.c_uint64, C.c_int, C.c_float, C.c_size_t
+        L.tinykg_status_string.argtypes = [C.c_int]
+        L.tinykg_status_string.restype = C.c_char_p
+        L.tinykg_packed_bytes.argtypes = [i64, i64, i32]
+        L.tinykg_packed_bytes.restype = sz
+        L.tinykg_num_groups.argtypes = [i64, i64, i32]
+        L.tinykg_num_groups.restype = i64
+        L.tinykg_quantize.argtypes = [vp, i64, i64, i32, i32, u64, vp, vp, vp, vp]
+        L.tinykg_quantize_ex.argtypes = [vp, i64, i64, i32, i32, u64, u64, i32, vp, vp, vp, vp]
+        L.tinykg_dequantize.argtypes = [vp, vp, vp, i64, i64, i32, i32, vp, vp]
+        if hasattr(L, "tinykg_graph_create"):
+            L.tinykg_graph_create.argtypes = [i64, C.c_int32, i64, vp, vp, vp, vp, C.POINTER(vp)]
+            L.tinykg_graph_destroy.argtypes = [vp]
+            L.tinykg_graph_destroy.restype = None
+            L.tinykg_graph_num_nodes.argtypes = [vp]
+            L.tinykg_graph_num_nodes.restype = i64
+            L.tinykg_graph_num_edges.argtypes = [vp]
+            L.tinykg_graph_num_edges.restype = i64
+            L.tinykg_kg_aggregate_workspace_bytes.argtypes = [vp, i32, i32, i32, i32]
+            L.tinykg_kg_aggregate_workspace_bytes.restype = sz
+            L.tinykg_kg_aggregate_fwd.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, f32, i32, i32,
+                                                  u64, vp, C.POINTER(Saved), vp, sz, vp]
+            L.tinykg_kg_aggregate_bwd.argtypes = [vp, C.POINTER(Saved), vp, vp, vp, i32, i32, i32,
+                                                  f32, i32, i32, vp, vp, vp, vp, vp, vp, sz, vp]
+        _lib = L
+    return _lib
+
+
+def _stream():
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _ptr(t):
+    return C.c_void_p(0 if t is None else t.data_ptr())
+
+
+def _dev(t, dtype, what):
+    if not (isinstance(t, torch.Tensor) and t.is_cuda and t.dtype == dtype and t.is_contiguous()):
+        raise TypeError(f"{what}: expected a contiguous {dtype} CUDA tensor")
+    return t
+
+
+def _ok(status, what):
+    if status != 0:
+        raise TinyKGError(status, what)
+
+
+def tinykg_packed_bytes(rows, dim, bits):
+    return int(lib().tinykg_packed_bytes(rows, dim, bits))
+
+
+def tinykg_num_groups(rows, dim, group):
+    return int(lib().tinykg_num_groups(rows, dim, group))
+
+
+def alloc_quantized(rows, dim, bits, group, device="cuda"):
+    """Device buffers in tinykg_quantize's output layout: packed, gmin, gscale."""
+    ng = max(tinykg_num_groups(rows, dim, group), 0)
+    return (torch.empty(tinykg_packed_bytes(rows, dim, bits), dtype=torch.uint8, device=device),
+            torch.empty(ng, dtype=torch.float32, device=device),
+            torch.empty(ng, dtype=torch.float32, device=device))
+
+
+def tinykg_quantize(act, bits, group, seed, out=None, first_index=0, rounding=ROUND_STOCHASTIC):
+    """act: [rows, dim] fp32 CUDA tensor -> (packed uint8, gmin fp32, gscale fp32)."""
+    _dev(act, torch.float32, "act")
+    if act.dim() != 2:
+        raise TypeError("act must be 2-D [rows, dim]")
+    rows, dim = act.shape
+    packed, gmin, gscale = out if out is not None else alloc_quantized(rows, dim, bits, group, act.device)
+    st = lib().tinykg_quantize_ex(_ptr(act), rows, dim, bits, group, C.c_uint64(seed),
+                                  C.c_uint64(first_index), rounding, _ptr(packed), _ptr(gmin),
+                                  _ptr(gscale), _stream())
+    _ok(st, "tinykg_quantize")
+    return packed, gmin, gscale
+
+
+def tinykg_dequantize(packed, gmin, gscale, rows, dim, bits, group, out=None):
+    _dev(packed, torch.uint8, "packed")
+    _dev(gmin, torch.float32, "gmin")
+    _dev(gscale, torch.float32, "gscale")
+    if out is None:
+        out = torch.empty((rows, dim), dtype=torch.float32, device=packed.device)
+    st = lib().tinykg_dequantize(_ptr(packed), _ptr(gmin), _ptr(gscale), rows, dim, bits, group,
+                                 _ptr(out), _stream())
+    _ok(st, "tinykg_dequantize")
+    return out
+
+
+class Graph:
+    """Owner of a tinykg_graph handle."""
+
+    def __init__(self, n_nodes, n_rel, head, rel, tail):
+        for t, nm in ((head, "head"), (rel, "rel"), (tail, "tail")):
+            _dev(t, torch.int32, nm)
+        self.n_nodes, self.n_rel, self.n_edges = int(n_nodes), int(n_rel), int(head.numel())
+        h = C.c_void_p()
+        st = lib().tinykg_graph_create(self.n_nodes, self.n_rel, self.n_edges, _ptr(head), _ptr(rel),
+                                       _ptr(tail), _stream(), C.byref(h))
+        _ok(st, "tinykg_graph_create")
+        self.handle = h
+
+    def close(self):
+        if getattr(self, "handle", None) is not None and self.handle:
+            lib().tinykg_graph_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+class SavedContext:
+    """Device buffers of one layer's saved context + the tinykg_saved struct."""
+
+    def __init__(self, n_nodes, d_in, d_out, bits, group, device="cuda"):
+        self.n_nodes, self.d_in, self.d_out, self.bits, self.group = n_nodes, d_in, d_out, bits, group
+        if bits == 32:
+            self.packed_E = torch.empty(n_nodes * d_in * 4, dtype=torch.uint8, device=device)
+            self.packed_H = torch.empty(n_nodes * d_in * 4, dtype=torch.uint8, device=device)
+            self.gmin_E = self.gscale_E = self.gmin_H = self.gscale_H = None
+        else:
+            self.packed_E, self.gmin_E, self.gscale_E = alloc_quantized(n_nodes, d_in, bits, group, device)
+            self.packed_H, self.gmin_H, self.gscale_H = alloc_quantized(n_nodes, d_in, bits, group, device)
+        self.mask_J = torch.empty((n_nodes * d_out + 7) // 8, dtype=torch.uint8, device=device)
+        self.struct = Saved(_ptr(self.packed_E), _ptr(self.gmin_E), _ptr(self.gscale_E),
+                            _ptr(self.packed_H), _ptr(self.gmin_H), _ptr(self.gscale_H),
+                            _ptr(self.mask_J))
+
+    def nbytes(self):
+        ts = [self.packed_E, self.gmin_E, self.gscale_E, self.packed_H, self.gmin_H, self.gscale_H,
+              self.mask_J]
+        return sum(t.numel() * t.element_size() for t in ts if t is not None)
+
+
+def tinykg_kg_aggregate_workspace_bytes(graph, d_in, d_rel, d_out, is_bwd):
+    return int(lib().tinykg_kg_aggregate_workspace_bytes(graph.handle, d_in, d_rel, d_out,
+                                                         1 if is_bwd else 0))
+
+
+def tinykg_kg_aggregate_fwd(graph, E, Wr, er, W, leaky_slope, bits, group, seed, saved, workspace,
+                            E_out=None):
+    for t, nm in ((E, "E"), (Wr, "Wr"), (er, "er"), (W, "W")):
+        _dev(t, torch.float32, nm)
+    d_in, d_rel, d_out = E.shape[1], Wr.shape[1], W.shape[0]
+    if E_out is None:
+        E_out = torch.empty((graph.n_nodes, d_out), dtype=torch.float32, device=E.device)
+    st = lib().tinykg_kg_aggregate_fwd(graph.handle, _ptr(E), _ptr(Wr), _ptr(er), _ptr(W), d_in,
+                                       d_rel, d_out, float(leaky_slope), bits, group,
+                                       C.c_uint64(seed), _ptr(E_out), C.byref(saved.struct),
+                                       _ptr(workspace), workspace.numel(), _stream())
+    _ok(st, "tinykg_kg_aggregate_fwd")
+    return E_out
+
+
+def tinykg_kg_aggregate_bwd(graph, saved, Wr, er, W, leaky_slope, bits, group, grad_E_out,
+                            workspace, out=None):
+    for t, nm in ((Wr, "Wr"), (er, "er"), (W, "W"), (grad_E_out, "grad_E_out")):
+        _dev(t, torch.float32, nm)
+    d_in, d_rel, d_out = Wr.shape[2], Wr.shape[1], W.shape[0]
+    if out is None:
+        dev = Wr.device
+        out = (torch.empty((graph.n_nodes, d_in), dtype=torch.float32, device=dev),
+               torch.empty_like(Wr), torch.empty_like(er), torch.empty_like(W))
+    gE, gWr, ger, gW = out
+    st = lib().tinykg_kg_aggregate_bwd(graph.handle, C.byref(saved.struct), _ptr(Wr), _ptr(er),
+                                       _ptr(W), d_in, d_rel, d_out, float(leaky_slope), bits, group,
+                                       _ptr(grad_E_out), _ptr(gE), _ptr(gWr), _ptr(ger), _ptr(gW),
+                                       _ptr(workspace), workspace.numel(), _stream())
+    _ok(st, "tinykg_kg_aggregate_bwd")
+    return gE, gWr, ger, gW

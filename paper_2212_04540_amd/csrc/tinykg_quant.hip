@@ -1,0 +1,405 @@
+// Fused quantize + bit-pack and unpack + dequantize kernels for gfx950.
+//
+// Quant / Dequant are Eq. (3) / Eq. (4) of Sec. 3.3; the packed layout is the
+// "bit-stream" of Sec. 4.1.4.  The exact arithmetic (operation order, rounding
+// noise, packing order) is stated in include/tinykg.h.
+//
+// This file must be compiled with -ffp-contract=off: every float operation of
+// the quantizer rounds once, in the order written.
+//
+// Kernel shape (quantize).  The path is bound by HBM reads (4 B/element in,
+// bits/8 + 8/group out) only if the per-element VALU work stays small, so the
+// layout is chosen to make each lane own 16 CONSECUTIVE elements:
+//   * a wave streams tiles of 1024 elements; the four coalesced 128-bit loads
+//     of a tile go through a wave-private 4 KiB LDS slab (XOR-swizzled so both
+//     the row-wise write and the lane-contiguous read are bank-conflict free);
+//   * 16 elements per lane means a group of G elements spans G/16 <= 16 lanes,
+//     i.e. one DPP row: min/max finish with at most four DPP steps, and the two
+//     IEEE divides (R/B, B/R) are paid once per 16 elements;
+//   * one Philox4x32-10 block yields 8 x 16 random bits, so a lane needs exactly
+//     two blocks, whose counters are (first_index + element)/8;
+//   * the 16 codes of a lane are 16*bits contiguous bits of the stream: one
+//     2/4/8/16-byte store per lane, contiguous across the wave.
+// The next tile's loads are issued before the current tile is processed.
+#include "tinykg_common.h"
+
+#include <float.h>
+
+namespace tinykg {
+
+namespace {
+
+constexpr int kWave = 64;
+constexpr int kElemsPerLane = 16;
+constexpr int kTileElems = kWave * kElemsPerLane;  // 1024 elements = 4 KiB of fp32
+constexpr int kWavesPerBlock = 4;
+constexpr int kBlock = kWave * kWavesPerBlock;
+
+// ---- cross-lane exchange inside a DPP row (16 lanes) ------------------------
+template <int CTRL>
+__device__ __forceinline__ float dpp(float v) {
+  return __int_as_float(
+      __builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xF, 0xF, true));
+}
+constexpr int kQuadSwap1 = 0xB1;   // quad_perm:[1,0,3,2]
+constexpr int kQuadSwap2 = 0x4E;   // quad_perm:[2,3,0,1]
+constexpr int kHalfMirror = 0x141; // row_half_mirror
+constexpr int kRowMirror = 0x140;  // row_mirror
+
+// All-reduce over LPG (2,4,8,16) adjacent lanes: after each step the reduced
+// sub-block is uniform, so mirroring pairs it with its neighbour sub-block.
+template <int LPG>
+__device__ __forceinline__ void group_minmax(float& mn, float& mx) {
+  if (LPG >= 2) { mn = fminf(mn, dpp<kQuadSwap1>(mn)); mx = fmaxf(mx, dpp<kQuadSwap1>(mx)); }
+  if (LPG >= 4) { mn = fminf(mn, dpp<kQuadSwap2>(mn)); mx = fmaxf(mx, dpp<kQuadSwap2>(mx)); }
+  if (LPG >= 8) { mn = fminf(mn, dpp<kHalfMirror>(mn)); mx = fmaxf(mx, dpp<kHalfMirror>(mx)); }
+  if (LPG >= 16) { mn = fminf(mn, dpp<kRowMirror>(mn)); mx = fmaxf(mx, dpp<kRowMirror>(mx)); }
+}
+
+// ---- Philox4x32-10 (Salmon et al., SC'11) -----------------------------------
+// Counter (c0, c1, 0, 0), key (k0, k1).  The third and fourth counter words are
+// zero by construction, which removes one multiply from the first round.
+struct Philox4 { uint32_t w[4]; };
+
+__device__ __forceinline__ Philox4 philox4x32_10(uint32_t c0, uint32_t c1, uint32_t k0,
+                                                 uint32_t k1) {
+  constexpr uint32_t M0 = 0xD2511F53u, M1 = 0xCD9E8D57u;
+  constexpr uint32_t W0 = 0x9E3779B9u, W1 = 0xBB67AE85u;
+  uint32_t c2 = 0u, c3 = 0u;
+#pragma unroll
+  for (int r = 0; r < 10; ++r) {
+    const uint64_t p0 = (uint64_t)M0 * c0;
+    const uint64_t p1 = (uint64_t)M1 * c2;
+    const uint32_t n0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0;
+    const uint32_t n2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1;
+    c1 = (uint32_t)p1;
+    c3 = (uint32_t)p0;
+    c0 = n0;
+    c2 = n2;
+    k0 += W0;
+    k1 += W1;
+  }
+  return Philox4{{c0, c1, c2, c3}};
+}
+
+// Physical 16-byte slot of logical chunk `c` (0..255) of a wave's slab.  The
+// owner lane of chunk c is i = c/4.  Only the low two bits are permuted, by
+// s(i) = (bit2(i), bit1(i) ^ bit3(i)), so (a) consecutive chunks written by
+// consecutive lanes still cover contiguous 64-byte runs, and (b) when every lane
+// reads its j-th chunk, any 8 (or 16) neighbouring lanes touch 8 (or 16)
+// different 16-byte bank groups.
+__device__ __forceinline__ int slab_slot(int c) {
+  const int s = ((c >> 3) & 2) | (((c >> 3) ^ (c >> 5)) & 1);
+  return c ^ s;
+}
+
+template <int BITS, int GROUP, int ROUNDING>
+__global__ __launch_bounds__(kBlock) void quantize_kernel(
+    const float* __restrict__ act, int64_t n, uint32_t seed_lo, uint32_t seed_hi,
+    uint64_t first_index, uint8_t* __restrict__ packed, float* __restrict__ gmin,
+    float* __restrict__ gscale) {
+  constexpr int LPG = GROUP / kElemsPerLane;       // lanes per group
+  constexpr float Bf = (float)((1 << BITS) - 1);   // B = 2^b - 1
+  constexpr int kWords = (kElemsPerLane * BITS + 31) / 32;
+
+  __shared__ float4 slab[kWavesPerBlock][kTileElems / 4];
+
+  const int lane = threadIdx.x & (kWave - 1);
+  const int wave = threadIdx.x >> 6;
+  float4* my = slab[wave];
+
+  const int64_t n_tiles = (n + kTileElems - 1) / kTileElems;
+  const int64_t stride = (int64_t)gridDim.x * kWavesPerBlock;
+  int64_t tile = (int64_t)blockIdx.x * kWavesPerBlock + wave;
+  if (tile >= n_tiles) return;
+
+  const float4* src = reinterpret_cast<const float4*>(act);
+  const int64_t n_chunks = n >> 2;  // n is a multiple of 32
+
+  float4 nxt[4];
+  {
+    const int64_t c0 = tile * (kTileElems / 4) + lane;
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int64_t c = c0 + u * kWave;
+      nxt[u] = c < n_chunks ? src[c] : make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+  }
+
+  for (; tile < n_tiles; tile += stride) {
+    // stage the tile: row-wise (coalesced order) into the swizzled slab
+#pragma unroll
+    for (int u = 0; u < 4; ++u) my[slab_slot(u * kWave + lane)] = nxt[u];
+    // prefetch the next tile of this wave while this one is processed
+    {
+      const int64_t c0 = (tile + stride) * (kTileElems / 4) + lane;
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int64_t c = c0 + u * kWave;
+        nxt[u] = c < n_chunks ? src[c] : make_float4(0.f, 0.f, 0.f, 0.f);
+      }
+    }
+    // lane-contiguous read-back: elements [16*lane, 16*lane+16) of the tile
+    float x[kElemsPerLane];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const float4 v = my[slab_slot(4 * lane + j)];
+      x[4 * j + 0] = v.x; x[4 * j + 1] = v.y; x[4 * j + 2] = v.z; x[4 * j + 3] = v.w;
+    }
+
+    const int64_t e0 = tile * kTileElems + (int64_t)lane * kElemsPerLane;  // first element
+    const bool live = e0 < n;
+
+    // Z = min, max of the group
+    float mn = x[0], mx = x[0];
+#pragma unroll
+    for (int j = 1; j < kElemsPerLane; ++j) { mn = fminf(mn, x[j]); mx = fmaxf(mx, x[j]); }
+    group_minmax<LPG>(mn, mx);
+    mn = mn + 0.0f;                       // -0 -> +0
+    mx = mx + 0.0f;
+    const float range = mx - mn;          // R
+    const float scale = range / Bf;       // R / B, correctly rounded
+    float inv = 0.0f;                     // B / R, correctly rounded, kept finite
+    if (range > 0.0f) inv = fminf(Bf / range, FLT_MAX);
+
+    // rounding noise: two Philox blocks cover this lane's 16 elements
+    uint32_t rnd[8];
+    if (ROUNDING == TINYKG_ROUND_STOCHASTIC) {
+      const uint64_t q = (first_index + (uint64_t)e0) >> 3;
+      const Philox4 a = philox4x32_10((uint32_t)q, (uint32_t)(q >> 32), seed_lo, seed_hi);
+      const uint64_t q1 = q + 1;
+      const Philox4 b = philox4x32_10((uint32_t)q1, (uint32_t)(q1 >> 32), seed_lo, seed_hi);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) { rnd[i] = a.w[i]; rnd[4 + i] = b.w[i]; }
+    }
+
+    uint32_t words[kWords];
+#pragma unroll
+    for (int w = 0; w < kWords; ++w) words[w] = 0u;
+#pragma unroll
+    for (int j = 0; j < kElemsPerLane; ++j) {
+      const float t = x[j] - mn;                 // e - Z
+      float xb = t * inv;                        // (e - Z) / R * B
+      xb = fminf(xb, Bf);
+      const float f = floorf(xb);
+      const float p = xb - f;                    // exact
+      uint32_t code = (uint32_t)f;
+      if (ROUNDING == TINYKG_ROUND_STOCHASTIC) {
+        const uint32_t wv = rnd[j >> 1];
+        const uint32_t h = (j & 1) ? (wv >> 16) : (wv & 0xFFFFu);
+        code += ((float)h < p * 65536.0f) ? 1u : 0u;
+      } else {
+        code += (p >= 0.5f) ? 1u : 0u;
+      }
+      if (x[j] == mx && range > 0.0f) code = (uint32_t)Bf;   // the maximum is code B
+      words[(j * BITS) >> 5] |= code << ((j * BITS) & 31);
+    }
+
+    if (live) {
+      const int64_t bit0 = e0 * BITS;            // multiple of 16
+      uint8_t* dst = packed + (bit0 >> 3);
+      if (BITS == 1) {
+        *reinterpret_cast<uint16_t*>(dst) = (uint16_t)words[0];
+      } else if (BITS == 2) {
+        *reinterpret_cast<uint32_t*>(dst) = words[0];
+      } else if (BITS == 4) {
+        *reinterpret_cast<uint2*>(dst) = make_uint2(words[0], words[kWords > 1 ? 1 : 0]);
+      } else {
+        *reinterpret_cast<uint4*>(dst) = make_uint4(words[0], words[kWords > 1 ? 1 : 0],
+                                                    words[kWords > 2 ? 2 : 0],
+                                                    words[kWords > 3 ? 3 : 0]);
+      }
+      if ((lane & (LPG - 1)) == 0) {
+        const int64_t g = e0 / GROUP;
+        gmin[g] = mn;
+        gscale[g] = scale;
+      }
+    }
+  }
+}
+
+// ---- unpack + dequantize ------------------------------------------------------
+// One thread per 4 consecutive elements (one 128-bit store); the thread reads
+// only the 4*bits bits it needs, so loads and stores stay contiguous per wave.
+template <int BITS>
+__global__ __launch_bounds__(256) void dequantize_kernel(
+    const uint8_t* __restrict__ packed, const float* __restrict__ gmin,
+    const float* __restrict__ gscale, int64_t n_chunks, int group_chunks_log2,
+    float* __restrict__ out) {
+  constexpr uint32_t B = (1u << BITS) - 1u;
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  for (int64_t c = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; c < n_chunks; c += stride) {
+    uint32_t bitsv;
+    if (BITS == 8) {
+      bitsv = reinterpret_cast<const uint32_t*>(packed)[c];
+    } else if (BITS == 4) {
+      bitsv = reinterpret_cast<const uint16_t*>(packed)[c];
+    } else if (BITS == 2) {
+      bitsv = packed[c];
+    } else {
+      bitsv = (packed[c >> 1] >> ((c & 1) * 4)) & 0xFu;
+    }
+    const int64_t g = c >> group_chunks_log2;
+    const float z = gmin[g], s = gscale[g];
+    float4 v;
+    v.x = fmaf((float)(bitsv & B), s, z);
+    v.y = fmaf((float)((bitsv >> BITS) & B), s, z);
+    v.z = fmaf((float)((bitsv >> (2 * BITS)) & B), s, z);
+    v.w = fmaf((float)((bitsv >> (3 * BITS)) & B), s, z);
+    reinterpret_cast<float4*>(out)[c] = v;
+  }
+}
+
+int ilog2(int v) {
+  int l = 0;
+  while ((1 << l) < v) ++l;
+  return l;
+}
+
+template <int BITS, int ROUNDING>
+tinykg_status launch_quantize_g(const float* act, int64_t n, int group, uint64_t seed,
+                                uint64_t first_index, uint8_t* packed, float* gmin, float* gscale,
+                                hipStream_t stream) {
+  const int64_t n_tiles = (n + kTileElems - 1) / kTileElems;
+  const int64_t want = (n_tiles + kWavesPerBlock - 1) / kWavesPerBlock;
+  const int64_t cap = (int64_t)num_cus() * 8;
+  const dim3 grid((unsigned)(want < cap ? want : cap));
+  const uint32_t lo = (uint32_t)seed, hi = (uint32_t)(seed >> 32);
+#define TINYKG_Q_LAUNCH(G)                                                                   \
+  hipLaunchKernelGGL((quantize_kernel<BITS, G, ROUNDING>), grid, dim3(kBlock), 0, stream, act, n, \
+                     lo, hi, first_index, packed, gmin, gscale)
+  switch (group) {
+    case 32: TINYKG_Q_LAUNCH(32); break;
+    case 64: TINYKG_Q_LAUNCH(64); break;
+    case 128: TINYKG_Q_LAUNCH(128); break;
+    case 256: TINYKG_Q_LAUNCH(256); break;
+    default: return TINYKG_ERR_INVALID_ARG;
+  }
+#undef TINYKG_Q_LAUNCH
+  return launch_status();
+}
+
+template <int ROUNDING>
+tinykg_status launch_quantize_b(const float* act, int64_t n, int bits, int group, uint64_t seed,
+                                uint64_t first_index, uint8_t* packed, float* gmin, float* gscale,
+                                hipStream_t stream) {
+  switch (bits) {
+    case 1: return launch_quantize_g<1, ROUNDING>(act, n, group, seed, first_index, packed, gmin, gscale, stream);
+    case 2: return launch_quantize_g<2, ROUNDING>(act, n, group, seed, first_index, packed, gmin, gscale, stream);
+    case 4: return launch_quantize_g<4, ROUNDING>(act, n, group, seed, first_index, packed, gmin, gscale, stream);
+    case 8: return launch_quantize_g<8, ROUNDING>(act, n, group, seed, first_index, packed, gmin, gscale, stream);
+    default: return TINYKG_ERR_INVALID_ARG;
+  }
+}
+
+}  // namespace
+
+int num_cus() {
+  static int cached = 0;
+  if (cached == 0) {
+    int dev = 0, cus = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
+        cus <= 0)
+      cus = 256;
+    cached = cus;
+  }
+  return cached;
+}
+
+tinykg_status launch_quantize(const float* act, int64_t n, int bits, int group, uint64_t seed,
+                              uint64_t first_index, int rounding, uint8_t* packed, float* gmin,
+                              float* gscale, hipStream_t stream) {
+  if (!bits_ok(bits) || !group_ok(group)) return TINYKG_ERR_INVALID_ARG;
+  if (rounding != TINYKG_ROUND_STOCHASTIC && rounding != TINYKG_ROUND_NEAREST)
+    return TINYKG_ERR_INVALID_ARG;
+  if (n < 0 || n % group != 0 || first_index % (uint64_t)group != 0) return TINYKG_ERR_SHAPE;
+  if (n == 0) return TINYKG_OK;
+  if (!act || !packed || !gmin || !gscale) return TINYKG_ERR_INVALID_ARG;
+  if (!aligned16(act) || !aligned16(packed) || !aligned16(gmin) || !aligned16(gscale))
+    return TINYKG_ERR_INVALID_ARG;
+  if (rounding == TINYKG_ROUND_STOCHASTIC)
+    return launch_quantize_b<TINYKG_ROUND_STOCHASTIC>(act, n, bits, group, seed, first_index,
+                                                      packed, gmin, gscale, stream);
+  return launch_quantize_b<TINYKG_ROUND_NEAREST>(act, n, bits, group, seed, first_index, packed,
+                                                 gmin, gscale, stream);
+}
+
+tinykg_status launch_dequantize(const uint8_t* packed, const float* gmin, const float* gscale,
+                                int64_t n, int bits, int group, float* out, hipStream_t stream) {
+  if (!bits_ok(bits) || !group_ok(group)) return TINYKG_ERR_INVALID_ARG;
+  if (n < 0 || n % group != 0) return TINYKG_ERR_SHAPE;
+  if (n == 0) return TINYKG_OK;
+  if (!packed || !gmin || !gscale || !out) return TINYKG_ERR_INVALID_ARG;
+  if (!aligned16(packed) || !aligned16(gmin) || !aligned16(gscale) || !aligned16(out))
+    return TINYKG_ERR_INVALID_ARG;
+  const int64_t n_chunks = n >> 2;
+  const int64_t want = (n_chunks + 255) / 256;
+  const int64_t cap = (int64_t)num_cus() * 32;
+  const dim3 grid((unsigned)(want < cap ? want : cap));
+  const int gl2 = ilog2(group / 4);
+#define TINYKG_DQ_LAUNCH(BITS)                                                              \
+  hipLaunchKernelGGL((dequantize_kernel<BITS>), grid, dim3(256), 0, stream, packed, gmin, gscale, \
+                     n_chunks, gl2, out)
+  switch (bits) {
+    case 1: TINYKG_DQ_LAUNCH(1); break;
+    case 2: TINYKG_DQ_LAUNCH(2); break;
+    case 4: TINYKG_DQ_LAUNCH(4); break;
+    default: TINYKG_DQ_LAUNCH(8); break;
+  }
+#undef TINYKG_DQ_LAUNCH
+  return launch_status();
+}
+
+}  // namespace tinykg
+
+extern "C" {
+
+const char* tinykg_status_string(tinykg_status s) {
+  switch (s) {
+    case TINYKG_OK: return "ok";
+    case TINYKG_ERR_INVALID_ARG: return "invalid argument";
+    case TINYKG_ERR_SHAPE: return "shape mismatch";
+    case TINYKG_ERR_UNSUPPORTED: return "unsupported size";
+    case TINYKG_ERR_WORKSPACE: return "workspace too small";
+    case TINYKG_ERR_DEVICE: return "HIP runtime error";
+  }
+  return "unknown status";
+}
+
+size_t tinykg_packed_bytes(int64_t rows, int64_t dim, int bits) {
+  if (rows < 0 || dim < 0 || bits <= 0) return 0;
+  return (size_t)(((unsigned __int128)rows * (unsigned __int128)dim * (unsigned)bits + 7) / 8);
+}
+
+int64_t tinykg_num_groups(int64_t rows, int64_t dim, int group) {
+  if (rows < 0 || dim < 0 || group <= 0) return 0;
+  return rows * dim / group;
+}
+
+tinykg_status tinykg_quantize_ex(const float* act, int64_t rows, int64_t dim, int bits, int group,
+                                 uint64_t seed, uint64_t first_index, int rounding,
+                                 uint8_t* packed, float* gmin, float* gscale, void* stream) {
+  if (rows < 0 || dim < 0) return TINYKG_ERR_SHAPE;
+  if (rows != 0 && dim > INT64_MAX / rows) return TINYKG_ERR_SHAPE;
+  return tinykg::launch_quantize(act, rows * dim, bits, group, seed, first_index, rounding, packed,
+                                 gmin, gscale, (hipStream_t)stream);
+}
+
+tinykg_status tinykg_quantize(const float* act, int64_t rows, int64_t dim, int bits, int group,
+                              uint64_t seed, uint8_t* packed, float* gmin, float* gscale,
+                              void* stream) {
+  return tinykg_quantize_ex(act, rows, dim, bits, group, seed, 0, TINYKG_ROUND_STOCHASTIC, packed,
+                            gmin, gscale, stream);
+}
+
+tinykg_status tinykg_dequantize(const uint8_t* packed, const float* gmin, const float* gscale,
+                                int64_t rows, int64_t dim, int bits, int group, float* out,
+                                void* stream) {
+  if (rows < 0 || dim < 0) return TINYKG_ERR_SHAPE;
+  if (rows != 0 && dim > INT64_MAX / rows) return TINYKG_ERR_SHAPE;
+  return tinykg::launch_dequantize(packed, gmin, gscale, rows * dim, bits, group, out,
+                                   (hipStream_t)stream);
+}
+
+}  // extern "C"

@@ -209,6 +209,7 @@ def test_constant_negzero_and_tiny_groups():
             c = codes.reshape(5, 64)
             assert np.all(c[0] == 0) and gmin[0] == np.float32(2.5) and gscale[0] == 0
             assert np.all(c[1] == 0) and gmin[1].view(np.uint32) == 0  # stored as +0
+            assert gscale[1].view(np.uint32) == 0                      # R/B is +0 too
             assert c[2, 0] == 0 and c[2, 63] == B and np.all(c[2] <= B)
             assert np.all(np.diff(c[2].astype(int)) >= -1)
             xh = ref.dequantize(ref.pack(codes, bits), gmin, gscale, 5, 64, bits, 64)

@@ -15,8 +15,7 @@ COMMON = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-I", os.path.j
 SOURCES = {
     "tinykg_quant.hip": ["-ffp-contract=off"],
     "tinykg_graph.hip": [],
-    "tinykg_agg_fwd.hip": [],
-    "tinykg_agg_bwd.hip": [],
+    "tinykg_agg.hip": [],
 }
 
 

@@ -1,17 +1,145 @@
-// placeholder entry points until the aggregation kernels land
-#include "tinykg_common.h"
-extern "C" {
-tinykg_status tinykg_graph_create(int64_t, int32_t, int64_t, const int32_t*, const int32_t*,
-                                  const int32_t*, void*, tinykg_graph**) { return TINYKG_ERR_UNSUPPORTED; }
-void tinykg_graph_destroy(tinykg_graph*) {}
-int64_t tinykg_graph_num_nodes(const tinykg_graph*) { return 0; }
-int64_t tinykg_graph_num_edges(const tinykg_graph*) { return 0; }
-size_t tinykg_kg_aggregate_workspace_bytes(const tinykg_graph*, int, int, int, int) { return 0; }
-tinykg_status tinykg_kg_aggregate_fwd(const tinykg_graph*, const float*, const float*, const float*,
-                                      const float*, int, int, int, float, int, int, uint64_t, float*,
-                                      const tinykg_saved*, void*, size_t, void*) { return TINYKG_ERR_UNSUPPORTED; }
-tinykg_status tinykg_kg_aggregate_bwd(const tinykg_graph*, const tinykg_saved*, const float*,
-                                      const float*, const float*, int, int, int, float, int, int,
-                                      const float*, float*, float*, float*, float*, void*, size_t,
-                                      void*) { return TINYKG_ERR_UNSUPPORTED; }
+// tinykg_graph: the immutable sparse structure shared by every layer and step
+// (Sec. 3.2, "Memory Analysis": the adjacency is kept once for all layers).
+//
+// Built on the host, off the hot path, from device COO triplets:
+//   * head order  -- triplets sorted by (head, relation, tail): CSR row pointers
+//     and the tail of every edge.  The softmax / gather kernels walk it.
+//   * relation order -- the same edges sorted by (relation, tail, head), cut into
+//     chunks that never straddle a relation.  The projection kernels (dense
+//     contractions with one W_r) walk it; sorting by tail inside a relation puts
+//     the edges of a hot tail next to each other, so their gradient rows are
+//     summed before they leave the workgroup.
+#include "tinykg_graph.h"
+
+#include <algorithm>
+#include <numeric>
+#include <vector>
+
+namespace tinykg {
+
+namespace {
+
+template <typename T>
+tinykg_status upload(const std::vector<T>& v, T** out) {
+  *out = nullptr;
+  const size_t bytes = std::max<size_t>(v.size(), 1) * sizeof(T);
+  TINYKG_HIP_TRY(hipMalloc(reinterpret_cast<void**>(out), bytes));
+  if (!v.empty()) TINYKG_HIP_TRY(hipMemcpy(*out, v.data(), v.size() * sizeof(T), hipMemcpyHostToDevice));
+  return TINYKG_OK;
 }
+
+void release(tinykg_graph* g) {
+  if (!g) return;
+  void* ptrs[] = {g->rowptr, g->h_tail, g->r_head, g->r_tail, g->r_eid, g->chunk_rel,
+                  g->chunk_start, g->chunk_count, g->rel_chunk_ptr};
+  for (void* p : ptrs)
+    if (p) (void)hipFree(p);
+  delete g;
+}
+
+}  // namespace
+
+}  // namespace tinykg
+
+extern "C" {
+
+tinykg_status tinykg_graph_create(int64_t n_nodes, int32_t n_rel, int64_t n_edges,
+                                  const int32_t* head, const int32_t* rel, const int32_t* tail,
+                                  void* stream, tinykg_graph** out) {
+  using namespace tinykg;
+  if (!out) return TINYKG_ERR_INVALID_ARG;
+  if (n_nodes < 0 || n_rel < 0 || n_edges < 0) return TINYKG_ERR_SHAPE;
+  if (n_nodes >= (int64_t)1 << 31 || n_edges >= (int64_t)1 << 31 || n_rel > 65535)
+    return TINYKG_ERR_UNSUPPORTED;
+  if (n_edges > 0 && (!head || !rel || !tail)) return TINYKG_ERR_INVALID_ARG;
+  if (n_edges > 0 && n_rel == 0) return TINYKG_ERR_INVALID_ARG;
+
+  const size_t T = (size_t)n_edges;
+  std::vector<int32_t> hh(T), hr(T), ht(T);
+  if (T) {
+    hipStream_t st = (hipStream_t)stream;
+    TINYKG_HIP_TRY(hipMemcpyAsync(hh.data(), head, T * 4, hipMemcpyDeviceToHost, st));
+    TINYKG_HIP_TRY(hipMemcpyAsync(hr.data(), rel, T * 4, hipMemcpyDeviceToHost, st));
+    TINYKG_HIP_TRY(hipMemcpyAsync(ht.data(), tail, T * 4, hipMemcpyDeviceToHost, st));
+    TINYKG_HIP_TRY(hipStreamSynchronize(st));
+  }
+  for (size_t e = 0; e < T; ++e) {
+    if (hh[e] < 0 || hh[e] >= n_nodes || ht[e] < 0 || ht[e] >= n_nodes) return TINYKG_ERR_INVALID_ARG;
+    if (hr[e] < 0 || hr[e] >= n_rel) return TINYKG_ERR_INVALID_ARG;
+  }
+
+  // head order: (head, relation, tail)
+  std::vector<int32_t> ord(T);
+  std::iota(ord.begin(), ord.end(), 0);
+  std::sort(ord.begin(), ord.end(), [&](int32_t a, int32_t b) {
+    if (hh[a] != hh[b]) return hh[a] < hh[b];
+    if (hr[a] != hr[b]) return hr[a] < hr[b];
+    if (ht[a] != ht[b]) return ht[a] < ht[b];
+    return a < b;
+  });
+  std::vector<int32_t> rowptr((size_t)n_nodes + 1, 0), h_tail(T), h_head(T), h_rel(T);
+  for (size_t i = 0; i < T; ++i) {
+    const int32_t e = ord[i];
+    h_head[i] = hh[e]; h_rel[i] = hr[e]; h_tail[i] = ht[e];
+    rowptr[(size_t)hh[e] + 1]++;
+  }
+  for (int64_t i = 0; i < n_nodes; ++i) rowptr[(size_t)i + 1] += rowptr[(size_t)i];
+
+  // relation order over head-order edge ids: (relation, tail, head)
+  std::vector<int32_t> rord(T);
+  std::iota(rord.begin(), rord.end(), 0);
+  std::sort(rord.begin(), rord.end(), [&](int32_t a, int32_t b) {
+    if (h_rel[a] != h_rel[b]) return h_rel[a] < h_rel[b];
+    if (h_tail[a] != h_tail[b]) return h_tail[a] < h_tail[b];
+    return a < b;   // head order already ascends in head
+  });
+  std::vector<int32_t> r_head(T), r_tail(T), r_eid(T);
+  std::vector<int64_t> rel_count((size_t)n_rel, 0);
+  for (size_t i = 0; i < T; ++i) {
+    const int32_t e = rord[i];
+    r_head[i] = h_head[e]; r_tail[i] = h_tail[e]; r_eid[i] = e;
+    rel_count[(size_t)h_rel[e]]++;
+  }
+
+  // chunks: runs of at most chunk_edges consecutive relation-order edges of one
+  // relation; about 2048 of them so that the per-chunk partial gradients stay small.
+  int64_t chunk_edges = ((n_edges / 2048 + 63) / 64) * 64;
+  if (chunk_edges < 64) chunk_edges = 64;
+  std::vector<int32_t> chunk_rel, chunk_start, chunk_count, rel_chunk_ptr((size_t)n_rel + 1, 0);
+  int64_t pos = 0;
+  for (int32_t r = 0; r < n_rel; ++r) {
+    rel_chunk_ptr[(size_t)r] = (int32_t)chunk_rel.size();
+    int64_t left = rel_count[(size_t)r];
+    while (left > 0) {
+      const int64_t c = std::min(left, chunk_edges);
+      chunk_rel.push_back(r);
+      chunk_start.push_back((int32_t)pos);
+      chunk_count.push_back((int32_t)c);
+      pos += c; left -= c;
+    }
+  }
+  rel_chunk_ptr[(size_t)n_rel] = (int32_t)chunk_rel.size();
+
+  tinykg_graph* g = new tinykg_graph();
+  g->n_nodes = n_nodes; g->n_edges = n_edges; g->n_rel = n_rel;
+  g->n_chunks = (int32_t)chunk_rel.size();
+  g->chunk_edges = (int32_t)chunk_edges;
+  tinykg_status st = upload(rowptr, &g->rowptr);
+  if (st == TINYKG_OK) st = upload(h_tail, &g->h_tail);
+  if (st == TINYKG_OK) st = upload(r_head, &g->r_head);
+  if (st == TINYKG_OK) st = upload(r_tail, &g->r_tail);
+  if (st == TINYKG_OK) st = upload(r_eid, &g->r_eid);
+  if (st == TINYKG_OK) st = upload(chunk_rel, &g->chunk_rel);
+  if (st == TINYKG_OK) st = upload(chunk_start, &g->chunk_start);
+  if (st == TINYKG_OK) st = upload(chunk_count, &g->chunk_count);
+  if (st == TINYKG_OK) st = upload(rel_chunk_ptr, &g->rel_chunk_ptr);
+  if (st != TINYKG_OK) { release(g); return st; }
+  *out = g;
+  return TINYKG_OK;
+}
+
+void tinykg_graph_destroy(tinykg_graph* g) { tinykg::release(g); }
+int64_t tinykg_graph_num_nodes(const tinykg_graph* g) { return g ? g->n_nodes : 0; }
+int64_t tinykg_graph_num_edges(const tinykg_graph* g) { return g ? g->n_edges : 0; }
+
+}  // extern "C"

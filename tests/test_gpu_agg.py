@@ -1,0 +1,241 @@
+"""GPU parity: the HIP attentive-aggregation layer against the CPU oracle, through
+the C ABI.
+
+Protocol (bit-exactness is only defined for identical inputs):
+  1. Q(E): GPU bytes == oracle quantizer on the same E                     (bit-exact)
+  2. E_out: GPU fp32 vs oracle (double, rounded once)                      (1e-5)
+  3. Q(H), mask: oracle quantizer on the GPU's own fp32 H (bits=32 run);
+     mask bits == sign of the GPU's own E_out                              (bit-exact)
+  4. backward: the oracle starts from the bytes the GPU saved              (1e-5)
+  5. E_out with a compressed context is bitwise E_out with bits=32 (the forward
+     pass is exact -- Fig. 1)
+Tolerance ("1e-5 relative" for fp32 tensors whose entries are sums):
+  |gpu - ref| <= 1e-5 * max(|ref|, rms(ref tensor), rms(ref row)),
+where a row is the vector of one node (last axis).  The row term is there because
+an entry of grad_E is a sum over all in-edges of its node: every term carries the
+fp32 rounding of its factors (pi_j, grad_H, both fp32 by the method's own choice of
+full-precision operators), so the reachable absolute error scales with the size of
+the terms of that node -- the row's scale -- and not with the entry itself, which
+cancellation can make arbitrarily small (a Zipf tail with 10^5 in-edges has row rms
+~50 and entries near 0).
+"""
+import numpy as np
+import pytest
+
+torch = pytest.importorskip("torch")
+
+from oracle import ref
+from workloads import gen
+
+pytestmark = pytest.mark.gpu
+SLOPE = 0.2
+
+
+@pytest.fixture(scope="module")
+def tk():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import paper_2212_04540_amd as tk
+    tk.lib()
+    return tk
+
+
+def close(got, want, what, tol=1e-5):
+    got = got.cpu().numpy().astype(np.float64) if hasattr(got, "cpu") else np.asarray(got, np.float64)
+    want = np.asarray(want, np.float64)
+    assert got.shape == want.shape, f"{what}: shape {got.shape} vs {want.shape}"
+    scale = np.sqrt(np.mean(want ** 2)) if want.size else 0.0
+    row = np.sqrt(np.mean(want ** 2, axis=-1, keepdims=True)) if want.ndim >= 2 else 0.0
+    bound = tol * np.maximum(np.maximum(np.abs(want), scale), row)
+    err = np.abs(got - want)
+    if not np.all(err <= bound):
+        i = np.unravel_index(np.argmax(err - bound), err.shape)
+        raise AssertionError(f"{what}: worst at {i}: got {got[i]!r} want {want[i]!r} "
+                             f"(err {err[i]:.3e}, bound {bound[i]:.3e}); "
+                             f"{np.count_nonzero(err > bound)} of {err.size} out of tolerance")
+
+
+class Layer:
+    """One layer on the GPU, with everything the checks need copied back."""
+
+    def __init__(self, tk, N, R, head, rel, tail, E, Wr, er, W, G):
+        self.tk = tk
+        self.N, self.R = N, R
+        self.host = dict(head=head, rel=rel, tail=tail, E=E, Wr=Wr, er=er, W=W, G=G)
+        self.d, self.k, self.dout = E.shape[1], Wr.shape[1], W.shape[0]
+        dev = "cuda"
+        self.graph = tk.Graph(N, R, *(torch.from_numpy(np.ascontiguousarray(a)).to(dev) for a in (head, rel, tail)))
+        self.t = {k: torch.from_numpy(np.ascontiguousarray(v)).to(dev) for k, v in
+                  dict(E=E, Wr=Wr, er=er, W=W, G=G).items()}
+        nb = max(tk.tinykg_kg_aggregate_workspace_bytes(self.graph, self.d, self.k, self.dout, False),
+                 tk.tinykg_kg_aggregate_workspace_bytes(self.graph, self.d, self.k, self.dout, True), 16)
+        self.ws = torch.empty(nb, dtype=torch.uint8, device=dev)
+
+    def forward(self, bits, group, seed):
+        tk = self.tk
+        saved = tk.SavedContext(self.N, self.d, self.dout, bits, group)
+        Eo = tk.tinykg_kg_aggregate_fwd(self.graph, self.t["E"], self.t["Wr"], self.t["er"], self.t["W"],
+                                        SLOPE, bits, group, seed, saved, self.ws)
+        torch.cuda.synchronize()
+        return Eo, saved
+
+    def backward(self, saved, bits, group):
+        tk = self.tk
+        out = tk.tinykg_kg_aggregate_bwd(self.graph, saved, self.t["Wr"], self.t["er"], self.t["W"], SLOPE,
+                                         bits, group, self.t["G"], self.ws)
+        torch.cuda.synchronize()
+        return out
+
+    def saved_to_host(self, saved):
+        if saved.bits == 32:
+            return {"bits": 32, "mask": saved.mask_J.cpu().numpy(),
+                    "E": saved.packed_E.cpu().numpy().view(np.float32).reshape(self.N, self.d),
+                    "H": saved.packed_H.cpu().numpy().view(np.float32).reshape(self.N, self.d)}
+        return {"bits": saved.bits, "group": saved.group, "mask": saved.mask_J.cpu().numpy(),
+                "packed_E": saved.packed_E.cpu().numpy(), "gmin_E": saved.gmin_E.cpu().numpy(),
+                "gscale_E": saved.gscale_E.cpu().numpy(), "packed_H": saved.packed_H.cpu().numpy(),
+                "gmin_H": saved.gmin_H.cpu().numpy(), "gscale_H": saved.gscale_H.cpu().numpy()}
+
+
+def run_protocol(tk, N, R, head, rel, tail, d, dout, bits, group, seed=5, data_seed=0, threads=4,
+                 e_std=0.1):
+    E = gen.entity_embeddings(N, d, seed=data_seed + 1, std=e_std)
+    Wr, er, W = gen.layer_params(R, d, d, dout, seed=data_seed + 2)
+    G = gen.upstream_grad(N, dout, seed=data_seed + 3)
+    L = Layer(tk, N, R, head, rel, tail, E, Wr, er, W, G)
+    h = L.host
+
+    # exact forward with an uncompressed context: exposes the GPU's own H
+    Eo32, sv32 = L.forward(32, group, seed)
+    ctx32 = L.saved_to_host(sv32)
+    wEo, wH, wmask = ref.aggregate_fwd(N, head, rel, tail, E, Wr, er, W, SLOPE, threads=threads)
+    close(Eo32, wEo, "E_out")                                           # (2)
+    close(ctx32["H"], wH, "H")
+    assert np.array_equal(ctx32["E"].view(np.uint32), E.view(np.uint32))
+    gmask = ref.unpack(ctx32["mask"], N * dout, 1).reshape(N, dout)
+    Eo_host = Eo32.cpu().numpy()
+    assert np.array_equal(gmask != 0, Eo_host > 0), "mask is not the sign of the GPU's own J"
+    J64 = np.where(wEo > 0, wEo, wEo / SLOPE)
+    safe = np.abs(J64) > 1e-5 * np.sqrt(np.mean(J64.astype(np.float64) ** 2))
+    assert np.array_equal((gmask != 0)[safe], (wmask != 0)[safe])
+
+    # compressed context
+    Eo, sv = L.forward(bits, group, seed)
+    assert torch.equal(Eo, Eo32), "compression changed the forward output"       # (5)
+    ctx = L.saved_to_host(sv)
+    assert np.array_equal(ctx["mask"], ctx32["mask"])
+    if bits != 32:
+        wp, wmn, wsc = ref.quantize(E, bits, group, seed)                          # (1)
+        assert np.array_equal(ctx["packed_E"], wp) and np.array_equal(ctx["gmin_E"].view(np.uint32), wmn.view(np.uint32))
+        assert np.array_equal(ctx["gscale_E"].view(np.uint32), wsc.view(np.uint32))
+        hp, hmn, hsc = ref.quantize(ctx32["H"], bits, group, (seed + 1) & (2 ** 64 - 1))   # (3)
+        assert np.array_equal(ctx["packed_H"], hp) and np.array_equal(ctx["gmin_H"].view(np.uint32), hmn.view(np.uint32))
+        assert np.array_equal(ctx["gscale_H"].view(np.uint32), hsc.view(np.uint32))
+
+    # backward from the GPU's saved bytes                                        # (4)
+    for b, s, c in ((32, sv32, ctx32), (bits, sv, ctx)):
+        grads = L.backward(s, b, group)
+        Eh, Hh, mk = ref.restore_context(c, N, d, dout)
+        want = ref.aggregate_bwd(N, head, rel, tail, Eh, Hh, mk, Wr, er, W, SLOPE, G, threads=threads)
+        for a, w, nm in zip(grads, want, ("grad_E", "grad_Wr", "grad_er", "grad_W")):
+            close(a, w, f"{nm} (bits={b})")
+    L.graph.close()
+    return L
+
+
+@pytest.mark.parametrize("d,dout,bits,group", [(64, 64, 2, 64), (32, 16, 2, 64), (128, 128, 4, 128),
+                                               (64, 32, 8, 32), (64, 64, 1, 256), (32, 48, 4, 32),
+                                               (128, 16, 2, 64)])
+def test_small_graph_all_shapes(tk, d, dout, bits, group):
+    # several node tiles and edge tiles with ragged tails: 333 nodes -> pad so N*d % group == 0
+    N, R, T = 336, 5, 3000
+    head, rel, tail = gen.kg_triplets(N, R, T, seed=d + dout)
+    run_protocol(tk, N, R, head, rel, tail, d, dout, bits, group, data_seed=d)
+
+
+def test_ten_node_graph(tk):
+    # the brute-force-pinned size: 10 nodes (padded by isolated nodes to a multiple of the group)
+    N, R, T = 16, 3, 24
+    rng = np.random.default_rng(0)
+    head = rng.integers(0, 9, size=T).astype(np.int32)
+    rel = rng.integers(0, R, size=T).astype(np.int32)
+    tail = rng.integers(0, 10, size=T).astype(np.int32)
+    head[1], rel[1], tail[1] = head[0], rel[0], tail[0]      # repeated triplet
+    tail[2] = head[2]                                        # self-loop
+    run_protocol(tk, N, R, head, rel, tail, 64, 64, 2, 64, e_std=0.7)
+
+
+def test_no_edges_and_isolated_nodes(tk):
+    N, R = 64, 4
+    empty = np.zeros(0, dtype=np.int32)
+    L = run_protocol(tk, N, R, empty, empty, empty, 64, 64, 2, 64)
+    # H = E when nothing is aggregated
+    one = np.array([3], dtype=np.int32)
+    run_protocol(tk, N, R, one, np.array([2], np.int32), np.array([60], np.int32), 64, 32, 2, 64)
+
+
+def test_hot_tail_hot_head_and_empty_relations(tk):
+    # 60% of the first edge set points at one tail (long same-tail runs in every chunk);
+    # one head owns thousands of edges (many chunks of one relation); relations 1, 3 unused
+    N, R = 512, 5
+    rng = np.random.default_rng(1)
+    T1 = 6000
+    head = rng.integers(0, N, size=T1).astype(np.int32)
+    tail = np.where(rng.random(T1) < 0.6, 7, rng.integers(0, N, size=T1)).astype(np.int32)
+    rel = rng.choice([0, 2, 4], size=T1).astype(np.int32)
+    T2 = 5000
+    head2 = np.full(T2, 11, dtype=np.int32)
+    tail2 = rng.integers(0, N, size=T2).astype(np.int32)
+    rel2 = np.zeros(T2, dtype=np.int32)
+    run_protocol(tk, N, R, np.concatenate([head, head2]), np.concatenate([rel, rel2]),
+                 np.concatenate([tail, tail2]), 64, 64, 2, 64)
+
+
+def test_zero_relation_maps_give_the_normalised_adjacency_spmm(tk):
+    # W_r = 0 => uniform attention => H = E + D^-1 A E  (Eq. 2's spmm), on the GPU path
+    import scipy.sparse as sp
+    N, R, T, d = 256, 3, 2000, 64
+    head, rel, tail = gen.kg_triplets(N, R, T, seed=9)
+    E = gen.entity_embeddings(N, d, seed=1, std=1.0)
+    Wr, er, W = gen.layer_params(R, d, d, d, seed=2)
+    Wr[:] = 0
+    W = np.eye(d, dtype=np.float32)
+    G = gen.upstream_grad(N, d, seed=3)
+    L = Layer(tk, N, R, head, rel, tail, E, Wr, er, W, G)
+    Eo, sv = L.forward(32, 64, 0)
+    A = sp.coo_matrix((np.ones(T), (head, tail)), shape=(N, N)).tocsr()
+    deg = np.asarray(A.sum(axis=1)).ravel()
+    Ahat = sp.diags(np.where(deg > 0, 1.0 / np.maximum(deg, 1), 0.0)) @ A
+    Hw = E.astype(np.float64) + Ahat @ E.astype(np.float64)
+    close(L.saved_to_host(sv)["H"], Hw, "H = E + D^-1 A E")
+    L.graph.close()
+
+
+def test_error_paths(tk):
+    N, R, T = 64, 2, 100
+    head, rel, tail = gen.kg_triplets(N, R, T, seed=0)
+    g = tk.Graph(N, R, *(torch.from_numpy(a).cuda() for a in (head, rel, tail)))
+    assert tk.tinykg_kg_aggregate_workspace_bytes(g, 48, 48, 64, False) == 0       # unsupported dims
+    E = torch.zeros((N, 64), device="cuda"); Wr = torch.zeros((R, 64, 64), device="cuda")
+    er = torch.zeros((R, 64), device="cuda"); W = torch.zeros((64, 64), device="cuda")
+    sv = tk.SavedContext(N, 64, 64, 2, 64)
+    small = torch.empty(16, dtype=torch.uint8, device="cuda")
+    with pytest.raises(tk.TinyKGError) as e:
+        tk.tinykg_kg_aggregate_fwd(g, E, Wr, er, W, 0.2, 2, 64, 0, sv, small)
+    assert e.value.status == 4                                                      # workspace
+    ws = torch.empty(tk.tinykg_kg_aggregate_workspace_bytes(g, 64, 64, 64, True), dtype=torch.uint8, device="cuda")
+    with pytest.raises(tk.TinyKGError) as e:
+        tk.tinykg_kg_aggregate_fwd(g, E, Wr, er, W, 0.2, 3, 64, 0, sv, ws)
+    assert e.value.status == 1                                                      # bits = 3
+    bad = torch.from_numpy(np.array([N], dtype=np.int32)).cuda()
+    ok = torch.zeros(1, dtype=torch.int32, device="cuda")
+    with pytest.raises(tk.TinyKGError):
+        tk.Graph(N, R, bad, ok, ok)                                                  # head id out of range
+    g.close()
+
+
+def test_config1_full_size(tk):
+    # 100k entities, dim 64, 16 relations, 1M triplets, Zipf(1.1) tails, INT2 / group 64
+    N, R, T, d = 100_000, 16, 1_000_000, 64
+    head, rel, tail = gen.kg_triplets(N, R, T, seed=0, tail_zipf=1.1)
+    run_protocol(tk, N, R, head, rel, tail, d, d, 2, 64, seed=1, threads=ref.default_threads())

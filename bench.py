@@ -1,0 +1,202 @@
+#!/usr/bin/env python3
+"""Benchmark of the TinyKG hot path on one MI355X.
+
+A "step" is one pass of the whole hot path over one batch of synthetic input:
+the attentive aggregation layer's forward pass (which quantises and bit-packs the
+saved activations E and H and keeps a 1-bit mask of J) followed by its backward
+pass (which unpacks and dequantises them inside its gathers), on the 100k-entity /
+1M-triplet configuration.  Inputs are resident in HBM before the timed region.
+
+Prints ONE JSON line.  `value` is algorithmic bytes per step / step time; the
+`roofline` object prices the dominant kernel of the step against its own bound;
+`compressor` reports the standalone quantize+pack / unpack+dequantize kernels on
+the 2 GiB heavy-tailed activation (HBM-bound, the streaming roofline of the
+method); `cpu_baseline` times the CPU oracle on the same workload.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0        # MI355X HBM3E
+MFMA_FP32_PEAK_TFLOPS = 157.3
+
+# configs[1]
+N, D, R, T = 100_000, 64, 16, 1_000_000
+BITS, GROUP, SLOPE = 2, 64, 0.2
+# configs[2] (one cell of the sweep is timed by default: INT2, group 64)
+C2_ROWS, C2_DIM = 1 << 23, 64
+
+
+def bytes_per_activation(bits, group):
+    return bits / 8 + 8 / group
+
+
+def step_algorithmic_bytes():
+    """Compulsory bytes of one forward+backward step (per-edge and per-node terms)."""
+    bpa = bytes_per_activation(BITS, GROUP)
+    fwd_edge = 4 * D + 4 + 4 + 4            # e_t row, tail id, relation id, score
+    fwd_node = 4 * D + 4 * D + 2 * D * bpa + D / 8   # E in, E' out, Q(E)+Q(H) saved, mask
+    bwd_edge = D * bpa + 12                 # packed e_t row, ids + score gradient
+    bwd_node = 4 * D + D * bpa + D / 8 + 4 * D       # grad_E' in, H_hat, mask, grad_E out
+    return T * (fwd_edge + bwd_edge) + N * (fwd_node + bwd_node)
+
+
+def edge_bwd_flops():
+    """Contractions of the edge-level backward kernel: per triplet six k x d products
+    (recompute W_r e_t and W_r e_h, W_r^T grad_a, W_r^T grad_b, two outer products)."""
+    return T * 6 * 2 * D * D
+
+
+def make_inputs(torch):
+    from workloads import gen
+    head, rel, tail = gen.kg_triplets(N, R, T, seed=0, tail_zipf=1.1)
+    E = gen.entity_embeddings(N, D, seed=1)
+    Wr, er, W = gen.layer_params(R, D, D, D, seed=2)
+    G = gen.upstream_grad(N, D, seed=3)
+    return dict(head=head, rel=rel, tail=tail, E=E, Wr=Wr, er=er, W=W, G=G)
+
+
+def cpu_baseline(inp, seed):
+    """The oracle as it stands, on this host's cores, on the full configs[1] step."""
+    from oracle import ref
+    threads = ref.default_threads()
+    t0 = time.perf_counter()
+    Eo, H, mask = ref.aggregate_fwd(N, inp["head"], inp["rel"], inp["tail"], inp["E"], inp["Wr"],
+                                    inp["er"], inp["W"], SLOPE, threads=threads)
+    ctx = ref.save_context(inp["E"], H, mask, BITS, GROUP, seed)
+    Eh, Hh, mk = ref.restore_context(ctx, N, D, D)
+    ref.aggregate_bwd(N, inp["head"], inp["rel"], inp["tail"], Eh, Hh, mk, inp["Wr"], inp["er"],
+                      inp["W"], SLOPE, inp["G"], threads=threads)
+    dt = time.perf_counter() - t0
+    return {"value": round(step_algorithmic_bytes() / dt / 1e9, 4), "unit": "GB/s", "cores": threads,
+            "kind": "oracle", "seconds": round(dt, 3),
+            "sample": "one full configs[1] step (forward, INT2/G64 save, restore, backward); "
+                      "aggregation loops threaded over heads, quantizer single-threaded"}
+
+
+def compressor_line(tk, torch, iters=20):
+    """quantize+pack and unpack+dequantize on the 2 GiB Student-t activation."""
+    g = torch.Generator(device="cuda")
+    g.manual_seed(0)
+    x = torch.empty((C2_ROWS, C2_DIM), dtype=torch.float32, device="cuda")
+    step = 1 << 20
+    for r0 in range(0, C2_ROWS, step):      # Student-t(3) = z / sqrt(chi2_3 / 3), drawn in slabs
+        z = torch.randn((step, C2_DIM), generator=g, device="cuda")
+        chi = torch.randn((step, C2_DIM, 3), generator=g, device="cuda").square_().sum(-1)
+        x[r0:r0 + step] = z / (chi / 3).sqrt_()
+    del z, chi
+    n = x.numel()
+    buf = tk.alloc_quantized(C2_ROWS, C2_DIM, BITS, GROUP)
+    out = torch.empty_like(x)
+    for _ in range(3):
+        tk.tinykg_quantize(x, BITS, GROUP, 1, out=buf)
+        tk.tinykg_dequantize(*buf, C2_ROWS, C2_DIM, BITS, GROUP, out=out)
+    torch.cuda.synchronize()
+    tk.tinykg_profile_enable(True)
+    for _ in range(iters):
+        tk.tinykg_quantize(x, BITS, GROUP, 1, out=buf)
+        tk.tinykg_dequantize(*buf, C2_ROWS, C2_DIM, BITS, GROUP, out=out)
+    torch.cuda.synchronize()
+    rep = tk.tinykg_profile_report()
+    tk.tinykg_profile_enable(False)
+    bpe = 4 + bytes_per_activation(BITS, GROUP)
+    res = {"workload": f"configs[2] cell: {C2_ROWS}x{C2_DIM} fp32 Student-t(3), INT{BITS}, group {GROUP}",
+           "bytes_per_element": bpe}
+    for key, name in (("quantize", "quantize_kernel"), ("dequantize", "dequantize_kernel")):
+        cnt, ms = rep[name]
+        gbs = n * bpe / (ms / cnt) / 1e6
+        res[key] = {"ms": round(ms / cnt, 4), "GB/s": round(gbs, 1), "frac_of_hbm_peak": round(gbs / HBM_PEAK_GBS, 4)}
+    del x, out, buf
+    torch.cuda.empty_cache()
+    return res
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-compressor", action="store_true")
+    a = ap.parse_args()
+    if a.gpus != 1:
+        sys.exit("bench.py: this build runs on ONE GPU (the paper's method is single-GPU); "
+                 "run with --gpus 1")
+
+    import torch
+    import paper_2212_04540_amd as tk
+    if not torch.cuda.is_available():
+        sys.exit("bench.py needs a GPU")
+    tk.lib()
+    dev = "cuda"
+    inp = make_inputs(torch)
+    t = {k: torch.from_numpy(v).to(dev) for k, v in inp.items()}
+    graph = tk.Graph(N, R, t["head"], t["rel"], t["tail"])
+    saved = tk.SavedContext(N, D, D, BITS, GROUP)
+    ws = torch.empty(max(tk.tinykg_kg_aggregate_workspace_bytes(graph, D, D, D, False),
+                         tk.tinykg_kg_aggregate_workspace_bytes(graph, D, D, D, True)),
+                     dtype=torch.uint8, device=dev)
+    E_out = torch.empty((N, D), dtype=torch.float32, device=dev)
+    grads = (torch.empty((N, D), dtype=torch.float32, device=dev), torch.empty_like(t["Wr"]),
+             torch.empty_like(t["er"]), torch.empty_like(t["W"]))
+
+    def step(i):
+        tk.tinykg_kg_aggregate_fwd(graph, t["E"], t["Wr"], t["er"], t["W"], SLOPE, BITS, GROUP, 1 + 2 * i,
+                                   saved, ws, E_out=E_out)
+        tk.tinykg_kg_aggregate_bwd(graph, saved, t["Wr"], t["er"], t["W"], SLOPE, BITS, GROUP, t["G"], ws,
+                                   out=grads)
+
+    for i in range(a.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    tk.tinykg_profile_enable(True)           # per-kernel HIP events inside the timed region
+    t0 = time.perf_counter()
+    for i in range(a.steps):
+        step(a.warmup + i)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    rep = tk.tinykg_profile_report()
+    tk.tinykg_profile_enable(False)
+
+    ms_per_step = dt / a.steps * 1e3
+    alg = step_algorithmic_bytes()
+    kernels = {k: {"launches_per_step": v[0] / a.steps, "ms_per_step": round(v[1] / a.steps, 4)}
+               for k, v in rep.items()}
+    dom_ms = rep["edge_bwd_kernel"][1] / rep["edge_bwd_kernel"][0]
+    achieved = edge_bwd_flops() / (dom_ms * 1e-3) / 1e12
+    out = {
+        "metric": "quantize+pack and dequant+agg-bwd HBM GB/s (fraction of peak); bytes/activation",
+        "value": round(alg / (ms_per_step * 1e-3) / 1e9, 2), "unit": "GB/s",
+        "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": "configs[1]: one KGAT-style attentive aggregation layer, forward+backward, "
+                               "100k entities, dim 64, 16 relations, 1M triplets (Zipf 1.1 tails), "
+                               "saved inputs INT2 group 64",
+                   "bits": BITS, "group": GROUP, "bytes_per_activation": bytes_per_activation(BITS, GROUP),
+                   "compression_ratio": round(4 / bytes_per_activation(BITS, GROUP), 3),
+                   "algorithmic_bytes_per_step": alg,
+                   "saved_context_bytes": saved.nbytes(), "fp32_context_bytes": 2 * N * D * 4 + N * D * 4},
+        "frac_of_hbm_peak": round(alg / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 5),
+        "roofline": {"kernel": "edge_bwd_kernel", "bound": "mfma", "achieved": round(achieved, 3),
+                     "peak": MFMA_FP32_PEAK_TFLOPS, "unit": "TFLOP/s",
+                     "frac": round(achieved / MFMA_FP32_PEAK_TFLOPS, 4), "traffic": None,
+                     "avg_launch_ms": round(dom_ms, 4)},
+        "kernels": kernels,
+    }
+    if not a.no_compressor:
+        out["compressor"] = compressor_line(tk, torch)
+    if not a.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(inp, 1)
+    graph.close()
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -156,6 +156,21 @@ tinykg_status tinykg_kg_aggregate_bwd(const tinykg_graph* g, const tinykg_saved*
                                       float* grad_er, float* grad_W, void* workspace,
                                       size_t workspace_bytes, void* stream);
 
+/* ------------------------------------------------------------------------- *
+ * Measurement hooks (not part of the method): when enabled, every kernel launch
+ * made by the entry points above is bracketed by a pair of HIP events recorded
+ * on the caller's stream, so a benchmark can read each kernel's device time over
+ * exactly the launches it timed.  One global recorder per process, not
+ * thread-safe; at most 8192 launches are kept between two resets (later ones are
+ * not recorded).
+ * ------------------------------------------------------------------------- */
+/* on != 0: drop earlier records and start recording; on == 0: stop recording. */
+void tinykg_profile_enable(int on);
+/* Waits for the recorded events, then writes one line per kernel name,
+ * "<name> <launches> <total_ms>\n", into buf (NUL-terminated, truncated to cap).
+ * Returns the number of bytes the full text needs (excluding the NUL). */
+size_t tinykg_profile_report(char* buf, size_t cap);
+
 #ifdef __cplusplus
 }
 #endif

@@ -21,7 +21,8 @@ EXPORTS = [
     "tinykg_status_string", "tinykg_packed_bytes", "tinykg_num_groups", "tinykg_quantize",
     "tinykg_quantize_ex", "tinykg_dequantize", "tinykg_graph_create", "tinykg_graph_destroy",
     "tinykg_graph_num_nodes", "tinykg_graph_num_edges", "tinykg_kg_aggregate_workspace_bytes",
-    "tinykg_kg_aggregate_fwd", "tinykg_kg_aggregate_bwd",
+    "tinykg_kg_aggregate_fwd", "tinykg_kg_aggregate_bwd", "tinykg_profile_enable",
+    "tinykg_profile_report",
 ]
 
 
@@ -71,6 +72,10 @@ def lib():
                                                   u64, vp, C.POINTER(Saved), vp, sz, vp]
             L.tinykg_kg_aggregate_bwd.argtypes = [vp, C.POINTER(Saved), vp, vp, vp, i32, i32, i32,
                                                   f32, i32, i32, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.tinykg_profile_enable.argtypes = [i32]
+        L.tinykg_profile_enable.restype = None
+        L.tinykg_profile_report.argtypes = [C.c_char_p, sz]
+        L.tinykg_profile_report.restype = sz
         _lib = L
     return _lib
 
@@ -133,6 +138,22 @@ def tinykg_dequantize(packed, gmin, gscale, rows, dim, bits, group, out=None):
     st = lib().tinykg_dequantize(_ptr(packed), _ptr(gmin), _ptr(gscale), rows, dim, bits, group,
                                  _ptr(out), _stream())
     _ok(st, "tinykg_dequantize")
+    return out
+
+
+def tinykg_profile_enable(on):
+    lib().tinykg_profile_enable(1 if on else 0)
+
+
+def tinykg_profile_report():
+    """{kernel name: (launches, total device ms)} over the launches recorded since enable(1)."""
+    need = lib().tinykg_profile_report(None, 0)
+    buf = C.create_string_buffer(need + 1)
+    lib().tinykg_profile_report(buf, need + 1)
+    out = {}
+    for line in buf.value.decode().splitlines():
+        name, n, ms = line.split()
+        out[name] = (int(n), float(ms))
     return out
 
 

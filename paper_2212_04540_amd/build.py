@@ -16,6 +16,7 @@ SOURCES = {
     "tinykg_quant.hip": ["-ffp-contract=off"],
     "tinykg_graph.hip": [],
     "tinykg_agg.hip": [],
+    "tinykg_profile.hip": [],
 }
 
 

@@ -674,6 +674,7 @@ tinykg_status launch_score(const tinykg_graph* g, Source src, const float* Wr, c
   tinykg_status rc = set_smem(kern, smem);
   if (rc != TINYKG_OK) return rc;
   ChunkList cl{g->chunk_rel, g->chunk_start, g->chunk_count};
+  ProfileScope prof("score_kernel", st);
   hipLaunchKernelGGL(kern, dim3(g->n_chunks), dim3(kThreads), smem, st, src, Wr, er, g->r_head,
                      g->r_tail, g->r_eid, cl, s);
   return launch_status();
@@ -691,11 +692,15 @@ tinykg_status fwd_impl(const tinykg_graph* g, const float* E, const float* Wr, c
   tinykg_status rc = launch_score<D, 32>(g, src, Wr, er, s, st);
   if (rc != TINYKG_OK) return rc;
   const int wave_blocks = (int)std::max<int64_t>(1, std::min<int64_t>((N + 3) / 4, (int64_t)num_cus() * 16));
-  hipLaunchKernelGGL((attend_fwd_kernel<D>), dim3(wave_blocks), dim3(kThreads), 0, st, E, g->rowptr,
-                     g->h_tail, s, N, H);
+  {
+    ProfileScope prof("attend_fwd_kernel", st);
+    hipLaunchKernelGGL((attend_fwd_kernel<D>), dim3(wave_blocks), dim3(kThreads), 0, st, E, g->rowptr,
+                       g->h_tail, s, N, H);
+  }
   if ((rc = launch_status()) != TINYKG_OK) return rc;
   // save the context (Fig. 1): Q(E; seed), Q(H; seed + 1)
   if (bits == 32) {
+    ProfileScope prof("copy_E_fp32", st);
     TINYKG_HIP_TRY(hipMemcpyAsync(sv->packed_E, E, (size_t)N * D * 4, hipMemcpyDeviceToDevice, st));
   } else {
     rc = launch_quantize(E, N * D, bits, group, seed, 0, TINYKG_ROUND_STOCHASTIC, sv->packed_E,
@@ -709,6 +714,7 @@ tinykg_status fwd_impl(const tinykg_graph* g, const float* E, const float* Wr, c
   const size_t smem = (size_t)(DOP * (D + 4) + 64 * (D + 4) + 64 * (DOP + 4)) * 4;
   auto kern = dense_fwd_kernel<D>;
   if ((rc = set_smem(kern, smem)) != TINYKG_OK) return rc;
+  ProfileScope prof("dense_fwd_kernel", st);
   hipLaunchKernelGGL(kern, dim3(dense_grid(N)), dim3(kThreads), smem, st, H, W, d_out, slope, N,
                      E_out, sv->mask_J);
   return launch_status();
@@ -743,38 +749,49 @@ tinykg_status bwd_impl(const tinykg_graph* g, const tinykg_saved* sv, const floa
     auto kern = dense_bwd_kernel<D, BITS>;
     if ((rc = set_smem(kern, smem)) != TINYKG_OK) return rc;
     const int grid = dense_grid(N);
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(kThreads), smem, st, srcH, sv->mask_J, gEout, W, d_out,
-                       slope, N, gH, pW);
+    {
+      ProfileScope prof("dense_bwd_kernel", st);
+      hipLaunchKernelGGL(kern, dim3(grid), dim3(kThreads), smem, st, srcH, sv->mask_J, gEout, W,
+                         d_out, slope, N, gH, pW);
+    }
     if ((rc = launch_status()) != TINYKG_OK) return rc;
     const int stride = d_out * D;
+    ProfileScope prof("reduce_segments_kernel", st);
     hipLaunchKernelGGL(reduce_segments_kernel, dim3((stride + 255) / 256, 1), dim3(256), 0, st, pW,
                        (const int32_t*)nullptr, grid, stride, gW);
     if ((rc = launch_status()) != TINYKG_OK) return rc;
   }
   const int fill_blocks = (int)std::max<int64_t>(1, std::min<int64_t>((N * D + 255) / 256, (int64_t)num_cus() * 16));
   if (N > 0) {
+    ProfileScope prof("zero_f64_kernel", st);
     hipLaunchKernelGGL(zero_f64_kernel, dim3(fill_blocks), dim3(256), 0, st, acc, N * D);
     if ((rc = launch_status()) != TINYKG_OK) return rc;
   }
   if (g->n_chunks > 0) {
     if ((rc = launch_score<D, BITS>(g, srcE, Wr, er, s, st)) != TINYKG_OK) return rc;
     const int wave_blocks = (int)std::max<int64_t>(1, std::min<int64_t>((N + 3) / 4, (int64_t)num_cus() * 16));
-    hipLaunchKernelGGL((attend_bwd_kernel<D, BITS>), dim3(wave_blocks), dim3(kThreads), 0, st, srcE,
-                       gH, g->rowptr, g->h_tail, s, N, pi, gs);
+    {
+      ProfileScope prof("attend_bwd_kernel", st);
+      hipLaunchKernelGGL((attend_bwd_kernel<D, BITS>), dim3(wave_blocks), dim3(kThreads), 0, st, srcE,
+                         gH, g->rowptr, g->h_tail, s, N, pi, gs);
+    }
     if ((rc = launch_status()) != TINYKG_OK) return rc;
     const size_t smem = (size_t)(D * LD + 4 * TE * LD + D + 4 * TE) * 4;
     auto kern = edge_bwd_kernel<D, TE, BITS>;
     if ((rc = set_smem(kern, smem)) != TINYKG_OK) return rc;
     ChunkList cl{g->chunk_rel, g->chunk_start, g->chunk_count};
+    ProfileScope prof("edge_bwd_kernel", st);
     hipLaunchKernelGGL(kern, dim3(g->n_chunks), dim3(kThreads), smem, st, srcE, Wr, er, g->r_head,
                        g->r_tail, g->r_eid, cl, pi, gs, gH, acc, pWr, per);
     if ((rc = launch_status()) != TINYKG_OK) return rc;
   }
   if (N > 0) {
+    ProfileScope prof("finish_grad_kernel", st);
     hipLaunchKernelGGL(finish_grad_kernel, dim3(fill_blocks), dim3(256), 0, st, acc, gH, N * D, gE);
     if ((rc = launch_status()) != TINYKG_OK) return rc;
   }
   if (g->n_rel > 0) {
+    ProfileScope prof("reduce_segments_kernel", st);
     hipLaunchKernelGGL(reduce_segments_kernel, dim3((D * D + 255) / 256, g->n_rel), dim3(256), 0, st,
                        pWr, g->rel_chunk_ptr, 0, D * D, gWr);
     if ((rc = launch_status()) != TINYKG_OK) return rc;

@@ -36,5 +36,19 @@ tinykg_status launch_quantize(const float* act, int64_t n, int bits, int group, 
 tinykg_status launch_dequantize(const uint8_t* packed, const float* gmin, const float* gscale,
                                 int64_t n, int bits, int group, float* out, hipStream_t stream);
 
+// Brackets the kernel launches made while it is alive with two events on `st`
+// (only while tinykg_profile_enable(1) is in effect).
+class ProfileScope {
+ public:
+  ProfileScope(const char* name, hipStream_t st);
+  ~ProfileScope();
+  ProfileScope(const ProfileScope&) = delete;
+  ProfileScope& operator=(const ProfileScope&) = delete;
+
+ private:
+  int slot_;
+  hipStream_t st_;
+};
+
 }  // namespace tinykg
 #endif

@@ -1,0 +1,78 @@
+// Per-kernel device-time recorder behind tinykg_profile_enable / _report.
+#include "tinykg_common.h"
+
+#include <cstdio>
+#include <cstring>
+#include <map>
+#include <string>
+#include <vector>
+
+namespace tinykg {
+
+namespace {
+struct Record { const char* name; hipEvent_t start, stop; bool closed; };
+bool g_on = false;
+std::vector<Record> g_records;
+constexpr size_t kMaxRecords = 8192;
+
+void drop_records() {
+  for (Record& r : g_records) { (void)hipEventDestroy(r.start); (void)hipEventDestroy(r.stop); }
+  g_records.clear();
+}
+}  // namespace
+
+ProfileScope::ProfileScope(const char* name, hipStream_t st) : slot_(-1), st_(st) {
+  if (!g_on || g_records.size() >= kMaxRecords) return;
+  Record r{name, nullptr, nullptr, false};
+  if (hipEventCreate(&r.start) != hipSuccess) return;
+  if (hipEventCreate(&r.stop) != hipSuccess) { (void)hipEventDestroy(r.start); return; }
+  (void)hipEventRecord(r.start, st);
+  g_records.push_back(r);
+  slot_ = (int)g_records.size() - 1;
+}
+
+ProfileScope::~ProfileScope() {
+  if (slot_ < 0 || (size_t)slot_ >= g_records.size()) return;
+  (void)hipEventRecord(g_records[(size_t)slot_].stop, st_);
+  g_records[(size_t)slot_].closed = true;
+}
+
+}  // namespace tinykg
+
+extern "C" {
+
+void tinykg_profile_enable(int on) {
+  using namespace tinykg;
+  if (on) drop_records();
+  g_on = on != 0;
+}
+
+size_t tinykg_profile_report(char* buf, size_t cap) {
+  using namespace tinykg;
+  std::map<std::string, std::pair<long, double>> agg;
+  std::vector<std::string> order;
+  for (Record& r : g_records) {
+    if (!r.closed) continue;
+    if (hipEventSynchronize(r.stop) != hipSuccess) continue;
+    float ms = 0.f;
+    if (hipEventElapsedTime(&ms, r.start, r.stop) != hipSuccess) continue;
+    auto it = agg.find(r.name);
+    if (it == agg.end()) { order.push_back(r.name); it = agg.emplace(r.name, std::make_pair(0L, 0.0)).first; }
+    it->second.first += 1;
+    it->second.second += ms;
+  }
+  std::string text;
+  char line[256];
+  for (const std::string& n : order) {
+    std::snprintf(line, sizeof line, "%s %ld %.6f\n", n.c_str(), agg[n].first, agg[n].second);
+    text += line;
+  }
+  if (buf && cap > 0) {
+    const size_t k = text.size() < cap - 1 ? text.size() : cap - 1;
+    std::memcpy(buf, text.data(), k);
+    buf[k] = '\0';
+  }
+  return text.size();
+}
+
+}  // extern "C"

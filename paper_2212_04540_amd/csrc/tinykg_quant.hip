@@ -265,6 +265,7 @@ tinykg_status launch_quantize_g(const float* act, int64_t n, int group, uint64_t
   const int64_t cap = (int64_t)num_cus() * 8;
   const dim3 grid((unsigned)(want < cap ? want : cap));
   const uint32_t lo = (uint32_t)seed, hi = (uint32_t)(seed >> 32);
+  ProfileScope prof("quantize_kernel", stream);
 #define TINYKG_Q_LAUNCH(G)                                                                   \
   hipLaunchKernelGGL((quantize_kernel<BITS, G, ROUNDING>), grid, dim3(kBlock), 0, stream, act, n, \
                      lo, hi, first_index, packed, gmin, gscale)
@@ -338,6 +339,7 @@ tinykg_status launch_dequantize(const uint8_t* packed, const float* gmin, const 
   const int64_t cap = (int64_t)num_cus() * 32;
   const dim3 grid((unsigned)(want < cap ? want : cap));
   const int gl2 = ilog2(group / 4);
+  ProfileScope prof("dequantize_kernel", stream);
 #define TINYKG_DQ_LAUNCH(BITS)                                                              \
   hipLaunchKernelGGL((dequantize_kernel<BITS>), grid, dim3(256), 0, stream, packed, gmin, gscale, \
                      n_chunks, gl2, out)

@@ -99,6 +99,8 @@ def compressor_line(tk, torch, iters=20):
         tk.tinykg_dequantize(*buf, C2_ROWS, C2_DIM, BITS, GROUP, out=out)
     torch.cuda.synchronize()
     tk.tinykg_profile_enable(True)
+    for _ in range(5):
+        tk.tinykg_profile_copy(out, x)      # plain copy of known size: practical HBM ceiling
     for _ in range(iters):
         tk.tinykg_quantize(x, BITS, GROUP, 1, out=buf)
         tk.tinykg_dequantize(*buf, C2_ROWS, C2_DIM, BITS, GROUP, out=out)
@@ -112,6 +114,9 @@ def compressor_line(tk, torch, iters=20):
         cnt, ms = rep[name]
         gbs = n * bpe / (ms / cnt) / 1e6
         res[key] = {"ms": round(ms / cnt, 4), "GB/s": round(gbs, 1), "frac_of_hbm_peak": round(gbs / HBM_PEAK_GBS, 4)}
+    cnt, ms = rep["calibration_copy_kernel"]
+    gbs = 2 * n * 4 / (ms / cnt) / 1e6
+    res["plain_copy"] = {"ms": round(ms / cnt, 4), "GB/s": round(gbs, 1), "frac_of_hbm_peak": round(gbs / HBM_PEAK_GBS, 4)}
     del x, out, buf
     torch.cuda.empty_cache()
     return res

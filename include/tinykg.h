@@ -170,6 +170,10 @@ void tinykg_profile_enable(int on);
  * "<name> <launches> <total_ms>\n", into buf (NUL-terminated, truncated to cap).
  * Returns the number of bytes the full text needs (excluding the NUL). */
 size_t tinykg_profile_report(char* buf, size_t cap);
+/* A plain 128-bit-per-lane copy kernel (calibration_copy_kernel) of `bytes` bytes
+ * (multiple of 16; dst/src device, 16-byte aligned): reads `bytes`, writes `bytes`.
+ * Its known traffic calibrates the profiler's HBM byte counters. */
+tinykg_status tinykg_profile_copy(void* dst, const void* src, size_t bytes, void* stream);
 
 #ifdef __cplusplus
 }

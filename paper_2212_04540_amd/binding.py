@@ -22,7 +22,7 @@ EXPORTS = [
     "tinykg_quantize_ex", "tinykg_dequantize", "tinykg_graph_create", "tinykg_graph_destroy",
     "tinykg_graph_num_nodes", "tinykg_graph_num_edges", "tinykg_kg_aggregate_workspace_bytes",
     "tinykg_kg_aggregate_fwd", "tinykg_kg_aggregate_bwd", "tinykg_profile_enable",
-    "tinykg_profile_report",
+    "tinykg_profile_report", "tinykg_profile_copy",
 ]
 
 
@@ -76,6 +76,7 @@ def lib():
         L.tinykg_profile_enable.restype = None
         L.tinykg_profile_report.argtypes = [C.c_char_p, sz]
         L.tinykg_profile_report.restype = sz
+        L.tinykg_profile_copy.argtypes = [vp, vp, sz, vp]
         _lib = L
     return _lib
 
@@ -155,6 +156,13 @@ def tinykg_profile_report():
         name, n, ms = line.split()
         out[name] = (int(n), float(ms))
     return out
+
+
+def tinykg_profile_copy(dst, src):
+    """Plain copy kernel of known size (dst, src: same-size CUDA tensors)."""
+    nbytes = src.numel() * src.element_size()
+    assert dst.numel() * dst.element_size() == nbytes
+    _ok(lib().tinykg_profile_copy(_ptr(dst), _ptr(src), nbytes, _stream()), "tinykg_profile_copy")
 
 
 class Graph:

@@ -37,9 +37,27 @@ ProfileScope::~ProfileScope() {
   g_records[(size_t)slot_].closed = true;
 }
 
+__global__ void calibration_copy_kernel(const float4* __restrict__ src, float4* __restrict__ dst,
+                                        size_t n16) {
+  const size_t stride = (size_t)gridDim.x * blockDim.x;
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride) dst[i] = src[i];
+}
+
 }  // namespace tinykg
 
 extern "C" {
+
+tinykg_status tinykg_profile_copy(void* dst, const void* src, size_t bytes, void* stream) {
+  using namespace tinykg;
+  if (bytes == 0) return TINYKG_OK;
+  if (!dst || !src || !aligned16(dst) || !aligned16(src) || bytes % 16 != 0) return TINYKG_ERR_INVALID_ARG;
+  const size_t n16 = bytes / 16;
+  const size_t want = (n16 + 255) / 256, cap = (size_t)num_cus() * 32;
+  ProfileScope prof("calibration_copy_kernel", (hipStream_t)stream);
+  hipLaunchKernelGGL(calibration_copy_kernel, dim3((unsigned)(want < cap ? want : cap)), dim3(256), 0,
+                     (hipStream_t)stream, static_cast<const float4*>(src), static_cast<float4*>(dst), n16);
+  return launch_status();
+}
 
 void tinykg_profile_enable(int on) {
   using namespace tinykg;

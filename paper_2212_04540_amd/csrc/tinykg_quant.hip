@@ -20,7 +20,8 @@
 //     two blocks, whose counters are (first_index + element)/8;
 //   * the 16 codes of a lane are 16*bits contiguous bits of the stream: one
 //     2/4/8/16-byte store per lane, contiguous across the wave.
-// The next tile's loads are issued before the current tile is processed.
+// Every wave handles exactly one tile (grid = tiles / 4): blocks retire in address
+// order, which keeps the DRAM access stream sequential.
 #include "tinykg_common.h"
 
 #include <float.h>
@@ -56,6 +57,8 @@ __device__ __forceinline__ void group_minmax(float& mn, float& mx) {
   if (LPG >= 16) { mn = fminf(mn, dpp<kRowMirror>(mn)); mx = fmaxf(mx, dpp<kRowMirror>(mx)); }
 }
 
+__device__ __forceinline__ uint32_t xor3(uint32_t a, uint32_t b, uint32_t c);
+
 // ---- Philox4x32-10 (Salmon et al., SC'11) -----------------------------------
 // Counter (c0, c1, 0, 0), key (k0, k1).  The third and fourth counter words are
 // zero by construction, which removes one multiply from the first round.
@@ -70,8 +73,8 @@ __device__ __forceinline__ Philox4 philox4x32_10(uint32_t c0, uint32_t c1, uint3
   for (int r = 0; r < 10; ++r) {
     const uint64_t p0 = (uint64_t)M0 * c0;
     const uint64_t p1 = (uint64_t)M1 * c2;
-    const uint32_t n0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0;
-    const uint32_t n2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1;
+    const uint32_t n0 = xor3((uint32_t)(p1 >> 32), c1, k0);
+    const uint32_t n2 = xor3((uint32_t)(p0 >> 32), c3, k1);
     c1 = (uint32_t)p1;
     c3 = (uint32_t)p0;
     c0 = n0;
@@ -93,6 +96,39 @@ __device__ __forceinline__ int slab_slot(int c) {
   return c ^ s;
 }
 
+// -ceil(X) as an integer in one instruction (floor of the negated operand).
+__device__ __forceinline__ int neg_ceil_to_int(float X) {
+  int r;
+  asm("v_cvt_flr_i32_f32_e64 %0, -%1" : "=v"(r) : "v"(X));
+  return r;
+}
+
+__device__ __forceinline__ uint32_t xor3(uint32_t a, uint32_t b, uint32_t c) {
+  return __builtin_amdgcn_bitop3_b32(a, b, c, 0x96);   // a ^ b ^ c in one VALU op
+}
+
+// (16-bit half HALF of w) - a, the half selected by the instruction's operand
+// select (no separate mask / shift).
+template <int HALF>
+__device__ __forceinline__ uint32_t half_minus(uint32_t w, uint32_t a) {
+  uint32_t r;
+  if (HALF == 0)
+    asm("v_sub_u32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:WORD_0 src1_sel:DWORD"
+        : "=v"(r) : "v"(w), "v"(a));
+  else
+    asm("v_sub_u32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:WORD_1 src1_sel:DWORD"
+        : "=v"(r) : "v"(w), "v"(a));
+  return r;
+}
+
+// (S >> 16) << pos in one instruction (operand select picks the high half).
+__device__ __forceinline__ uint32_t place_high_half(uint32_t S, uint32_t pos) {
+  uint32_t r;
+  asm("v_lshlrev_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:WORD_1"
+      : "=v"(r) : "s"(pos), "v"(S));
+  return r;
+}
+
 template <int BITS, int GROUP, int ROUNDING>
 __global__ __launch_bounds__(kBlock) void quantize_kernel(
     const float* __restrict__ act, int64_t n, uint32_t seed_lo, uint32_t seed_hi,
@@ -100,6 +136,7 @@ __global__ __launch_bounds__(kBlock) void quantize_kernel(
     float* __restrict__ gscale) {
   constexpr int LPG = GROUP / kElemsPerLane;       // lanes per group
   constexpr float Bf = (float)((1 << BITS) - 1);   // B = 2^b - 1
+  constexpr float B16 = Bf * 65536.0f;
   constexpr int kWords = (kElemsPerLane * BITS + 31) / 32;
 
   __shared__ float4 slab[kWavesPerBlock][kTileElems / 4];
@@ -108,145 +145,153 @@ __global__ __launch_bounds__(kBlock) void quantize_kernel(
   const int wave = threadIdx.x >> 6;
   float4* my = slab[wave];
 
-  const int64_t n_tiles = (n + kTileElems - 1) / kTileElems;
-  const int64_t stride = (int64_t)gridDim.x * kWavesPerBlock;
-  int64_t tile = (int64_t)blockIdx.x * kWavesPerBlock + wave;
-  if (tile >= n_tiles) return;
+  const int64_t tile = (int64_t)blockIdx.x * kWavesPerBlock + wave;   // one tile per wave
+  const int64_t e0 = tile * kTileElems + (int64_t)lane * kElemsPerLane;  // lane's first element
+  if (tile * kTileElems >= n) return;
 
-  const float4* src = reinterpret_cast<const float4*>(act);
-  const int64_t n_chunks = n >> 2;  // n is a multiple of 32
-
-  float4 nxt[4];
+  // stage the tile: coalesced 128-bit loads, row-wise into the swizzled slab
   {
+    const float4* src = reinterpret_cast<const float4*>(act);
+    const int64_t n_chunks = n >> 2;  // n is a multiple of 32
     const int64_t c0 = tile * (kTileElems / 4) + lane;
+    float4 v[4];
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
       const int64_t c = c0 + u * kWave;
-      nxt[u] = c < n_chunks ? src[c] : make_float4(0.f, 0.f, 0.f, 0.f);
+      v[u] = c < n_chunks ? src[c] : make_float4(0.f, 0.f, 0.f, 0.f);
     }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) my[slab_slot(u * kWave + lane)] = v[u];
+  }
+  // lane-contiguous read-back: elements [16*lane, 16*lane+16) of the tile
+  float x[kElemsPerLane];
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const float4 v = my[slab_slot(4 * lane + j)];
+    x[4 * j + 0] = v.x; x[4 * j + 1] = v.y; x[4 * j + 2] = v.z; x[4 * j + 3] = v.w;
+  }
+  const bool live = e0 < n;
+
+  // Z = min, max of the group
+  float mn = x[0], mx = x[0];
+#pragma unroll
+  for (int j = 1; j < kElemsPerLane; ++j) { mn = fminf(mn, x[j]); mx = fmaxf(mx, x[j]); }
+  group_minmax<LPG>(mn, mx);
+  mn = mn + 0.0f;                       // -0 -> +0
+  mx = mx + 0.0f;
+  const float range = mx - mn;          // R
+  const float scale = range / Bf;       // R / B, correctly rounded
+  float inv = 0.0f;                     // B / R, correctly rounded, kept finite
+  if (range > 0.0f) inv = fminf(Bf / range, FLT_MAX);
+  // the maximum is code B by definition; a constant group has no such element
+  const float mxx = range > 0.0f ? mx : __builtin_nanf("");
+
+  // rounding noise: two Philox blocks cover this lane's 16 elements.  What is
+  // kept is 65535 - h (the complement of each 16-bit half).
+  uint32_t nrnd[8];
+  if (ROUNDING == TINYKG_ROUND_STOCHASTIC) {
+    const uint64_t q = (first_index + (uint64_t)e0) >> 3;
+    const Philox4 a = philox4x32_10((uint32_t)q, (uint32_t)(q >> 32), seed_lo, seed_hi);
+    const uint64_t q1 = q + 1;
+    const Philox4 b = philox4x32_10((uint32_t)q1, (uint32_t)(q1 >> 32), seed_lo, seed_hi);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) { nrnd[i] = ~a.w[i]; nrnd[4 + i] = ~b.w[i]; }
   }
 
-  for (; tile < n_tiles; tile += stride) {
-    // stage the tile: row-wise (coalesced order) into the swizzled slab
+  // With X = xb * 2^16 (exact), floor(xb) + [h < frac(xb) * 2^16] equals
+  // (ceil(X) + 65535 - h) >> 16, and nearest rounding is (floor(X) + 2^15) >> 16.
+  uint32_t words[kWords];
 #pragma unroll
-    for (int u = 0; u < 4; ++u) my[slab_slot(u * kWave + lane)] = nxt[u];
-    // prefetch the next tile of this wave while this one is processed
-    {
-      const int64_t c0 = (tile + stride) * (kTileElems / 4) + lane;
+  for (int w = 0; w < kWords; ++w) words[w] = 0u;
 #pragma unroll
-      for (int u = 0; u < 4; ++u) {
-        const int64_t c = c0 + u * kWave;
-        nxt[u] = c < n_chunks ? src[c] : make_float4(0.f, 0.f, 0.f, 0.f);
-      }
-    }
-    // lane-contiguous read-back: elements [16*lane, 16*lane+16) of the tile
-    float x[kElemsPerLane];
+  for (int j = 0; j < kElemsPerLane; j += 2) {
+    uint32_t placed[2];
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const float4 v = my[slab_slot(4 * lane + j)];
-      x[4 * j + 0] = v.x; x[4 * j + 1] = v.y; x[4 * j + 2] = v.z; x[4 * j + 3] = v.w;
-    }
-
-    const int64_t e0 = tile * kTileElems + (int64_t)lane * kElemsPerLane;  // first element
-    const bool live = e0 < n;
-
-    // Z = min, max of the group
-    float mn = x[0], mx = x[0];
-#pragma unroll
-    for (int j = 1; j < kElemsPerLane; ++j) { mn = fminf(mn, x[j]); mx = fmaxf(mx, x[j]); }
-    group_minmax<LPG>(mn, mx);
-    mn = mn + 0.0f;                       // -0 -> +0
-    mx = mx + 0.0f;
-    const float range = mx - mn;          // R
-    const float scale = range / Bf;       // R / B, correctly rounded
-    float inv = 0.0f;                     // B / R, correctly rounded, kept finite
-    if (range > 0.0f) inv = fminf(Bf / range, FLT_MAX);
-
-    // rounding noise: two Philox blocks cover this lane's 16 elements
-    uint32_t rnd[8];
-    if (ROUNDING == TINYKG_ROUND_STOCHASTIC) {
-      const uint64_t q = (first_index + (uint64_t)e0) >> 3;
-      const Philox4 a = philox4x32_10((uint32_t)q, (uint32_t)(q >> 32), seed_lo, seed_hi);
-      const uint64_t q1 = q + 1;
-      const Philox4 b = philox4x32_10((uint32_t)q1, (uint32_t)(q1 >> 32), seed_lo, seed_hi);
-#pragma unroll
-      for (int i = 0; i < 4; ++i) { rnd[i] = a.w[i]; rnd[4 + i] = b.w[i]; }
-    }
-
-    uint32_t words[kWords];
-#pragma unroll
-    for (int w = 0; w < kWords; ++w) words[w] = 0u;
-#pragma unroll
-    for (int j = 0; j < kElemsPerLane; ++j) {
-      const float t = x[j] - mn;                 // e - Z
-      float xb = t * inv;                        // (e - Z) / R * B
-      xb = fminf(xb, Bf);
-      const float f = floorf(xb);
-      const float p = xb - f;                    // exact
-      uint32_t code = (uint32_t)f;
+    for (int u = 0; u < 2; ++u) {
+      const float t = x[j + u] - mn;             // e - Z
+      const float xb = fminf(t * inv, Bf);       // (e - Z) / R * B, inside [0, B]
+      float X = xb * 65536.0f;
+      X = (x[j + u] == mxx) ? B16 : X;
+      uint32_t S;                                // code in bits 16.., rubbish below
       if (ROUNDING == TINYKG_ROUND_STOCHASTIC) {
-        const uint32_t wv = rnd[j >> 1];
-        const uint32_t h = (j & 1) ? (wv >> 16) : (wv & 0xFFFFu);
-        code += ((float)h < p * 65536.0f) ? 1u : 0u;
+        const uint32_t a = (uint32_t)neg_ceil_to_int(X);
+        S = u == 0 ? half_minus<0>(nrnd[j >> 1], a) : half_minus<1>(nrnd[j >> 1], a);
       } else {
-        code += (p >= 0.5f) ? 1u : 0u;
+        S = (uint32_t)X + 32768u;
       }
-      if (x[j] == mx && range > 0.0f) code = (uint32_t)Bf;   // the maximum is code B
-      words[(j * BITS) >> 5] |= code << ((j * BITS) & 31);
+      placed[u] = place_high_half(S, ((j + u) * BITS) & 31);
     }
+    words[(j * BITS) >> 5] |= placed[0] | placed[1];   // both land in the same word
+  }
 
-    if (live) {
-      const int64_t bit0 = e0 * BITS;            // multiple of 16
-      uint8_t* dst = packed + (bit0 >> 3);
-      if (BITS == 1) {
-        *reinterpret_cast<uint16_t*>(dst) = (uint16_t)words[0];
-      } else if (BITS == 2) {
-        *reinterpret_cast<uint32_t*>(dst) = words[0];
-      } else if (BITS == 4) {
-        *reinterpret_cast<uint2*>(dst) = make_uint2(words[0], words[kWords > 1 ? 1 : 0]);
-      } else {
-        *reinterpret_cast<uint4*>(dst) = make_uint4(words[0], words[kWords > 1 ? 1 : 0],
-                                                    words[kWords > 2 ? 2 : 0],
-                                                    words[kWords > 3 ? 3 : 0]);
-      }
-      if ((lane & (LPG - 1)) == 0) {
-        const int64_t g = e0 / GROUP;
-        gmin[g] = mn;
-        gscale[g] = scale;
-      }
+  if (live) {
+    const int64_t bit0 = e0 * BITS;            // multiple of 16
+    uint8_t* dst = packed + (bit0 >> 3);
+    if (BITS == 1) {
+      *reinterpret_cast<uint16_t*>(dst) = (uint16_t)words[0];
+    } else if (BITS == 2) {
+      *reinterpret_cast<uint32_t*>(dst) = words[0];
+    } else if (BITS == 4) {
+      *reinterpret_cast<uint2*>(dst) = make_uint2(words[0], words[kWords > 1 ? 1 : 0]);
+    } else {
+      *reinterpret_cast<uint4*>(dst) = make_uint4(words[0], words[kWords > 1 ? 1 : 0],
+                                                  words[kWords > 2 ? 2 : 0],
+                                                  words[kWords > 3 ? 3 : 0]);
+    }
+    if ((lane & (LPG - 1)) == 0) {
+      const int64_t g = e0 / GROUP;
+      gmin[g] = mn;
+      gscale[g] = scale;
     }
   }
 }
 
 // ---- unpack + dequantize ------------------------------------------------------
-// One thread per 4 consecutive elements (one 128-bit store); the thread reads
-// only the 4*bits bits it needs, so loads and stores stay contiguous per wave.
+// A block owns kDqU * 256 consecutive 128-bit output chunks; thread t handles
+// chunks t, t+256, ... of it, so every load and store instruction of a wave is
+// contiguous.  All loads of a thread are issued before its first store, and each
+// thread reads only the 4*bits bits a chunk needs.
+constexpr int kDqU = 4;
+
+template <int BITS>
+__device__ __forceinline__ uint32_t load_codes4(const uint8_t* __restrict__ packed, int64_t c) {
+  if (BITS == 8) return reinterpret_cast<const uint32_t*>(packed)[c];
+  if (BITS == 4) return reinterpret_cast<const uint16_t*>(packed)[c];
+  if (BITS == 2) return packed[c];
+  return (packed[c >> 1] >> ((c & 1) * 4)) & 0xFu;
+}
+
 template <int BITS>
 __global__ __launch_bounds__(256) void dequantize_kernel(
     const uint8_t* __restrict__ packed, const float* __restrict__ gmin,
     const float* __restrict__ gscale, int64_t n_chunks, int group_chunks_log2,
     float* __restrict__ out) {
   constexpr uint32_t B = (1u << BITS) - 1u;
-  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
-  for (int64_t c = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; c < n_chunks; c += stride) {
-    uint32_t bitsv;
-    if (BITS == 8) {
-      bitsv = reinterpret_cast<const uint32_t*>(packed)[c];
-    } else if (BITS == 4) {
-      bitsv = reinterpret_cast<const uint16_t*>(packed)[c];
-    } else if (BITS == 2) {
-      bitsv = packed[c];
-    } else {
-      bitsv = (packed[c >> 1] >> ((c & 1) * 4)) & 0xFu;
+  const int64_t c0 = (int64_t)blockIdx.x * (256 * kDqU) + threadIdx.x;
+  uint32_t w[kDqU];
+  float z[kDqU], s[kDqU];
+#pragma unroll
+  for (int u = 0; u < kDqU; ++u) {
+    const int64_t c = c0 + u * 256;
+    w[u] = 0; z[u] = 0.f; s[u] = 0.f;
+    if (c < n_chunks) {
+      w[u] = load_codes4<BITS>(packed, c);
+      const int64_t g = c >> group_chunks_log2;
+      z[u] = gmin[g];
+      s[u] = gscale[g];
     }
-    const int64_t g = c >> group_chunks_log2;
-    const float z = gmin[g], s = gscale[g];
-    float4 v;
-    v.x = fmaf((float)(bitsv & B), s, z);
-    v.y = fmaf((float)((bitsv >> BITS) & B), s, z);
-    v.z = fmaf((float)((bitsv >> (2 * BITS)) & B), s, z);
-    v.w = fmaf((float)((bitsv >> (3 * BITS)) & B), s, z);
-    reinterpret_cast<float4*>(out)[c] = v;
+  }
+#pragma unroll
+  for (int u = 0; u < kDqU; ++u) {
+    const int64_t c = c0 + u * 256;
+    if (c < n_chunks) {
+      float4 v;
+      v.x = fmaf((float)(w[u] & B), s[u], z[u]);
+      v.y = fmaf((float)((w[u] >> BITS) & B), s[u], z[u]);
+      v.z = fmaf((float)((w[u] >> (2 * BITS)) & B), s[u], z[u]);
+      v.w = fmaf((float)((w[u] >> (3 * BITS)) & B), s[u], z[u]);
+      reinterpret_cast<float4*>(out)[c] = v;
+    }
   }
 }
 
@@ -262,8 +307,8 @@ tinykg_status launch_quantize_g(const float* act, int64_t n, int group, uint64_t
                                 hipStream_t stream) {
   const int64_t n_tiles = (n + kTileElems - 1) / kTileElems;
   const int64_t want = (n_tiles + kWavesPerBlock - 1) / kWavesPerBlock;
-  const int64_t cap = (int64_t)num_cus() * 8;
-  const dim3 grid((unsigned)(want < cap ? want : cap));
+  if (want >= ((int64_t)1 << 31)) return TINYKG_ERR_UNSUPPORTED;
+  const dim3 grid((unsigned)want);   // one 1024-element tile per wave, four waves per block
   const uint32_t lo = (uint32_t)seed, hi = (uint32_t)(seed >> 32);
   ProfileScope prof("quantize_kernel", stream);
 #define TINYKG_Q_LAUNCH(G)                                                                   \
@@ -335,9 +380,9 @@ tinykg_status launch_dequantize(const uint8_t* packed, const float* gmin, const 
   if (!aligned16(packed) || !aligned16(gmin) || !aligned16(gscale) || !aligned16(out))
     return TINYKG_ERR_INVALID_ARG;
   const int64_t n_chunks = n >> 2;
-  const int64_t want = (n_chunks + 255) / 256;
-  const int64_t cap = (int64_t)num_cus() * 32;
-  const dim3 grid((unsigned)(want < cap ? want : cap));
+  const int64_t want = (n_chunks + 256 * kDqU - 1) / (256 * kDqU);
+  if (want >= ((int64_t)1 << 31)) return TINYKG_ERR_UNSUPPORTED;
+  const dim3 grid((unsigned)want);
   const int gl2 = ilog2(group / 4);
   ProfileScope prof("dequantize_kernel", stream);
 #define TINYKG_DQ_LAUNCH(BITS)                                                              \

@@ -34,6 +34,10 @@ constexpr int kWave = 64;
 constexpr int kElemsPerLane = 16;
 constexpr int kTileElems = kWave * kElemsPerLane;  // 1024 elements = 4 KiB of fp32
 constexpr int kWavesPerBlock = 4;
+#ifndef TINYKG_Q_TPW
+#define TINYKG_Q_TPW 1
+#endif
+constexpr int kTilesPerWave = TINYKG_Q_TPW;      // consecutive tiles handled by one wave
 constexpr int kBlock = kWave * kWavesPerBlock;
 
 // ---- cross-lane exchange inside a DPP row (16 lanes) ------------------------
@@ -145,30 +149,39 @@ __global__ __launch_bounds__(kBlock) void quantize_kernel(
   const int wave = threadIdx.x >> 6;
   float4* my = slab[wave];
 
-  const int64_t tile = (int64_t)blockIdx.x * kWavesPerBlock + wave;   // one tile per wave
-  const int64_t e0 = tile * kTileElems + (int64_t)lane * kElemsPerLane;  // lane's first element
-  if (tile * kTileElems >= n) return;
-
-  // stage the tile: coalesced 128-bit loads, row-wise into the swizzled slab
-  {
-    const float4* src = reinterpret_cast<const float4*>(act);
-    const int64_t n_chunks = n >> 2;  // n is a multiple of 32
-    const int64_t c0 = tile * (kTileElems / 4) + lane;
-    float4 v[4];
+  // kTilesPerWave consecutive tiles per wave; all their loads are issued up front
+  const int64_t tile0 = ((int64_t)blockIdx.x * kWavesPerBlock + wave) * kTilesPerWave;
+  if (tile0 * kTileElems >= n) return;
+  float4 v[kTilesPerWave][4];
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      const int64_t c = c0 + u * kWave;
-      v[u] = c < n_chunks ? src[c] : make_float4(0.f, 0.f, 0.f, 0.f);
+  for (int tt = 0; tt < kTilesPerWave; ++tt) {
+    const int64_t tile = tile0 + tt;
+    const float4* src = reinterpret_cast<const float4*>(act) + tile * (kTileElems / 4) + lane;
+    if ((tile + 1) * kTileElems <= n) {          // whole tile in range (wave-uniform)
+#pragma unroll
+      for (int u = 0; u < 4; ++u) v[tt][u] = src[u * kWave];
+    } else {
+      const int64_t left = (n >> 2) - tile * (kTileElems / 4) - lane;   // chunks from `src` on
+#pragma unroll
+      for (int u = 0; u < 4; ++u)
+        v[tt][u] = u * kWave < left ? src[u * kWave] : make_float4(0.f, 0.f, 0.f, 0.f);
     }
-#pragma unroll
-    for (int u = 0; u < 4; ++u) my[slab_slot(u * kWave + lane)] = v[u];
   }
+
+#pragma unroll
+  for (int tt = 0; tt < kTilesPerWave; ++tt) {
+  const int64_t tile = tile0 + tt;
+  if (tile * kTileElems >= n) break;
+  const int64_t e0 = tile * kTileElems + (int64_t)lane * kElemsPerLane;  // lane's first element
+  // stage the tile row-wise (coalesced order) into the swizzled slab
+#pragma unroll
+  for (int u = 0; u < 4; ++u) my[slab_slot(u * kWave + lane)] = v[tt][u];
   // lane-contiguous read-back: elements [16*lane, 16*lane+16) of the tile
   float x[kElemsPerLane];
 #pragma unroll
   for (int j = 0; j < 4; ++j) {
-    const float4 v = my[slab_slot(4 * lane + j)];
-    x[4 * j + 0] = v.x; x[4 * j + 1] = v.y; x[4 * j + 2] = v.z; x[4 * j + 3] = v.w;
+    const float4 r4 = my[slab_slot(4 * lane + j)];
+    x[4 * j + 0] = r4.x; x[4 * j + 1] = r4.y; x[4 * j + 2] = r4.z; x[4 * j + 3] = r4.w;
   }
   const bool live = e0 < n;
 
@@ -180,12 +193,18 @@ __global__ __launch_bounds__(kBlock) void quantize_kernel(
   mn = mn + 0.0f;                       // -0 -> +0
   mx = mx + 0.0f;
   const float range = mx - mn;          // R
-  const float scale = range / Bf;       // R / B, correctly rounded
-  float inv = 0.0f;                     // B / R, correctly rounded, kept finite
-  if (range > 0.0f) inv = fminf(Bf / range, FLT_MAX);
-  // the maximum is code B by definition; a constant group has no such element
+  // R / B and B / R (both correctly rounded) with ONE divide sequence: the even
+  // lane of each pair computes R / B, the odd lane B / R, then they swap results
+  // (a group always spans at least two lanes).
+  const bool odd = lane & 1;
+  const float q = (odd ? Bf : range) / (odd ? range : Bf);
+  const float qs = dpp<kQuadSwap1>(q);
+  const float scale = odd ? qs : q;     // R / B
+  float inv = 0.0f;                     // B / R, kept finite; 0 for a constant group
+  if (range > 0.0f) inv = fminf(odd ? q : qs, FLT_MAX);
+  // An element with e - Z >= R is the group maximum: code B by definition.
+  const float top = range > 0.0f ? range : __builtin_nanf("");   // never matches if constant
   const float mxx = range > 0.0f ? mx : __builtin_nanf("");
-
   // rounding noise: two Philox blocks cover this lane's 16 elements.  What is
   // kept is 65535 - h (the complement of each 16-bit half).
   uint32_t nrnd[8];
@@ -209,9 +228,18 @@ __global__ __launch_bounds__(kBlock) void quantize_kernel(
 #pragma unroll
     for (int u = 0; u < 2; ++u) {
       const float t = x[j + u] - mn;             // e - Z
-      const float xb = fminf(t * inv, Bf);       // (e - Z) / R * B, inside [0, B]
-      float X = xb * 65536.0f;
-      X = (x[j + u] == mxx) ? B16 : X;
+      float X;
+      if (BITS <= 4) {
+        // t < R implies t * inv < B (inv = fl(B/R)), so no clamp is needed; an element
+        // with t == R that is not the maximum rounds up to B for every noise value when
+        // B <= 15 (its fractional part is at least 1 - 2^-20), so one test covers both.
+        X = (t * inv) * 65536.0f;
+        X = (t >= top) ? B16 : X;
+      } else {
+        const float xb = fminf(t * inv, Bf);     // (e - Z) / R * B, inside [0, B]
+        X = xb * 65536.0f;
+        X = (x[j + u] == mxx) ? B16 : X;
+      }
       uint32_t S;                                // code in bits 16.., rubbish below
       if (ROUNDING == TINYKG_ROUND_STOCHASTIC) {
         const uint32_t a = (uint32_t)neg_ceil_to_int(X);
@@ -244,6 +272,7 @@ __global__ __launch_bounds__(kBlock) void quantize_kernel(
       gscale[g] = scale;
     }
   }
+  }  // tiles of this wave
 }
 
 // ---- unpack + dequantize ------------------------------------------------------
@@ -306,9 +335,10 @@ tinykg_status launch_quantize_g(const float* act, int64_t n, int group, uint64_t
                                 uint64_t first_index, uint8_t* packed, float* gmin, float* gscale,
                                 hipStream_t stream) {
   const int64_t n_tiles = (n + kTileElems - 1) / kTileElems;
-  const int64_t want = (n_tiles + kWavesPerBlock - 1) / kWavesPerBlock;
+  const int64_t per_block = kWavesPerBlock * kTilesPerWave;
+  const int64_t want = (n_tiles + per_block - 1) / per_block;
   if (want >= ((int64_t)1 << 31)) return TINYKG_ERR_UNSUPPORTED;
-  const dim3 grid((unsigned)want);   // one 1024-element tile per wave, four waves per block
+  const dim3 grid((unsigned)want);
   const uint32_t lo = (uint32_t)seed, hi = (uint32_t)(seed >> 32);
   ProfileScope prof("quantize_kernel", stream);
 #define TINYKG_Q_LAUNCH(G)                                                                   \

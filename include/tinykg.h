@@ -157,6 +157,45 @@ tinykg_status tinykg_kg_aggregate_bwd(const tinykg_graph* g, const tinykg_saved*
                                       size_t workspace_bytes, void* stream);
 
 /* ------------------------------------------------------------------------- *
+ * Readout and loss for a stack of layers (Sec. 3.2: after L layers a readout forms
+ * the final embedding -- here the concatenation of E^(0..L), "layer-aggregation" --
+ * and a downstream loss is optimised).  Score y(u, i) = <concat_l e_u^(l), concat_l
+ * e_i^(l)>; pairwise ranking (BPR) loss = mean over the batch of
+ * softplus(y(u, i-) - y(u, i+)).
+ * ------------------------------------------------------------------------- */
+
+/* layers: HOST array of n_layers DEVICE pointers, layer l being [n_nodes, dims[l]]
+ * fp32 (dims: HOST array, each a multiple of 4, at most 128).  users/pos/neg:
+ * DEVICE int32 [batch], ids in [0, n_nodes) (not checked).  Writes loss[0] (DEVICE,
+ * the mean loss) and coef (DEVICE, 2*batch floats): coef[b] = sigmoid(y_neg - y_pos) /
+ * batch, the derivative of the loss with respect to (y_neg - y_pos) of sample b; the
+ * second half coef[batch + b] holds the per-sample loss terms (summed in fixed order). */
+tinykg_status tinykg_bpr_loss(const float* const* layers, const int* dims, int n_layers,
+                              int64_t n_nodes, const int32_t* users, const int32_t* pos,
+                              const int32_t* neg, int64_t batch, float* loss, float* coef,
+                              void* stream);
+
+/* Gradient of that loss with respect to ONE layer tensor E_l [n_nodes, dim]:
+ * row u += coef (e_neg - e_pos), row pos -= coef e_u, row neg += coef e_u, summed
+ * over the batch.  accumulate == 0: grad is cleared first; != 0: the rows are
+ * added to what grad holds (the gradient arriving from the layer above). */
+tinykg_status tinykg_bpr_grad(const float* E_l, int dim, int64_t n_nodes, const int32_t* users,
+                              const int32_t* pos, const int32_t* neg, const float* coef,
+                              int64_t batch, int accumulate, float* grad, void* stream);
+
+/* Row gather / scatter-add used by the readout so that the full fp32 layer tensors
+ * need not outlive the next layer's forward pass (Sec. 3.3: exact activations are
+ * discarded layer by layer): out[r, :] = E[idx[r], :] and dst[idx[r], :] += src[r, :].
+ * E/dst are [*, dim] fp32 (dim a multiple of 4 for the gather), idx DEVICE int32
+ * [n_rows] (ids not checked), out/src [n_rows, dim]. */
+tinykg_status tinykg_gather_rows(const float* E, int dim, const int32_t* idx, int64_t n_rows,
+                                 float* out, void* stream);
+tinykg_status tinykg_scatter_add_rows(const float* src, int dim, const int32_t* idx, int64_t n_rows,
+                                      float* dst, void* stream);
+/* dst[0..n) = 0 with a fill kernel (n a multiple of 4, dst DEVICE, 16-byte aligned). */
+tinykg_status tinykg_fill_zero(float* dst, int64_t n, void* stream);
+
+/* ------------------------------------------------------------------------- *
  * Measurement hooks (not part of the method): when enabled, every kernel launch
  * made by the entry points above is bracketed by a pair of HIP events recorded
  * on the caller's stream, so a benchmark can read each kernel's device time over

@@ -263,3 +263,56 @@ def restore_context(ctx, n_nodes, d_in, d_out):
     Eh = dequantize(ctx["packed_E"], ctx["gmin_E"], ctx["gscale_E"], n_nodes, d_in, b, g)
     Hh = dequantize(ctx["packed_H"], ctx["gmin_H"], ctx["gscale_H"], n_nodes, d_in, b, g)
     return Eh, Hh, mask
+
+
+# ------------------------------------------------ readout + ranking loss ------
+def bpr_loss_grad(layers, users, pos, neg):
+    """Readout = concatenation of the layer tensors (Sec. 3.2, layer-aggregation);
+    y(u, i) = <z_u, z_i>; loss = mean_b softplus(y(u_b, neg_b) - y(u_b, pos_b)).
+    Plain numpy, float64.  layers: list of [n, d_l] arrays.  Returns the loss, the
+    per-sample coefficient sigmoid(y_neg - y_pos) / batch, and one gradient array per
+    layer (same shapes as `layers`)."""
+    Z = np.concatenate([np.asarray(a, dtype=np.float64) for a in layers], axis=1)
+    users, pos, neg = (np.asarray(a, dtype=np.int64) for a in (users, pos, neg))
+    batch = users.size
+    diff = np.einsum("bd,bd->b", Z[users], Z[neg] - Z[pos])
+    loss = np.mean(np.logaddexp(0.0, diff))
+    coef = 1.0 / (1.0 + np.exp(-diff)) / batch
+    gZ = np.zeros_like(Z)
+    np.add.at(gZ, users, coef[:, None] * (Z[neg] - Z[pos]))
+    np.add.at(gZ, pos, -coef[:, None] * Z[users])
+    np.add.at(gZ, neg, coef[:, None] * Z[users])
+    grads, o = [], 0
+    for a in layers:
+        d = np.asarray(a).shape[1]
+        grads.append(gZ[:, o:o + d])
+        o += d
+    return loss, coef, grads
+
+
+def stack_step(n_nodes, head, rel, tail, E0, params, slope, bits, group, seed, users, pos, neg,
+               threads=1):
+    """One training step of a stack of layers, every stage from the oracle's own
+    values: forward through the layers (saving compressed contexts: layer l uses
+    seeds seed+2l and seed+2l+1), readout + loss, backward.  Returns a dict."""
+    acts = [np.ascontiguousarray(E0, dtype=np.float32)]
+    ctxs = []
+    for l, (Wr, er, W) in enumerate(params):
+        Eo, H, mask = aggregate_fwd(n_nodes, head, rel, tail, acts[-1], Wr, er, W, slope, threads)
+        ctxs.append(save_context(acts[-1], H, mask, bits, group, seed + 2 * l))
+        acts.append(Eo)
+    loss, coef, rgrads = bpr_loss_grad(acts, users, pos, neg)
+    g = rgrads[-1].astype(np.float32)
+    layer_grads = [None] * len(acts)
+    layer_grads[-1] = g
+    pgrads = [None] * len(params)
+    for l in range(len(params) - 1, -1, -1):
+        Wr, er, W = params[l]
+        d_in, d_out = acts[l].shape[1], acts[l + 1].shape[1]
+        Eh, Hh, mk = restore_context(ctxs[l], n_nodes, d_in, d_out)
+        gE, gWr, ger, gW = aggregate_bwd(n_nodes, head, rel, tail, Eh, Hh, mk, Wr, er, W, slope, g, threads)
+        g = (gE.astype(np.float64) + rgrads[l]).astype(np.float32)
+        layer_grads[l] = g
+        pgrads[l] = (gWr, ger, gW)
+    return {"acts": acts, "ctxs": ctxs, "loss": loss, "coef": coef, "layer_grads": layer_grads,
+            "param_grads": pgrads}

@@ -22,7 +22,8 @@ EXPORTS = [
     "tinykg_quantize_ex", "tinykg_dequantize", "tinykg_graph_create", "tinykg_graph_destroy",
     "tinykg_graph_num_nodes", "tinykg_graph_num_edges", "tinykg_kg_aggregate_workspace_bytes",
     "tinykg_kg_aggregate_fwd", "tinykg_kg_aggregate_bwd", "tinykg_profile_enable",
-    "tinykg_profile_report", "tinykg_profile_copy",
+    "tinykg_profile_report", "tinykg_profile_copy", "tinykg_bpr_loss", "tinykg_bpr_grad",
+    "tinykg_gather_rows", "tinykg_scatter_add_rows", "tinykg_fill_zero",
 ]
 
 
@@ -77,6 +78,11 @@ def lib():
         L.tinykg_profile_report.argtypes = [C.c_char_p, sz]
         L.tinykg_profile_report.restype = sz
         L.tinykg_profile_copy.argtypes = [vp, vp, sz, vp]
+        L.tinykg_bpr_loss.argtypes = [C.POINTER(vp), C.POINTER(i32), i32, i64, vp, vp, vp, i64, vp, vp, vp]
+        L.tinykg_bpr_grad.argtypes = [vp, i32, i64, vp, vp, vp, vp, i64, i32, vp, vp]
+        L.tinykg_gather_rows.argtypes = [vp, i32, vp, i64, vp, vp]
+        L.tinykg_scatter_add_rows.argtypes = [vp, i32, vp, i64, vp, vp]
+        L.tinykg_fill_zero.argtypes = [vp, i64, vp]
         _lib = L
     return _lib
 
@@ -163,6 +169,58 @@ def tinykg_profile_copy(dst, src):
     nbytes = src.numel() * src.element_size()
     assert dst.numel() * dst.element_size() == nbytes
     _ok(lib().tinykg_profile_copy(_ptr(dst), _ptr(src), nbytes, _stream()), "tinykg_profile_copy")
+
+
+def tinykg_bpr_loss(layers, users, pos, neg, loss=None, coef=None):
+    """layers: list of [n_nodes, d_l] fp32 CUDA tensors.  Returns (loss[1], coef[2*batch])."""
+    n_nodes, batch = layers[0].shape[0], users.numel()
+    for t in layers:
+        _dev(t, torch.float32, "layer")
+    for t, nm in ((users, "users"), (pos, "pos"), (neg, "neg")):
+        _dev(t, torch.int32, nm)
+    if loss is None:
+        loss = torch.empty(1, dtype=torch.float32, device=users.device)
+    if coef is None:
+        coef = torch.empty(2 * batch, dtype=torch.float32, device=users.device)
+    ptrs = (C.c_void_p * len(layers))(*[t.data_ptr() for t in layers])
+    dims = (C.c_int * len(layers))(*[t.shape[1] for t in layers])
+    _ok(lib().tinykg_bpr_loss(ptrs, dims, len(layers), n_nodes, _ptr(users), _ptr(pos), _ptr(neg), batch,
+                              _ptr(loss), _ptr(coef), _stream()), "tinykg_bpr_loss")
+    return loss, coef
+
+
+def tinykg_bpr_grad(E_l, users, pos, neg, coef, grad, accumulate):
+    _dev(E_l, torch.float32, "E_l")
+    _dev(grad, torch.float32, "grad")
+    _ok(lib().tinykg_bpr_grad(_ptr(E_l), E_l.shape[1], E_l.shape[0], _ptr(users), _ptr(pos), _ptr(neg),
+                              _ptr(coef), users.numel(), 1 if accumulate else 0, _ptr(grad), _stream()),
+        "tinykg_bpr_grad")
+    return grad
+
+
+def tinykg_gather_rows(E, idx, out=None):
+    _dev(E, torch.float32, "E")
+    _dev(idx, torch.int32, "idx")
+    if out is None:
+        out = torch.empty((idx.numel(), E.shape[1]), dtype=torch.float32, device=E.device)
+    _ok(lib().tinykg_gather_rows(_ptr(E), E.shape[1], _ptr(idx), idx.numel(), _ptr(out), _stream()),
+        "tinykg_gather_rows")
+    return out
+
+
+def tinykg_fill_zero(dst):
+    _dev(dst, torch.float32, "dst")
+    _ok(lib().tinykg_fill_zero(_ptr(dst), dst.numel(), _stream()), "tinykg_fill_zero")
+    return dst
+
+
+def tinykg_scatter_add_rows(src, idx, dst):
+    _dev(src, torch.float32, "src")
+    _dev(dst, torch.float32, "dst")
+    _dev(idx, torch.int32, "idx")
+    _ok(lib().tinykg_scatter_add_rows(_ptr(src), src.shape[1], _ptr(idx), idx.numel(), _ptr(dst), _stream()),
+        "tinykg_scatter_add_rows")
+    return dst
 
 
 class Graph:

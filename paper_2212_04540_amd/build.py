@@ -17,6 +17,7 @@ SOURCES = {
     "tinykg_graph.hip": [],
     "tinykg_agg.hip": [],
     "tinykg_profile.hip": [],
+    "tinykg_bpr.hip": [],
 }
 
 

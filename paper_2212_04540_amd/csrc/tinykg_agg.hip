@@ -186,15 +186,23 @@ __device__ __forceinline__ float wave_sum(float v) {
   return v;
 }
 
-// Softmax statistics of the scores of one head's out-edges [e0, e0+deg).
+__device__ __forceinline__ double wave_sum(double v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+  return v;
+}
+
+// Softmax statistics of the scores of one head's out-edges [e0, e0+deg).  Sums over
+// a head run in double: a Zipf head has 10^5 and more out-edges, and its fp32
+// running sums would lose the 1e-5 the result is held to.
 __device__ __forceinline__ void softmax_stats(const float* __restrict__ s, int e0, int deg, int lane,
                                               float& m, float& z) {
   m = -INFINITY;
   for (int i = lane; i < deg; i += 64) m = fmaxf(m, s[e0 + i]);
   m = wave_max(m);
-  z = 0.f;
-  for (int i = lane; i < deg; i += 64) z += expf(s[e0 + i] - m);
-  z = wave_sum(z);
+  double zd = 0.0;
+  for (int i = lane; i < deg; i += 64) zd += (double)expf(s[e0 + i] - m);
+  z = (float)wave_sum(zd);
 }
 
 template <int D>
@@ -210,29 +218,30 @@ __global__ __launch_bounds__(kThreads) void attend_fwd_kernel(const float* __res
   const float4* E4 = reinterpret_cast<const float4*>(E);
   for (int64_t h = (int64_t)blockIdx.x * (kThreads / 64) + (threadIdx.x >> 6); h < N; h += n_waves) {
     const int e0 = rowptr[h], deg = rowptr[h + 1] - e0;
-    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+    double ax = 0.0, ay = 0.0, az = 0.0, aw = 0.0;
     if (deg > 0) {
       float m, z;
       softmax_stats(s, e0, deg, lane, m, z);
       for (int base = 0; base < deg; base += ES) {
         const int j = base + sub;
         if (j < deg) {
-          const float p = expf(s[e0 + j] - m) / z;
+          const double p = (double)(expf(s[e0 + j] - m) / z);
           const float4 x = E4[(int64_t)h_tail[e0 + j] * LPR + li];
-          acc.x = fmaf(p, x.x, acc.x); acc.y = fmaf(p, x.y, acc.y);
-          acc.z = fmaf(p, x.z, acc.z); acc.w = fmaf(p, x.w, acc.w);
+          ax = fma(p, (double)x.x, ax); ay = fma(p, (double)x.y, ay);
+          az = fma(p, (double)x.z, az); aw = fma(p, (double)x.w, aw);
         }
       }
 #pragma unroll
       for (int o = LPR; o < 64; o <<= 1) {
-        acc.x += __shfl_xor(acc.x, o); acc.y += __shfl_xor(acc.y, o);
-        acc.z += __shfl_xor(acc.z, o); acc.w += __shfl_xor(acc.w, o);
+        ax += __shfl_xor(ax, o); ay += __shfl_xor(ay, o);
+        az += __shfl_xor(az, o); aw += __shfl_xor(aw, o);
       }
     }
     if (sub == 0) {
       const float4 eh = E4[h * LPR + li];
       reinterpret_cast<float4*>(H)[h * LPR + li] =
-          make_float4(eh.x + acc.x, eh.y + acc.y, eh.z + acc.z, eh.w + acc.w);
+          make_float4((float)((double)eh.x + ax), (float)((double)eh.y + ay),
+                      (float)((double)eh.z + az), (float)((double)eh.w + aw));
     }
   }
 }
@@ -254,7 +263,7 @@ __global__ __launch_bounds__(kThreads) void attend_bwd_kernel(Source src, const 
     float m, z;
     softmax_stats(s, e0, deg, lane, m, z);
     const float4 g4 = reinterpret_cast<const float4*>(gH)[h * LPR + li];
-    float cpart = 0.f;
+    double cpart = 0.0;
     for (int base = 0; base < deg; base += ES) {
       const int j = base + sub;
       float dot = 0.f, p = 0.f;
@@ -266,13 +275,14 @@ __global__ __launch_bounds__(kThreads) void attend_bwd_kernel(Source src, const 
 #pragma unroll
       for (int o = 1; o < LPR; o <<= 1) dot += __shfl_xor(dot, o);   // g_j on every lane of the slot
       if (j < deg) {
-        cpart = fmaf(p, dot, cpart);
+        cpart = fma((double)p, (double)dot, cpart);
         if (li == 0) { pi[e0 + j] = p; gs[e0 + j] = dot; }
       }
     }
-    float c = cpart;   // equal on the lanes of a slot: sum once per slot
+    double cd = cpart;   // equal on the lanes of a slot: sum once per slot
 #pragma unroll
-    for (int o = LPR; o < 64; o <<= 1) c += __shfl_xor(c, o);
+    for (int o = LPR; o < 64; o <<= 1) cd += __shfl_xor(cd, o);
+    const float c = (float)cd;
     // grad_s_j = pi_j (g_j - sum_j' pi_j' g_j'); each lane re-reads what it wrote itself
     for (int base = 0; base < deg; base += ES) {
       const int j = base + sub;
@@ -438,9 +448,9 @@ __global__ void reduce_segments_kernel(const float* __restrict__ part,
   const int seg = blockIdx.y;
   const int p0 = seg_ptr ? seg_ptr[seg] : 0, p1 = seg_ptr ? seg_ptr[seg + 1] : n_single;
   for (int j = blockIdx.x * blockDim.x + threadIdx.x; j < stride; j += gridDim.x * blockDim.x) {
-    float s = 0.f;
-    for (int p = p0; p < p1; ++p) s += part[(size_t)p * stride + j];
-    out[(size_t)seg * stride + j] = s;
+    double s = 0.0;   // thousands of partials of both signs: summed in double, rounded once
+    for (int p = p0; p < p1; ++p) s += (double)part[(size_t)p * stride + j];
+    out[(size_t)seg * stride + j] = (float)s;
   }
 }
 
@@ -567,8 +577,12 @@ __global__ __launch_bounds__(kThreads) void edge_bwd_kernel(
       const int blk = wave + 4 * j;
       if (blk < NCB * NIB) {
         const int cb = blk / NIB, ib = blk % NIB;
-        mfma_block<KMAJOR, KMAJOR>(dA_s + cb * 32, LD, Et_s + ib * 32, LD, TE, accW[j]);
-        mfma_block<KMAJOR, KMAJOR>(dB_s + cb * 32, LD, Eh_s + ib * 32, LD, TE, accW[j]);
+        // two-level sum: a fresh accumulator per tile, added to the chunk's accumulator
+        // (keeps the fp32 running sum short when a relation has 10^5 and more edges)
+        floatx16 accT = {0};
+        mfma_block<KMAJOR, KMAJOR>(dA_s + cb * 32, LD, Et_s + ib * 32, LD, TE, accT);
+        mfma_block<KMAJOR, KMAJOR>(dB_s + cb * 32, LD, Eh_s + ib * 32, LD, TE, accT);
+        accW[j] += accT;
       }
     }
     __syncthreads();   // every read of Et_s / Eh_s is done: reuse them as staging

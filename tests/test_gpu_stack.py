@@ -1,0 +1,128 @@
+"""GPU parity of the multi-layer composition (forward through the layers, readout +
+ranking loss, backward), stage by stage: each stage of the oracle is fed what the GPU
+fed to the same stage (the GPU's own layer inputs, saved bytes, incoming gradients), so
+every comparison has identical inputs.  Tolerance as in test_gpu_agg.py."""
+import numpy as np
+import pytest
+
+torch = pytest.importorskip("torch")
+
+from oracle import ref
+from workloads import gen
+from test_gpu_agg import close
+
+pytestmark = pytest.mark.gpu
+SLOPE = 0.2
+
+
+@pytest.fixture(scope="module")
+def tk():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import paper_2212_04540_amd as tk
+    tk.lib()
+    return tk
+
+
+def run_stack(tk, N, R, head, rel, tail, dims, bits, group, batch, seed=3, threads=4, sample_hi=None):
+    dev = "cuda"
+    rng = np.random.default_rng(5)
+    E0 = gen.entity_embeddings(N, dims[0], seed=1, std=0.1)
+    params = [gen.layer_params(R, dims[l], dims[l], dims[l + 1], seed=20 + l) for l in range(len(dims) - 1)]
+    hi = N if sample_hi is None else sample_hi
+    users = rng.integers(0, hi, batch).astype(np.int32)
+    pos = rng.integers(0, hi, batch).astype(np.int32)
+    neg = rng.integers(0, hi, batch).astype(np.int32)
+    users[1] = users[0]; neg[2] = pos[3]                      # repeated ids
+    graph = tk.Graph(N, R, *(torch.from_numpy(a).to(dev) for a in (head, rel, tail)))
+    stack = tk.KGStack(graph, dims, bits, group, SLOPE, keep_activations=True)
+    tp = [tuple(torch.from_numpy(a).to(dev) for a in p) for p in params]
+    tu, tpz, tn = (torch.from_numpy(a).to(dev) for a in (users, pos, neg))
+    loss = stack.forward(torch.from_numpy(E0).to(dev), tp, seed, tu, tpz, tn)
+    layer_grads, pgrads = stack.backward(tp)
+    torch.cuda.synchronize()
+    L = len(dims) - 1
+
+    # footprint ledger: 2 N d_l (b/8 + 8/G) + N d_{l+1} / 8 per layer
+    want_bytes = sum(2 * N * dims[l] * (bits / 8 + 8 / group) + N * dims[l + 1] / 8 for l in range(L))
+    assert stack.saved_context_bytes() == want_bytes
+    assert stack.fp32_context_bytes() == sum(2 * N * dims[l] * 4 + N * dims[l + 1] / 8 for l in range(L))
+
+    # forward, layer by layer, from the GPU's own layer input
+    acts = [a.cpu().numpy() for a in stack.acts]
+    for l in range(L):
+        wEo, wH, wmask = ref.aggregate_fwd(N, head, rel, tail, acts[l], *params[l], SLOPE, threads=threads)
+        close(acts[l + 1], wEo, f"E^({l + 1})")
+        sv = stack.saved[l]
+        wp, wmn, wsc = ref.quantize(acts[l], bits, group, seed + 2 * l)
+        assert np.array_equal(sv.packed_E.cpu().numpy(), wp), f"layer {l}: Q(E) differs"
+        assert np.array_equal(sv.gmin_E.cpu().numpy().view(np.uint32), wmn.view(np.uint32))
+    # readout rows, loss, coefficients
+    ids = np.concatenate([users, pos, neg])
+    for l in range(L + 1):
+        assert np.array_equal(stack.rows[l].cpu().numpy(), acts[l][ids])
+    wloss, wcoef, _ = ref.bpr_loss_grad(acts, users, pos, neg)
+    assert abs(float(loss.cpu()[0]) - wloss) <= 1e-5 * abs(wloss)
+    close(stack.coef[:batch], wcoef, "coef")
+    # backward, layer by layer, from the GPU's own incoming gradient and saved bytes
+    _, _, rgrads = ref.bpr_loss_grad(acts, users, pos, neg)
+    g = [x.cpu().numpy() for x in layer_grads]
+    close(g[L], rgrads[L], f"grad_E^({L})")
+    for l in range(L - 1, -1, -1):
+        sv = stack.saved[l]
+        ctx = {"bits": bits, "group": group, "mask": sv.mask_J.cpu().numpy(),
+               "packed_E": sv.packed_E.cpu().numpy(), "gmin_E": sv.gmin_E.cpu().numpy(),
+               "gscale_E": sv.gscale_E.cpu().numpy(), "packed_H": sv.packed_H.cpu().numpy(),
+               "gmin_H": sv.gmin_H.cpu().numpy(), "gscale_H": sv.gscale_H.cpu().numpy()}
+        Eh, Hh, mk = ref.restore_context(ctx, N, dims[l], dims[l + 1])
+        wgE, wgWr, wger, wgW = ref.aggregate_bwd_f64(N, head, rel, tail, Eh, Hh, mk, *params[l],
+                                                     float(np.float32(SLOPE)), g[l + 1], threads=threads)
+        close(g[l], wgE + rgrads[l], f"grad_E^({l})")
+        for a, w, nm in zip(pgrads[l], (wgWr, wger, wgW), ("grad_Wr", "grad_er", "grad_W")):
+            close(a, w, f"{nm} layer {l}")
+    graph.close()
+    return stack
+
+
+def test_small_stack_matches_oracle_stage_by_stage(tk):
+    N, R, T = 600, 6, 5000
+    head, rel, tail = gen.kg_triplets(N, R, T, seed=4, tail_zipf=1.1)
+    run_stack(tk, N, R, head, rel, tail, [64, 64, 32, 16], 2, 64, batch=256)
+
+
+def test_small_stack_end_to_end_against_the_oracle_chain(tk):
+    # every stage from the oracle's own values (errors may compound through the layers)
+    N, R, T = 300, 4, 2500
+    head, rel, tail = gen.kg_triplets(N, R, T, seed=6)
+    dims = [64, 32, 16]
+    dev = "cuda"
+    E0 = gen.entity_embeddings(N, dims[0], seed=1, std=0.1)
+    params = [gen.layer_params(R, dims[l], dims[l], dims[l + 1], seed=30 + l) for l in range(2)]
+    rng = np.random.default_rng(9)
+    users, pos, neg = (rng.integers(0, N, 128).astype(np.int32) for _ in range(3))
+    want = ref.stack_step(N, head, rel, tail, E0, params, SLOPE, 32, 64, 0, users, pos, neg, threads=4)
+    graph = tk.Graph(N, R, *(torch.from_numpy(a).to(dev) for a in (head, rel, tail)))
+    stack = tk.KGStack(graph, dims, 32, 64, SLOPE)
+    tp = [tuple(torch.from_numpy(a).to(dev) for a in p) for p in params]
+    loss = stack.forward(torch.from_numpy(E0).to(dev), tp, 0, *(torch.from_numpy(a).to(dev) for a in (users, pos, neg)))
+    layer_grads, pgrads = stack.backward(tp)
+    torch.cuda.synchronize()
+    assert abs(float(loss.cpu()[0]) - want["loss"]) <= 1e-5 * want["loss"]
+    close(layer_grads[0], want["layer_grads"][0], "grad_E0", tol=1e-4)
+    for l in range(2):
+        for a, w, nm in zip(pgrads[l], want["param_grads"][l], ("grad_Wr", "grad_er", "grad_W")):
+            close(a, w, f"{nm} layer {l}", tol=1e-4)
+    graph.close()
+
+
+def test_config3_user_item_entity_graph(tk):
+    # stand-in for Amazon-book (Table 1): 70k users, 25k items, 90k attribute entities,
+    # 40 KG relations + 2 interaction relations, 3M KG triplets + 2 x 850k interaction edges,
+    # Zipf(1.2) degrees; layers 64 -> 64 -> 32 -> 16, INT2 / group 64, 4096 BPR triples
+    nu, ni, na = 70_000, 25_000, 90_000
+    head, rel, tail = gen.user_item_entity_graph(nu, ni, na, 40, 3_000_000, 850_000, seed=0, zipf=1.2)
+    N = nu + ni + na
+    stack = run_stack(tk, N, 42, head, rel, tail, [64, 64, 32, 16], 2, 64, batch=4096,
+                      threads=ref.default_threads(), sample_hi=nu + ni)
+    ratio = stack.fp32_context_bytes() / stack.saved_context_bytes()
+    assert 9.0 < ratio < 10.7          # 10.67x on E and H, less the uncompressed 1-bit masks

@@ -218,6 +218,7 @@ __global__ __launch_bounds__(kThreads) void attend_fwd_kernel(const float* __res
   const float4* E4 = reinterpret_cast<const float4*>(E);
   for (int64_t h = (int64_t)blockIdx.x * (kThreads / 64) + (threadIdx.x >> 6); h < N; h += n_waves) {
     const int e0 = rowptr[h], deg = rowptr[h + 1] - e0;
+    if (deg > kHeavyDegree) continue;   // handled segment-wise by the heavy_* kernels
     double ax = 0.0, ay = 0.0, az = 0.0, aw = 0.0;
     if (deg > 0) {
       float m, z;
@@ -259,7 +260,7 @@ __global__ __launch_bounds__(kThreads) void attend_bwd_kernel(Source src, const 
   const int64_t n_waves = (int64_t)gridDim.x * (kThreads / 64);
   for (int64_t h = (int64_t)blockIdx.x * (kThreads / 64) + (threadIdx.x >> 6); h < N; h += n_waves) {
     const int e0 = rowptr[h], deg = rowptr[h + 1] - e0;
-    if (deg == 0) continue;
+    if (deg == 0 || deg > kHeavyDegree) continue;   // heavy heads: heavy_* kernels
     float m, z;
     softmax_stats(s, e0, deg, lane, m, z);
     const float4 g4 = reinterpret_cast<const float4*>(gH)[h * LPR + li];
@@ -289,6 +290,152 @@ __global__ __launch_bounds__(kThreads) void attend_bwd_kernel(Source src, const 
       if (j < deg && li == 0) gs[e0 + j] = pi[e0 + j] * (gs[e0 + j] - c);
     }
   }
+}
+
+
+// ---------------------------------------------------------------- heavy heads ----
+// A head with more than kHeavyDegree out-edges is processed in segments of that many
+// edges, one wave per segment, and a small per-head pass merges the segments.  The
+// softmax is merged in the usual shifted form: a segment keeps (m_s, z_s, acc_s) with
+// z_s = sum exp(s_j - m_s), acc_s = sum exp(s_j - m_s) e_t, and the head's values are
+// M = max m_s, Z = sum z_s exp(m_s - M), acc = sum acc_s exp(m_s - M).
+struct HeavyList {
+  const int32_t* head;     // [n_heavy]
+  const int32_t* seg_ptr;  // [n_heavy + 1]
+  const int32_t* seg_q;    // [n_hseg]
+  const int32_t* seg_e0;   // [n_hseg]
+  const int32_t* seg_cnt;  // [n_hseg]
+  int n_heavy, n_hseg;
+};
+
+// Per segment: pm, pz and (WITH_ACC) the unnormalised weighted row sum pacc [n_hseg, D].
+template <int D, bool WITH_ACC>
+__global__ __launch_bounds__(kThreads) void heavy_part1_kernel(const float* __restrict__ E,
+                                                               const int32_t* __restrict__ h_tail,
+                                                               const float* __restrict__ s, HeavyList hl,
+                                                               float* __restrict__ pm, double* __restrict__ pz,
+                                                               double* __restrict__ pacc) {
+  constexpr int LPR = D / 4, ES = 64 / LPR;
+  const int lane = threadIdx.x & 63, sub = lane / LPR, li = lane % LPR;
+  const int sg = blockIdx.x * (kThreads / 64) + (threadIdx.x >> 6);
+  if (sg >= hl.n_hseg) return;
+  const int e0 = hl.seg_e0[sg], cnt = hl.seg_cnt[sg];
+  float m = -INFINITY;
+  for (int i = lane; i < cnt; i += 64) m = fmaxf(m, s[e0 + i]);
+  m = wave_max(m);
+  double zd = 0.0;
+  for (int i = lane; i < cnt; i += 64) zd += (double)expf(s[e0 + i] - m);
+  zd = wave_sum(zd);
+  if (lane == 0) { pm[sg] = m; pz[sg] = zd; }
+  if (WITH_ACC) {
+    const float4* E4 = reinterpret_cast<const float4*>(E);
+    double ax = 0.0, ay = 0.0, az = 0.0, aw = 0.0;
+    for (int base = 0; base < cnt; base += ES) {
+      const int j = base + sub;
+      if (j < cnt) {
+        const double p = (double)expf(s[e0 + j] - m);
+        const float4 x = E4[(int64_t)h_tail[e0 + j] * LPR + li];
+        ax = fma(p, (double)x.x, ax); ay = fma(p, (double)x.y, ay);
+        az = fma(p, (double)x.z, az); aw = fma(p, (double)x.w, aw);
+      }
+    }
+#pragma unroll
+    for (int o = LPR; o < 64; o <<= 1) {
+      ax += __shfl_xor(ax, o); ay += __shfl_xor(ay, o);
+      az += __shfl_xor(az, o); aw += __shfl_xor(aw, o);
+    }
+    if (sub == 0) {
+      double* out = pacc + (int64_t)sg * D + li * 4;
+      out[0] = ax; out[1] = ay; out[2] = az; out[3] = aw;
+    }
+  }
+}
+
+// Per heavy head: M, Z (-> hm, hz) and, WITH_ACC, H_h = e_h + acc / Z.
+template <int D, bool WITH_ACC>
+__global__ __launch_bounds__(kThreads) void heavy_merge1_kernel(const float* __restrict__ E, HeavyList hl,
+                                                                const float* __restrict__ pm,
+                                                                const double* __restrict__ pz,
+                                                                const double* __restrict__ pacc,
+                                                                float* __restrict__ hm, double* __restrict__ hz,
+                                                                float* __restrict__ H) {
+  const int lane = threadIdx.x & 63;
+  const int q = blockIdx.x * (kThreads / 64) + (threadIdx.x >> 6);
+  if (q >= hl.n_heavy) return;
+  const int a = hl.seg_ptr[q], b = hl.seg_ptr[q + 1];
+  float M = -INFINITY;
+  for (int i = a + lane; i < b; i += 64) M = fmaxf(M, pm[i]);
+  M = wave_max(M);
+  double Z = 0.0;
+  for (int i = a + lane; i < b; i += 64) Z += pz[i] * (double)expf(pm[i] - M);
+  Z = wave_sum(Z);
+  if (lane == 0) { hm[q] = M; hz[q] = Z; }
+  if (WITH_ACC) {
+    const int64_t h = hl.head[q];
+    for (int i = lane; i < D; i += 64) {
+      double acc = 0.0;
+      for (int sgi = a; sgi < b; ++sgi) acc += pacc[(int64_t)sgi * D + i] * (double)expf(pm[sgi] - M);
+      H[h * D + i] = (float)((double)E[h * D + i] + acc / Z);
+    }
+  }
+}
+
+// Backward, per segment: pi_j = exp(s_j - M) / Z, g_j = grad_H_h . e_hat_t (kept in gs),
+// and the segment's part of c = sum pi_j g_j.
+template <int D, int BITS>
+__global__ __launch_bounds__(kThreads) void heavy_part2_kernel(Source src, const float* __restrict__ gH,
+                                                               const int32_t* __restrict__ h_tail,
+                                                               const float* __restrict__ s, HeavyList hl,
+                                                               const float* __restrict__ hm,
+                                                               const double* __restrict__ hz,
+                                                               float* __restrict__ pi, float* __restrict__ gs,
+                                                               double* __restrict__ pc) {
+  constexpr int LPR = D / 4, ES = 64 / LPR;
+  const int lane = threadIdx.x & 63, sub = lane / LPR, li = lane % LPR;
+  const int sg = blockIdx.x * (kThreads / 64) + (threadIdx.x >> 6);
+  if (sg >= hl.n_hseg) return;
+  const int e0 = hl.seg_e0[sg], cnt = hl.seg_cnt[sg], q = hl.seg_q[sg];
+  const int64_t h = hl.head[q];
+  const float M = hm[q];
+  const float Zf = (float)hz[q];
+  const float4 g4 = reinterpret_cast<const float4*>(gH)[h * LPR + li];
+  double cpart = 0.0;
+  for (int base = 0; base < cnt; base += ES) {
+    const int j = base + sub;
+    float dot = 0.f, p = 0.f;
+    if (j < cnt) {
+      p = expf(s[e0 + j] - M) / Zf;
+      const float4 x = fetch_chunk<BITS>(src, (int64_t)h_tail[e0 + j] * LPR + li);
+      dot = fmaf(g4.x, x.x, fmaf(g4.y, x.y, fmaf(g4.z, x.z, g4.w * x.w)));
+    }
+#pragma unroll
+    for (int o = 1; o < LPR; o <<= 1) dot += __shfl_xor(dot, o);
+    if (j < cnt) {
+      cpart = fma((double)p, (double)dot, cpart);
+      if (li == 0) { pi[e0 + j] = p; gs[e0 + j] = dot; }
+    }
+  }
+#pragma unroll
+  for (int o = LPR; o < 64; o <<= 1) cpart += __shfl_xor(cpart, o);
+  if (lane == 0) pc[sg] = cpart;
+}
+
+// Backward, per segment: c = sum of the head's segment parts (fixed order), then
+// grad_s_j = pi_j (g_j - c).
+__global__ __launch_bounds__(kThreads) void heavy_part3_kernel(HeavyList hl, const double* __restrict__ pc,
+                                                               const float* __restrict__ pi,
+                                                               float* __restrict__ gs) {
+  const int lane = threadIdx.x & 63;
+  const int sg = blockIdx.x * (kThreads / 64) + (threadIdx.x >> 6);
+  if (sg >= hl.n_hseg) return;
+  const int q = hl.seg_q[sg];
+  const int a = hl.seg_ptr[q], b = hl.seg_ptr[q + 1];
+  double c = 0.0;
+  for (int i = a + lane; i < b; i += 64) c += pc[i];
+  c = wave_sum(c);
+  const float cf = (float)c;
+  const int e0 = hl.seg_e0[sg], cnt = hl.seg_cnt[sg];
+  for (int i = lane; i < cnt; i += 64) gs[e0 + i] = pi[e0 + i] * (gs[e0 + i] - cf);
 }
 
 // ------------------------------------------------------------- dense stage ----
@@ -474,8 +621,9 @@ template <int D, int TE, int BITS>
 __global__ __launch_bounds__(kThreads) void edge_bwd_kernel(
     Source src, const float* __restrict__ Wr, const float* __restrict__ er,
     const int32_t* __restrict__ r_head, const int32_t* __restrict__ r_tail,
-    const int32_t* __restrict__ r_eid, ChunkList chunks, const float* __restrict__ pi,
-    const float* __restrict__ gs, const float* __restrict__ gH, double* __restrict__ gE,
+    const int32_t* __restrict__ r_eid, const uint8_t* __restrict__ r_hperm, ChunkList chunks,
+    const float* __restrict__ pi, const float* __restrict__ gs, const float* __restrict__ gH,
+    double* __restrict__ gE,
     float* __restrict__ part_Wr, float* __restrict__ part_er) {
   constexpr int LD = D + 4, LPR = D / 4, NCB = D / 32, NIB = D / 32, NEB = TE / 32;
   constexpr int NBW = (NCB * NIB + 3) / 4;        // grad_W_r blocks per wave
@@ -490,6 +638,7 @@ __global__ __launch_bounds__(kThreads) void edge_bwd_kernel(
   float* pi_s = gs_s + TE;
   int* tl_s = reinterpret_cast<int*>(pi_s + TE);
   int* hd_s = tl_s + TE;
+  int* hp_s = hd_s + TE;   // tile rows in ascending-head order
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int ch = blockIdx.x;
@@ -521,13 +670,13 @@ __global__ __launch_bounds__(kThreads) void edge_bwd_kernel(
     }
     if (tid < TE) {
       float g = 0.f, p = 0.f;
-      int t = -1, h = -1;
+      int t = -1, h = -1, hp = 0;
       if (tid < nrow) {
         const int pos = start + t0 + tid;
         const int e = r_eid[pos];
-        t = r_tail[pos]; h = r_head[pos]; g = gs[e]; p = pi[e];
+        t = r_tail[pos]; h = r_head[pos]; g = gs[e]; p = pi[e]; hp = r_hperm[pos];
       }
-      gs_s[tid] = g; pi_s[tid] = p; tl_s[tid] = t; hd_s[tid] = h;
+      gs_s[tid] = g; pi_s[tid] = p; tl_s[tid] = t; hd_s[tid] = h; hp_s[tid] = hp;
     }
     __syncthreads();
     // recompute a, b; grad_a = gs * tanh(b); grad_b = gs * a * (1 - tanh(b)^2)
@@ -600,7 +749,8 @@ __global__ __launch_bounds__(kThreads) void edge_bwd_kernel(
       }
     }
     __syncthreads();
-    // scatter: tails are sorted inside the chunk, so runs of one tail are summed first
+    // scatter: rows of one tail are adjacent (the chunk is sorted by tail) and rows of one
+    // head are adjacent in the tile's head order, so runs are summed before the atomics
     {
       const int i = tid % D, qpart = tid / D;
       const int e_end = min((qpart + 1) * RP, nrow);
@@ -612,7 +762,14 @@ __global__ __launch_bounds__(kThreads) void edge_bwd_kernel(
           unsafeAtomicAdd(gE + (int64_t)t * D + i, run);
           run = 0.0;
         }
-        unsafeAtomicAdd(gE + (int64_t)h * D + i, (double)Eh_s[e * LD + i]);
+      }
+      for (int k = qpart * RP; k < e_end; ++k) {
+        const int e = hp_s[k], h = hd_s[e];
+        run += (double)Eh_s[e * LD + i];
+        if (k + 1 == e_end || hd_s[hp_s[k + 1]] != h) {
+          unsafeAtomicAdd(gE + (int64_t)h * D + i, run);
+          run = 0.0;
+        }
       }
     }
   }
@@ -646,16 +803,35 @@ int dense_grid(int64_t N) {
   return (int)std::max<int64_t>(1, std::min(tiles, cap));
 }
 
-struct FwdWs { size_t s, H, total; };
+struct HeavyWs { size_t pm, pz, pacc, pc, hm, hz, end; };
+HeavyWs heavy_layout(const tinykg_graph* g, int d, size_t at) {
+  HeavyWs w;
+  w.pm = at;
+  w.pz = w.pm + align256((size_t)g->n_hseg * 4);
+  w.pacc = w.pz + align256((size_t)g->n_hseg * 8);
+  w.pc = w.pacc + align256((size_t)g->n_hseg * d * 8);
+  w.hm = w.pc + align256((size_t)g->n_hseg * 8);
+  w.hz = w.hm + align256((size_t)g->n_heavy * 4);
+  w.end = w.hz + align256((size_t)g->n_heavy * 8);
+  return w;
+}
+
+HeavyList heavy_list(const tinykg_graph* g) {
+  return HeavyList{g->heavy_head, g->heavy_seg_ptr, g->hseg_q, g->hseg_e0, g->hseg_cnt, g->n_heavy,
+                   g->n_hseg};
+}
+
+struct FwdWs { size_t s, H, total; HeavyWs hv; };
 FwdWs fwd_layout(const tinykg_graph* g, int d) {
   FwdWs w;
   w.s = 0;
   w.H = align256((size_t)g->n_edges * 4);
-  w.total = w.H + align256((size_t)g->n_nodes * d * 4);
+  w.hv = heavy_layout(g, d, w.H + align256((size_t)g->n_nodes * d * 4));
+  w.total = w.hv.end;
   return w;
 }
 
-struct BwdWs { size_t s, pi, gs, gH, acc, pW, pWr, per, total; };
+struct BwdWs { size_t s, pi, gs, gH, acc, pW, pWr, per, total; HeavyWs hv; };
 BwdWs bwd_layout(const tinykg_graph* g, int d, int d_out) {
   BwdWs w;
   const size_t e = align256((size_t)g->n_edges * 4);
@@ -664,7 +840,8 @@ BwdWs bwd_layout(const tinykg_graph* g, int d, int d_out) {
   w.pW = w.acc + align256((size_t)g->n_nodes * d * 8);
   w.pWr = w.pW + align256((size_t)dense_grid(g->n_nodes) * d_out * d * 4);
   w.per = w.pWr + align256((size_t)g->n_chunks * d * d * 4);
-  w.total = w.per + align256((size_t)g->n_chunks * d * 4);
+  w.hv = heavy_layout(g, d, w.per + align256((size_t)g->n_chunks * d * 4));
+  w.total = w.hv.end;
   return w;
 }
 
@@ -712,6 +889,20 @@ tinykg_status fwd_impl(const tinykg_graph* g, const float* E, const float* Wr, c
                        g->h_tail, s, N, H);
   }
   if ((rc = launch_status()) != TINYKG_OK) return rc;
+  if (g->n_heavy > 0) {
+    const HeavyList hl = heavy_list(g);
+    float* pm = reinterpret_cast<float*>(ws + L.hv.pm);
+    double* pz = reinterpret_cast<double*>(ws + L.hv.pz);
+    double* pacc = reinterpret_cast<double*>(ws + L.hv.pacc);
+    float* hm = reinterpret_cast<float*>(ws + L.hv.hm);
+    double* hz = reinterpret_cast<double*>(ws + L.hv.hz);
+    ProfileScope prof("heavy_head_kernels", st);
+    hipLaunchKernelGGL((heavy_part1_kernel<D, true>), dim3((g->n_hseg + 3) / 4), dim3(kThreads), 0, st, E,
+                       g->h_tail, s, hl, pm, pz, pacc);
+    hipLaunchKernelGGL((heavy_merge1_kernel<D, true>), dim3((g->n_heavy + 3) / 4), dim3(kThreads), 0, st, E,
+                       hl, pm, pz, pacc, hm, hz, H);
+    if ((rc = launch_status()) != TINYKG_OK) return rc;
+  }
   // save the context (Fig. 1): Q(E; seed), Q(H; seed + 1)
   if (bits == 32) {
     ProfileScope prof("copy_E_fp32", st);
@@ -790,13 +981,32 @@ tinykg_status bwd_impl(const tinykg_graph* g, const tinykg_saved* sv, const floa
                          gH, g->rowptr, g->h_tail, s, N, pi, gs);
     }
     if ((rc = launch_status()) != TINYKG_OK) return rc;
-    const size_t smem = (size_t)(D * LD + 4 * TE * LD + D + 4 * TE) * 4;
+    if (g->n_heavy > 0) {
+      const HeavyList hl = heavy_list(g);
+      float* pm = reinterpret_cast<float*>(ws + L.hv.pm);
+      double* pz = reinterpret_cast<double*>(ws + L.hv.pz);
+      double* pc = reinterpret_cast<double*>(ws + L.hv.pc);
+      float* hm = reinterpret_cast<float*>(ws + L.hv.hm);
+      double* hz = reinterpret_cast<double*>(ws + L.hv.hz);
+      ProfileScope prof("heavy_head_kernels", st);
+      const dim3 gs_grid((g->n_hseg + 3) / 4), gh_grid((g->n_heavy + 3) / 4);
+      hipLaunchKernelGGL((heavy_part1_kernel<D, false>), gs_grid, dim3(kThreads), 0, st,
+                         (const float*)nullptr, g->h_tail, s, hl, pm, pz, (double*)nullptr);
+      hipLaunchKernelGGL((heavy_merge1_kernel<D, false>), gh_grid, dim3(kThreads), 0, st,
+                         (const float*)nullptr, hl, pm, pz, (const double*)nullptr, hm, hz, (float*)nullptr);
+      hipLaunchKernelGGL((heavy_part2_kernel<D, BITS>), gs_grid, dim3(kThreads), 0, st, srcE, gH, g->h_tail,
+                         s, hl, hm, hz, pi, gs, pc);
+      hipLaunchKernelGGL(heavy_part3_kernel, gs_grid, dim3(kThreads), 0, st, hl, pc, pi, gs);
+      if ((rc = launch_status()) != TINYKG_OK) return rc;
+    }
+    const size_t smem = (size_t)(D * LD + 4 * TE * LD + D + 5 * TE) * 4;
     auto kern = edge_bwd_kernel<D, TE, BITS>;
     if ((rc = set_smem(kern, smem)) != TINYKG_OK) return rc;
     ChunkList cl{g->chunk_rel, g->chunk_start, g->chunk_count};
     ProfileScope prof("edge_bwd_kernel", st);
     hipLaunchKernelGGL(kern, dim3(g->n_chunks), dim3(kThreads), smem, st, srcE, Wr, er, g->r_head,
-                       g->r_tail, g->r_eid, cl, pi, gs, gH, acc, pWr, per);
+                       g->r_tail, g->r_eid, TE == 64 ? g->r_hperm64 : g->r_hperm32, cl, pi, gs, gH, acc,
+                       pWr, per);
     if ((rc = launch_status()) != TINYKG_OK) return rc;
   }
   if (N > 0) {

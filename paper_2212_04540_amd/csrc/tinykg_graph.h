@@ -20,6 +20,23 @@ struct tinykg_graph {
   int32_t* chunk_start = nullptr;    // [n_chunks] first relation-order position
   int32_t* chunk_count = nullptr;    // [n_chunks]
   int32_t* rel_chunk_ptr = nullptr;  // [n_rel + 1] chunks of relation r: [ptr[r], ptr[r+1])
+  // heads with more than kHeavyDegree out-edges are cut into segments of that many
+  // head-order edges, so that one wave never walks a 10^5-edge neighbourhood alone
+  int32_t n_heavy = 0, n_hseg = 0;
+  int32_t* heavy_head = nullptr;     // [n_heavy] node id
+  int32_t* heavy_seg_ptr = nullptr;  // [n_heavy + 1] segments of heavy head q: [ptr[q], ptr[q+1])
+  int32_t* hseg_q = nullptr;         // [n_hseg] index of the segment's head in heavy_head
+  int32_t* hseg_e0 = nullptr;        // [n_hseg] first head-order edge
+  int32_t* hseg_cnt = nullptr;       // [n_hseg] number of edges
+  // for every tile of 64 (resp. 32) consecutive relation-order edges of a chunk: the
+  // tile-local row indices sorted by head, so equal heads can be summed before they are
+  // scattered
+  uint8_t* r_hperm64 = nullptr;      // [n_edges]
+  uint8_t* r_hperm32 = nullptr;      // [n_edges]
 };
+
+namespace tinykg {
+constexpr int kHeavyDegree = 1024;
+}
 
 #endif

@@ -31,7 +31,8 @@ tinykg_status upload(const std::vector<T>& v, T** out) {
 void release(tinykg_graph* g) {
   if (!g) return;
   void* ptrs[] = {g->rowptr, g->h_tail, g->r_head, g->r_tail, g->r_eid, g->chunk_rel,
-                  g->chunk_start, g->chunk_count, g->rel_chunk_ptr};
+                  g->chunk_start, g->chunk_count, g->rel_chunk_ptr, g->heavy_head, g->heavy_seg_ptr,
+                  g->hseg_q, g->hseg_e0, g->hseg_cnt, g->r_hperm64, g->r_hperm32};
   for (void* p : ptrs)
     if (p) (void)hipFree(p);
   delete g;
@@ -120,6 +121,35 @@ tinykg_status tinykg_graph_create(int64_t n_nodes, int32_t n_rel, int64_t n_edge
   }
   rel_chunk_ptr[(size_t)n_rel] = (int32_t)chunk_rel.size();
 
+  // heavy heads and their segments
+  std::vector<int32_t> heavy_head, heavy_seg_ptr(1, 0), hseg_q, hseg_e0, hseg_cnt;
+  for (int64_t h = 0; h < n_nodes; ++h) {
+    const int32_t e0 = rowptr[(size_t)h], deg = rowptr[(size_t)h + 1] - e0;
+    if (deg <= kHeavyDegree) continue;
+    const int32_t q = (int32_t)heavy_head.size();
+    heavy_head.push_back((int32_t)h);
+    for (int32_t o = 0; o < deg; o += kHeavyDegree) {
+      hseg_q.push_back(q);
+      hseg_e0.push_back(e0 + o);
+      hseg_cnt.push_back(std::min<int32_t>(kHeavyDegree, deg - o));
+    }
+    heavy_seg_ptr.push_back((int32_t)hseg_q.size());
+  }
+  // tile-local head-sorted row orders (tiles are counted from each chunk's start)
+  std::vector<uint8_t> hperm64(T), hperm32(T);
+  for (size_t c = 0; c < chunk_rel.size(); ++c) {
+    for (int te : {64, 32}) {
+      std::vector<uint8_t>& out = te == 64 ? hperm64 : hperm32;
+      for (int32_t t0 = 0; t0 < chunk_count[c]; t0 += te) {
+        const int32_t base = chunk_start[c] + t0, nrow = std::min<int32_t>(te, chunk_count[c] - t0);
+        uint8_t idx[64];
+        for (int i = 0; i < nrow; ++i) idx[i] = (uint8_t)i;
+        std::stable_sort(idx, idx + nrow, [&](uint8_t a, uint8_t b) { return r_head[(size_t)base + a] < r_head[(size_t)base + b]; });
+        for (int i = 0; i < nrow; ++i) out[(size_t)base + i] = idx[i];
+      }
+    }
+  }
+
   tinykg_graph* g = new tinykg_graph();
   g->n_nodes = n_nodes; g->n_edges = n_edges; g->n_rel = n_rel;
   g->n_chunks = (int32_t)chunk_rel.size();
@@ -133,6 +163,15 @@ tinykg_status tinykg_graph_create(int64_t n_nodes, int32_t n_rel, int64_t n_edge
   if (st == TINYKG_OK) st = upload(chunk_start, &g->chunk_start);
   if (st == TINYKG_OK) st = upload(chunk_count, &g->chunk_count);
   if (st == TINYKG_OK) st = upload(rel_chunk_ptr, &g->rel_chunk_ptr);
+  g->n_heavy = (int32_t)heavy_head.size();
+  g->n_hseg = (int32_t)hseg_q.size();
+  if (st == TINYKG_OK) st = upload(heavy_head, &g->heavy_head);
+  if (st == TINYKG_OK) st = upload(heavy_seg_ptr, &g->heavy_seg_ptr);
+  if (st == TINYKG_OK) st = upload(hseg_q, &g->hseg_q);
+  if (st == TINYKG_OK) st = upload(hseg_e0, &g->hseg_e0);
+  if (st == TINYKG_OK) st = upload(hseg_cnt, &g->hseg_cnt);
+  if (st == TINYKG_OK) st = upload(hperm64, &g->r_hperm64);
+  if (st == TINYKG_OK) st = upload(hperm32, &g->r_hperm32);
   if (st != TINYKG_OK) { release(g); return st; }
   *out = g;
   return TINYKG_OK;

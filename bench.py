@@ -122,6 +122,74 @@ def compressor_line(tk, torch, iters=20):
     return res
 
 
+def stack_workload(a, which):
+    """configs[3] / configs[4]: a stack of layers, forward + ranking loss + backward.
+    Reported for the step time and the saved-activation footprint; not the default."""
+    import numpy as np
+    import torch
+    import paper_2212_04540_amd as tk
+    from workloads import gen
+    dev = "cuda"
+    t_prep = time.perf_counter()
+    if which == "config3":
+        nu, ni, na = 70_000, 25_000, 90_000
+        head, rel, tail = gen.user_item_entity_graph(nu, ni, na, 40, 3_000_000, 850_000, seed=0, zipf=1.2)
+        n_nodes, n_rel, dims, bits, group, sample_hi = nu + ni + na, 42, [64, 64, 32, 16], 2, 64, nu + ni
+        name = ("configs[3]: 3-layer KG GNN step on a 185k-node user-item-entity graph (3M KG triplets + "
+                "2 x 850k interaction edges, Zipf 1.2), dims 64-64-32-16, INT2 group 64, BPR on 4096 triples")
+    else:
+        n_nodes, n_rel, n_edges = 20_000_000, 60, 150_000_000
+        head, rel, tail = gen.kg_triplets(n_nodes, n_rel, n_edges, seed=0, tail_zipf=1.05)
+        dims, bits, group, sample_hi = [128, 128, 128], a.bits or 4, 128, n_nodes
+        name = ("configs[4]: 20M entities x dim 128, 60 relations, 150M triplets (Zipf 1.05 tails), "
+                f"two layers, saved activations {'fp32' if bits == 32 else 'INT%d group 128' % bits}")
+    T = head.size
+    graph = tk.Graph(n_nodes, n_rel, *(torch.from_numpy(x).to(dev) for x in (head, rel, tail)))
+    del head, rel, tail
+    g = torch.Generator(device=dev)
+    g.manual_seed(1)
+    E0 = torch.randn((n_nodes, dims[0]), generator=g, device=dev) * 0.1
+    params = [tuple(torch.from_numpy(x).to(dev) for x in gen.layer_params(n_rel, dims[l], dims[l], dims[l + 1], seed=20 + l))
+              for l in range(len(dims) - 1)]
+    rng = np.random.default_rng(5)
+    u, p, n = (torch.from_numpy(rng.integers(0, sample_hi, 4096).astype(np.int32)).to(dev) for _ in range(3))
+    stack = tk.KGStack(graph, dims, bits, group, SLOPE)
+    prep_s = time.perf_counter() - t_prep
+    torch.cuda.reset_peak_memory_stats()
+    for i in range(a.warmup):
+        stack.forward(E0, params, i, u, p, n)
+        stack.backward(params)
+    torch.cuda.synchronize()
+    tk.tinykg_profile_enable(True)
+    t0 = time.perf_counter()
+    for i in range(a.steps):
+        stack.forward(E0, params, a.warmup + i, u, p, n)
+        stack.backward(params)
+    torch.cuda.synchronize()
+    dt = (time.perf_counter() - t0) / a.steps
+    rep = tk.tinykg_profile_report()
+    tk.tinykg_profile_enable(False)
+    bpa = 4.0 if bits == 32 else bytes_per_activation(bits, group)
+    alg = 0.0
+    for l in range(len(dims) - 1):
+        d, do = dims[l], dims[l + 1]
+        alg += T * (4 * d + 12 + d * bpa + 12) + n_nodes * (4 * d + 4 * do + 2 * d * bpa + do / 8 + 4 * do + d * bpa + do / 8 + 4 * d)
+    out = {"metric": "quantize+pack and dequant+agg-bwd HBM GB/s (fraction of peak); bytes/activation",
+           "value": round(alg / dt / 1e9, 2), "unit": "GB/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
+           "ms_per_step": round(dt * 1e3, 3), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+           "dtype": "f32", "data": "synthetic",
+           "config": {"workload": name, "bits": bits, "group": group, "bytes_per_activation": bpa,
+                      "saved_context_bytes": stack.saved_context_bytes(),
+                      "fp32_context_bytes": stack.fp32_context_bytes(),
+                      "readout_rows_bytes": stack.readout_rows_bytes(),
+                      "peak_device_bytes_torch": torch.cuda.max_memory_allocated(),
+                      "host_preparation_s": round(prep_s, 1)},
+           "kernels": {k: {"launches_per_step": v[0] / a.steps, "ms_per_step": round(v[1] / a.steps, 4)}
+                       for k, v in rep.items()}}
+    graph.close()
+    print(json.dumps(out))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -129,6 +197,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-compressor", action="store_true")
+    ap.add_argument("--workload", choices=["config1", "config3", "config4"], default="config1",
+                    help="config1 (default, the headline step); config3 / config4: multi-layer steps")
+    ap.add_argument("--bits", type=int, default=0, help="config4 only: 4 (default) or 32 for the fp32 run")
     a = ap.parse_args()
     if a.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU (the paper's method is single-GPU); "
@@ -139,6 +210,8 @@ def main():
     if not torch.cuda.is_available():
         sys.exit("bench.py needs a GPU")
     tk.lib()
+    if a.workload != "config1":
+        return stack_workload(a, a.workload)
     dev = "cuda"
     inp = make_inputs(torch)
     t = {k: torch.from_numpy(v).to(dev) for k, v in inp.items()}

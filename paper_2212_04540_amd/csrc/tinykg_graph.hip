@@ -28,6 +28,16 @@ tinykg_status upload(const std::vector<T>& v, T** out) {
   return TINYKG_OK;
 }
 
+// One stable counting-sort pass: reorders `ord` by key[ord[i]] (keys in [0, n_keys)).
+void counting_pass(std::vector<int32_t>& ord, const std::vector<int32_t>& key, size_t n_keys) {
+  std::vector<int64_t> cnt(n_keys + 1, 0);
+  for (int32_t e : ord) cnt[(size_t)key[(size_t)e] + 1]++;
+  for (size_t k = 0; k < n_keys; ++k) cnt[k + 1] += cnt[k];
+  std::vector<int32_t> out(ord.size());
+  for (int32_t e : ord) out[(size_t)cnt[(size_t)key[(size_t)e]]++] = e;
+  ord.swap(out);
+}
+
 void release(tinykg_graph* g) {
   if (!g) return;
   void* ptrs[] = {g->rowptr, g->h_tail, g->r_head, g->r_tail, g->r_eid, g->chunk_rel,
@@ -69,15 +79,12 @@ tinykg_status tinykg_graph_create(int64_t n_nodes, int32_t n_rel, int64_t n_edge
     if (hr[e] < 0 || hr[e] >= n_rel) return TINYKG_ERR_INVALID_ARG;
   }
 
-  // head order: (head, relation, tail)
+  // head order: (head, relation, tail, input position) -- three stable counting passes
   std::vector<int32_t> ord(T);
   std::iota(ord.begin(), ord.end(), 0);
-  std::sort(ord.begin(), ord.end(), [&](int32_t a, int32_t b) {
-    if (hh[a] != hh[b]) return hh[a] < hh[b];
-    if (hr[a] != hr[b]) return hr[a] < hr[b];
-    if (ht[a] != ht[b]) return ht[a] < ht[b];
-    return a < b;
-  });
+  counting_pass(ord, ht, (size_t)n_nodes);
+  counting_pass(ord, hr, (size_t)n_rel);
+  counting_pass(ord, hh, (size_t)n_nodes);
   std::vector<int32_t> rowptr((size_t)n_nodes + 1, 0), h_tail(T), h_head(T), h_rel(T);
   for (size_t i = 0; i < T; ++i) {
     const int32_t e = ord[i];
@@ -86,14 +93,12 @@ tinykg_status tinykg_graph_create(int64_t n_nodes, int32_t n_rel, int64_t n_edge
   }
   for (int64_t i = 0; i < n_nodes; ++i) rowptr[(size_t)i + 1] += rowptr[(size_t)i];
 
-  // relation order over head-order edge ids: (relation, tail, head)
+  // relation order over head-order edge ids: (relation, tail, head) -- two stable passes
+  // over a sequence that already ascends in head
   std::vector<int32_t> rord(T);
   std::iota(rord.begin(), rord.end(), 0);
-  std::sort(rord.begin(), rord.end(), [&](int32_t a, int32_t b) {
-    if (h_rel[a] != h_rel[b]) return h_rel[a] < h_rel[b];
-    if (h_tail[a] != h_tail[b]) return h_tail[a] < h_tail[b];
-    return a < b;   // head order already ascends in head
-  });
+  counting_pass(rord, h_tail, (size_t)n_nodes);
+  counting_pass(rord, h_rel, (size_t)n_rel);
   std::vector<int32_t> r_head(T), r_tail(T), r_eid(T);
   std::vector<int64_t> rel_count((size_t)n_rel, 0);
   for (size_t i = 0; i < T; ++i) {

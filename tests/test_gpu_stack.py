@@ -126,3 +126,14 @@ def test_config3_user_item_entity_graph(tk):
                       threads=ref.default_threads(), sample_hi=nu + ni)
     ratio = stack.fp32_context_bytes() / stack.saved_context_bytes()
     assert 9.0 < ratio < 10.7          # 10.67x on E and H, less the uncompressed 1-bit masks
+
+
+def test_config4_at_one_hundredth_scale(tk):
+    # the scale-out case (20M entities x dim 128, 60 relations, 150M triplets, Zipf(1.05)
+    # tails, two layers, INT4 / group 128) with every count divided by 100
+    N, R, T = 200_000, 60, 1_500_000
+    head, rel, tail = gen.kg_triplets(N, R, T, seed=0, tail_zipf=1.05)
+    stack = run_stack(tk, N, R, head, rel, tail, [128, 128, 128], 4, 128, batch=4096,
+                      threads=ref.default_threads())
+    ratio = stack.fp32_context_bytes() / stack.saved_context_bytes()
+    assert 6.4 < ratio < 7.2           # 7.11x on E and H, less the 1-bit masks (6.5x overall)

@@ -587,18 +587,25 @@ __global__ __launch_bounds__(kThreads) void dense_bwd_kernel(Source srcH,
   }
 }
 
-// out[seg][j] = sum over p in [ptr[seg], ptr[seg+1]) of part[p * stride + j], in
-// ascending p (fixed order).  seg_ptr == nullptr: one segment [0, n_single).
-__global__ void reduce_segments_kernel(const float* __restrict__ part,
-                                       const int32_t* __restrict__ seg_ptr, int n_single,
-                                       int stride, float* __restrict__ out) {
+// out[seg][j] = sum over p in [ptr[seg], ptr[seg+1]) of part[p * stride + j].  Fixed
+// order: thread group k of 4 sums partials p0+k, p0+k+4, ... in double, the four group
+// sums are then added in order 0..3.  seg_ptr == nullptr: one segment [0, n_single).
+// Launch with 256 threads: 64 consecutive j per block.
+__global__ __launch_bounds__(256) void reduce_segments_kernel(const float* __restrict__ part,
+                                                              const int32_t* __restrict__ seg_ptr,
+                                                              int n_single, int stride,
+                                                              float* __restrict__ out) {
+  __shared__ double red[4][64];
   const int seg = blockIdx.y;
   const int p0 = seg_ptr ? seg_ptr[seg] : 0, p1 = seg_ptr ? seg_ptr[seg + 1] : n_single;
-  for (int j = blockIdx.x * blockDim.x + threadIdx.x; j < stride; j += gridDim.x * blockDim.x) {
-    double s = 0.0;   // thousands of partials of both signs: summed in double, rounded once
-    for (int p = p0; p < p1; ++p) s += (double)part[(size_t)p * stride + j];
-    out[(size_t)seg * stride + j] = (float)s;
-  }
+  const int j = blockIdx.x * 64 + (threadIdx.x & 63), k = threadIdx.x >> 6;
+  double s = 0.0;
+  if (j < stride)
+    for (int p = p0 + k; p < p1; p += 4) s += (double)part[(size_t)p * stride + j];
+  red[k][threadIdx.x & 63] = s;
+  __syncthreads();
+  if (k == 0 && j < stride)
+    out[(size_t)seg * stride + j] = (float)(((red[0][j & 63] + red[1][j & 63]) + red[2][j & 63]) + red[3][j & 63]);
 }
 
 // The edge stage accumulates grad_E in double: a hot tail sums 10^5 and more O(1)
@@ -962,7 +969,7 @@ tinykg_status bwd_impl(const tinykg_graph* g, const tinykg_saved* sv, const floa
     if ((rc = launch_status()) != TINYKG_OK) return rc;
     const int stride = d_out * D;
     ProfileScope prof("reduce_segments_kernel", st);
-    hipLaunchKernelGGL(reduce_segments_kernel, dim3((stride + 255) / 256, 1), dim3(256), 0, st, pW,
+    hipLaunchKernelGGL(reduce_segments_kernel, dim3((stride + 63) / 64, 1), dim3(256), 0, st, pW,
                        (const int32_t*)nullptr, grid, stride, gW);
     if ((rc = launch_status()) != TINYKG_OK) return rc;
   }
@@ -1016,10 +1023,10 @@ tinykg_status bwd_impl(const tinykg_graph* g, const tinykg_saved* sv, const floa
   }
   if (g->n_rel > 0) {
     ProfileScope prof("reduce_segments_kernel", st);
-    hipLaunchKernelGGL(reduce_segments_kernel, dim3((D * D + 255) / 256, g->n_rel), dim3(256), 0, st,
+    hipLaunchKernelGGL(reduce_segments_kernel, dim3((D * D + 63) / 64, g->n_rel), dim3(256), 0, st,
                        pWr, g->rel_chunk_ptr, 0, D * D, gWr);
     if ((rc = launch_status()) != TINYKG_OK) return rc;
-    hipLaunchKernelGGL(reduce_segments_kernel, dim3(1, g->n_rel), dim3(256), 0, st, per,
+    hipLaunchKernelGGL(reduce_segments_kernel, dim3((D + 63) / 64, g->n_rel), dim3(256), 0, st, per,
                        g->rel_chunk_ptr, 0, D, ger);
     if ((rc = launch_status()) != TINYKG_OK) return rc;
   }

@@ -77,6 +77,43 @@ __device__ __forceinline__ void mfma_block(const float* __restrict__ A, int lda,
   }
 }
 
+// Two 32x32 blocks that share their A operand (all three operands stored with k
+// contiguous): accA += W x T, accB += W x H.  The operands of 32 k-values per lane are
+// loaded with 128-bit LDS reads before the 2 x 32 MFMAs that consume them are issued, so
+// the matrix pipe is not stalled on LDS latency between instructions.
+template <int K>
+__device__ __forceinline__ void mfma_dual_kcont(const float* __restrict__ W, int ldw,
+                                                const float* __restrict__ T, const float* __restrict__ H,
+                                                int ld, floatx16& accA, floatx16& accB) {
+  const int lane = threadIdx.x & 63, r = lane & 31, hh = lane >> 5;
+  constexpr int KH = K / 2;                       // k-values per lane
+  constexpr int STEP = KH < 32 ? KH : 32;
+  const float* wp = W + r * ldw + hh * KH;
+  const float* tp = T + r * ld + hh * KH;
+  const float* hp = H + r * ld + hh * KH;
+#pragma unroll
+  for (int s0 = 0; s0 < KH; s0 += STEP) {
+    float4 w[STEP / 4], t[STEP / 4], h[STEP / 4];
+#pragma unroll
+    for (int i = 0; i < STEP / 4; ++i) {
+      w[i] = *reinterpret_cast<const float4*>(wp + s0 + 4 * i);
+      t[i] = *reinterpret_cast<const float4*>(tp + s0 + 4 * i);
+      h[i] = *reinterpret_cast<const float4*>(hp + s0 + 4 * i);
+    }
+#pragma unroll
+    for (int i = 0; i < STEP / 4; ++i) {
+      accA = __builtin_amdgcn_mfma_f32_32x32x2f32(w[i].x, t[i].x, accA, 0, 0, 0);
+      accB = __builtin_amdgcn_mfma_f32_32x32x2f32(w[i].x, h[i].x, accB, 0, 0, 0);
+      accA = __builtin_amdgcn_mfma_f32_32x32x2f32(w[i].y, t[i].y, accA, 0, 0, 0);
+      accB = __builtin_amdgcn_mfma_f32_32x32x2f32(w[i].y, h[i].y, accB, 0, 0, 0);
+      accA = __builtin_amdgcn_mfma_f32_32x32x2f32(w[i].z, t[i].z, accA, 0, 0, 0);
+      accB = __builtin_amdgcn_mfma_f32_32x32x2f32(w[i].z, h[i].z, accB, 0, 0, 0);
+      accA = __builtin_amdgcn_mfma_f32_32x32x2f32(w[i].w, t[i].w, accA, 0, 0, 0);
+      accB = __builtin_amdgcn_mfma_f32_32x32x2f32(w[i].w, h[i].w, accB, 0, 0, 0);
+    }
+  }
+}
+
 // Where a saved (or exact) activation matrix lives.  bits == 32: plain fp32.
 struct Source {
   const uint8_t* data;
@@ -154,8 +191,7 @@ __global__ __launch_bounds__(kThreads) void score_kernel(Source src, const float
     for (int blk = wave; blk < NCB * NEB; blk += 4) {
       const int cb = blk % NCB, eb = blk / NCB;
       floatx16 accA = {0}, accB = {0};
-      mfma_block<KCONT, KCONT>(Wr_s + cb * 32 * LD, LD, Et_s + eb * 32 * LD, LD, D, accA);
-      mfma_block<KCONT, KCONT>(Wr_s + cb * 32 * LD, LD, Eh_s + eb * 32 * LD, LD, D, accB);
+      mfma_dual_kcont<D>(Wr_s + cb * 32 * LD, LD, Et_s + eb * 32 * LD, Eh_s + eb * 32 * LD, LD, accA, accB);
       float p = 0.f;
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
@@ -690,8 +726,7 @@ __global__ __launch_bounds__(kThreads) void edge_bwd_kernel(
     for (int blk = wave; blk < NCB * NEB; blk += 4) {
       const int cb = blk % NCB, eb = blk / NCB;
       floatx16 accA = {0}, accB = {0};
-      mfma_block<KCONT, KCONT>(Wr_s + cb * 32 * LD, LD, Et_s + eb * 32 * LD, LD, D, accA);
-      mfma_block<KCONT, KCONT>(Wr_s + cb * 32 * LD, LD, Eh_s + eb * 32 * LD, LD, D, accB);
+      mfma_dual_kcont<D>(Wr_s + cb * 32 * LD, LD, Et_s + eb * 32 * LD, Eh_s + eb * 32 * LD, LD, accA, accB);
       const int e = eb * 32 + (lane & 31);
       const float g = gs_s[e];
 #pragma unroll

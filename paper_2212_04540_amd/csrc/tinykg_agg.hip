@@ -47,6 +47,16 @@ __device__ __forceinline__ int acc_row(int v, int lane) {
   return (v & 3) + 4 * (lane >> 5) + 8 * (v >> 2);
 }
 
+// tanh without branches: sign(x) * (1 - 2 / (exp(2|x|) + 1)) on the hardware exp2 / rcp
+// units.  Absolute error below 2e-7 for every x (the subtraction from 1 bounds it by
+// the error of the quotient), which is what the score s = a . tanh(b) and its
+// derivative 1 - tanh^2 need; exp overflow gives exactly +-1.
+__device__ __forceinline__ float fast_tanh(float x) {
+  const float e = __builtin_amdgcn_exp2f(fabsf(x) * 2.885390081777927f);   // exp(2|x|)
+  const float t = fmaf(-2.0f, __builtin_amdgcn_rcpf(e + 1.0f), 1.0f);
+  return copysignf(t, x);
+}
+
 template <int AM, int BM>
 __device__ __forceinline__ void mfma_block(const float* __restrict__ A, int lda,
                                            const float* __restrict__ B, int ldb, int K,
@@ -196,7 +206,7 @@ __global__ __launch_bounds__(kThreads) void score_kernel(Source src, const float
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
         const int c = cb * 32 + acc_row(v, lane);
-        p = fmaf(accA[v], tanhf(accB[v] + er_s[c]), p);
+        p = fmaf(accA[v], fast_tanh(accB[v] + er_s[c]), p);
       }
       part[(cb * 2 + (lane >> 5)) * TE + eb * 32 + (lane & 31)] = p;
     }
@@ -207,6 +217,151 @@ __global__ __launch_bounds__(kThreads) void score_kernel(Source src, const float
       for (int k = 0; k < NP; ++k) s += part[k * TE + tid];
       s_out[r_eid[start + t0 + tid]] = s;
     }
+  }
+}
+
+
+// ------------------------------------------------- scores, wave-independent form ----
+// Half of one activation row (D/2 consecutive elements) as a lane fetched it: raw
+// words plus the group's (min, scale); dequantised (Eq. 4) only when consumed, so a
+// prefetched row costs D/2 * bits / 32 registers.
+template <int D, int BITS>
+struct HalfRow {
+  static constexpr int KH = D / 2;
+  static constexpr int EB = BITS == 32 ? 32 : BITS;
+  static constexpr int NW = (KH * EB + 31) / 32;
+  uint32_t w[NW];
+  float z, s;
+
+  __device__ __forceinline__ void load(const Source& src, int64_t node, int hh) {
+    const int64_t f0 = node * D + hh * KH;   // first element; KH*EB bits, aligned to its size
+    if (BITS == 32) {
+      const float4* p = reinterpret_cast<const float4*>(src.data) + (f0 >> 2);
+#pragma unroll
+      for (int i = 0; i < KH / 4; ++i) {
+        const float4 v = p[i];
+        w[4 * i + 0] = __float_as_uint(v.x); w[4 * i + 1] = __float_as_uint(v.y);
+        w[4 * i + 2] = __float_as_uint(v.z); w[4 * i + 3] = __float_as_uint(v.w);
+      }
+      z = 0.f; s = 0.f;
+    } else {
+      const uint8_t* p = src.data + ((f0 * EB) >> 3);
+      if (KH * EB == 16) {
+        w[0] = *reinterpret_cast<const uint16_t*>(p);
+      } else if (NW == 1) {
+        w[0] = *reinterpret_cast<const uint32_t*>(p);
+      } else if (NW == 2) {
+        const uint2 v = *reinterpret_cast<const uint2*>(p);
+        w[0] = v.x; w[NW > 1 ? 1 : 0] = v.y;
+      } else {
+#pragma unroll
+        for (int i = 0; i < NW / 4; ++i) {
+          const uint4 v = reinterpret_cast<const uint4*>(p)[i];
+          w[(4 * i + 0) % NW] = v.x; w[(4 * i + 1) % NW] = v.y;
+          w[(4 * i + 2) % NW] = v.z; w[(4 * i + 3) % NW] = v.w;
+        }
+      }
+      const int64_t g = f0 >> (src.group_chunks_log2 + 2);
+      z = src.gmin[g]; s = src.gscale[g];
+    }
+  }
+  __device__ __forceinline__ float get(int i) const {
+    if (BITS == 32) return __uint_as_float(w[i % NW]);
+    constexpr uint32_t B = (1u << (EB & 31)) - 1u;
+    const uint32_t code = (w[((i * EB) >> 5) % NW] >> ((i * EB) & 31)) & B;
+    return fmaf((float)code, s, z);
+  }
+};
+
+// One wave owns 32 relation-order edges end to end: it fetches (and dequantises) the
+// two rows of each edge straight into MFMA operand registers -- lane l holds elements
+// [32*(l/32), +D/2) of the tail and head rows of edge l%32 -- multiplies them with all
+// of W_r (shared through LDS, the only shared state), and reduces a . tanh(b) inside
+// the wave.  No workgroup barrier after W_r is staged; the rows of the wave's next
+// 32 edges are in flight while the current ones are multiplied.  D = 32 or 64.
+template <int D, int BITS>
+__global__ __launch_bounds__(kThreads) void score_wave_kernel(Source src, const float* __restrict__ Wr,
+                                                              const float* __restrict__ er,
+                                                              const int32_t* __restrict__ r_head,
+                                                              const int32_t* __restrict__ r_tail,
+                                                              const int32_t* __restrict__ r_eid,
+                                                              ChunkList chunks, float* __restrict__ s_out) {
+  constexpr int LD = D + 4, LPR = D / 4, KH = D / 2, NCB = D / 32;
+  float* Wr_s = reinterpret_cast<float*>(smem_raw);
+  float* er_s = Wr_s + D * LD;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int ch = blockIdx.x;
+  const int rel = chunks.rel[ch], start = chunks.start[ch], count = chunks.count[ch];
+  const int r = lane & 31, hh = lane >> 5;
+  const int n_wt = (count + 31) >> 5;   // 32-edge wave tiles of this chunk
+  int wt = wave;
+
+  int t_nx = 0, h_nx = 0, e_nx = -1;    // edge of the tile whose rows are fetched next
+  auto load_idx = [&](int tile) {
+    const int row = tile * 32 + r;
+    t_nx = 0; h_nx = 0; e_nx = -1;      // past the end: node 0 (a valid row), no store
+    if (row < count) { const int pos = start + row; t_nx = r_tail[pos]; h_nx = r_head[pos]; e_nx = r_eid[pos]; }
+  };
+  // the first tile's rows are requested before W_r is staged, so both latencies overlap
+  HalfRow<D, BITS> nt, nh;
+  load_idx(wt);
+  nt.load(src, t_nx, hh);
+  nh.load(src, h_nx, hh);
+  int e_cur = e_nx;
+  if (wt + 4 < n_wt) load_idx(wt + 4);
+
+  const float4* Wg = reinterpret_cast<const float4*>(Wr + (size_t)rel * D * D);
+  for (int q = tid; q < D * LPR; q += kThreads)
+    *reinterpret_cast<float4*>(Wr_s + (q / LPR) * LD + (q % LPR) * 4) = Wg[q];
+  for (int c = tid; c < D; c += kThreads) er_s[c] = er[(size_t)rel * D + c];
+  __syncthreads();
+  if (wt >= n_wt) return;
+
+  for (; wt < n_wt; wt += 4) {
+    float tv[KH], hv[KH];
+#pragma unroll
+    for (int i = 0; i < KH; ++i) { tv[i] = nt.get(i); hv[i] = nh.get(i); }
+    const int eid = e_cur;
+    if (wt + 4 < n_wt) {                // rows of the next tile: in flight during the MFMAs
+      nt.load(src, t_nx, hh);
+      nh.load(src, h_nx, hh);
+      e_cur = e_nx;
+      if (wt + 8 < n_wt) load_idx(wt + 8);
+    }
+    floatx16 accA[NCB], accB[NCB];
+#pragma unroll
+    for (int cb = 0; cb < NCB; ++cb) { accA[cb] = floatx16{0}; accB[cb] = floatx16{0}; }
+    // W_r is re-read from LDS for every tile (the opaque zero keeps the compiler from
+    // parking all of it in registers, which would halve the waves per SIMD)
+    int wofs = 0;
+    asm volatile("" : "+v"(wofs));
+    const float* wrow = Wr_s + r * LD + hh * KH + wofs;
+#pragma unroll
+    for (int s0 = 0; s0 < KH; s0 += 4) {
+#pragma unroll
+      for (int cb = 0; cb < NCB; ++cb) {
+        const float4 w4 = *reinterpret_cast<const float4*>(wrow + cb * 32 * LD + s0);
+        accA[cb] = __builtin_amdgcn_mfma_f32_32x32x2f32(w4.x, tv[s0 + 0], accA[cb], 0, 0, 0);
+        accB[cb] = __builtin_amdgcn_mfma_f32_32x32x2f32(w4.x, hv[s0 + 0], accB[cb], 0, 0, 0);
+        accA[cb] = __builtin_amdgcn_mfma_f32_32x32x2f32(w4.y, tv[s0 + 1], accA[cb], 0, 0, 0);
+        accB[cb] = __builtin_amdgcn_mfma_f32_32x32x2f32(w4.y, hv[s0 + 1], accB[cb], 0, 0, 0);
+        accA[cb] = __builtin_amdgcn_mfma_f32_32x32x2f32(w4.z, tv[s0 + 2], accA[cb], 0, 0, 0);
+        accB[cb] = __builtin_amdgcn_mfma_f32_32x32x2f32(w4.z, hv[s0 + 2], accB[cb], 0, 0, 0);
+        accA[cb] = __builtin_amdgcn_mfma_f32_32x32x2f32(w4.w, tv[s0 + 3], accA[cb], 0, 0, 0);
+        accB[cb] = __builtin_amdgcn_mfma_f32_32x32x2f32(w4.w, hv[s0 + 3], accB[cb], 0, 0, 0);
+      }
+    }
+    float p = 0.f;
+#pragma unroll
+    for (int cb = 0; cb < NCB; ++cb) {
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int c = cb * 32 + acc_row(v, lane);
+        p = fmaf(accA[cb][v], fast_tanh(accB[cb][v] + er_s[c]), p);
+      }
+    }
+    p += __shfl_xor(p, 32);
+    if (hh == 0 && eid >= 0) s_out[eid] = p;
   }
 }
 
@@ -735,7 +890,7 @@ __global__ __launch_bounds__(kThreads) void edge_bwd_kernel(
         float da[4], db[4];
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
-          const float vv = tanhf(accB[4 * vg + u] + er_s[c0 + u]);
+          const float vv = fast_tanh(accB[4 * vg + u] + er_s[c0 + u]);
           da[u] = g * vv;
           db[u] = g * accA[4 * vg + u] * (1.f - vv * vv);
         }
@@ -900,16 +1055,25 @@ template <int D, int BITS>
 tinykg_status launch_score(const tinykg_graph* g, Source src, const float* Wr, const float* er,
                            float* s, hipStream_t st) {
   if (g->n_chunks == 0) return TINYKG_OK;
-  constexpr int TE = D == 128 ? 32 : 64;
   constexpr int LD = D + 4;
-  const size_t smem = (size_t)(D * LD + 2 * TE * LD + D + (D / 32) * 2 * TE) * 4;
-  auto kern = score_kernel<D, TE, BITS>;
-  tinykg_status rc = set_smem(kern, smem);
-  if (rc != TINYKG_OK) return rc;
   ChunkList cl{g->chunk_rel, g->chunk_start, g->chunk_count};
   ProfileScope prof("score_kernel", st);
-  hipLaunchKernelGGL(kern, dim3(g->n_chunks), dim3(kThreads), smem, st, src, Wr, er, g->r_head,
-                     g->r_tail, g->r_eid, cl, s);
+  if constexpr (D <= 64) {
+    const size_t smem = (size_t)(D * LD + D) * 4;
+    auto kern = score_wave_kernel<D, BITS>;
+    tinykg_status rc = set_smem(kern, smem);
+    if (rc != TINYKG_OK) return rc;
+    hipLaunchKernelGGL(kern, dim3(g->n_chunks), dim3(kThreads), smem, st, src, Wr, er, g->r_head,
+                       g->r_tail, g->r_eid, cl, s);
+  } else {
+    constexpr int TE = 32;
+    const size_t smem = (size_t)(D * LD + 2 * TE * LD + D + (D / 32) * 2 * TE) * 4;
+    auto kern = score_kernel<D, TE, BITS>;
+    tinykg_status rc = set_smem(kern, smem);
+    if (rc != TINYKG_OK) return rc;
+    hipLaunchKernelGGL(kern, dim3(g->n_chunks), dim3(kThreads), smem, st, src, Wr, er, g->r_head,
+                       g->r_tail, g->r_eid, cl, s);
+  }
   return launch_status();
 }
 

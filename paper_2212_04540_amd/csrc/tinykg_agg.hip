@@ -984,6 +984,314 @@ __global__ __launch_bounds__(kThreads) void edge_bwd_kernel(
   if (tid < D) part_er[(size_t)ch * D + tid] = er_acc;
 }
 
+// ------------------------------- edge-level backward, wave-independent form ----
+// D = 32 or 64.  A workgroup of eight waves shares only W_r and e_r; every wave owns
+// 32-edge tiles of the chunk end to end, with two wave-private LDS buffers X, Y of
+// [32][D+4] floats that are reused three times per tile:
+//   1. X, Y <- e_hat_t, e_hat_h rows (also kept in registers as MFMA operands)
+//      a^T, b^T [e][c] = rows x W_r^T            (operands: registers x W_r in LDS)
+//      grad_a, grad_b in place; grad_e_r column sums stay inside a lane
+//      grad_W_r[c][i] += grad_a^T e_t + grad_b^T e_h   (registers x X, Y)
+//   2. X, Y <- grad_a, grad_b
+//      Pt, Ph [e][i] = grad_a W_r, grad_b W_r    (X, Y x W_r in LDS)
+//   3. X, Y <- Pt, Ph; rows walked in tail order / head order, equal neighbours summed
+//      in double, one fp64 atomic per run and column.
+// The transposed form of step 1 (edge index on the accumulator rows, channel on the
+// lanes) is what lets grad_a / grad_b feed the grad_W_r products without leaving the
+// registers.  There is no workgroup barrier between staging W_r and the final fixed-order
+// combination of the eight waves' grad_W_r / grad_e_r partial sums.
+constexpr int kEdgeWaves = 8;
+
+template <int D>
+constexpr int edge_wave_region() { return 2 * 32 * (D + 4) + 5 * 32; }   // floats per wave
+
+// Phase boundary inside a wave that passes data between its lanes through LDS: the
+// LDS queue of a wave is in order, so no hardware wait is needed; the compiler must
+// only keep the phases apart (which also bounds how many loads it hoists at once).
+__device__ __forceinline__ void phase_fence() {
+  __builtin_amdgcn_sched_barrier(0);
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_sched_barrier(0);
+}
+
+template <int D, int BITS>
+__global__ __launch_bounds__(kEdgeWaves * 64) void edge_wave_kernel(
+    Source src, const float* __restrict__ Wr, const float* __restrict__ er,
+    const int32_t* __restrict__ r_head, const int32_t* __restrict__ r_tail,
+    const int32_t* __restrict__ r_eid, const uint8_t* __restrict__ r_hperm, ChunkList chunks,
+    const float* __restrict__ pi, const float* __restrict__ gs, const float* __restrict__ gH,
+    double* __restrict__ gE, float* __restrict__ part_Wr, float* __restrict__ part_er) {
+  constexpr int LD = D + 4, LPR = D / 4, KH = D / 2, NB = D / 32, NW = kEdgeWaves;
+  constexpr int NT = NW * 64, BUF = 32 * LD, REGION = edge_wave_region<D>();
+  constexpr int NQ = 64 / D, RP = 32 / NQ;        // scatter: row parts of a wave
+  constexpr bool PF = BITS != 32;                 // prefetch the next tile's rows
+  float* Wr_s = reinterpret_cast<float*>(smem_raw);
+  float* er_s = Wr_s + D * LD;
+  float* regions = er_s + D;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  float* X_s = regions + wave * REGION;
+  float* Y_s = X_s + BUF;
+  float* gs_s = Y_s + BUF;
+  float* pi_s = gs_s + 32;
+  int* tl_s = reinterpret_cast<int*>(pi_s + 32);
+  int* hd_s = tl_s + 32;
+  int* hp_s = hd_s + 32;
+
+  const int ch = blockIdx.x;
+  const int rel = chunks.rel[ch], start = chunks.start[ch], count = chunks.count[ch];
+  const int r = lane & 31, hh = lane >> 5;
+  const int n_wt = (count + 31) >> 5;
+  int wt = wave;
+
+  int t_nx = 0, h_nx = 0, e_nx = -1, hp_nx = 0;
+  auto load_idx = [&](int tile) {
+    const int row = tile * 32 + r;
+    t_nx = 0; h_nx = 0; e_nx = -1; hp_nx = 0;   // past the end: node 0 (a valid row), weight 0
+    if (row < count) {
+      const int pos = start + row;
+      t_nx = r_tail[pos]; h_nx = r_head[pos]; e_nx = r_eid[pos]; hp_nx = r_hperm[pos];
+    }
+  };
+  HalfRow<D, BITS> nt, nh;
+  float g_ld = 0.f, p_ld = 0.f;
+  int t_ld = 0, h_ld = 0, hp_ld = 0;
+  auto load_rows = [&]() {
+    nt.load(src, t_nx, hh);
+    nh.load(src, h_nx, hh);
+    g_ld = 0.f; p_ld = 0.f;
+    if (e_nx >= 0) { g_ld = gs[e_nx]; p_ld = pi[e_nx]; }
+    t_ld = t_nx; h_ld = h_nx; hp_ld = hp_nx;
+  };
+  if (PF) {
+    load_idx(wt);
+    load_rows();
+    if (wt + NW < n_wt) load_idx(wt + NW);
+  }
+
+  const float4* Wg = reinterpret_cast<const float4*>(Wr + (size_t)rel * D * D);
+  for (int q = tid; q < D * LPR; q += NT)
+    *reinterpret_cast<float4*>(Wr_s + (q / LPR) * LD + (q % LPR) * 4) = Wg[q];
+  for (int c = tid; c < D; c += NT) er_s[c] = er[(size_t)rel * D + c];
+  __syncthreads();
+
+  float er_c[NB], er_acc[NB];
+#pragma unroll
+  for (int cb = 0; cb < NB; ++cb) { er_c[cb] = er_s[cb * 32 + r]; er_acc[cb] = 0.f; }
+  floatx16 accW[NB * NB];
+#pragma unroll
+  for (int j = 0; j < NB * NB; ++j) accW[j] = floatx16{0};
+
+  for (; wt < n_wt; wt += NW) {
+    if (!PF) { load_idx(wt); load_rows(); }
+    const int nrow = min(32, count - wt * 32);
+    if (hh == 0) { gs_s[r] = g_ld; pi_s[r] = p_ld; tl_s[r] = t_ld; hd_s[r] = h_ld; hp_s[r] = hp_ld; }
+#pragma unroll
+    for (int i = 0; i < KH; i += 4) {
+      *reinterpret_cast<float4*>(X_s + r * LD + hh * KH + i) =
+          make_float4(nt.get(i), nt.get(i + 1), nt.get(i + 2), nt.get(i + 3));
+      *reinterpret_cast<float4*>(Y_s + r * LD + hh * KH + i) =
+          make_float4(nh.get(i), nh.get(i + 1), nh.get(i + 2), nh.get(i + 3));
+    }
+    if (PF && wt + NW < n_wt) {         // rows of the wave's next tile: in flight during the MFMAs
+      load_rows();
+      if (wt + 2 * NW < n_wt) load_idx(wt + 2 * NW);
+    }
+    phase_fence();
+
+    // ---- 1a. a^T, b^T: accumulator row = edge, lane column = channel
+    floatx16 accA[NB], accB[NB];
+#pragma unroll
+    for (int cb = 0; cb < NB; ++cb) { accA[cb] = floatx16{0}; accB[cb] = floatx16{0}; }
+    {
+      int wofs = 0;
+      asm volatile("" : "+v"(wofs));    // W_r is re-read from LDS, never parked in registers
+      const float* wrow = Wr_s + r * LD + hh * KH + wofs;
+      const float* trow = X_s + r * LD + hh * KH + wofs;
+      const float* hrow = Y_s + r * LD + hh * KH + wofs;
+#pragma unroll
+      for (int s0 = 0; s0 < KH; s0 += 4) {
+        const float4 t4 = *reinterpret_cast<const float4*>(trow + s0);
+        const float4 h4 = *reinterpret_cast<const float4*>(hrow + s0);
+#pragma unroll
+        for (int cb = 0; cb < NB; ++cb) {
+          const float4 w4 = *reinterpret_cast<const float4*>(wrow + cb * 32 * LD + s0);
+          accA[cb] = __builtin_amdgcn_mfma_f32_32x32x2f32(t4.x, w4.x, accA[cb], 0, 0, 0);
+          accB[cb] = __builtin_amdgcn_mfma_f32_32x32x2f32(h4.x, w4.x, accB[cb], 0, 0, 0);
+          accA[cb] = __builtin_amdgcn_mfma_f32_32x32x2f32(t4.y, w4.y, accA[cb], 0, 0, 0);
+          accB[cb] = __builtin_amdgcn_mfma_f32_32x32x2f32(h4.y, w4.y, accB[cb], 0, 0, 0);
+          accA[cb] = __builtin_amdgcn_mfma_f32_32x32x2f32(t4.z, w4.z, accA[cb], 0, 0, 0);
+          accB[cb] = __builtin_amdgcn_mfma_f32_32x32x2f32(h4.z, w4.z, accB[cb], 0, 0, 0);
+          accA[cb] = __builtin_amdgcn_mfma_f32_32x32x2f32(t4.w, w4.w, accA[cb], 0, 0, 0);
+          accB[cb] = __builtin_amdgcn_mfma_f32_32x32x2f32(h4.w, w4.w, accB[cb], 0, 0, 0);
+        }
+      }
+    }
+    phase_fence();
+    // ---- 1b. grad_a = gs tanh(b), grad_b = gs a (1 - tanh(b)^2), in place
+    {
+      float er_t[NB];
+#pragma unroll
+      for (int cb = 0; cb < NB; ++cb) er_t[cb] = 0.f;
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const float4 g4 = *reinterpret_cast<const float4*>(gs_s + 8 * q + 4 * hh);   // edges of registers 4q..4q+3
+        const float gq[4] = {g4.x, g4.y, g4.z, g4.w};
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+#pragma unroll
+          for (int cb = 0; cb < NB; ++cb) {
+            const float vv = fast_tanh(accB[cb][4 * q + u] + er_c[cb]);
+            const float db = gq[u] * accA[cb][4 * q + u] * (1.f - vv * vv);
+            accA[cb][4 * q + u] = gq[u] * vv;
+            accB[cb][4 * q + u] = db;
+            er_t[cb] += db;
+          }
+        }
+      }
+#pragma unroll
+      for (int cb = 0; cb < NB; ++cb) er_acc[cb] += er_t[cb];
+    }
+    phase_fence();
+    // ---- 1c. grad_W_r[c][i] += sum_e grad_a[e][c] e_t[e][i] + grad_b[e][c] e_h[e][i]
+    //      (two-level sum: a fresh accumulator per tile keeps the fp32 running sum short)
+#pragma unroll
+    for (int ib = 0; ib < NB; ++ib) {
+      floatx16 accT[NB];
+#pragma unroll
+      for (int cb = 0; cb < NB; ++cb) accT[cb] = floatx16{0};
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int e = (v & 3) + 8 * (v >> 2) + 4 * hh;
+        const float bt = X_s[e * LD + ib * 32 + r];
+        const float bh = Y_s[e * LD + ib * 32 + r];
+#pragma unroll
+        for (int cb = 0; cb < NB; ++cb) {
+          accT[cb] = __builtin_amdgcn_mfma_f32_32x32x2f32(accA[cb][v], bt, accT[cb], 0, 0, 0);
+          accT[cb] = __builtin_amdgcn_mfma_f32_32x32x2f32(accB[cb][v], bh, accT[cb], 0, 0, 0);
+        }
+      }
+#pragma unroll
+      for (int cb = 0; cb < NB; ++cb) accW[cb * NB + ib] += accT[cb];
+    }
+    phase_fence();
+    // ---- 2. X, Y <- grad_a, grad_b as [e][c]
+#pragma unroll
+    for (int cb = 0; cb < NB; ++cb) {
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int e = acc_row(v, lane);
+        X_s[e * LD + cb * 32 + r] = accA[cb][v];
+        Y_s[e * LD + cb * 32 + r] = accB[cb][v];
+      }
+    }
+    // grad_H rows of the tile's heads, weighted by pi (the e_t term of H_h): requested
+    // here so that they arrive while the next products run
+    float ghv[RP];
+    {
+      const int i = lane % D, e0 = (lane / D) * RP;
+#pragma unroll
+      for (int k = 0; k < RP; ++k) ghv[k] = gH[(int64_t)hd_s[e0 + k] * D + i];
+    }
+    phase_fence();
+    // Pt, Ph [e][i] = sum_c grad_a[e][c] W_r[c][i]; half hh walks c = (s&7) + 16 (s>>3) + 8 hh,
+    // which keeps the two halves of a W_r read in different LDS banks
+    floatx16 accPt[NB], accPh[NB];
+#pragma unroll
+    for (int ib = 0; ib < NB; ++ib) { accPt[ib] = floatx16{0}; accPh[ib] = floatx16{0}; }
+    {
+      int wofs = 0;
+      asm volatile("" : "+v"(wofs));
+      const float* wcol = Wr_s + r + wofs;
+#pragma unroll
+      for (int s0 = 0; s0 < KH; s0 += 4) {
+        const int c0 = (s0 & 7) + 16 * (s0 >> 3) + 8 * hh;
+        const float4 a4 = *reinterpret_cast<const float4*>(X_s + r * LD + c0);
+        const float4 b4 = *reinterpret_cast<const float4*>(Y_s + r * LD + c0);
+        const float av[4] = {a4.x, a4.y, a4.z, a4.w}, bv[4] = {b4.x, b4.y, b4.z, b4.w};
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+#pragma unroll
+          for (int ib = 0; ib < NB; ++ib) {
+            const float w = wcol[(c0 + u) * LD + ib * 32];
+            accPt[ib] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[u], w, accPt[ib], 0, 0, 0);
+            accPh[ib] = __builtin_amdgcn_mfma_f32_32x32x2f32(bv[u], w, accPh[ib], 0, 0, 0);
+          }
+        }
+      }
+    }
+    phase_fence();
+    // ---- 3. X, Y <- Pt, Ph as [e][i]; scatter
+#pragma unroll
+    for (int ib = 0; ib < NB; ++ib) {
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int e = acc_row(v, lane);
+        X_s[e * LD + ib * 32 + r] = accPt[ib][v];
+        Y_s[e * LD + ib * 32 + r] = accPh[ib][v];
+      }
+    }
+    phase_fence();
+    {
+      // rows of one tail are adjacent (the chunk is sorted by tail) and rows of one head
+      // are adjacent in the tile's head order: runs are summed before the atomics
+      const int i = lane % D, e0 = (lane / D) * RP;
+      const int e_end = min(e0 + RP, nrow);
+      double run = 0.0;
+#pragma unroll
+      for (int k = 0; k < RP; ++k) {
+        const int e = e0 + k;
+        if (e < e_end) {
+          const int t = tl_s[e];
+          run += (double)fmaf(pi_s[e], ghv[k], X_s[e * LD + i]);
+          if (e + 1 == e_end || tl_s[e + 1] != t) {
+            unsafeAtomicAdd(gE + (int64_t)t * D + i, run);
+            run = 0.0;
+          }
+        }
+      }
+      for (int k = e0; k < e_end; ++k) {
+        const int e = hp_s[k], h = hd_s[e];
+        run += (double)Y_s[e * LD + i];
+        if (k + 1 == e_end || hd_s[hp_s[k + 1]] != h) {
+          unsafeAtomicAdd(gE + (int64_t)h * D + i, run);
+          run = 0.0;
+        }
+      }
+    }
+    phase_fence();   // the next tile overwrites X, Y and the index arrays
+  }
+
+  // fixed-order combination of the eight waves' partial sums
+  {
+    float* mine = regions + wave * REGION;
+#pragma unroll
+    for (int j = 0; j < NB * NB; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) mine[(j * 16 + v) * 64 + lane] = accW[j][v];
+#pragma unroll
+    for (int cb = 0; cb < NB; ++cb) {
+      const float both = er_acc[cb] + __shfl_xor(er_acc[cb], 32);
+      if (hh == 0) mine[NB * NB * 1024 + cb * 32 + r] = both;
+    }
+  }
+  __syncthreads();
+  float* outW = part_Wr + (size_t)ch * D * D;
+  for (int f = tid; f < D * D; f += NT) {
+    float sum = 0.f;
+#pragma unroll
+    for (int w = 0; w < NW; ++w) sum += regions[w * REGION + f];
+    const int l = f & 63, v = (f >> 6) & 15, j = f >> 10;
+    const int cb = j / NB, ib = j % NB;
+    outW[(cb * 32 + acc_row(v, l)) * D + ib * 32 + (l & 31)] = sum;
+  }
+  if (tid < D) {
+    float sum = 0.f;
+#pragma unroll
+    for (int w = 0; w < NW; ++w) sum += regions[w * REGION + NB * NB * 1024 + tid];
+    part_er[(size_t)ch * D + tid] = sum;
+  }
+}
+
 // ------------------------------------------------------------- host helpers ----
 size_t align256(size_t b) { return (b + 255) & ~(size_t)255; }
 
@@ -1205,14 +1513,23 @@ tinykg_status bwd_impl(const tinykg_graph* g, const tinykg_saved* sv, const floa
       hipLaunchKernelGGL(heavy_part3_kernel, gs_grid, dim3(kThreads), 0, st, hl, pc, pi, gs);
       if ((rc = launch_status()) != TINYKG_OK) return rc;
     }
-    const size_t smem = (size_t)(D * LD + 4 * TE * LD + D + 5 * TE) * 4;
-    auto kern = edge_bwd_kernel<D, TE, BITS>;
-    if ((rc = set_smem(kern, smem)) != TINYKG_OK) return rc;
     ChunkList cl{g->chunk_rel, g->chunk_start, g->chunk_count};
-    ProfileScope prof("edge_bwd_kernel", st);
-    hipLaunchKernelGGL(kern, dim3(g->n_chunks), dim3(kThreads), smem, st, srcE, Wr, er, g->r_head,
-                       g->r_tail, g->r_eid, TE == 64 ? g->r_hperm64 : g->r_hperm32, cl, pi, gs, gH, acc,
-                       pWr, per);
+    if constexpr (D <= 64) {
+      const size_t smem = (size_t)(D * LD + D + kEdgeWaves * edge_wave_region<D>()) * 4;
+      auto kern = edge_wave_kernel<D, BITS>;
+      if ((rc = set_smem(kern, smem)) != TINYKG_OK) return rc;
+      ProfileScope prof("edge_bwd_kernel", st);
+      hipLaunchKernelGGL(kern, dim3(g->n_chunks), dim3(kEdgeWaves * 64), smem, st, srcE, Wr, er,
+                         g->r_head, g->r_tail, g->r_eid, g->r_hperm32, cl, pi, gs, gH, acc, pWr, per);
+    } else {
+      const size_t smem = (size_t)(D * LD + 4 * TE * LD + D + 5 * TE) * 4;
+      auto kern = edge_bwd_kernel<D, TE, BITS>;
+      if ((rc = set_smem(kern, smem)) != TINYKG_OK) return rc;
+      ProfileScope prof("edge_bwd_kernel", st);
+      hipLaunchKernelGGL(kern, dim3(g->n_chunks), dim3(kThreads), smem, st, srcE, Wr, er, g->r_head,
+                         g->r_tail, g->r_eid, TE == 64 ? g->r_hperm64 : g->r_hperm32, cl, pi, gs, gH,
+                         acc, pWr, per);
+    }
     if ((rc = launch_status()) != TINYKG_OK) return rc;
   }
   if (N > 0) {

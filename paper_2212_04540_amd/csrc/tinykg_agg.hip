@@ -1003,7 +1003,7 @@ __global__ __launch_bounds__(kThreads) void edge_bwd_kernel(
 constexpr int kEdgeWaves = 8;
 
 template <int D>
-constexpr int edge_wave_region() { return 2 * 32 * (D + 4) + 5 * 32; }   // floats per wave
+constexpr int edge_wave_region() { return 2 * 32 * (D + 4) + 6 * 32; }   // floats per wave
 
 // Phase boundary inside a wave that passes data between its lanes through LDS: the
 // LDS queue of a wave is in order, so no hardware wait is needed; the compiler must
@@ -1033,9 +1033,10 @@ __global__ __launch_bounds__(kEdgeWaves * 64) void edge_wave_kernel(
   float* Y_s = X_s + BUF;
   float* gs_s = Y_s + BUF;
   float* pi_s = gs_s + 32;
-  int* tl_s = reinterpret_cast<int*>(pi_s + 32);
-  int* hd_s = tl_s + 32;
-  int* hp_s = hd_s + 32;
+  int* tl_s = reinterpret_cast<int*>(pi_s + 32);   // tail of row e; sign bit: a tail run ends here
+  int* hd_s = tl_s + 32;                           // head of row e
+  int* hp_s = hd_s + 32;                           // row of head-order rank k
+  int* hr_s = hp_s + 32;                           // head of rank k; sign bit: a head run ends here
 
   const int ch = blockIdx.x;
   const int rel = chunks.rel[ch], start = chunks.start[ch], count = chunks.count[ch];
@@ -1084,7 +1085,20 @@ __global__ __launch_bounds__(kEdgeWaves * 64) void edge_wave_kernel(
   for (; wt < n_wt; wt += NW) {
     if (!PF) { load_idx(wt); load_rows(); }
     const int nrow = min(32, count - wt * 32);
-    if (hh == 0) { gs_s[r] = g_ld; pi_s[r] = p_ld; tl_s[r] = t_ld; hd_s[r] = h_ld; hp_s[r] = hp_ld; }
+    {
+      // where the scatter has to flush its running sums: at the last row of a run of
+      // equal tails (rows are in tail order) resp. equal heads (ranks are in head order),
+      // at the end of a lane's row part and at the tile's last row
+      const int h_rank = __shfl(h_ld, hp_ld);                   // head of rank r
+      const int t_next = __shfl_down(t_ld, 1), h_next = __shfl_down(h_rank, 1);
+      const bool stop = r + 1 == nrow || (r + 1) % RP == 0;
+      const int t_flag = (r < nrow && (stop || t_next != t_ld)) ? (int)0x80000000 : 0;
+      const int h_flag = (r < nrow && (stop || h_next != h_rank)) ? (int)0x80000000 : 0;
+      if (hh == 0) {
+        gs_s[r] = g_ld; pi_s[r] = p_ld; hd_s[r] = h_ld; hp_s[r] = hp_ld;
+        tl_s[r] = t_ld | t_flag; hr_s[r] = h_rank | h_flag;
+      }
+    }
 #pragma unroll
     for (int i = 0; i < KH; i += 4) {
       *reinterpret_cast<float4*>(X_s + r * LD + hh * KH + i) =
@@ -1154,24 +1168,44 @@ __global__ __launch_bounds__(kEdgeWaves * 64) void edge_wave_kernel(
     phase_fence();
     // ---- 1c. grad_W_r[c][i] += sum_e grad_a[e][c] e_t[e][i] + grad_b[e][c] e_h[e][i]
     //      (two-level sum: a fresh accumulator per tile keeps the fp32 running sum short)
+    //      The operands of four accumulator registers (eight edges) are fetched from LDS
+    //      while the products of the previous four run; the scheduling fences keep the
+    //      compiler from fetching all of them at once, which would not fit the registers.
 #pragma unroll
     for (int ib = 0; ib < NB; ++ib) {
       floatx16 accT[NB];
 #pragma unroll
       for (int cb = 0; cb < NB; ++cb) accT[cb] = floatx16{0};
+      float bt[2][4], bh[2][4];
+      auto fetch = [&](int q, float* t4, float* h4) {
 #pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const int e = (v & 3) + 8 * (v >> 2) + 4 * hh;
-        const float bt = X_s[e * LD + ib * 32 + r];
-        const float bh = Y_s[e * LD + ib * 32 + r];
-#pragma unroll
-        for (int cb = 0; cb < NB; ++cb) {
-          accT[cb] = __builtin_amdgcn_mfma_f32_32x32x2f32(accA[cb][v], bt, accT[cb], 0, 0, 0);
-          accT[cb] = __builtin_amdgcn_mfma_f32_32x32x2f32(accB[cb][v], bh, accT[cb], 0, 0, 0);
+        for (int u = 0; u < 4; ++u) {
+          const int e = u + 8 * q + 4 * hh;          // = acc_row(4 q + u, lane)
+          t4[u] = X_s[e * LD + ib * 32 + r];
+          h4[u] = Y_s[e * LD + ib * 32 + r];
         }
+      };
+      fetch(0, bt[0], bh[0]);
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        if (q < 3) fetch(q + 1, bt[(q + 1) & 1], bh[(q + 1) & 1]);
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+#pragma unroll
+          for (int cb = 0; cb < NB; ++cb) {
+            accT[cb] = __builtin_amdgcn_mfma_f32_32x32x2f32(accA[cb][4 * q + u], bt[q & 1][u], accT[cb], 0, 0, 0);
+            accT[cb] = __builtin_amdgcn_mfma_f32_32x32x2f32(accB[cb][4 * q + u], bh[q & 1][u], accT[cb], 0, 0, 0);
+          }
+        }
+        __builtin_amdgcn_sched_barrier(0);
       }
 #pragma unroll
-      for (int cb = 0; cb < NB; ++cb) accW[cb * NB + ib] += accT[cb];
+      for (int cb = 0; cb < NB; ++cb) {
+        accW[cb * NB + ib] += accT[cb];
+        // pins the addition here: sunk to the end of the loop body it would keep the
+        // tile's accumulators alive through the scatter
+        asm volatile("" : "+v"(accW[cb * NB + ib]));
+      }
     }
     phase_fence();
     // ---- 2. X, Y <- grad_a, grad_b as [e][c]
@@ -1184,78 +1218,79 @@ __global__ __launch_bounds__(kEdgeWaves * 64) void edge_wave_kernel(
         Y_s[e * LD + cb * 32 + r] = accB[cb][v];
       }
     }
-    // grad_H rows of the tile's heads, weighted by pi (the e_t term of H_h): requested
-    // here so that they arrive while the next products run
+    // grad_H rows of the tile's heads (the e_t term of H_h): requested here so that they
+    // arrive while the next products run
+    const int si = lane % D, se0 = (lane / D) * RP;   // scatter: this lane's column and rows
     float ghv[RP];
-    {
-      const int i = lane % D, e0 = (lane / D) * RP;
 #pragma unroll
-      for (int k = 0; k < RP; ++k) ghv[k] = gH[(int64_t)hd_s[e0 + k] * D + i];
-    }
-    phase_fence();
-    // Pt, Ph [e][i] = sum_c grad_a[e][c] W_r[c][i]; half hh walks c = (s&7) + 16 (s>>3) + 8 hh,
-    // which keeps the two halves of a W_r read in different LDS banks
-    floatx16 accPt[NB], accPh[NB];
+    for (int k = 0; k < RP; ++k) ghv[k] = gH[(int64_t)hd_s[se0 + k] * D + si];
+    // with D == 64 a row is the whole wave and its flag is uniform: a scalar branch
+    auto flush_here = [](int flagged) {
+      return (D == 64 ? __builtin_amdgcn_readfirstlane(flagged) : flagged) < 0;
+    };
+    // P[e][i] = sum_c G[e][c] W_r[c][i] for G = grad_a (tails), then grad_b (heads); half hh
+    // walks c = (s&7) + 16 (s>>3) + 8 hh, which keeps the two halves of a W_r read in
+    // different LDS banks.  Then P goes back to the same buffer as [e][i] and its rows are
+    // walked in tail order resp. head order: every LDS read is independent of the running
+    // sum, a run inside a tile has at most 32 terms and is summed in fp32, and one fp64
+    // atomic per run and column leaves the wave.  Rows past the end of the chunk carry
+    // exact zeros (their weights gs, pi are 0) and no flag.
 #pragma unroll
-    for (int ib = 0; ib < NB; ++ib) { accPt[ib] = floatx16{0}; accPh[ib] = floatx16{0}; }
-    {
-      int wofs = 0;
-      asm volatile("" : "+v"(wofs));
-      const float* wcol = Wr_s + r + wofs;
+    for (int side = 0; side < 2; ++side) {
+      float* P_s = side == 0 ? X_s : Y_s;
+      phase_fence();
+      floatx16 accP[NB];
 #pragma unroll
-      for (int s0 = 0; s0 < KH; s0 += 4) {
-        const int c0 = (s0 & 7) + 16 * (s0 >> 3) + 8 * hh;
-        const float4 a4 = *reinterpret_cast<const float4*>(X_s + r * LD + c0);
-        const float4 b4 = *reinterpret_cast<const float4*>(Y_s + r * LD + c0);
-        const float av[4] = {a4.x, a4.y, a4.z, a4.w}, bv[4] = {b4.x, b4.y, b4.z, b4.w};
+      for (int ib = 0; ib < NB; ++ib) accP[ib] = floatx16{0};
+      {
+        int wofs = 0;
+        asm volatile("" : "+v"(wofs));
+        const float* wcol = Wr_s + r + wofs;
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
+        for (int s0 = 0; s0 < KH; s0 += 4) {
+          const int c0 = (s0 & 7) + 16 * (s0 >> 3) + 8 * hh;
+          const float4 a4 = *reinterpret_cast<const float4*>(P_s + r * LD + c0);
+          const float av[4] = {a4.x, a4.y, a4.z, a4.w};
 #pragma unroll
-          for (int ib = 0; ib < NB; ++ib) {
-            const float w = wcol[(c0 + u) * LD + ib * 32];
-            accPt[ib] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[u], w, accPt[ib], 0, 0, 0);
-            accPh[ib] = __builtin_amdgcn_mfma_f32_32x32x2f32(bv[u], w, accPh[ib], 0, 0, 0);
+          for (int u = 0; u < 4; ++u) {
+#pragma unroll
+            for (int ib = 0; ib < NB; ++ib)
+              accP[ib] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[u], wcol[(c0 + u) * LD + ib * 32], accP[ib], 0, 0, 0);
           }
         }
       }
-    }
-    phase_fence();
-    // ---- 3. X, Y <- Pt, Ph as [e][i]; scatter
+      phase_fence();
 #pragma unroll
-    for (int ib = 0; ib < NB; ++ib) {
+      for (int ib = 0; ib < NB; ++ib) {
 #pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const int e = acc_row(v, lane);
-        X_s[e * LD + ib * 32 + r] = accPt[ib][v];
-        Y_s[e * LD + ib * 32 + r] = accPh[ib][v];
+        for (int v = 0; v < 16; ++v) P_s[acc_row(v, lane) * LD + ib * 32 + r] = accP[ib][v];
       }
-    }
-    phase_fence();
-    {
-      // rows of one tail are adjacent (the chunk is sorted by tail) and rows of one head
-      // are adjacent in the tile's head order: runs are summed before the atomics
-      const int i = lane % D, e0 = (lane / D) * RP;
-      const int e_end = min(e0 + RP, nrow);
-      double run = 0.0;
+      phase_fence();
+      constexpr int RB = RP < 16 ? RP : 16;        // rows whose LDS reads are issued together
+      float run = 0.f;
 #pragma unroll
-      for (int k = 0; k < RP; ++k) {
-        const int e = e0 + k;
-        if (e < e_end) {
-          const int t = tl_s[e];
-          run += (double)fmaf(pi_s[e], ghv[k], X_s[e * LD + i]);
-          if (e + 1 == e_end || tl_s[e + 1] != t) {
-            unsafeAtomicAdd(gE + (int64_t)t * D + i, run);
-            run = 0.0;
+      for (int k0 = 0; k0 < RP; k0 += RB) {
+        int node[RB];
+        float val[RB];
+#pragma unroll
+        for (int k = 0; k < RB; ++k) {
+          if (side == 0) {
+            node[k] = tl_s[se0 + k0 + k];
+            val[k] = fmaf(pi_s[se0 + k0 + k], ghv[k0 + k], P_s[(se0 + k0 + k) * LD + si]);
+          } else {
+            node[k] = hr_s[se0 + k0 + k];
+            val[k] = P_s[hp_s[se0 + k0 + k] * LD + si];
           }
         }
-      }
-      for (int k = e0; k < e_end; ++k) {
-        const int e = hp_s[k], h = hd_s[e];
-        run += (double)Y_s[e * LD + i];
-        if (k + 1 == e_end || hd_s[hp_s[k + 1]] != h) {
-          unsafeAtomicAdd(gE + (int64_t)h * D + i, run);
-          run = 0.0;
+#pragma unroll
+        for (int k = 0; k < RB; ++k) {
+          run += val[k];
+          if (flush_here(node[k])) {
+            unsafeAtomicAdd(gE + (int64_t)(node[k] & 0x7fffffff) * D + si, (double)run);
+            run = 0.f;
+          }
         }
+        __builtin_amdgcn_sched_barrier(0);
       }
     }
     phase_fence();   // the next tile overwrites X, Y and the index arrays

@@ -104,7 +104,8 @@ tinykg_status tinykg_dequantize(const uint8_t* packed, const float* gmin, const 
 typedef struct tinykg_graph tinykg_graph;
 
 /* head/rel/tail: DEVICE int32 arrays of n_edges entries, any order; ids must lie
- * in [0, n_nodes) and [0, n_rel) (else ERR_INVALID_ARG).  Synchronises `stream`,
+ * in [0, n_nodes) and [0, n_rel) (else ERR_INVALID_ARG).  Limits: n_nodes < 2^30,
+ * n_edges < 2^31, n_rel <= 65535 (else ERR_UNSUPPORTED).  Synchronises `stream`,
  * allocates device memory owned by the graph.  *out is set only on TINYKG_OK. */
 tinykg_status tinykg_graph_create(int64_t n_nodes, int32_t n_rel, int64_t n_edges,
                                   const int32_t* head, const int32_t* rel, const int32_t* tail,

@@ -692,8 +692,8 @@ __global__ __launch_bounds__(kThreads) void dense_fwd_kernel(const float* __rest
   }
 }
 
-// grad_J = grad_E' * (mask ? 1 : slope); grad_H = grad_J W; per-workgroup partial
-// of grad_W = grad_J^T H_hat.
+// grad_J = grad_E' * (mask ? 1 : slope); grad_H = grad_J W (also written to grad_E, which
+// the edge stage then adds to); per-workgroup partial of grad_W = grad_J^T H_hat.
 template <int D, int BITS>
 __global__ __launch_bounds__(kThreads) void dense_bwd_kernel(Source srcH,
                                                              const uint8_t* __restrict__ mask,
@@ -701,6 +701,7 @@ __global__ __launch_bounds__(kThreads) void dense_bwd_kernel(Source srcH,
                                                              const float* __restrict__ W, int d_out,
                                                              float slope, int64_t N,
                                                              float* __restrict__ gH,
+                                                             float* __restrict__ gE,
                                                              float* __restrict__ part_W) {
   constexpr int LD = D + 4, LPR = D / 4, TN = 64, NIB = D / 32;
   const int DOP = (d_out + 31) & ~31, LDJ = DOP + 4, NOB = DOP / 32;
@@ -750,7 +751,7 @@ __global__ __launch_bounds__(kThreads) void dense_bwd_kernel(Source srcH,
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
         const int64_t n = n0 + nb * 32 + acc_row(v, lane);
-        if (n < N) gH[n * D + ib * 32 + (lane & 31)] = acc[v];
+        if (n < N) { gH[n * D + ib * 32 + (lane & 31)] = acc[v]; gE[n * D + ib * 32 + (lane & 31)] = acc[v]; }
       }
     }
     // grad_W partial: [o][i] += sum_n gJ[n][o] H_hat[n][i]
@@ -799,19 +800,41 @@ __global__ __launch_bounds__(256) void reduce_segments_kernel(const float* __res
     out[(size_t)seg * stride + j] = (float)(((red[0][j & 63] + red[1][j & 63]) + red[2][j & 63]) + red[3][j & 63]);
 }
 
-// The edge stage accumulates grad_E in double: a hot tail sums 10^5 and more O(1)
-// terms of both signs, which fp32 accumulation cannot hold to 1e-5 of the result.
+// Where the edge stage adds its gradient rows.  grad_E itself (fp32, preset to grad_H,
+// the e_h term of H_h = e_h + sum pi e_t) takes the rows of ordinary nodes with fp32
+// atomics.  A node that receives more than kAccHeavyDegree rows -- a hot tail sums 10^5
+// and more O(1) terms of both signs, which fp32 accumulation cannot hold to 1e-5 of the
+// result -- has a row of doubles in the compact buffer `heavy` instead; finish_heavy_kernel
+// folds that row into grad_E at the end.  A staged node id carries the choice in bit 30.
+struct GradSink {
+  float* gE;              // [n_nodes, D]
+  double* heavy;          // [n_acc_heavy, D]
+  const int32_t* slot;    // [n_nodes] row of `heavy`, or -1
+};
+constexpr int kHeavyBit = 0x40000000;
+
+template <int D>
+__device__ __forceinline__ void sink_add(const GradSink& sink, int flagged_node, int col, float v) {
+  const int node = flagged_node & kNodeIdMask;
+  if (flagged_node & kHeavyBit)
+    unsafeAtomicAdd(sink.heavy + (int64_t)sink.slot[node] * D + col, (double)v);
+  else
+    unsafeAtomicAdd(sink.gE + (int64_t)node * D + col, v);
+}
+
 __global__ void zero_f64_kernel(double* __restrict__ dst, int64_t n) {
   const int64_t stride = (int64_t)gridDim.x * blockDim.x;
   for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) dst[i] = 0.0;
 }
 
-// grad_E = edge terms + grad_H (the e_h term of H_h = e_h + sum pi e_t), rounded once.
-__global__ void finish_grad_kernel(const double* __restrict__ acc, const float* __restrict__ gH,
-                                   int64_t n, float* __restrict__ gE) {
+// grad_E rows of the nodes that accumulated in double: edge terms + grad_H, rounded once.
+__global__ void finish_heavy_kernel(const double* __restrict__ heavy, const int32_t* __restrict__ node,
+                                    int64_t n, int D, float* __restrict__ gE) {
   const int64_t stride = (int64_t)gridDim.x * blockDim.x;
-  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride)
-    gE[i] = (float)(acc[i] + (double)gH[i]);
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) {
+    float* dst = gE + (int64_t)node[i / D] * D + i % D;
+    *dst = (float)(heavy[i] + (double)*dst);
+  }
 }
 
 // ------------------------------------------------------- edge-level backward ----
@@ -821,8 +844,7 @@ __global__ __launch_bounds__(kThreads) void edge_bwd_kernel(
     const int32_t* __restrict__ r_head, const int32_t* __restrict__ r_tail,
     const int32_t* __restrict__ r_eid, const uint8_t* __restrict__ r_hperm, ChunkList chunks,
     const float* __restrict__ pi, const float* __restrict__ gs, const float* __restrict__ gH,
-    double* __restrict__ gE,
-    float* __restrict__ part_Wr, float* __restrict__ part_er) {
+    GradSink sink, float* __restrict__ part_Wr, float* __restrict__ part_er) {
   constexpr int LD = D + 4, LPR = D / 4, NCB = D / 32, NIB = D / 32, NEB = TE / 32;
   constexpr int NBW = (NCB * NIB + 3) / 4;        // grad_W_r blocks per wave
   constexpr int NQ = kThreads / D, RP = TE / NQ;  // scatter: row parts
@@ -873,6 +895,9 @@ __global__ __launch_bounds__(kThreads) void edge_bwd_kernel(
         const int pos = start + t0 + tid;
         const int e = r_eid[pos];
         t = r_tail[pos]; h = r_head[pos]; g = gs[e]; p = pi[e]; hp = r_hperm[pos];
+        if (hp & 0x40) t |= kHeavyBit;
+        if (hp & 0x80) h |= kHeavyBit;
+        hp &= 31;
       }
       gs_s[tid] = g; pi_s[tid] = p; tl_s[tid] = t; hd_s[tid] = h; hp_s[tid] = hp;
     }
@@ -951,21 +976,21 @@ __global__ __launch_bounds__(kThreads) void edge_bwd_kernel(
     {
       const int i = tid % D, qpart = tid / D;
       const int e_end = min((qpart + 1) * RP, nrow);
-      double run = 0.0;
+      float run = 0.f;   // a run inside a tile has at most TE terms
       for (int e = qpart * RP; e < e_end; ++e) {
-        const int t = tl_s[e], h = hd_s[e];
-        run += (double)fmaf(pi_s[e], gH[(int64_t)h * D + i], Et_s[e * LD + i]);
+        const int t = tl_s[e], h = hd_s[e] & kNodeIdMask;
+        run += fmaf(pi_s[e], gH[(int64_t)h * D + i], Et_s[e * LD + i]);
         if (e + 1 == e_end || tl_s[e + 1] != t) {
-          unsafeAtomicAdd(gE + (int64_t)t * D + i, run);
-          run = 0.0;
+          sink_add<D>(sink, t, i, run);
+          run = 0.f;
         }
       }
       for (int k = qpart * RP; k < e_end; ++k) {
         const int e = hp_s[k], h = hd_s[e];
-        run += (double)Eh_s[e * LD + i];
+        run += Eh_s[e * LD + i];
         if (k + 1 == e_end || hd_s[hp_s[k + 1]] != h) {
-          unsafeAtomicAdd(gE + (int64_t)h * D + i, run);
-          run = 0.0;
+          sink_add<D>(sink, h, i, run);
+          run = 0.f;
         }
       }
     }
@@ -1020,7 +1045,7 @@ __global__ __launch_bounds__(kEdgeWaves * 64) void edge_wave_kernel(
     const int32_t* __restrict__ r_head, const int32_t* __restrict__ r_tail,
     const int32_t* __restrict__ r_eid, const uint8_t* __restrict__ r_hperm, ChunkList chunks,
     const float* __restrict__ pi, const float* __restrict__ gs, const float* __restrict__ gH,
-    double* __restrict__ gE, float* __restrict__ part_Wr, float* __restrict__ part_er) {
+    GradSink sink, float* __restrict__ part_Wr, float* __restrict__ part_er) {
   constexpr int LD = D + 4, LPR = D / 4, KH = D / 2, NB = D / 32, NW = kEdgeWaves;
   constexpr int NT = NW * 64, BUF = 32 * LD, REGION = edge_wave_region<D>();
   constexpr int NQ = 64 / D, RP = 32 / NQ;        // scatter: row parts of a wave
@@ -1089,14 +1114,17 @@ __global__ __launch_bounds__(kEdgeWaves * 64) void edge_wave_kernel(
       // where the scatter has to flush its running sums: at the last row of a run of
       // equal tails (rows are in tail order) resp. equal heads (ranks are in head order),
       // at the end of a lane's row part and at the tile's last row
-      const int h_rank = __shfl(h_ld, hp_ld);                   // head of rank r
-      const int t_next = __shfl_down(t_ld, 1), h_next = __shfl_down(h_rank, 1);
+      // (bit 30 of a staged id: the node accumulates in double -- bits 6, 7 of the row's byte)
+      const int perm = hp_ld & 31;
+      const int t_id = t_ld | ((hp_ld & 0x40) ? kHeavyBit : 0), h_id = h_ld | ((hp_ld & 0x80) ? kHeavyBit : 0);
+      const int h_rank = __shfl(h_id, perm);                    // head of rank r
+      const int t_next = __shfl_down(t_id, 1), h_next = __shfl_down(h_rank, 1);
       const bool stop = r + 1 == nrow || (r + 1) % RP == 0;
-      const int t_flag = (r < nrow && (stop || t_next != t_ld)) ? (int)0x80000000 : 0;
+      const int t_flag = (r < nrow && (stop || t_next != t_id)) ? (int)0x80000000 : 0;
       const int h_flag = (r < nrow && (stop || h_next != h_rank)) ? (int)0x80000000 : 0;
       if (hh == 0) {
-        gs_s[r] = g_ld; pi_s[r] = p_ld; hd_s[r] = h_ld; hp_s[r] = hp_ld;
-        tl_s[r] = t_ld | t_flag; hr_s[r] = h_rank | h_flag;
+        gs_s[r] = g_ld; pi_s[r] = p_ld; hd_s[r] = h_ld; hp_s[r] = perm;
+        tl_s[r] = t_id | t_flag; hr_s[r] = h_rank | h_flag;
       }
     }
 #pragma unroll
@@ -1232,7 +1260,7 @@ __global__ __launch_bounds__(kEdgeWaves * 64) void edge_wave_kernel(
     // walks c = (s&7) + 16 (s>>3) + 8 hh, which keeps the two halves of a W_r read in
     // different LDS banks.  Then P goes back to the same buffer as [e][i] and its rows are
     // walked in tail order resp. head order: every LDS read is independent of the running
-    // sum, a run inside a tile has at most 32 terms and is summed in fp32, and one fp64
+    // sum, a run inside a tile has at most 32 terms and is summed in fp32, and one
     // atomic per run and column leaves the wave.  Rows past the end of the chunk carry
     // exact zeros (their weights gs, pi are 0) and no flag.
 #pragma unroll
@@ -1286,7 +1314,7 @@ __global__ __launch_bounds__(kEdgeWaves * 64) void edge_wave_kernel(
         for (int k = 0; k < RB; ++k) {
           run += val[k];
           if (flush_here(node[k])) {
-            unsafeAtomicAdd(gE + (int64_t)(node[k] & 0x7fffffff) * D + si, (double)run);
+            sink_add<D>(sink, node[k], si, run);
             run = 0.f;
           }
         }
@@ -1377,7 +1405,7 @@ BwdWs bwd_layout(const tinykg_graph* g, int d, int d_out) {
   const size_t e = align256((size_t)g->n_edges * 4);
   w.s = 0; w.pi = e; w.gs = 2 * e; w.gH = 3 * e;
   w.acc = w.gH + align256((size_t)g->n_nodes * d * 4);
-  w.pW = w.acc + align256((size_t)g->n_nodes * d * 8);
+  w.pW = w.acc + align256((size_t)g->n_acc_heavy * d * 8);
   w.pWr = w.pW + align256((size_t)dense_grid(g->n_nodes) * d_out * d * 4);
   w.per = w.pWr + align256((size_t)g->n_chunks * d * d * 4);
   w.hv = heavy_layout(g, d, w.per + align256((size_t)g->n_chunks * d * 4));
@@ -1479,7 +1507,7 @@ tinykg_status bwd_impl(const tinykg_graph* g, const tinykg_saved* sv, const floa
                        const float* er, const float* W, int d_out, float slope, int group,
                        const float* gEout, float* gE, float* gWr, float* ger, float* gW,
                        uint8_t* ws, hipStream_t st) {
-  constexpr int TE = D == 128 ? 32 : 64;
+  constexpr int TE = 32;   // edge tile of the d = 128 kernel
   constexpr int LD = D + 4;
   const int64_t N = g->n_nodes;
   const BwdWs L = bwd_layout(g, D, d_out);
@@ -1506,7 +1534,7 @@ tinykg_status bwd_impl(const tinykg_graph* g, const tinykg_saved* sv, const floa
     {
       ProfileScope prof("dense_bwd_kernel", st);
       hipLaunchKernelGGL(kern, dim3(grid), dim3(kThreads), smem, st, srcH, sv->mask_J, gEout, W,
-                         d_out, slope, N, gH, pW);
+                         d_out, slope, N, gH, gE, pW);
     }
     if ((rc = launch_status()) != TINYKG_OK) return rc;
     const int stride = d_out * D;
@@ -1515,10 +1543,11 @@ tinykg_status bwd_impl(const tinykg_graph* g, const tinykg_saved* sv, const floa
                        (const int32_t*)nullptr, grid, stride, gW);
     if ((rc = launch_status()) != TINYKG_OK) return rc;
   }
-  const int fill_blocks = (int)std::max<int64_t>(1, std::min<int64_t>((N * D + 255) / 256, (int64_t)num_cus() * 16));
-  if (N > 0) {
+  const int64_t n_heavy_elems = (int64_t)g->n_acc_heavy * D;
+  const int fill_blocks = (int)std::max<int64_t>(1, std::min<int64_t>((n_heavy_elems + 255) / 256, (int64_t)num_cus() * 16));
+  if (g->n_chunks > 0 && n_heavy_elems > 0) {
     ProfileScope prof("zero_f64_kernel", st);
-    hipLaunchKernelGGL(zero_f64_kernel, dim3(fill_blocks), dim3(256), 0, st, acc, N * D);
+    hipLaunchKernelGGL(zero_f64_kernel, dim3(fill_blocks), dim3(256), 0, st, acc, n_heavy_elems);
     if ((rc = launch_status()) != TINYKG_OK) return rc;
   }
   if (g->n_chunks > 0) {
@@ -1549,27 +1578,28 @@ tinykg_status bwd_impl(const tinykg_graph* g, const tinykg_saved* sv, const floa
       if ((rc = launch_status()) != TINYKG_OK) return rc;
     }
     ChunkList cl{g->chunk_rel, g->chunk_start, g->chunk_count};
+    const GradSink sink{gE, acc, g->acc_slot};
     if constexpr (D <= 64) {
       const size_t smem = (size_t)(D * LD + D + kEdgeWaves * edge_wave_region<D>()) * 4;
       auto kern = edge_wave_kernel<D, BITS>;
       if ((rc = set_smem(kern, smem)) != TINYKG_OK) return rc;
       ProfileScope prof("edge_bwd_kernel", st);
       hipLaunchKernelGGL(kern, dim3(g->n_chunks), dim3(kEdgeWaves * 64), smem, st, srcE, Wr, er,
-                         g->r_head, g->r_tail, g->r_eid, g->r_hperm32, cl, pi, gs, gH, acc, pWr, per);
+                         g->r_head, g->r_tail, g->r_eid, g->r_hperm32, cl, pi, gs, gH, sink, pWr, per);
     } else {
       const size_t smem = (size_t)(D * LD + 4 * TE * LD + D + 5 * TE) * 4;
       auto kern = edge_bwd_kernel<D, TE, BITS>;
       if ((rc = set_smem(kern, smem)) != TINYKG_OK) return rc;
       ProfileScope prof("edge_bwd_kernel", st);
       hipLaunchKernelGGL(kern, dim3(g->n_chunks), dim3(kThreads), smem, st, srcE, Wr, er, g->r_head,
-                         g->r_tail, g->r_eid, TE == 64 ? g->r_hperm64 : g->r_hperm32, cl, pi, gs, gH,
-                         acc, pWr, per);
+                         g->r_tail, g->r_eid, g->r_hperm32, cl, pi, gs, gH, sink, pWr, per);
     }
     if ((rc = launch_status()) != TINYKG_OK) return rc;
   }
-  if (N > 0) {
-    ProfileScope prof("finish_grad_kernel", st);
-    hipLaunchKernelGGL(finish_grad_kernel, dim3(fill_blocks), dim3(256), 0, st, acc, gH, N * D, gE);
+  if (g->n_chunks > 0 && n_heavy_elems > 0) {
+    ProfileScope prof("finish_heavy_kernel", st);
+    hipLaunchKernelGGL(finish_heavy_kernel, dim3(fill_blocks), dim3(256), 0, st, acc, g->acc_node,
+                       n_heavy_elems, D, gE);
     if ((rc = launch_status()) != TINYKG_OK) return rc;
   }
   if (g->n_rel > 0) {

@@ -28,15 +28,22 @@ struct tinykg_graph {
   int32_t* hseg_q = nullptr;         // [n_hseg] index of the segment's head in heavy_head
   int32_t* hseg_e0 = nullptr;        // [n_hseg] first head-order edge
   int32_t* hseg_cnt = nullptr;       // [n_hseg] number of edges
-  // for every tile of 64 (resp. 32) consecutive relation-order edges of a chunk: the
-  // tile-local row indices sorted by head, so equal heads can be summed before they are
-  // scattered
-  uint8_t* r_hperm64 = nullptr;      // [n_edges]
+  // for every tile of 32 consecutive relation-order edges of a chunk, one byte per edge:
+  // bits 0-4 the tile-local row indices sorted by head (equal heads can then be summed
+  // before they are scattered), bit 6 / bit 7: the tail / head of THIS row is a node that
+  // accumulates its gradient in double
   uint8_t* r_hperm32 = nullptr;      // [n_edges]
+  // nodes that receive more than kAccHeavyDegree gradient rows (in-edges + out-edges)
+  // accumulate them in double, in a compact buffer; all others in fp32
+  int32_t n_acc_heavy = 0;
+  int32_t* acc_slot = nullptr;       // [n_nodes] row of the compact buffer, or -1
+  int32_t* acc_node = nullptr;       // [n_acc_heavy] node of each row
 };
 
 namespace tinykg {
 constexpr int kHeavyDegree = 1024;
+constexpr int kAccHeavyDegree = 1024;
+constexpr int kNodeIdMask = 0x3fffffff;   // bits 30, 31 of a staged node id carry flags
 }
 
 #endif

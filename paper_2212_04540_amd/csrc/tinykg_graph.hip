@@ -42,7 +42,7 @@ void release(tinykg_graph* g) {
   if (!g) return;
   void* ptrs[] = {g->rowptr, g->h_tail, g->r_head, g->r_tail, g->r_eid, g->chunk_rel,
                   g->chunk_start, g->chunk_count, g->rel_chunk_ptr, g->heavy_head, g->heavy_seg_ptr,
-                  g->hseg_q, g->hseg_e0, g->hseg_cnt, g->r_hperm64, g->r_hperm32};
+                  g->hseg_q, g->hseg_e0, g->hseg_cnt, g->r_hperm32, g->acc_slot, g->acc_node};
   for (void* p : ptrs)
     if (p) (void)hipFree(p);
   delete g;
@@ -60,7 +60,7 @@ tinykg_status tinykg_graph_create(int64_t n_nodes, int32_t n_rel, int64_t n_edge
   using namespace tinykg;
   if (!out) return TINYKG_ERR_INVALID_ARG;
   if (n_nodes < 0 || n_rel < 0 || n_edges < 0) return TINYKG_ERR_SHAPE;
-  if (n_nodes >= (int64_t)1 << 31 || n_edges >= (int64_t)1 << 31 || n_rel > 65535)
+  if (n_nodes >= (int64_t)1 << 30 || n_edges >= (int64_t)1 << 31 || n_rel > 65535)
     return TINYKG_ERR_UNSUPPORTED;
   if (n_edges > 0 && (!head || !rel || !tail)) return TINYKG_ERR_INVALID_ARG;
   if (n_edges > 0 && n_rel == 0) return TINYKG_ERR_INVALID_ARG;
@@ -110,10 +110,7 @@ tinykg_status tinykg_graph_create(int64_t n_nodes, int32_t n_rel, int64_t n_edge
   // chunks: runs of at most chunk_edges consecutive relation-order edges of one
   // relation; about 2048 of them: few enough that the per-chunk partial gradients stay
   // small and a workgroup amortises staging W_r, enough to fill 256 compute units.
-  #ifndef TINYKG_X_CHUNKS
-#define TINYKG_X_CHUNKS 2048
-#endif
-  int64_t chunk_edges = ((n_edges / TINYKG_X_CHUNKS + 63) / 64) * 64;
+    int64_t chunk_edges = ((n_edges / 2048 + 63) / 64) * 64;
   if (chunk_edges < 64) chunk_edges = 64;
   std::vector<int32_t> chunk_rel, chunk_start, chunk_count, rel_chunk_ptr((size_t)n_rel + 1, 0);
   int64_t pos = 0;
@@ -144,17 +141,30 @@ tinykg_status tinykg_graph_create(int64_t n_nodes, int32_t n_rel, int64_t n_edge
     }
     heavy_seg_ptr.push_back((int32_t)hseg_q.size());
   }
-  // tile-local head-sorted row orders (tiles are counted from each chunk's start)
-  std::vector<uint8_t> hperm64(T), hperm32(T);
+  // nodes whose gradient rows are accumulated in double
+  std::vector<int32_t> acc_slot((size_t)n_nodes, -1), acc_node;
+  {
+    std::vector<int32_t> rows((size_t)n_nodes, 0);
+    for (size_t e = 0; e < T; ++e) { rows[(size_t)hh[e]]++; rows[(size_t)ht[e]]++; }
+    for (int64_t v = 0; v < n_nodes; ++v)
+      if (rows[(size_t)v] > kAccHeavyDegree) {
+        acc_slot[(size_t)v] = (int32_t)acc_node.size();
+        acc_node.push_back((int32_t)v);
+      }
+  }
+  // tile-local head-sorted row orders (tiles are counted from each chunk's start) and the
+  // two accumulation flags of every row
+  std::vector<uint8_t> hperm32(T);
   for (size_t c = 0; c < chunk_rel.size(); ++c) {
-    for (int te : {64, 32}) {
-      std::vector<uint8_t>& out = te == 64 ? hperm64 : hperm32;
-      for (int32_t t0 = 0; t0 < chunk_count[c]; t0 += te) {
-        const int32_t base = chunk_start[c] + t0, nrow = std::min<int32_t>(te, chunk_count[c] - t0);
-        uint8_t idx[64];
-        for (int i = 0; i < nrow; ++i) idx[i] = (uint8_t)i;
-        std::stable_sort(idx, idx + nrow, [&](uint8_t a, uint8_t b) { return r_head[(size_t)base + a] < r_head[(size_t)base + b]; });
-        for (int i = 0; i < nrow; ++i) out[(size_t)base + i] = idx[i];
+    for (int32_t t0 = 0; t0 < chunk_count[c]; t0 += 32) {
+      const int32_t base = chunk_start[c] + t0, nrow = std::min<int32_t>(32, chunk_count[c] - t0);
+      uint8_t idx[32];
+      for (int i = 0; i < nrow; ++i) idx[i] = (uint8_t)i;
+      std::stable_sort(idx, idx + nrow, [&](uint8_t a, uint8_t b) { return r_head[(size_t)base + a] < r_head[(size_t)base + b]; });
+      for (int i = 0; i < nrow; ++i) {
+        const size_t pos = (size_t)base + i;
+        hperm32[pos] = (uint8_t)(idx[i] | (acc_slot[(size_t)r_tail[pos]] >= 0 ? 0x40 : 0) |
+                                 (acc_slot[(size_t)r_head[pos]] >= 0 ? 0x80 : 0));
       }
     }
   }
@@ -179,8 +189,10 @@ tinykg_status tinykg_graph_create(int64_t n_nodes, int32_t n_rel, int64_t n_edge
   if (st == TINYKG_OK) st = upload(hseg_q, &g->hseg_q);
   if (st == TINYKG_OK) st = upload(hseg_e0, &g->hseg_e0);
   if (st == TINYKG_OK) st = upload(hseg_cnt, &g->hseg_cnt);
-  if (st == TINYKG_OK) st = upload(hperm64, &g->r_hperm64);
   if (st == TINYKG_OK) st = upload(hperm32, &g->r_hperm32);
+  g->n_acc_heavy = (int32_t)acc_node.size();
+  if (st == TINYKG_OK) st = upload(acc_slot, &g->acc_slot);
+  if (st == TINYKG_OK) st = upload(acc_node, &g->acc_node);
   if (st != TINYKG_OK) { release(g); return st; }
   *out = g;
   return TINYKG_OK;

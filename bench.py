@@ -53,6 +53,21 @@ def edge_bwd_flops():
     return T * 6 * 2 * D * D
 
 
+PROFILE_SUMMARY = os.path.join(ROOT, "profiles", "aggregation_step_configs1_and_compressor_configs2.txt")
+
+
+def profiled_traffic(kernel):
+    """HBM bytes per launch of `kernel` from the committed rocprofv3 counter summary
+    (FETCH_SIZE + WRITE_SIZE, each scaled by what the counter reads for a copy of known
+    size): measured offline with the commands that file lists, not in this run."""
+    try:
+        rows = [l.split() for l in open(PROFILE_SUMMARY) if l.startswith(kernel + "<") and len(l.split()) >= 6]
+        tot = [(float(r[-2]) + float(r[-1])) * 1e6 for r in rows if r[-1] != "nan" and r[-2] != "nan"]
+        return round(max(tot)) if tot else None
+    except (OSError, ValueError):
+        return None
+
+
 def make_inputs(torch):
     from workloads import gen
     head, rel, tail = gen.kg_triplets(N, R, T, seed=0, tail_zipf=1.1)
@@ -264,7 +279,10 @@ def main():
         "frac_of_hbm_peak": round(alg / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 5),
         "roofline": {"kernel": "edge_bwd_kernel", "bound": "mfma", "achieved": round(achieved, 3),
                      "peak": MFMA_FP32_PEAK_TFLOPS, "unit": "TFLOP/s",
-                     "frac": round(achieved / MFMA_FP32_PEAK_TFLOPS, 4), "traffic": None,
+                     "frac": round(achieved / MFMA_FP32_PEAK_TFLOPS, 4),
+                     "traffic": profiled_traffic("edge_wave_kernel"),
+                     "traffic_unit": "HBM bytes per launch (rocprofv3 --pmc FETCH_SIZE, WRITE_SIZE; "
+                                     "summary under profiles/)",
                      "avg_launch_ms": round(dom_ms, 4)},
         "kernels": kernels,
     }

@@ -97,15 +97,7 @@ def cpu_baseline(inp, seed):
 
 def compressor_line(tk, torch, iters=20):
     """quantize+pack and unpack+dequantize on the 2 GiB Student-t activation."""
-    g = torch.Generator(device="cuda")
-    g.manual_seed(0)
-    x = torch.empty((C2_ROWS, C2_DIM), dtype=torch.float32, device="cuda")
-    step = 1 << 20
-    for r0 in range(0, C2_ROWS, step):      # Student-t(3) = z / sqrt(chi2_3 / 3), drawn in slabs
-        z = torch.randn((step, C2_DIM), generator=g, device="cuda")
-        chi = torch.randn((step, C2_DIM, 3), generator=g, device="cuda").square_().sum(-1)
-        x[r0:r0 + step] = z / (chi / 3).sqrt_()
-    del z, chi
+    x = student_t_matrix(torch, C2_ROWS, C2_DIM)
     n = x.numel()
     buf = tk.alloc_quantized(C2_ROWS, C2_DIM, BITS, GROUP)
     out = torch.empty_like(x)
@@ -135,6 +127,96 @@ def compressor_line(tk, torch, iters=20):
     del x, out, buf
     torch.cuda.empty_cache()
     return res
+
+
+def student_t_matrix(torch, rows, dim, seed=0):
+    """Student-t(3) = z / sqrt(chi2_3 / 3), drawn on the device in slabs."""
+    g = torch.Generator(device="cuda")
+    g.manual_seed(seed)
+    x = torch.empty((rows, dim), dtype=torch.float32, device="cuda")
+    step = min(rows, 1 << 20)
+    for r0 in range(0, rows, step):
+        z = torch.randn((step, dim), generator=g, device="cuda")
+        chi = torch.randn((step, dim, 3), generator=g, device="cuda").square_().sum(-1)
+        x[r0:r0 + step] = z / (chi / 3).sqrt_()
+    return x
+
+
+def variance_stats(tk, torch, x, bits, group, seeds=64):
+    """Per-element variance of dequantize(quantize(x; seed)) over `seeds` seeds against
+    Proposition 1's closed form scale^2 p (1 - p) and its bound scale^2 / 4 (statistics of
+    the kernels' outputs, accumulated with torch on the device)."""
+    rows, dim = x.shape
+    s1 = torch.zeros((rows, dim), dtype=torch.float64, device="cuda")
+    s2 = torch.zeros_like(s1)
+    buf = tk.alloc_quantized(rows, dim, bits, group)
+    out = torch.empty_like(x)
+    for seed in range(seeds):
+        tk.tinykg_quantize(x, bits, group, 1000 + seed, out=buf)
+        tk.tinykg_dequantize(*buf, rows, dim, bits, group, out=out)
+        s1 += out
+        s2 += out.double() ** 2
+    var = s2 / seeds - (s1 / seeds) ** 2                     # population variance over the seeds
+    mn = buf[1].double().repeat_interleave(group).reshape(rows, dim)
+    sc = buf[2].double().repeat_interleave(group).reshape(rows, dim)
+    xb = torch.where(sc > 0, (x.double() - mn) / sc, torch.zeros_like(sc)).clamp_(0, (1 << bits) - 1)
+    pfrac = xb - xb.floor()
+    closed = sc * sc * pfrac * (1 - pfrac)
+    bound = sc * sc / 4
+    live = bound > 0
+    return {"seeds": seeds, "rows": rows,
+            "mean_var_over_closed_form": round(float(var.sum() / closed.sum()), 4),
+            "max_var_over_quarter_scale2": round(float((var[live] / bound[live]).max()), 4),
+            "mean_var_over_quarter_scale2": round(float((var[live] / bound[live]).mean()), 4)}
+
+
+def compressor_sweep(a):
+    """configs[2]: the 9 cells bits x group on the 2 GiB heavy-tailed activation.  Pack and
+    unpack are fused into quantize / dequantize and are not separately observable."""
+    import torch
+    import paper_2212_04540_amd as tk
+    x = student_t_matrix(torch, C2_ROWS, C2_DIM)
+    n = x.numel()
+    out = torch.empty_like(x)
+    sub = x[:4096].contiguous()
+    cells = []
+    for bits in (2, 4, 8):
+        for group in (32, 64, 256):
+            buf = tk.alloc_quantized(C2_ROWS, C2_DIM, bits, group)
+            for _ in range(2):
+                tk.tinykg_quantize(x, bits, group, 1, out=buf)
+                tk.tinykg_dequantize(*buf, C2_ROWS, C2_DIM, bits, group, out=out)
+            torch.cuda.synchronize()
+            tk.tinykg_profile_enable(True)
+            for i in range(a.steps):
+                tk.tinykg_quantize(x, bits, group, 1 + i, out=buf)
+                tk.tinykg_dequantize(*buf, C2_ROWS, C2_DIM, bits, group, out=out)
+            torch.cuda.synchronize()
+            rep = tk.tinykg_profile_report()
+            tk.tinykg_profile_enable(False)
+            bpe = 4 + bytes_per_activation(bits, group)
+            cell = {"bits": bits, "group": group, "bytes_per_activation": bytes_per_activation(bits, group),
+                    "compression_ratio": round(4 / bytes_per_activation(bits, group), 3)}
+            for key, name in (("quantize_pack", "quantize_kernel"), ("unpack_dequantize", "dequantize_kernel")):
+                cnt, ms = rep[name]
+                gbs = n * bpe / (ms / cnt) / 1e6
+                cell[key] = {"ms": round(ms / cnt, 4), "GB/s": round(gbs, 1),
+                             "frac_of_hbm_peak": round(gbs / HBM_PEAK_GBS, 4)}
+            cell["variance"] = variance_stats(tk, torch, sub, bits, group)
+            cells.append(cell)
+            del buf
+    ref = next(c for c in cells if c["bits"] == BITS and c["group"] == GROUP)
+    print(json.dumps({
+        "metric": "quantize+pack and dequant+agg-bwd HBM GB/s (fraction of peak); bytes/activation",
+        "value": ref["quantize_pack"]["GB/s"], "unit": "GB/s", "n_gpus": 1, "steps": a.steps, "warmup": 2,
+        "ms_per_step": ref["quantize_pack"]["ms"] + ref["unpack_dequantize"]["ms"], "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"configs[2]: compressor sweep on {C2_ROWS}x{C2_DIM} fp32 Student-t(3) (2 GiB), "
+                               "bits in {2,4,8} x group in {32,64,256}; value = quantize+pack of INT2/G64"},
+        "roofline": {"kernel": "quantize_kernel", "bound": "hbm", "achieved": ref["quantize_pack"]["GB/s"],
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": ref["quantize_pack"]["frac_of_hbm_peak"],
+                     "traffic": profiled_traffic("quantize_kernel")},
+        "cells": cells}))
 
 
 def stack_workload(a, which):
@@ -212,8 +294,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-compressor", action="store_true")
-    ap.add_argument("--workload", choices=["config1", "config3", "config4"], default="config1",
-                    help="config1 (default, the headline step); config3 / config4: multi-layer steps")
+    ap.add_argument("--workload", choices=["config1", "config2", "config3", "config4"], default="config1",
+                    help="config1 (default, the headline step); config2: the 9-cell compressor sweep; "
+                         "config3 / config4: multi-layer steps")
     ap.add_argument("--bits", type=int, default=0, help="config4 only: 4 (default) or 32 for the fp32 run")
     a = ap.parse_args()
     if a.gpus != 1:
@@ -225,6 +308,8 @@ def main():
     if not torch.cuda.is_available():
         sys.exit("bench.py needs a GPU")
     tk.lib()
+    if a.workload == "config2":
+        return compressor_sweep(a)
     if a.workload != "config1":
         return stack_workload(a, a.workload)
     dev = "cuda"

@@ -26,6 +26,8 @@
 
 #include <float.h>
 
+#include <type_traits>
+
 namespace tinykg {
 
 namespace {
@@ -62,12 +64,16 @@ __device__ __forceinline__ void group_minmax(float& mn, float& mx) {
 }
 
 __device__ __forceinline__ uint32_t xor3(uint32_t a, uint32_t b, uint32_t c);
+__device__ __forceinline__ uint32_t xnor3(uint32_t a, uint32_t b, uint32_t c);
 
 // ---- Philox4x32-10 (Salmon et al., SC'11) -----------------------------------
 // Counter (c0, c1, 0, 0), key (k0, k1).  The third and fourth counter words are
 // zero by construction, which removes one multiply from the first round.
 struct Philox4 { uint32_t w[4]; };
 
+// COMPLEMENT: return the bitwise complement of the four output words (the two words
+// that the last round produces by xor come out complemented at no cost).
+template <bool COMPLEMENT>
 __device__ __forceinline__ Philox4 philox4x32_10(uint32_t c0, uint32_t c1, uint32_t k0,
                                                  uint32_t k1) {
   constexpr uint32_t M0 = 0xD2511F53u, M1 = 0xCD9E8D57u;
@@ -77,8 +83,9 @@ __device__ __forceinline__ Philox4 philox4x32_10(uint32_t c0, uint32_t c1, uint3
   for (int r = 0; r < 10; ++r) {
     const uint64_t p0 = (uint64_t)M0 * c0;
     const uint64_t p1 = (uint64_t)M1 * c2;
-    const uint32_t n0 = xor3((uint32_t)(p1 >> 32), c1, k0);
-    const uint32_t n2 = xor3((uint32_t)(p0 >> 32), c3, k1);
+    const bool flip = COMPLEMENT && r == 9;
+    const uint32_t n0 = flip ? xnor3((uint32_t)(p1 >> 32), c1, k0) : xor3((uint32_t)(p1 >> 32), c1, k0);
+    const uint32_t n2 = flip ? xnor3((uint32_t)(p0 >> 32), c3, k1) : xor3((uint32_t)(p0 >> 32), c3, k1);
     c1 = (uint32_t)p1;
     c3 = (uint32_t)p0;
     c0 = n0;
@@ -86,6 +93,7 @@ __device__ __forceinline__ Philox4 philox4x32_10(uint32_t c0, uint32_t c1, uint3
     k0 += W0;
     k1 += W1;
   }
+  if (COMPLEMENT) { c1 = ~c1; c3 = ~c3; }
   return Philox4{{c0, c1, c2, c3}};
 }
 
@@ -109,6 +117,9 @@ __device__ __forceinline__ int neg_ceil_to_int(float X) {
 
 __device__ __forceinline__ uint32_t xor3(uint32_t a, uint32_t b, uint32_t c) {
   return __builtin_amdgcn_bitop3_b32(a, b, c, 0x96);   // a ^ b ^ c in one VALU op
+}
+__device__ __forceinline__ uint32_t xnor3(uint32_t a, uint32_t b, uint32_t c) {
+  return __builtin_amdgcn_bitop3_b32(a, b, c, 0x69);   // ~(a ^ b ^ c)
 }
 
 // (16-bit half HALF of w) - a, the half selected by the instruction's operand
@@ -202,55 +213,62 @@ __global__ __launch_bounds__(kBlock) void quantize_kernel(
   const float scale = odd ? qs : q;     // R / B
   float inv = 0.0f;                     // B / R, kept finite; 0 for a constant group
   if (range > 0.0f) inv = fminf(odd ? q : qs, FLT_MAX);
-  // An element with e - Z >= R is the group maximum: code B by definition.
-  const float top = range > 0.0f ? range : __builtin_nanf("");   // never matches if constant
-  const float mxx = range > 0.0f ? mx : __builtin_nanf("");
+  // (8-bit codes) an element equal to the group maximum gets code B by definition
+  const float mxx = range > 0.0f ? mx : __builtin_nanf("");   // never matches if constant
   // rounding noise: two Philox blocks cover this lane's 16 elements.  What is
   // kept is 65535 - h (the complement of each 16-bit half).
   uint32_t nrnd[8];
   if (ROUNDING == TINYKG_ROUND_STOCHASTIC) {
     const uint64_t q = (first_index + (uint64_t)e0) >> 3;
-    const Philox4 a = philox4x32_10((uint32_t)q, (uint32_t)(q >> 32), seed_lo, seed_hi);
+    const Philox4 a = philox4x32_10<true>((uint32_t)q, (uint32_t)(q >> 32), seed_lo, seed_hi);
     const uint64_t q1 = q + 1;
-    const Philox4 b = philox4x32_10((uint32_t)q1, (uint32_t)(q1 >> 32), seed_lo, seed_hi);
+    const Philox4 b = philox4x32_10<true>((uint32_t)q1, (uint32_t)(q1 >> 32), seed_lo, seed_hi);
 #pragma unroll
-    for (int i = 0; i < 4; ++i) { nrnd[i] = ~a.w[i]; nrnd[4 + i] = ~b.w[i]; }
+    for (int i = 0; i < 4; ++i) { nrnd[i] = a.w[i]; nrnd[4 + i] = b.w[i]; }
   }
 
   // With X = xb * 2^16 (exact), floor(xb) + [h < frac(xb) * 2^16] equals
   // (ceil(X) + 65535 - h) >> 16, and nearest rounding is (floor(X) + 2^15) >> 16.
   uint32_t words[kWords];
+  // SAFE: test every element against the maximum (needed for 8-bit codes, and for any
+  // width when B/R overflowed and was clamped, which leaves R * inv far below B).
+  auto encode = [&](auto safe_tag) {
+    constexpr bool SAFE = decltype(safe_tag)::value;
 #pragma unroll
-  for (int w = 0; w < kWords; ++w) words[w] = 0u;
+    for (int w = 0; w < kWords; ++w) words[w] = 0u;
 #pragma unroll
-  for (int j = 0; j < kElemsPerLane; j += 2) {
-    uint32_t placed[2];
+    for (int j = 0; j < kElemsPerLane; j += 2) {
+      uint32_t placed[2];
 #pragma unroll
-    for (int u = 0; u < 2; ++u) {
-      const float t = x[j + u] - mn;             // e - Z
-      float X;
-      if (BITS <= 4) {
-        // t < R implies t * inv < B (inv = fl(B/R)), so no clamp is needed; an element
-        // with t == R that is not the maximum rounds up to B for every noise value when
-        // B <= 15 (its fractional part is at least 1 - 2^-20), so one test covers both.
-        X = (t * inv) * 65536.0f;
-        X = (t >= top) ? B16 : X;
-      } else {
-        const float xb = fminf(t * inv, Bf);     // (e - Z) / R * B, inside [0, B]
-        X = xb * 65536.0f;
-        X = (x[j + u] == mxx) ? B16 : X;
+      for (int u = 0; u < 2; ++u) {
+        const float t = x[j + u] - mn;             // e - Z
+        float X;
+        if (!SAFE) {
+          // The clamp alone implements both the clamp and the maximum rule when B <= 15 and
+          // inv = fl(B/R): the maximum has t == R, and R * fl(B/R) is B or one of its two
+          // neighbours.  One ulp above is clamped to B; one ulp below leaves a fractional
+          // part of at least 1 - 2^-20, whose ceiling in 2^-16 units is a full step, so the
+          // element rounds up to B for every noise value (and under nearest rounding).
+          X = fminf((t * inv) * 65536.0f, B16);
+        } else {
+          const float xb = fminf(t * inv, Bf);     // (e - Z) / R * B, inside [0, B]
+          X = xb * 65536.0f;
+          X = (x[j + u] == mxx) ? B16 : X;
+        }
+        uint32_t S;                                // code in bits 16.., rubbish below
+        if (ROUNDING == TINYKG_ROUND_STOCHASTIC) {
+          const uint32_t a = (uint32_t)neg_ceil_to_int(X);
+          S = u == 0 ? half_minus<0>(nrnd[j >> 1], a) : half_minus<1>(nrnd[j >> 1], a);
+        } else {
+          S = (uint32_t)X + 32768u;
+        }
+        placed[u] = place_high_half(S, ((j + u) * BITS) & 31);
       }
-      uint32_t S;                                // code in bits 16.., rubbish below
-      if (ROUNDING == TINYKG_ROUND_STOCHASTIC) {
-        const uint32_t a = (uint32_t)neg_ceil_to_int(X);
-        S = u == 0 ? half_minus<0>(nrnd[j >> 1], a) : half_minus<1>(nrnd[j >> 1], a);
-      } else {
-        S = (uint32_t)X + 32768u;
-      }
-      placed[u] = place_high_half(S, ((j + u) * BITS) & 31);
+      words[(j * BITS) >> 5] |= placed[0] | placed[1];   // both land in the same word
     }
-    words[(j * BITS) >> 5] |= placed[0] | placed[1];   // both land in the same word
-  }
+  };
+  if (BITS <= 4 && __builtin_amdgcn_ballot_w64(inv == FLT_MAX) == 0) encode(std::false_type{});
+  else encode(std::true_type{});
 
   if (live) {
     const int64_t bit0 = e0 * BITS;            // multiple of 16

@@ -32,6 +32,18 @@ namespace tinykg {
 
 namespace {
 
+// Streaming accesses: every input byte is read once and every output byte written once,
+// so they are marked non-temporal (they should not displace anything from the caches).
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ float4 load_stream(const float4* p) {
+  const floatx4 v = __builtin_nontemporal_load(reinterpret_cast<const floatx4*>(p));
+  return make_float4(v.x, v.y, v.z, v.w);
+}
+__device__ __forceinline__ void store_stream(float4* p, const float4& v) {
+  const floatx4 q = {v.x, v.y, v.z, v.w};
+  __builtin_nontemporal_store(q, reinterpret_cast<floatx4*>(p));
+}
+
 constexpr int kWave = 64;
 constexpr int kElemsPerLane = 16;
 constexpr int kTileElems = kWave * kElemsPerLane;  // 1024 elements = 4 KiB of fp32
@@ -170,12 +182,12 @@ __global__ __launch_bounds__(kBlock) void quantize_kernel(
     const float4* src = reinterpret_cast<const float4*>(act) + tile * (kTileElems / 4) + lane;
     if ((tile + 1) * kTileElems <= n) {          // whole tile in range (wave-uniform)
 #pragma unroll
-      for (int u = 0; u < 4; ++u) v[tt][u] = src[u * kWave];
+      for (int u = 0; u < 4; ++u) v[tt][u] = load_stream(src + u * kWave);
     } else {
       const int64_t left = (n >> 2) - tile * (kTileElems / 4) - lane;   // chunks from `src` on
 #pragma unroll
       for (int u = 0; u < 4; ++u)
-        v[tt][u] = u * kWave < left ? src[u * kWave] : make_float4(0.f, 0.f, 0.f, 0.f);
+        v[tt][u] = u * kWave < left ? load_stream(src + u * kWave) : make_float4(0.f, 0.f, 0.f, 0.f);
     }
   }
 
@@ -185,13 +197,18 @@ __global__ __launch_bounds__(kBlock) void quantize_kernel(
   if (tile * kTileElems >= n) break;
   const int64_t e0 = tile * kTileElems + (int64_t)lane * kElemsPerLane;  // lane's first element
   // stage the tile row-wise (coalesced order) into the swizzled slab
+  // (slab_slot(u * 64 + lane) = u * 64 + slab_slot(lane): the swizzle only depends on
+  // bits 3..5 of the chunk index and only changes bits 0..1)
+  const int wslot = slab_slot(lane);
 #pragma unroll
-  for (int u = 0; u < 4; ++u) my[slab_slot(u * kWave + lane)] = v[tt][u];
+  for (int u = 0; u < 4; ++u) my[u * kWave + wslot] = v[tt][u];
   // lane-contiguous read-back: elements [16*lane, 16*lane+16) of the tile
+  // (slab_slot(4 * lane + j) = slab_slot(4 * lane) ^ j for j < 4)
+  const int rslot = slab_slot(4 * lane);
   float x[kElemsPerLane];
 #pragma unroll
   for (int j = 0; j < 4; ++j) {
-    const float4 r4 = my[slab_slot(4 * lane + j)];
+    const float4 r4 = my[rslot ^ j];
     x[4 * j + 0] = r4.x; x[4 * j + 1] = r4.y; x[4 * j + 2] = r4.z; x[4 * j + 3] = r4.w;
   }
   const bool live = e0 < n;
@@ -337,7 +354,7 @@ __global__ __launch_bounds__(256) void dequantize_kernel(
       v.y = fmaf((float)((w[u] >> BITS) & B), s[u], z[u]);
       v.z = fmaf((float)((w[u] >> (2 * BITS)) & B), s[u], z[u]);
       v.w = fmaf((float)((w[u] >> (3 * BITS)) & B), s[u], z[u]);
-      reinterpret_cast<float4*>(out)[c] = v;
+      store_stream(reinterpret_cast<float4*>(out) + c, v);
     }
   }
 }

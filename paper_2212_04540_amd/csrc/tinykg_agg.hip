@@ -330,7 +330,11 @@ __global__ __launch_bounds__(kThreads) void score_wave_kernel(Source src, const 
     }
     floatx16 accA[NCB], accB[NCB];
 #pragma unroll
-    for (int cb = 0; cb < NCB; ++cb) { accA[cb] = floatx16{0}; accB[cb] = floatx16{0}; }
+    for (int cb = 0; cb < NCB; ++cb) {
+      accA[cb] = floatx16{0};
+#pragma unroll
+      for (int v = 0; v < 16; ++v) accB[cb][v] = er_s[cb * 32 + acc_row(v, lane)];   // b starts from e_r
+    }
     // W_r is re-read from LDS for every tile (the opaque zero keeps the compiler from
     // parking all of it in registers, which would halve the waves per SIMD)
     int wofs = 0;
@@ -356,8 +360,7 @@ __global__ __launch_bounds__(kThreads) void score_wave_kernel(Source src, const 
     for (int cb = 0; cb < NCB; ++cb) {
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
-        const int c = cb * 32 + acc_row(v, lane);
-        p = fmaf(accA[cb][v], fast_tanh(accB[cb][v] + er_s[c]), p);
+        p = fmaf(accA[cb][v], fast_tanh(accB[cb][v]), p);
       }
     }
     p += __shfl_xor(p, 32);

@@ -811,18 +811,24 @@ __global__ __launch_bounds__(256) void reduce_segments_kernel(const float* __res
 // folds that row into grad_E at the end.  A staged node id carries the choice in bit 30.
 struct GradSink {
   float* gE;              // [n_nodes, D]
-  double* heavy;          // [n_acc_heavy, D]
+  double* heavy;          // [n_acc_heavy, kHeavyReplicas, D]
   const int32_t* slot;    // [n_nodes] row of `heavy`, or -1
 };
 constexpr int kHeavyBit = 0x40000000;
+// Every heavy node has kHeavyReplicas rows; a workgroup adds to the replica picked by its
+// index, which divides the number of atomics that queue up on one address (a node with
+// 10^5 and more rows is hit by every workgroup).
+constexpr int kHeavyReplicas = 16;
 
 template <int D>
 __device__ __forceinline__ void sink_add(const GradSink& sink, int flagged_node, int col, float v) {
   const int node = flagged_node & kNodeIdMask;
-  if (flagged_node & kHeavyBit)
-    unsafeAtomicAdd(sink.heavy + (int64_t)sink.slot[node] * D + col, (double)v);
-  else
+  if (flagged_node & kHeavyBit) {
+    const int64_t row = (int64_t)sink.slot[node] * kHeavyReplicas + (blockIdx.x & (kHeavyReplicas - 1));
+    unsafeAtomicAdd(sink.heavy + row * D + col, (double)v);
+  } else {
     unsafeAtomicAdd(sink.gE + (int64_t)node * D + col, v);
+  }
 }
 
 __global__ void zero_f64_kernel(double* __restrict__ dst, int64_t n) {
@@ -830,13 +836,17 @@ __global__ void zero_f64_kernel(double* __restrict__ dst, int64_t n) {
   for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) dst[i] = 0.0;
 }
 
-// grad_E rows of the nodes that accumulated in double: edge terms + grad_H, rounded once.
+// grad_E rows of the nodes that accumulated in double: replicas summed in order, plus
+// grad_H, rounded once.
 __global__ void finish_heavy_kernel(const double* __restrict__ heavy, const int32_t* __restrict__ node,
                                     int64_t n, int D, float* __restrict__ gE) {
   const int64_t stride = (int64_t)gridDim.x * blockDim.x;
   for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) {
-    float* dst = gE + (int64_t)node[i / D] * D + i % D;
-    *dst = (float)(heavy[i] + (double)*dst);
+    const int64_t q = i / D, col = i % D;
+    double sum = 0.0;
+    for (int k = 0; k < kHeavyReplicas; ++k) sum += heavy[(q * kHeavyReplicas + k) * D + col];
+    float* dst = gE + (int64_t)node[q] * D + col;
+    *dst = (float)(sum + (double)*dst);
   }
 }
 
@@ -1408,7 +1418,7 @@ BwdWs bwd_layout(const tinykg_graph* g, int d, int d_out) {
   const size_t e = align256((size_t)g->n_edges * 4);
   w.s = 0; w.pi = e; w.gs = 2 * e; w.gH = 3 * e;
   w.acc = w.gH + align256((size_t)g->n_nodes * d * 4);
-  w.pW = w.acc + align256((size_t)g->n_acc_heavy * d * 8);
+  w.pW = w.acc + align256((size_t)g->n_acc_heavy * kHeavyReplicas * d * 8);
   w.pWr = w.pW + align256((size_t)dense_grid(g->n_nodes) * d_out * d * 4);
   w.per = w.pWr + align256((size_t)g->n_chunks * d * d * 4);
   w.hv = heavy_layout(g, d, w.per + align256((size_t)g->n_chunks * d * 4));
@@ -1550,7 +1560,8 @@ tinykg_status bwd_impl(const tinykg_graph* g, const tinykg_saved* sv, const floa
   const int fill_blocks = (int)std::max<int64_t>(1, std::min<int64_t>((n_heavy_elems + 255) / 256, (int64_t)num_cus() * 16));
   if (g->n_chunks > 0 && n_heavy_elems > 0) {
     ProfileScope prof("zero_f64_kernel", st);
-    hipLaunchKernelGGL(zero_f64_kernel, dim3(fill_blocks), dim3(256), 0, st, acc, n_heavy_elems);
+    hipLaunchKernelGGL(zero_f64_kernel, dim3(fill_blocks), dim3(256), 0, st, acc,
+                       n_heavy_elems * kHeavyReplicas);
     if ((rc = launch_status()) != TINYKG_OK) return rc;
   }
   if (g->n_chunks > 0) {

@@ -154,6 +154,44 @@ __device__ __forceinline__ float4 fetch_chunk(const Source& src, int64_t c) {
   return v;
 }
 
+// The same four elements as a lane fetched them, not yet dequantised: lets a kernel
+// request the rows of its next tile before the current one is multiplied and decode them
+// only when they are staged.
+template <int BITS>
+struct RawChunk {
+  static constexpr int NW = BITS == 32 ? 4 : 1;
+  uint32_t w[NW];
+  float z, s;
+  __device__ __forceinline__ void load(const Source& src, int64_t c) {
+    if (BITS == 32) {
+      const float4 v = reinterpret_cast<const float4*>(src.data)[c];
+      w[0] = __float_as_uint(v.x); w[1 % NW] = __float_as_uint(v.y);
+      w[2 % NW] = __float_as_uint(v.z); w[3 % NW] = __float_as_uint(v.w);
+      z = 0.f; s = 0.f;
+      return;
+    }
+    if (BITS == 8) w[0] = reinterpret_cast<const uint32_t*>(src.data)[c];
+    else if (BITS == 4) w[0] = reinterpret_cast<const uint16_t*>(src.data)[c];
+    else if (BITS == 2) w[0] = src.data[c];
+    else w[0] = (src.data[c >> 1] >> ((c & 1) * 4)) & 0xFu;
+    const int64_t g = c >> src.group_chunks_log2;
+    z = src.gmin[g]; s = src.gscale[g];
+  }
+  __device__ __forceinline__ float4 get() const {
+    if (BITS == 32)
+      return make_float4(__uint_as_float(w[0]), __uint_as_float(w[1 % NW]), __uint_as_float(w[2 % NW]),
+                         __uint_as_float(w[3 % NW]));
+    constexpr uint32_t B = (BITS == 32) ? 0u : ((1u << (BITS & 31)) - 1u);
+    constexpr int SH = BITS & 31;
+    float4 v;
+    v.x = fmaf((float)(w[0] & B), s, z);
+    v.y = fmaf((float)((w[0] >> SH) & B), s, z);
+    v.z = fmaf((float)((w[0] >> (2 * SH)) & B), s, z);
+    v.w = fmaf((float)((w[0] >> (3 * SH)) & B), s, z);
+    return v;
+  }
+};
+
 struct ChunkList {
   const int32_t* rel;
   const int32_t* start;
@@ -169,6 +207,9 @@ __global__ __launch_bounds__(kThreads) void score_kernel(Source src, const float
                                                          const int32_t* __restrict__ r_eid,
                                                          ChunkList chunks, float* __restrict__ s_out) {
   constexpr int LD = D + 4, LPR = D / 4, NCB = D / 32, NEB = TE / 32, NP = NCB * 2;
+  constexpr int CPT = TE * LPR / kThreads;        // row chunks per thread and matrix
+  constexpr int RSTEP = kThreads / LPR;           // rows between a thread's chunks
+  static_assert(TE * LPR % kThreads == 0 && kThreads % LPR == 0, "tile does not split evenly");
   float* Wr_s = reinterpret_cast<float*>(smem_raw);
   float* Et_s = Wr_s + D * LD;
   float* Eh_s = Et_s + TE * LD;
@@ -178,6 +219,30 @@ __global__ __launch_bounds__(kThreads) void score_kernel(Source src, const float
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int ch = blockIdx.x;
   const int r = chunks.rel[ch], start = chunks.start[ch], count = chunks.count[ch];
+  const int row0 = tid / LPR, li = tid % LPR;     // this thread stages rows row0 + k * RSTEP
+
+  // Rows of tile k + 1 are requested (raw) while tile k is multiplied; their node ids one
+  // tile earlier still.  Rows past the end of the chunk read node 0 and are never used.
+  int tn[CPT], hn[CPT];
+  auto load_ids = [&](int t0) {
+#pragma unroll
+    for (int k = 0; k < CPT; ++k) {
+      const int row = t0 + row0 + k * RSTEP;
+      tn[k] = 0; hn[k] = 0;
+      if (row < count) { tn[k] = r_tail[start + row]; hn[k] = r_head[start + row]; }
+    }
+  };
+  RawChunk<BITS> rt[CPT], rh[CPT];
+  auto load_rows = [&]() {
+#pragma unroll
+    for (int k = 0; k < CPT; ++k) {
+      rt[k].load(src, (int64_t)tn[k] * LPR + li);
+      rh[k].load(src, (int64_t)hn[k] * LPR + li);
+    }
+  };
+  load_ids(0);
+  load_rows();
+  load_ids(TE);
 
   const float4* Wg = reinterpret_cast<const float4*>(Wr + (size_t)r * D * D);
   for (int q = tid; q < D * LPR; q += kThreads)
@@ -186,16 +251,15 @@ __global__ __launch_bounds__(kThreads) void score_kernel(Source src, const float
 
   for (int t0 = 0; t0 < count; t0 += TE) {
     const int nrow = min(TE, count - t0);
-    for (int q = tid; q < TE * LPR; q += kThreads) {
-      const int row = q / LPR, li = q % LPR;
-      float4 vt = make_float4(0.f, 0.f, 0.f, 0.f), vh = vt;
-      if (row < nrow) {
-        const int pos = start + t0 + row;
-        vt = fetch_chunk<BITS>(src, (int64_t)r_tail[pos] * LPR + li);
-        vh = fetch_chunk<BITS>(src, (int64_t)r_head[pos] * LPR + li);
-      }
-      *reinterpret_cast<float4*>(Et_s + row * LD + li * 4) = vt;
-      *reinterpret_cast<float4*>(Eh_s + row * LD + li * 4) = vh;
+#pragma unroll
+    for (int k = 0; k < CPT; ++k) {
+      const int row = row0 + k * RSTEP;
+      *reinterpret_cast<float4*>(Et_s + row * LD + li * 4) = rt[k].get();
+      *reinterpret_cast<float4*>(Eh_s + row * LD + li * 4) = rh[k].get();
+    }
+    if (t0 + TE < count) {
+      load_rows();
+      load_ids(t0 + 2 * TE);
     }
     __syncthreads();
     for (int blk = wave; blk < NCB * NEB; blk += 4) {
@@ -851,6 +915,12 @@ __global__ void finish_heavy_kernel(const double* __restrict__ heavy, const int3
 }
 
 // ------------------------------------------------------- edge-level backward ----
+// Cooperative form (d = 128: W_r alone takes 66 KiB of LDS, so a workgroup of four waves
+// shares one 32-edge tile).  Phases of a tile, separated by workgroup barriers:
+//   stage rows (prefetched raw one tile ahead, node ids two tiles ahead) and the tile's
+//   per-edge scalars and scatter flags -> a, b per channel block, grad_a / grad_b to LDS ->
+//   scatter rows Pt, Ph and the grad_W_r blocks of each wave -> Pt, Ph back to LDS ->
+//   flag-driven scatter (as in the wave-independent kernel below).
 template <int D, int TE, int BITS>
 __global__ __launch_bounds__(kThreads) void edge_bwd_kernel(
     Source src, const float* __restrict__ Wr, const float* __restrict__ er,
@@ -858,9 +928,14 @@ __global__ __launch_bounds__(kThreads) void edge_bwd_kernel(
     const int32_t* __restrict__ r_eid, const uint8_t* __restrict__ r_hperm, ChunkList chunks,
     const float* __restrict__ pi, const float* __restrict__ gs, const float* __restrict__ gH,
     GradSink sink, float* __restrict__ part_Wr, float* __restrict__ part_er) {
-  constexpr int LD = D + 4, LPR = D / 4, NCB = D / 32, NIB = D / 32, NEB = TE / 32;
+  static_assert(TE == 32, "flags and head order are per 32-edge tile");
+  constexpr int LD = D + 4, LPR = D / 4, NCB = D / 32, NIB = D / 32;
   constexpr int NBW = (NCB * NIB + 3) / 4;        // grad_W_r blocks per wave
+  constexpr int NSB = (NIB + 3) / 4;              // scatter-row blocks per wave
   constexpr int NQ = kThreads / D, RP = TE / NQ;  // scatter: row parts
+  constexpr int CPT = TE * LPR / kThreads;        // row chunks per thread and matrix
+  constexpr int RSTEP = kThreads / LPR;           // rows between a thread's chunks
+  static_assert(TE * LPR % kThreads == 0 && kThreads % LPR == 0 && kThreads % D == 0, "tile split");
   float* Wr_s = reinterpret_cast<float*>(smem_raw);
   float* Et_s = Wr_s + D * LD;
   float* Eh_s = Et_s + TE * LD;
@@ -869,18 +944,62 @@ __global__ __launch_bounds__(kThreads) void edge_bwd_kernel(
   float* er_s = dB_s + TE * LD;
   float* gs_s = er_s + D;
   float* pi_s = gs_s + TE;
-  int* tl_s = reinterpret_cast<int*>(pi_s + TE);
-  int* hd_s = tl_s + TE;
-  int* hp_s = hd_s + TE;   // tile rows in ascending-head order
+  int* tl_s = reinterpret_cast<int*>(pi_s + TE);   // tail of row e; sign bit: a tail run ends here
+  int* hd_s = tl_s + TE;                           // head of row e
+  int* hp_s = hd_s + TE;                           // row of head-order rank k
+  int* hr_s = hp_s + TE;                           // head of rank k; sign bit: a head run ends here
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int ch = blockIdx.x;
-  const int r = chunks.rel[ch], start = chunks.start[ch], count = chunks.count[ch];
+  const int rel = chunks.rel[ch], start = chunks.start[ch], count = chunks.count[ch];
+  const int row0 = tid / LPR, li = tid % LPR;     // this thread stages rows row0 + k * RSTEP
 
-  const float4* Wg = reinterpret_cast<const float4*>(Wr + (size_t)r * D * D);
+  // prefetch: raw rows of the next tile, node ids of the tile after it
+  int tn[CPT], hn[CPT];
+  auto load_ids = [&](int t0) {
+#pragma unroll
+    for (int k = 0; k < CPT; ++k) {
+      const int row = t0 + row0 + k * RSTEP;
+      tn[k] = 0; hn[k] = 0;
+      if (row < count) { tn[k] = r_tail[start + row]; hn[k] = r_head[start + row]; }
+    }
+  };
+  RawChunk<BITS> rt[CPT], rh[CPT];
+  auto load_rows = [&]() {
+#pragma unroll
+    for (int k = 0; k < CPT; ++k) {
+      rt[k].load(src, (int64_t)tn[k] * LPR + li);
+      rh[k].load(src, (int64_t)hn[k] * LPR + li);
+    }
+  };
+  // per-edge scalars of the tile, held by the first wave (lane l and l + 32: row l % 32)
+  const int er_row = lane & 31;
+  int t_nx = 0, h_nx = 0, e_nx = -1, hp_nx = 0;
+  auto load_edge = [&](int t0) {
+    t_nx = 0; h_nx = 0; e_nx = -1; hp_nx = 0;
+    if (wave == 0 && t0 + er_row < count) {
+      const int pos = start + t0 + er_row;
+      t_nx = r_tail[pos]; h_nx = r_head[pos]; e_nx = r_eid[pos]; hp_nx = r_hperm[pos];
+    }
+  };
+  float g_ld = 0.f, p_ld = 0.f;
+  int t_ld = 0, h_ld = 0, hp_ld = 0;
+  auto load_weights = [&]() {
+    g_ld = 0.f; p_ld = 0.f;
+    if (e_nx >= 0) { g_ld = gs[e_nx]; p_ld = pi[e_nx]; }
+    t_ld = t_nx; h_ld = h_nx; hp_ld = hp_nx;
+  };
+  load_ids(0);
+  load_edge(0);
+  load_rows();
+  load_weights();
+  load_ids(TE);
+  load_edge(TE);
+
+  const float4* Wg = reinterpret_cast<const float4*>(Wr + (size_t)rel * D * D);
   for (int q = tid; q < D * LPR; q += kThreads)
     *reinterpret_cast<float4*>(Wr_s + (q / LPR) * LD + (q % LPR) * 4) = Wg[q];
-  for (int c = tid; c < D; c += kThreads) er_s[c] = er[(size_t)r * D + c];
+  for (int c = tid; c < D; c += kThreads) er_s[c] = er[(size_t)rel * D + c];
 
   floatx16 accW[NBW];
 #pragma unroll
@@ -890,37 +1009,38 @@ __global__ __launch_bounds__(kThreads) void edge_bwd_kernel(
   for (int t0 = 0; t0 < count; t0 += TE) {
     const int nrow = min(TE, count - t0);
     __syncthreads();   // previous tile's scatter has finished reading LDS
-    for (int q = tid; q < TE * LPR; q += kThreads) {
-      const int row = q / LPR, li = q % LPR;
-      float4 vt = make_float4(0.f, 0.f, 0.f, 0.f), vh = vt;
-      if (row < nrow) {
-        const int pos = start + t0 + row;
-        vt = fetch_chunk<BITS>(src, (int64_t)r_tail[pos] * LPR + li);
-        vh = fetch_chunk<BITS>(src, (int64_t)r_head[pos] * LPR + li);
-      }
-      *reinterpret_cast<float4*>(Et_s + row * LD + li * 4) = vt;
-      *reinterpret_cast<float4*>(Eh_s + row * LD + li * 4) = vh;
+#pragma unroll
+    for (int k = 0; k < CPT; ++k) {
+      const int row = row0 + k * RSTEP;
+      *reinterpret_cast<float4*>(Et_s + row * LD + li * 4) = rt[k].get();
+      *reinterpret_cast<float4*>(Eh_s + row * LD + li * 4) = rh[k].get();
     }
-    if (tid < TE) {
-      float g = 0.f, p = 0.f;
-      int t = -1, h = -1, hp = 0;
-      if (tid < nrow) {
-        const int pos = start + t0 + tid;
-        const int e = r_eid[pos];
-        t = r_tail[pos]; h = r_head[pos]; g = gs[e]; p = pi[e]; hp = r_hperm[pos];
-        if (hp & 0x40) t |= kHeavyBit;
-        if (hp & 0x80) h |= kHeavyBit;
-        hp &= 31;
+    if (wave == 0) {
+      // where the scatter flushes its running sums (see the wave-independent kernel)
+      const int perm = hp_ld & 31;
+      const int t_id = t_ld | ((hp_ld & 0x40) ? kHeavyBit : 0), h_id = h_ld | ((hp_ld & 0x80) ? kHeavyBit : 0);
+      const int h_rank = __shfl(h_id, perm);
+      const int t_next = __shfl_down(t_id, 1), h_next = __shfl_down(h_rank, 1);
+      const bool stop = er_row + 1 == nrow || (er_row + 1) % RP == 0;
+      const int t_flag = (er_row < nrow && (stop || t_next != t_id)) ? (int)0x80000000 : 0;
+      const int h_flag = (er_row < nrow && (stop || h_next != h_rank)) ? (int)0x80000000 : 0;
+      if (lane < 32) {
+        gs_s[er_row] = g_ld; pi_s[er_row] = p_ld; hd_s[er_row] = h_ld; hp_s[er_row] = perm;
+        tl_s[er_row] = t_id | t_flag; hr_s[er_row] = h_rank | h_flag;
       }
-      gs_s[tid] = g; pi_s[tid] = p; tl_s[tid] = t; hd_s[tid] = h; hp_s[tid] = hp;
+    }
+    if (t0 + TE < count) {
+      load_rows();
+      load_weights();
+      load_ids(t0 + 2 * TE);
+      load_edge(t0 + 2 * TE);
     }
     __syncthreads();
     // recompute a, b; grad_a = gs * tanh(b); grad_b = gs * a * (1 - tanh(b)^2)
-    for (int blk = wave; blk < NCB * NEB; blk += 4) {
-      const int cb = blk % NCB, eb = blk / NCB;
+    for (int cb = wave; cb < NCB; cb += 4) {
       floatx16 accA = {0}, accB = {0};
-      mfma_dual_kcont<D>(Wr_s + cb * 32 * LD, LD, Et_s + eb * 32 * LD, Eh_s + eb * 32 * LD, LD, accA, accB);
-      const int e = eb * 32 + (lane & 31);
+      mfma_dual_kcont<D>(Wr_s + cb * 32 * LD, LD, Et_s, Eh_s, LD, accA, accB);
+      const int e = lane & 31;
       const float g = gs_s[e];
 #pragma unroll
       for (int vg = 0; vg < 4; ++vg) {
@@ -939,20 +1059,24 @@ __global__ __launch_bounds__(kThreads) void edge_bwd_kernel(
     __syncthreads();
     if (tid < D) {
       float sum = 0.f;
+#pragma unroll 8
       for (int e = 0; e < TE; ++e) sum += dB_s[e * LD + tid];
       er_acc += sum;
     }
+    // grad_H rows of the tile's heads (the e_t term of H_h): requested before the products
+    const int si = tid % D, se0 = (tid / D) * RP;   // scatter: this thread's column and rows
+    float ghv[RP];
+#pragma unroll
+    for (int k = 0; k < RP; ++k) ghv[k] = gH[(int64_t)hd_s[se0 + k] * D + si];
     // rows to scatter: Pt = grad_a W_r, Ph = grad_b W_r   ([e][i], contraction over c)
-    constexpr int NSB = (NEB * NIB + 3) / 4;
     floatx16 accPt[NSB], accPh[NSB];
 #pragma unroll
     for (int j = 0; j < NSB; ++j) {
       accPt[j] = floatx16{0}; accPh[j] = floatx16{0};
-      const int blk = wave + 4 * j;
-      if (blk < NEB * NIB) {
-        const int eb = blk % NEB, ib = blk / NEB;
-        mfma_block<KCONT, KMAJOR>(dA_s + eb * 32 * LD, LD, Wr_s + ib * 32, LD, D, accPt[j]);
-        mfma_block<KCONT, KMAJOR>(dB_s + eb * 32 * LD, LD, Wr_s + ib * 32, LD, D, accPh[j]);
+      const int ib = wave + 4 * j;
+      if (ib < NIB) {
+        mfma_block<KCONT, KMAJOR>(dA_s, LD, Wr_s + ib * 32, LD, D, accPt[j]);
+        mfma_block<KCONT, KMAJOR>(dB_s, LD, Wr_s + ib * 32, LD, D, accPh[j]);
       }
     }
     // grad_W_r block(s): [c][i] += sum_e grad_a[e][c] e_t[e][i] + grad_b[e][c] e_h[e][i]
@@ -972,37 +1096,40 @@ __global__ __launch_bounds__(kThreads) void edge_bwd_kernel(
     __syncthreads();   // every read of Et_s / Eh_s is done: reuse them as staging
 #pragma unroll
     for (int j = 0; j < NSB; ++j) {
-      const int blk = wave + 4 * j;
-      if (blk < NEB * NIB) {
-        const int eb = blk % NEB, ib = blk / NEB;
+      const int ib = wave + 4 * j;
+      if (ib < NIB) {
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
-          const int e = eb * 32 + acc_row(v, lane), i = ib * 32 + (lane & 31);
+          const int e = acc_row(v, lane), i = ib * 32 + (lane & 31);
           Et_s[e * LD + i] = accPt[j][v];
           Eh_s[e * LD + i] = accPh[j][v];
         }
       }
     }
     __syncthreads();
-    // scatter: rows of one tail are adjacent (the chunk is sorted by tail) and rows of one
-    // head are adjacent in the tile's head order, so runs are summed before the atomics
-    {
-      const int i = tid % D, qpart = tid / D;
-      const int e_end = min((qpart + 1) * RP, nrow);
-      float run = 0.f;   // a run inside a tile has at most TE terms
-      for (int e = qpart * RP; e < e_end; ++e) {
-        const int t = tl_s[e], h = hd_s[e] & kNodeIdMask;
-        run += fmaf(pi_s[e], gH[(int64_t)h * D + i], Et_s[e * LD + i]);
-        if (e + 1 == e_end || tl_s[e + 1] != t) {
-          sink_add<D>(sink, t, i, run);
-          run = 0.f;
+    // scatter: every LDS read is independent of the running sums; a run inside a tile is
+    // summed in fp32 and leaves as one atomic per column.  Rows past the end of the chunk
+    // carry exact zeros (their weights gs, pi are 0) and no flag.
+#pragma unroll
+    for (int side = 0; side < 2; ++side) {
+      int node[RP];
+      float val[RP];
+#pragma unroll
+      for (int k = 0; k < RP; ++k) {
+        if (side == 0) {
+          node[k] = tl_s[se0 + k];
+          val[k] = fmaf(pi_s[se0 + k], ghv[k], Et_s[(se0 + k) * LD + si]);
+        } else {
+          node[k] = hr_s[se0 + k];
+          val[k] = Eh_s[hp_s[se0 + k] * LD + si];
         }
       }
-      for (int k = qpart * RP; k < e_end; ++k) {
-        const int e = hp_s[k], h = hd_s[e];
-        run += Eh_s[e * LD + i];
-        if (k + 1 == e_end || hd_s[hp_s[k + 1]] != h) {
-          sink_add<D>(sink, h, i, run);
+      float run = 0.f;
+#pragma unroll
+      for (int k = 0; k < RP; ++k) {
+        run += val[k];
+        if (node[k] < 0) {
+          sink_add<D>(sink, node[k], si, run);
           run = 0.f;
         }
       }
@@ -1601,7 +1728,7 @@ tinykg_status bwd_impl(const tinykg_graph* g, const tinykg_saved* sv, const floa
       hipLaunchKernelGGL(kern, dim3(g->n_chunks), dim3(kEdgeWaves * 64), smem, st, srcE, Wr, er,
                          g->r_head, g->r_tail, g->r_eid, g->r_hperm32, cl, pi, gs, gH, sink, pWr, per);
     } else {
-      const size_t smem = (size_t)(D * LD + 4 * TE * LD + D + 5 * TE) * 4;
+      const size_t smem = (size_t)(D * LD + 4 * TE * LD + D + 6 * TE) * 4;
       auto kern = edge_bwd_kernel<D, TE, BITS>;
       if ((rc = set_smem(kern, smem)) != TINYKG_OK) return rc;
       ProfileScope prof("edge_bwd_kernel", st);

@@ -717,15 +717,28 @@ __global__ __launch_bounds__(kThreads) void dense_fwd_kernel(const float* __rest
     *reinterpret_cast<float4*>(W_s + row * LD + li * 4) = w;
   }
   const int64_t n_tiles = (N + TN - 1) / TN;
+  // the rows of the workgroup's next tile are requested while the current one is multiplied
+  constexpr int CPT = TN * LPR / kThreads;
+  float4 pre[CPT];
+  auto load_tile = [&](int64_t tile) {
+#pragma unroll
+    for (int k = 0; k < CPT; ++k) {
+      const int q = tid + k * kThreads;
+      const int64_t n = tile * TN + q / LPR;
+      pre[k] = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (n < N) pre[k] = reinterpret_cast<const float4*>(H)[n * LPR + q % LPR];
+    }
+  };
+  if (blockIdx.x < n_tiles) load_tile(blockIdx.x);
   for (int64_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
     const int64_t n0 = tile * TN;
     __syncthreads();   // previous tile's readers of H_s / J_s are done
-    for (int q = tid; q < TN * LPR; q += kThreads) {
-      const int row = q / LPR, li = q % LPR;
-      float4 x = make_float4(0.f, 0.f, 0.f, 0.f);
-      if (n0 + row < N) x = reinterpret_cast<const float4*>(H)[(n0 + row) * LPR + li];
-      *reinterpret_cast<float4*>(H_s + row * LD + li * 4) = x;
+#pragma unroll
+    for (int k = 0; k < CPT; ++k) {
+      const int q = tid + k * kThreads;
+      *reinterpret_cast<float4*>(H_s + (q / LPR) * LD + (q % LPR) * 4) = pre[k];
     }
+    if (tile + gridDim.x < n_tiles) load_tile(tile + gridDim.x);
     __syncthreads();
     for (int blk = wave; blk < 2 * NOB; blk += 4) {
       const int nb = blk & 1, ob = blk >> 1;
@@ -787,28 +800,57 @@ __global__ __launch_bounds__(kThreads) void dense_bwd_kernel(Source srcH,
   for (int j = 0; j < NIB; ++j) accW[j] = floatx16{0};
 
   const int64_t n_tiles = (N + TN - 1) / TN;
+  const int ocp = DOP / 4, oc = d_out / 4;
+  // the saved rows, upstream gradient and mask bits of the workgroup's next tile are
+  // requested while the current one is multiplied (d_out <= 128: at most 8 chunks a thread)
+  constexpr int CPT = TN * LPR / kThreads, GPT = TN * 32 / kThreads;
+  RawChunk<BITS> preH[CPT];
+  float4 preG[GPT];
+  uint32_t preM[GPT];
+  auto load_tile = [&](int64_t tile) {
+#pragma unroll
+    for (int k = 0; k < CPT; ++k) {
+      const int q = tid + k * kThreads;
+      const int64_t n = tile * TN + q / LPR;
+      preH[k].load(srcH, (n < N ? n : 0) * LPR + q % LPR);   // past the end: row 0, zeroed below
+    }
+#pragma unroll
+    for (int k = 0; k < GPT; ++k) {
+      const int q = tid + k * kThreads;
+      const int64_t n = tile * TN + q / ocp;
+      const int c4 = q % ocp;
+      preG[k] = make_float4(0.f, 0.f, 0.f, 0.f);
+      preM[k] = 0u;
+      if (q < TN * ocp && n < N && c4 < oc) {
+        preG[k] = reinterpret_cast<const float4*>(gEout)[n * oc + c4];
+        const int64_t bit = (n * oc + c4) * 4;
+        preM[k] = (mask[bit >> 3] >> (bit & 7)) & 0xFu;
+      }
+    }
+  };
+  if (blockIdx.x < n_tiles) load_tile(blockIdx.x);
   for (int64_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
     const int64_t n0 = tile * TN;
     __syncthreads();
-    for (int q = tid; q < TN * LPR; q += kThreads) {
-      const int row = q / LPR, li = q % LPR;
-      float4 x = make_float4(0.f, 0.f, 0.f, 0.f);
-      if (n0 + row < N) x = fetch_chunk<BITS>(srcH, (n0 + row) * LPR + li);
-      *reinterpret_cast<float4*>(Hh_s + row * LD + li * 4) = x;
+#pragma unroll
+    for (int k = 0; k < CPT; ++k) {
+      const int q = tid + k * kThreads;
+      const int row = q / LPR;
+      const float4 x = n0 + row < N ? preH[k].get() : make_float4(0.f, 0.f, 0.f, 0.f);
+      *reinterpret_cast<float4*>(Hh_s + row * LD + (q % LPR) * 4) = x;
     }
-    const int ocp = DOP / 4, oc = d_out / 4;
-    for (int q = tid; q < TN * ocp; q += kThreads) {
-      const int row = q / ocp, c4 = q % ocp;
-      float4 g = make_float4(0.f, 0.f, 0.f, 0.f);
-      if (n0 + row < N && c4 < oc) {
-        g = reinterpret_cast<const float4*>(gEout)[(n0 + row) * oc + c4];
-        const int64_t bit = ((n0 + row) * oc + c4) * 4;
-        const uint32_t mb = (mask[bit >> 3] >> (bit & 7)) & 0xFu;
+#pragma unroll
+    for (int k = 0; k < GPT; ++k) {
+      const int q = tid + k * kThreads;
+      if (q < TN * ocp) {
+        float4 g = preG[k];
+        const uint32_t mb = preM[k];
         g.x *= (mb & 1u) ? 1.f : slope; g.y *= (mb & 2u) ? 1.f : slope;
         g.z *= (mb & 4u) ? 1.f : slope; g.w *= (mb & 8u) ? 1.f : slope;
+        *reinterpret_cast<float4*>(gJ_s + (q / ocp) * LDJ + (q % ocp) * 4) = g;
       }
-      *reinterpret_cast<float4*>(gJ_s + row * LDJ + c4 * 4) = g;
     }
+    if (tile + gridDim.x < n_tiles) load_tile(tile + gridDim.x);
     __syncthreads();
     // grad_H tile: [n][i] = sum_o gJ[n][o] W[o][i]
     for (int blk = wave; blk < 2 * NIB; blk += 4) {

@@ -158,6 +158,30 @@ tinykg_status tinykg_kg_aggregate_bwd(const tinykg_graph* g, const tinykg_saved*
                                       size_t workspace_bytes, void* stream);
 
 /* ------------------------------------------------------------------------- *
+ * Uniform-attention layer: Eq. (2) exactly as printed, E' = sigma(A_hat E Theta), with the
+ * row-normalised adjacency plus self term of the KGCN / KGNN-LS family (Sec. 3.1):
+ *   H_h = e_h + (1 / deg(h)) sum over the out-edges (h, r, t) of e_t ;  J = H W^T ;
+ *   E' = LeakyReLU(J).
+ * It is the attentive layer with every attention weight pi = 1 / deg(h) (relations are
+ * ignored).  Context (Sec. 3.2): the spmm stage needs only A_hat, which the graph holds;
+ * the mm stage needs H; the activation needs one bit per element.  So `saved` carries
+ * Q(H; seed + 1) and mask_J only -- packed_E / gmin_E / gscale_E are not touched and may be
+ * NULL.  Backward (Eq. (2)): grad_J from the mask, grad_W = grad_J^T H_hat,
+ * grad_H = grad_J W, grad_E = grad_H + A_hat^T grad_H (row t receives grad_H_h / deg(h)
+ * from every in-edge).  Shapes, limits, workspace (use
+ * tinykg_kg_aggregate_workspace_bytes with d_rel = d_in) and error behaviour as for the
+ * attentive layer.
+ * ------------------------------------------------------------------------- */
+tinykg_status tinykg_kg_uniform_fwd(const tinykg_graph* g, const float* E, const float* W, int d_in,
+                                    int d_out, float leaky_slope, int bits, int group, uint64_t seed,
+                                    float* E_out, const tinykg_saved* saved, void* workspace,
+                                    size_t workspace_bytes, void* stream);
+tinykg_status tinykg_kg_uniform_bwd(const tinykg_graph* g, const tinykg_saved* saved, const float* W,
+                                    int d_in, int d_out, float leaky_slope, int bits, int group,
+                                    const float* grad_E_out, float* grad_E, float* grad_W,
+                                    void* workspace, size_t workspace_bytes, void* stream);
+
+/* ------------------------------------------------------------------------- *
  * Readout and loss for a stack of layers (Sec. 3.2: after L layers a readout forms
  * the final embedding -- here the concatenation of E^(0..L), "layer-aggregation" --
  * and a downstream loss is optimised).  Score y(u, i) = <concat_l e_u^(l), concat_l

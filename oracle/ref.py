@@ -316,3 +316,39 @@ def stack_step(n_nodes, head, rel, tail, E0, params, slope, bits, group, seed, u
         pgrads[l] = (gWr, ger, gW)
     return {"acts": acts, "ctxs": ctxs, "loss": loss, "coef": coef, "layer_grads": layer_grads,
             "param_grads": pgrads}
+
+
+# ------------------------------------------------ uniform-attention layer ------
+def _uniform_adjacency(n_nodes, head, tail):
+    """Row-normalised adjacency A_hat[h, t] = (number of edges h -> t) / deg(h) as a scipy
+    CSR matrix (float64); rows of nodes without out-edges are empty."""
+    import scipy.sparse as sp
+    head = np.asarray(head, dtype=np.int64)
+    tail = np.asarray(tail, dtype=np.int64)
+    deg = np.bincount(head, minlength=n_nodes).astype(np.float64)
+    w = 1.0 / deg[head] if head.size else np.zeros(0)
+    return sp.csr_matrix((w, (head, tail)), shape=(n_nodes, n_nodes))
+
+
+def uniform_fwd(n_nodes, head, tail, E, W, slope):
+    """E' = LeakyReLU((E + A_hat E) W^T) -- Eq. (2) as printed (spmm, mm, activation) with
+    the row-normalised adjacency plus self term; every step in float64, outputs rounded
+    to fp32 once.  Returns E' [n, d_out], H = E + A_hat E [n, d_in] and the mask [J > 0]."""
+    A = _uniform_adjacency(n_nodes, head, tail)
+    E64 = np.asarray(E, dtype=np.float64)
+    H = E64 + A @ E64
+    J = H @ np.asarray(W, dtype=np.float64).T
+    out = np.where(J > 0, J, np.float64(slope) * J)
+    return out.astype(np.float32), H.astype(np.float32), (J > 0).astype(np.uint8)
+
+
+def uniform_bwd(n_nodes, head, tail, Hhat, mask, W, slope, gEout):
+    """Backward of Eq. (2) at the saved context (H_hat, mask): grad_J = grad_E' * (mask ? 1 :
+    slope); grad_W = grad_J^T H_hat; grad_H = grad_J W; grad_E = grad_H + A_hat^T grad_H.
+    float64 throughout, outputs rounded to fp32 once."""
+    A = _uniform_adjacency(n_nodes, head, tail)
+    gJ = np.asarray(gEout, dtype=np.float64) * np.where(np.asarray(mask) != 0, 1.0, np.float64(slope))
+    gW = gJ.T @ np.asarray(Hhat, dtype=np.float64)
+    gH = gJ @ np.asarray(W, dtype=np.float64)
+    gE = gH + A.T @ gH
+    return gE.astype(np.float32), gW.astype(np.float32)

@@ -21,7 +21,8 @@ EXPORTS = [
     "tinykg_status_string", "tinykg_packed_bytes", "tinykg_num_groups", "tinykg_quantize",
     "tinykg_quantize_ex", "tinykg_dequantize", "tinykg_graph_create", "tinykg_graph_destroy",
     "tinykg_graph_num_nodes", "tinykg_graph_num_edges", "tinykg_kg_aggregate_workspace_bytes",
-    "tinykg_kg_aggregate_fwd", "tinykg_kg_aggregate_bwd", "tinykg_profile_enable",
+    "tinykg_kg_aggregate_fwd", "tinykg_kg_aggregate_bwd", "tinykg_kg_uniform_fwd",
+    "tinykg_kg_uniform_bwd", "tinykg_profile_enable",
     "tinykg_profile_report", "tinykg_profile_copy", "tinykg_bpr_loss", "tinykg_bpr_grad",
     "tinykg_gather_rows", "tinykg_scatter_add_rows", "tinykg_fill_zero",
 ]
@@ -73,6 +74,10 @@ def lib():
                                                   u64, vp, C.POINTER(Saved), vp, sz, vp]
             L.tinykg_kg_aggregate_bwd.argtypes = [vp, C.POINTER(Saved), vp, vp, vp, i32, i32, i32,
                                                   f32, i32, i32, vp, vp, vp, vp, vp, vp, sz, vp]
+            L.tinykg_kg_uniform_fwd.argtypes = [vp, vp, vp, i32, i32, f32, i32, i32, u64, vp,
+                                                C.POINTER(Saved), vp, sz, vp]
+            L.tinykg_kg_uniform_bwd.argtypes = [vp, C.POINTER(Saved), vp, i32, i32, f32, i32, i32,
+                                                vp, vp, vp, vp, sz, vp]
         L.tinykg_profile_enable.argtypes = [i32]
         L.tinykg_profile_enable.restype = None
         L.tinykg_profile_report.argtypes = [C.c_char_p, sz]
@@ -251,14 +256,17 @@ class Graph:
 class SavedContext:
     """Device buffers of one layer's saved context + the tinykg_saved struct."""
 
-    def __init__(self, n_nodes, d_in, d_out, bits, group, device="cuda"):
+    def __init__(self, n_nodes, d_in, d_out, bits, group, device="cuda", with_E=True):
+        """with_E=False: the context of the uniform-attention layer (Q(H) and the mask only)."""
         self.n_nodes, self.d_in, self.d_out, self.bits, self.group = n_nodes, d_in, d_out, bits, group
+        self.packed_E = self.gmin_E = self.gscale_E = self.gmin_H = self.gscale_H = None
         if bits == 32:
-            self.packed_E = torch.empty(n_nodes * d_in * 4, dtype=torch.uint8, device=device)
+            if with_E:
+                self.packed_E = torch.empty(n_nodes * d_in * 4, dtype=torch.uint8, device=device)
             self.packed_H = torch.empty(n_nodes * d_in * 4, dtype=torch.uint8, device=device)
-            self.gmin_E = self.gscale_E = self.gmin_H = self.gscale_H = None
         else:
-            self.packed_E, self.gmin_E, self.gscale_E = alloc_quantized(n_nodes, d_in, bits, group, device)
+            if with_E:
+                self.packed_E, self.gmin_E, self.gscale_E = alloc_quantized(n_nodes, d_in, bits, group, device)
             self.packed_H, self.gmin_H, self.gscale_H = alloc_quantized(n_nodes, d_in, bits, group, device)
         self.mask_J = torch.empty((n_nodes * d_out + 7) // 8, dtype=torch.uint8, device=device)
         self.struct = Saved(_ptr(self.packed_E), _ptr(self.gmin_E), _ptr(self.gscale_E),
@@ -307,3 +315,31 @@ def tinykg_kg_aggregate_bwd(graph, saved, Wr, er, W, leaky_slope, bits, group, g
                                        _ptr(workspace), workspace.numel(), _stream())
     _ok(st, "tinykg_kg_aggregate_bwd")
     return gE, gWr, ger, gW
+
+
+def tinykg_kg_uniform_fwd(graph, E, W, leaky_slope, bits, group, seed, saved, workspace, E_out=None):
+    for t, nm in ((E, "E"), (W, "W")):
+        _dev(t, torch.float32, nm)
+    d_in, d_out = E.shape[1], W.shape[0]
+    if E_out is None:
+        E_out = torch.empty((graph.n_nodes, d_out), dtype=torch.float32, device=E.device)
+    st = lib().tinykg_kg_uniform_fwd(graph.handle, _ptr(E), _ptr(W), d_in, d_out, float(leaky_slope),
+                                     bits, group, C.c_uint64(seed), _ptr(E_out), C.byref(saved.struct),
+                                     _ptr(workspace), workspace.numel(), _stream())
+    _ok(st, "tinykg_kg_uniform_fwd")
+    return E_out
+
+
+def tinykg_kg_uniform_bwd(graph, saved, W, leaky_slope, bits, group, grad_E_out, workspace, out=None):
+    for t, nm in ((W, "W"), (grad_E_out, "grad_E_out")):
+        _dev(t, torch.float32, nm)
+    d_in, d_out = W.shape[1], W.shape[0]
+    if out is None:
+        out = (torch.empty((graph.n_nodes, d_in), dtype=torch.float32, device=W.device),
+               torch.empty_like(W))
+    gE, gW = out
+    st = lib().tinykg_kg_uniform_bwd(graph.handle, C.byref(saved.struct), _ptr(W), d_in, d_out,
+                                     float(leaky_slope), bits, group, _ptr(grad_E_out), _ptr(gE),
+                                     _ptr(gW), _ptr(workspace), workspace.numel(), _stream())
+    _ok(st, "tinykg_kg_uniform_bwd")
+    return gE, gW

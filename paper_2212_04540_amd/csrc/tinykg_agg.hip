@@ -956,6 +956,66 @@ __global__ void finish_heavy_kernel(const double* __restrict__ heavy, const int3
   }
 }
 
+// ---------------------------------------------- uniform attention, backward ----
+// grad_E_t += grad_H_h / deg(h) over the in-edges (h -> t) of t: the transposed sparse
+// product of Eq. (2)'s grad_E = ctx(A_hat, grad_H) for the row-normalised adjacency
+// (pi = 1 / deg).  One wave per 32 consecutive relation-order edges (sorted by tail inside
+// a relation): rows of equal tails are summed in fp32 before one atomic per run and column.
+__global__ void zero_f32_fill_kernel(float* __restrict__ dst, int64_t n) {
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) dst[i] = 0.f;
+}
+
+template <int D>
+__global__ __launch_bounds__(kThreads) void uniform_bwd_kernel(
+    const int32_t* __restrict__ r_head, const int32_t* __restrict__ r_tail,
+    const uint8_t* __restrict__ r_hperm, const int32_t* __restrict__ rowptr,
+    const float* __restrict__ gH, int64_t n_edges, GradSink sink) {
+  constexpr int NQ = D >= 64 ? 1 : 64 / D, RP = 32 / NQ;   // row parts of a wave
+  constexpr int CPL = D >= 64 ? D / 64 : 1;                // columns per lane
+  __shared__ int tl_s[kThreads / 64][32];
+  __shared__ int hd_s[kThreads / 64][32];
+  __shared__ float w_s[kThreads / 64][32];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, r = lane & 31;
+  const int64_t pos0 = ((int64_t)blockIdx.x * (kThreads / 64) + wave) * 32;
+  if (pos0 >= n_edges) return;
+  const int nrow = (int)min((int64_t)32, n_edges - pos0);
+  int t_id = 0, h = 0;
+  float w = 0.f;
+  if (r < nrow) {
+    const int64_t pos = pos0 + r;
+    h = r_head[pos];
+    t_id = r_tail[pos] | ((r_hperm[pos] & 0x40) ? kHeavyBit : 0);
+    w = 1.0f / (float)(rowptr[h + 1] - rowptr[h]);
+  }
+  const int t_next = __shfl_down(t_id, 1);
+  const bool stop = r + 1 == nrow || (r + 1) % RP == 0;
+  const int flag = (r < nrow && (stop || t_next != t_id)) ? (int)0x80000000 : 0;
+  if (lane < 32) { tl_s[wave][r] = t_id | flag; hd_s[wave][r] = h; w_s[wave][r] = w; }
+  __builtin_amdgcn_wave_barrier();
+  const int col = lane % (D >= 64 ? 64 : D), e0 = (D >= 64 ? 0 : lane / D) * RP;
+#pragma unroll
+  for (int cp = 0; cp < CPL; ++cp) {
+    const int c = col + 64 * cp;
+    int node[RP];
+    float val[RP];
+#pragma unroll
+    for (int k = 0; k < RP; ++k) {
+      node[k] = tl_s[wave][e0 + k];
+      val[k] = w_s[wave][e0 + k] * gH[(int64_t)hd_s[wave][e0 + k] * D + c];   // rows past the end: w = 0, row 0
+    }
+    float run = 0.f;
+#pragma unroll
+    for (int k = 0; k < RP; ++k) {
+      run += val[k];
+      if (node[k] < 0) {
+        sink_add<D>(sink, node[k], c, run);
+        run = 0.f;
+      }
+    }
+  }
+}
+
 // ------------------------------------------------------- edge-level backward ----
 // Cooperative form (d = 128: W_r alone takes 66 KiB of LDS, so a workgroup of four waves
 // shares one 32-edge tile).  Phases of a tile, separated by workgroup barriers:
@@ -1639,7 +1699,18 @@ tinykg_status fwd_impl(const tinykg_graph* g, const float* E, const float* Wr, c
   float* s = reinterpret_cast<float*>(ws + L.s);
   float* H = bits == 32 ? reinterpret_cast<float*>(sv->packed_H) : reinterpret_cast<float*>(ws + L.H);
   Source src{reinterpret_cast<const uint8_t*>(E), nullptr, nullptr, 0};
-  tinykg_status rc = launch_score<D, 32>(g, src, Wr, er, s, st);
+  tinykg_status rc = TINYKG_OK;
+  const bool uniform = Wr == nullptr;     // pi = 1 / deg: the softmax of all-zero scores
+  if (uniform) {
+    if (g->n_edges > 0) {
+      ProfileScope prof("zero_scores_kernel", st);
+      const int blocks = (int)std::min<int64_t>((g->n_edges + 255) / 256, (int64_t)num_cus() * 16);
+      hipLaunchKernelGGL(zero_f32_fill_kernel, dim3(blocks), dim3(256), 0, st, s, g->n_edges);
+      rc = launch_status();
+    }
+  } else {
+    rc = launch_score<D, 32>(g, src, Wr, er, s, st);
+  }
   if (rc != TINYKG_OK) return rc;
   const int wave_blocks = (int)std::max<int64_t>(1, std::min<int64_t>((N + 3) / 4, (int64_t)num_cus() * 16));
   {
@@ -1663,13 +1734,18 @@ tinykg_status fwd_impl(const tinykg_graph* g, const float* E, const float* Wr, c
     if ((rc = launch_status()) != TINYKG_OK) return rc;
   }
   // save the context (Fig. 1): Q(E; seed), Q(H; seed + 1)
+  // (the uniform layer's backward pass never reads E: only Q(H) and the mask are kept)
   if (bits == 32) {
-    ProfileScope prof("copy_E_fp32", st);
-    TINYKG_HIP_TRY(hipMemcpyAsync(sv->packed_E, E, (size_t)N * D * 4, hipMemcpyDeviceToDevice, st));
+    if (!uniform) {
+      ProfileScope prof("copy_E_fp32", st);
+      TINYKG_HIP_TRY(hipMemcpyAsync(sv->packed_E, E, (size_t)N * D * 4, hipMemcpyDeviceToDevice, st));
+    }
   } else {
-    rc = launch_quantize(E, N * D, bits, group, seed, 0, TINYKG_ROUND_STOCHASTIC, sv->packed_E,
-                         sv->gmin_E, sv->gscale_E, st);
-    if (rc != TINYKG_OK) return rc;
+    if (!uniform) {
+      rc = launch_quantize(E, N * D, bits, group, seed, 0, TINYKG_ROUND_STOCHASTIC, sv->packed_E,
+                           sv->gmin_E, sv->gscale_E, st);
+      if (rc != TINYKG_OK) return rc;
+    }
     rc = launch_quantize(H, N * D, bits, group, seed + 1, 0, TINYKG_ROUND_STOCHASTIC, sv->packed_H,
                          sv->gmin_H, sv->gscale_H, st);
     if (rc != TINYKG_OK) return rc;
@@ -1733,7 +1809,16 @@ tinykg_status bwd_impl(const tinykg_graph* g, const tinykg_saved* sv, const floa
                        n_heavy_elems * kHeavyReplicas);
     if ((rc = launch_status()) != TINYKG_OK) return rc;
   }
-  if (g->n_chunks > 0) {
+  const bool uniform = Wr == nullptr;     // pi = 1 / deg: only the transposed sparse product is left
+  if (uniform && g->n_edges > 0) {
+    const GradSink sink{gE, acc, g->acc_slot};
+    const int64_t waves = (g->n_edges + 31) / 32;
+    ProfileScope prof("uniform_bwd_kernel", st);
+    hipLaunchKernelGGL((uniform_bwd_kernel<D>), dim3((unsigned)((waves + 3) / 4)), dim3(kThreads), 0, st,
+                       g->r_head, g->r_tail, g->r_hperm32, g->rowptr, gH, g->n_edges, sink);
+    if ((rc = launch_status()) != TINYKG_OK) return rc;
+  }
+  if (!uniform && g->n_chunks > 0) {
     if ((rc = launch_score<D, BITS>(g, srcE, Wr, er, s, st)) != TINYKG_OK) return rc;
     const int wave_blocks = (int)std::max<int64_t>(1, std::min<int64_t>((N + 3) / 4, (int64_t)num_cus() * 16));
     {
@@ -1785,7 +1870,7 @@ tinykg_status bwd_impl(const tinykg_graph* g, const tinykg_saved* sv, const floa
                        n_heavy_elems, D, gE);
     if ((rc = launch_status()) != TINYKG_OK) return rc;
   }
-  if (g->n_rel > 0) {
+  if (!uniform && g->n_rel > 0) {
     ProfileScope prof("reduce_segments_kernel", st);
     hipLaunchKernelGGL(reduce_segments_kernel, dim3((D * D + 63) / 64, g->n_rel), dim3(256), 0, st,
                        pWr, g->rel_chunk_ptr, 0, D * D, gWr);
@@ -1821,6 +1906,17 @@ tinykg_status check_saved(const tinykg_saved* sv, int bits) {
     if (!aligned16(sv->gmin_E) || !aligned16(sv->gscale_E) || !aligned16(sv->gmin_H) ||
         !aligned16(sv->gscale_H))
       return TINYKG_ERR_INVALID_ARG;
+  }
+  return TINYKG_OK;
+}
+
+// the uniform layer keeps only Q(H) and the mask
+tinykg_status check_saved_uniform(const tinykg_saved* sv, int bits) {
+  if (!sv || !sv->packed_H || !sv->mask_J) return TINYKG_ERR_INVALID_ARG;
+  if (!aligned16(sv->packed_H) || !aligned16(sv->mask_J)) return TINYKG_ERR_INVALID_ARG;
+  if (bits != 32) {
+    if (!sv->gmin_H || !sv->gscale_H) return TINYKG_ERR_INVALID_ARG;
+    if (!aligned16(sv->gmin_H) || !aligned16(sv->gscale_H)) return TINYKG_ERR_INVALID_ARG;
   }
   return TINYKG_OK;
 }
@@ -1896,6 +1992,52 @@ tinykg_status tinykg_kg_aggregate_bwd(const tinykg_graph* g, const tinykg_saved*
     case 32: return bwd_bits<32>(bits, g, saved, Wr, er, W, d_out, leaky_slope, group, grad_E_out, grad_E, grad_Wr, grad_er, grad_W, ws, st);
     case 64: return bwd_bits<64>(bits, g, saved, Wr, er, W, d_out, leaky_slope, group, grad_E_out, grad_E, grad_Wr, grad_er, grad_W, ws, st);
     case 128: return bwd_bits<128>(bits, g, saved, Wr, er, W, d_out, leaky_slope, group, grad_E_out, grad_E, grad_Wr, grad_er, grad_W, ws, st);
+  }
+  return TINYKG_ERR_UNSUPPORTED;
+}
+
+tinykg_status tinykg_kg_uniform_fwd(const tinykg_graph* g, const float* E, const float* W, int d_in,
+                                    int d_out, float leaky_slope, int bits, int group, uint64_t seed,
+                                    float* E_out, const tinykg_saved* saved, void* workspace,
+                                    size_t workspace_bytes, void* stream) {
+  using namespace tinykg;
+  tinykg_status rc = check_common(g, d_in, d_in, d_out, bits, group);
+  if (rc != TINYKG_OK) return rc;
+  if ((rc = check_saved_uniform(saved, bits)) != TINYKG_OK) return rc;
+  if (g->n_nodes == 0) return TINYKG_OK;
+  if (!E || !W || !E_out || !aligned16(E) || !aligned16(W) || !aligned16(E_out))
+    return TINYKG_ERR_INVALID_ARG;
+  if (!workspace || !aligned16(workspace) || workspace_bytes < fwd_layout(g, d_in).total)
+    return TINYKG_ERR_WORKSPACE;
+  hipStream_t st = (hipStream_t)stream;
+  uint8_t* ws = static_cast<uint8_t*>(workspace);
+  switch (d_in) {
+    case 32: return fwd_impl<32>(g, E, nullptr, nullptr, W, d_out, leaky_slope, bits, group, seed, E_out, saved, ws, st);
+    case 64: return fwd_impl<64>(g, E, nullptr, nullptr, W, d_out, leaky_slope, bits, group, seed, E_out, saved, ws, st);
+    case 128: return fwd_impl<128>(g, E, nullptr, nullptr, W, d_out, leaky_slope, bits, group, seed, E_out, saved, ws, st);
+  }
+  return TINYKG_ERR_UNSUPPORTED;
+}
+
+tinykg_status tinykg_kg_uniform_bwd(const tinykg_graph* g, const tinykg_saved* saved, const float* W,
+                                    int d_in, int d_out, float leaky_slope, int bits, int group,
+                                    const float* grad_E_out, float* grad_E, float* grad_W,
+                                    void* workspace, size_t workspace_bytes, void* stream) {
+  using namespace tinykg;
+  tinykg_status rc = check_common(g, d_in, d_in, d_out, bits, group);
+  if (rc != TINYKG_OK) return rc;
+  if ((rc = check_saved_uniform(saved, bits)) != TINYKG_OK) return rc;
+  if (!W || !grad_W || !aligned16(W) || !aligned16(grad_W)) return TINYKG_ERR_INVALID_ARG;
+  if (g->n_nodes > 0 && (!grad_E_out || !grad_E || !aligned16(grad_E_out) || !aligned16(grad_E)))
+    return TINYKG_ERR_INVALID_ARG;
+  if (!workspace || !aligned16(workspace) || workspace_bytes < bwd_layout(g, d_in, d_out).total)
+    return TINYKG_ERR_WORKSPACE;
+  hipStream_t st = (hipStream_t)stream;
+  uint8_t* ws = static_cast<uint8_t*>(workspace);
+  switch (d_in) {
+    case 32: return bwd_bits<32>(bits, g, saved, nullptr, nullptr, W, d_out, leaky_slope, group, grad_E_out, grad_E, nullptr, nullptr, grad_W, ws, st);
+    case 64: return bwd_bits<64>(bits, g, saved, nullptr, nullptr, W, d_out, leaky_slope, group, grad_E_out, grad_E, nullptr, nullptr, grad_W, ws, st);
+    case 128: return bwd_bits<128>(bits, g, saved, nullptr, nullptr, W, d_out, leaky_slope, group, grad_E_out, grad_E, nullptr, nullptr, grad_W, ws, st);
   }
   return TINYKG_ERR_UNSUPPORTED;
 }

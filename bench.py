@@ -219,6 +219,63 @@ def compressor_sweep(a):
         "cells": cells}))
 
 
+def uniform_workload(a):
+    """The uniform-attention layer (Eq. 2 as printed, row-normalised adjacency) on the
+    configs[1] graph: no projections, so the step is bound by gathers and streams."""
+    import torch
+    import paper_2212_04540_amd as tk
+    dev = "cuda"
+    inp = make_inputs(torch)
+    t = {k: torch.from_numpy(v).to(dev) for k, v in inp.items()}
+    graph = tk.Graph(N, R, t["head"], t["rel"], t["tail"])
+    saved = tk.SavedContext(N, D, D, BITS, GROUP, with_E=False)
+    ws = torch.empty(max(tk.tinykg_kg_aggregate_workspace_bytes(graph, D, D, D, False),
+                         tk.tinykg_kg_aggregate_workspace_bytes(graph, D, D, D, True)),
+                     dtype=torch.uint8, device=dev)
+    E_out = torch.empty((N, D), dtype=torch.float32, device=dev)
+    grads = (torch.empty((N, D), dtype=torch.float32, device=dev), torch.empty_like(t["W"]))
+
+    def step(i):
+        tk.tinykg_kg_uniform_fwd(graph, t["E"], t["W"], SLOPE, BITS, GROUP, 1 + 2 * i, saved, ws, E_out=E_out)
+        tk.tinykg_kg_uniform_bwd(graph, saved, t["W"], SLOPE, BITS, GROUP, t["G"], ws, out=grads)
+
+    for i in range(a.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    tk.tinykg_profile_enable(True)
+    t0 = time.perf_counter()
+    for i in range(a.steps):
+        step(a.warmup + i)
+    torch.cuda.synchronize()
+    dt = (time.perf_counter() - t0) / a.steps
+    rep = tk.tinykg_profile_report()
+    tk.tinykg_profile_enable(False)
+    bpa = bytes_per_activation(BITS, GROUP)
+    fwd_edge, fwd_node = 4 * D + 4, 4 * D + 4 * D + D * bpa + D / 8       # e_t row + tail id; E, E', Q(H), mask
+    bwd_edge, bwd_node = 4 * D + 8, 4 * D + D * bpa + D / 8 + 4 * D       # grad_H row + ids; grad_E', H_hat, mask, grad_E
+    alg = T * (fwd_edge + bwd_edge) + N * (fwd_node + bwd_node)
+    kernels = {k: {"launches_per_step": v[0] / a.steps, "ms_per_step": round(v[1] / a.steps, 4)}
+               for k, v in rep.items()}
+    gather_ms = rep["uniform_bwd_kernel"][1] / rep["uniform_bwd_kernel"][0]
+    gather_bytes = T * bwd_edge + N * 4 * D
+    print(json.dumps({
+        "metric": "quantize+pack and dequant+agg-bwd HBM GB/s (fraction of peak); bytes/activation",
+        "value": round(alg / dt / 1e9, 2), "unit": "GB/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
+        "ms_per_step": round(dt * 1e3, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "uniform-attention layer (Eq. 2, row-normalised adjacency), forward+backward, on "
+                               "the configs[1] graph: 100k entities, dim 64, 1M triplets, saved Q(H) INT2 group 64",
+                   "bits": BITS, "group": GROUP, "bytes_per_activation": bpa,
+                   "algorithmic_bytes_per_step": alg, "saved_context_bytes": saved.nbytes()},
+        "frac_of_hbm_peak": round(alg / dt / 1e9 / HBM_PEAK_GBS, 5),
+        "roofline": {"kernel": "uniform_bwd_kernel", "bound": "hbm",
+                     "achieved": round(gather_bytes / (gather_ms * 1e-3) / 1e9, 1), "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": round(gather_bytes / (gather_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+                     "traffic": None, "avg_launch_ms": round(gather_ms, 4)},
+        "kernels": kernels}))
+    graph.close()
+
+
 def stack_workload(a, which):
     """configs[3] / configs[4]: a stack of layers, forward + ranking loss + backward.
     Reported for the step time and the saved-activation footprint; not the default."""
@@ -294,9 +351,10 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-compressor", action="store_true")
-    ap.add_argument("--workload", choices=["config1", "config2", "config3", "config4"], default="config1",
+    ap.add_argument("--workload", choices=["config1", "config2", "config3", "config4", "uniform"], default="config1",
                     help="config1 (default, the headline step); config2: the 9-cell compressor sweep; "
-                         "config3 / config4: multi-layer steps")
+                         "config3 / config4: multi-layer steps; uniform: the uniform-attention "
+                         "layer on the config1 graph")
     ap.add_argument("--bits", type=int, default=0, help="config4 only: 4 (default) or 32 for the fp32 run")
     a = ap.parse_args()
     if a.gpus != 1:
@@ -310,6 +368,8 @@ def main():
     tk.lib()
     if a.workload == "config2":
         return compressor_sweep(a)
+    if a.workload == "uniform":
+        return uniform_workload(a)
     if a.workload != "config1":
         return stack_workload(a, a.workload)
     dev = "cuda"

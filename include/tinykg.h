@@ -81,6 +81,15 @@ tinykg_status tinykg_quantize_ex(const float* act, int64_t rows, int64_t dim, in
                                  uint64_t seed, uint64_t first_index, int rounding,
                                  uint8_t* packed, float* gmin, float* gscale, void* stream);
 
+/* The same quantizer for bfloat16 activations (Sec. 4.1.4: half-precision inputs are
+ * supported, for mixed-precision training).  act: [rows, dim] bfloat16 (the upper 16 bits
+ * of an fp32 value), DEVICE.  Every value is widened to fp32 exactly and then quantized
+ * as above, so packed / gmin / gscale are byte for byte those of tinykg_quantize_ex on the
+ * widened fp32 tensor.  Other arguments, limits and errors as tinykg_quantize_ex. */
+tinykg_status tinykg_quantize_bf16(const uint16_t* act, int64_t rows, int64_t dim, int bits,
+                                   int group, uint64_t seed, uint64_t first_index, int rounding,
+                                   uint8_t* packed, float* gmin, float* gscale, void* stream);
+
 /* Dequant of Sec. 3.3, Eq. (4): out[i] = fma(code_i, gscale[i/group], gmin[i/group])
  * (R * code / B + Z with scale = R / B, one rounding).  Arguments as above;
  * out is [rows, dim] fp32. */

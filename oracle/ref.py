@@ -352,3 +352,17 @@ def uniform_bwd(n_nodes, head, tail, Hhat, mask, W, slope, gEout):
     gH = gJ @ np.asarray(W, dtype=np.float64)
     gE = gH + A.T @ gH
     return gE.astype(np.float32), gW.astype(np.float32)
+
+
+# ------------------------------------------------ bfloat16 activations ------
+def widen_bf16(act_u16):
+    """bfloat16 bit patterns (uint16) -> the fp32 values they denote (exact: bfloat16 is
+    the upper half of an fp32)."""
+    a = np.ascontiguousarray(act_u16, dtype=np.uint16)
+    return (a.astype(np.uint32) << np.uint32(16)).view(np.float32)
+
+
+def quantize_bf16(act_u16, bits, group, seed, first_index=0, rounding=0):
+    """Quant of Eq. (3) for half-precision inputs (Sec. 4.1.4): the fp32 quantizer applied to
+    the exactly widened values."""
+    return quantize(widen_bf16(act_u16), bits, group, seed, first_index, rounding)

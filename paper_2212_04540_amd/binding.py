@@ -19,7 +19,7 @@ ROUND_NEAREST = 1
 
 EXPORTS = [
     "tinykg_status_string", "tinykg_packed_bytes", "tinykg_num_groups", "tinykg_quantize",
-    "tinykg_quantize_ex", "tinykg_dequantize", "tinykg_graph_create", "tinykg_graph_destroy",
+    "tinykg_quantize_ex", "tinykg_quantize_bf16", "tinykg_dequantize", "tinykg_graph_create", "tinykg_graph_destroy",
     "tinykg_graph_num_nodes", "tinykg_graph_num_edges", "tinykg_kg_aggregate_workspace_bytes",
     "tinykg_kg_aggregate_fwd", "tinykg_kg_aggregate_bwd", "tinykg_kg_uniform_fwd",
     "tinykg_kg_uniform_bwd", "tinykg_profile_enable",
@@ -59,6 +59,7 @@ def lib():
         L.tinykg_num_groups.restype = i64
         L.tinykg_quantize.argtypes = [vp, i64, i64, i32, i32, u64, vp, vp, vp, vp]
         L.tinykg_quantize_ex.argtypes = [vp, i64, i64, i32, i32, u64, u64, i32, vp, vp, vp, vp]
+        L.tinykg_quantize_bf16.argtypes = [vp, i64, i64, i32, i32, u64, u64, i32, vp, vp, vp, vp]
         L.tinykg_dequantize.argtypes = [vp, vp, vp, i64, i64, i32, i32, vp, vp]
         if hasattr(L, "tinykg_graph_create"):
             L.tinykg_graph_create.argtypes = [i64, C.c_int32, i64, vp, vp, vp, vp, C.POINTER(vp)]
@@ -343,3 +344,17 @@ def tinykg_kg_uniform_bwd(graph, saved, W, leaky_slope, bits, group, grad_E_out,
                                      _ptr(gW), _ptr(workspace), workspace.numel(), _stream())
     _ok(st, "tinykg_kg_uniform_bwd")
     return gE, gW
+
+
+def tinykg_quantize_bf16(act, bits, group, seed, out=None, first_index=0, rounding=ROUND_STOCHASTIC):
+    """act: [rows, dim] torch.bfloat16 on the device."""
+    _dev(act, torch.bfloat16, "act")
+    rows, dim = act.shape
+    if out is None:
+        out = alloc_quantized(rows, dim, bits, group, act.device)
+    packed, gmin, gscale = out
+    st = lib().tinykg_quantize_bf16(_ptr(act), rows, dim, bits, group, C.c_uint64(seed),
+                                    C.c_uint64(first_index), rounding, _ptr(packed), _ptr(gmin),
+                                    _ptr(gscale), _stream())
+    _ok(st, "tinykg_quantize_bf16")
+    return packed, gmin, gscale

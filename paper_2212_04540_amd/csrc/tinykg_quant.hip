@@ -156,9 +156,12 @@ __device__ __forceinline__ uint32_t place_high_half(uint32_t S, uint32_t pos) {
   return r;
 }
 
-template <int BITS, int GROUP, int ROUNDING>
+// IN = float: fp32 activations.  IN = uint16_t: bfloat16 activations (Sec. 4.1.4: half-precision
+// inputs, for mixed-precision training); each value is widened to fp32 exactly and then takes
+// the same path, so the output is that of the fp32 quantizer on the widened tensor.
+template <typename IN, int BITS, int GROUP, int ROUNDING>
 __global__ __launch_bounds__(kBlock) void quantize_kernel(
-    const float* __restrict__ act, int64_t n, uint32_t seed_lo, uint32_t seed_hi,
+    const IN* __restrict__ act, int64_t n, uint32_t seed_lo, uint32_t seed_hi,
     uint64_t first_index, uint8_t* __restrict__ packed, float* __restrict__ gmin,
     float* __restrict__ gscale) {
   constexpr int LPG = GROUP / kElemsPerLane;       // lanes per group
@@ -173,13 +176,26 @@ __global__ __launch_bounds__(kBlock) void quantize_kernel(
   float4* my = slab[wave];
 
   // kTilesPerWave consecutive tiles per wave; all their loads are issued up front
+  constexpr bool kBf16 = std::is_same<IN, uint16_t>::value;
   const int64_t tile0 = ((int64_t)blockIdx.x * kWavesPerBlock + wave) * kTilesPerWave;
   if (tile0 * kTileElems >= n) return;
   float4 v[kTilesPerWave][4];
+  uint4 hv[kTilesPerWave][2];   // bf16: the lane's 16 elements are 32 contiguous bytes, loaded directly
 #pragma unroll
   for (int tt = 0; tt < kTilesPerWave; ++tt) {
+    if constexpr (kBf16) {
+      const int64_t e = (tile0 + tt) * kTileElems + (int64_t)lane * kElemsPerLane;
+      hv[tt][0] = make_uint4(0u, 0u, 0u, 0u); hv[tt][1] = hv[tt][0];
+      if (e < n) {      // n and e are multiples of 16: the lane's 16 elements are all in range
+        const floatx4* src = reinterpret_cast<const floatx4*>(act + e);
+        const floatx4 q0 = __builtin_nontemporal_load(src), q1 = __builtin_nontemporal_load(src + 1);
+        hv[tt][0] = make_uint4(__float_as_uint(q0.x), __float_as_uint(q0.y), __float_as_uint(q0.z), __float_as_uint(q0.w));
+        hv[tt][1] = make_uint4(__float_as_uint(q1.x), __float_as_uint(q1.y), __float_as_uint(q1.z), __float_as_uint(q1.w));
+      }
+      continue;
+    }
     const int64_t tile = tile0 + tt;
-    const float4* src = reinterpret_cast<const float4*>(act) + tile * (kTileElems / 4) + lane;
+    const float4* src = reinterpret_cast<const float4*>(reinterpret_cast<const float*>(act)) + tile * (kTileElems / 4) + lane;
     if ((tile + 1) * kTileElems <= n) {          // whole tile in range (wave-uniform)
 #pragma unroll
       for (int u = 0; u < 4; ++u) v[tt][u] = load_stream(src + u * kWave);
@@ -197,19 +213,29 @@ __global__ __launch_bounds__(kBlock) void quantize_kernel(
   if (tile * kTileElems >= n) break;
   const int64_t e0 = tile * kTileElems + (int64_t)lane * kElemsPerLane;  // lane's first element
   // stage the tile row-wise (coalesced order) into the swizzled slab
-  // (slab_slot(u * 64 + lane) = u * 64 + slab_slot(lane): the swizzle only depends on
-  // bits 3..5 of the chunk index and only changes bits 0..1)
-  const int wslot = slab_slot(lane);
-#pragma unroll
-  for (int u = 0; u < 4; ++u) my[u * kWave + wslot] = v[tt][u];
-  // lane-contiguous read-back: elements [16*lane, 16*lane+16) of the tile
-  // (slab_slot(4 * lane + j) = slab_slot(4 * lane) ^ j for j < 4)
-  const int rslot = slab_slot(4 * lane);
   float x[kElemsPerLane];
+  if constexpr (kBf16) {
+    const uint32_t w[8] = {hv[tt][0].x, hv[tt][0].y, hv[tt][0].z, hv[tt][0].w,
+                           hv[tt][1].x, hv[tt][1].y, hv[tt][1].z, hv[tt][1].w};
 #pragma unroll
-  for (int j = 0; j < 4; ++j) {
-    const float4 r4 = my[rslot ^ j];
-    x[4 * j + 0] = r4.x; x[4 * j + 1] = r4.y; x[4 * j + 2] = r4.z; x[4 * j + 3] = r4.w;
+    for (int j = 0; j < 8; ++j) {       // bf16 -> fp32 is a 16-bit shift: exact
+      x[2 * j + 0] = __uint_as_float(w[j] << 16);
+      x[2 * j + 1] = __uint_as_float(w[j] & 0xFFFF0000u);
+    }
+  } else {
+    // (slab_slot(u * 64 + lane) = u * 64 + slab_slot(lane): the swizzle only depends on
+    // bits 3..5 of the chunk index and only changes bits 0..1)
+    const int wslot = slab_slot(lane);
+#pragma unroll
+    for (int u = 0; u < 4; ++u) my[u * kWave + wslot] = v[tt][u];
+    // lane-contiguous read-back: elements [16*lane, 16*lane+16) of the tile
+    // (slab_slot(4 * lane + j) = slab_slot(4 * lane) ^ j for j < 4)
+    const int rslot = slab_slot(4 * lane);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const float4 r4 = my[rslot ^ j];
+      x[4 * j + 0] = r4.x; x[4 * j + 1] = r4.y; x[4 * j + 2] = r4.z; x[4 * j + 3] = r4.w;
+    }
   }
   const bool live = e0 < n;
 
@@ -365,8 +391,8 @@ int ilog2(int v) {
   return l;
 }
 
-template <int BITS, int ROUNDING>
-tinykg_status launch_quantize_g(const float* act, int64_t n, int group, uint64_t seed,
+template <typename IN, int BITS, int ROUNDING>
+tinykg_status launch_quantize_g(const IN* act, int64_t n, int group, uint64_t seed,
                                 uint64_t first_index, uint8_t* packed, float* gmin, float* gscale,
                                 hipStream_t stream) {
   const int64_t n_tiles = (n + kTileElems - 1) / kTileElems;
@@ -377,7 +403,7 @@ tinykg_status launch_quantize_g(const float* act, int64_t n, int group, uint64_t
   const uint32_t lo = (uint32_t)seed, hi = (uint32_t)(seed >> 32);
   ProfileScope prof("quantize_kernel", stream);
 #define TINYKG_Q_LAUNCH(G)                                                                   \
-  hipLaunchKernelGGL((quantize_kernel<BITS, G, ROUNDING>), grid, dim3(kBlock), 0, stream, act, n, \
+  hipLaunchKernelGGL((quantize_kernel<IN, BITS, G, ROUNDING>), grid, dim3(kBlock), 0, stream, act, n, \
                      lo, hi, first_index, packed, gmin, gscale)
   switch (group) {
     case 32: TINYKG_Q_LAUNCH(32); break;
@@ -390,15 +416,15 @@ tinykg_status launch_quantize_g(const float* act, int64_t n, int group, uint64_t
   return launch_status();
 }
 
-template <int ROUNDING>
-tinykg_status launch_quantize_b(const float* act, int64_t n, int bits, int group, uint64_t seed,
+template <typename IN, int ROUNDING>
+tinykg_status launch_quantize_b(const IN* act, int64_t n, int bits, int group, uint64_t seed,
                                 uint64_t first_index, uint8_t* packed, float* gmin, float* gscale,
                                 hipStream_t stream) {
   switch (bits) {
-    case 1: return launch_quantize_g<1, ROUNDING>(act, n, group, seed, first_index, packed, gmin, gscale, stream);
-    case 2: return launch_quantize_g<2, ROUNDING>(act, n, group, seed, first_index, packed, gmin, gscale, stream);
-    case 4: return launch_quantize_g<4, ROUNDING>(act, n, group, seed, first_index, packed, gmin, gscale, stream);
-    case 8: return launch_quantize_g<8, ROUNDING>(act, n, group, seed, first_index, packed, gmin, gscale, stream);
+    case 1: return launch_quantize_g<IN, 1, ROUNDING>(act, n, group, seed, first_index, packed, gmin, gscale, stream);
+    case 2: return launch_quantize_g<IN, 2, ROUNDING>(act, n, group, seed, first_index, packed, gmin, gscale, stream);
+    case 4: return launch_quantize_g<IN, 4, ROUNDING>(act, n, group, seed, first_index, packed, gmin, gscale, stream);
+    case 8: return launch_quantize_g<IN, 8, ROUNDING>(act, n, group, seed, first_index, packed, gmin, gscale, stream);
     default: return TINYKG_ERR_INVALID_ARG;
   }
 }
@@ -418,9 +444,10 @@ int num_cus() {
   return cached;
 }
 
-tinykg_status launch_quantize(const float* act, int64_t n, int bits, int group, uint64_t seed,
-                              uint64_t first_index, int rounding, uint8_t* packed, float* gmin,
-                              float* gscale, hipStream_t stream) {
+template <typename IN>
+tinykg_status launch_quantize_any(const IN* act, int64_t n, int bits, int group, uint64_t seed,
+                                  uint64_t first_index, int rounding, uint8_t* packed, float* gmin,
+                                  float* gscale, hipStream_t stream) {
   if (!bits_ok(bits) || !group_ok(group)) return TINYKG_ERR_INVALID_ARG;
   if (rounding != TINYKG_ROUND_STOCHASTIC && rounding != TINYKG_ROUND_NEAREST)
     return TINYKG_ERR_INVALID_ARG;
@@ -430,10 +457,17 @@ tinykg_status launch_quantize(const float* act, int64_t n, int bits, int group, 
   if (!aligned16(act) || !aligned16(packed) || !aligned16(gmin) || !aligned16(gscale))
     return TINYKG_ERR_INVALID_ARG;
   if (rounding == TINYKG_ROUND_STOCHASTIC)
-    return launch_quantize_b<TINYKG_ROUND_STOCHASTIC>(act, n, bits, group, seed, first_index,
-                                                      packed, gmin, gscale, stream);
-  return launch_quantize_b<TINYKG_ROUND_NEAREST>(act, n, bits, group, seed, first_index, packed,
-                                                 gmin, gscale, stream);
+    return launch_quantize_b<IN, TINYKG_ROUND_STOCHASTIC>(act, n, bits, group, seed, first_index,
+                                                          packed, gmin, gscale, stream);
+  return launch_quantize_b<IN, TINYKG_ROUND_NEAREST>(act, n, bits, group, seed, first_index, packed,
+                                                     gmin, gscale, stream);
+}
+
+tinykg_status launch_quantize(const float* act, int64_t n, int bits, int group, uint64_t seed,
+                              uint64_t first_index, int rounding, uint8_t* packed, float* gmin,
+                              float* gscale, hipStream_t stream) {
+  return launch_quantize_any<float>(act, n, bits, group, seed, first_index, rounding, packed, gmin,
+                                    gscale, stream);
 }
 
 tinykg_status launch_dequantize(const uint8_t* packed, const float* gmin, const float* gscale,
@@ -503,6 +537,15 @@ tinykg_status tinykg_quantize(const float* act, int64_t rows, int64_t dim, int b
                               void* stream) {
   return tinykg_quantize_ex(act, rows, dim, bits, group, seed, 0, TINYKG_ROUND_STOCHASTIC, packed,
                             gmin, gscale, stream);
+}
+
+tinykg_status tinykg_quantize_bf16(const uint16_t* act, int64_t rows, int64_t dim, int bits,
+                                   int group, uint64_t seed, uint64_t first_index, int rounding,
+                                   uint8_t* packed, float* gmin, float* gscale, void* stream) {
+  if (rows < 0 || dim < 0) return TINYKG_ERR_SHAPE;
+  if (rows != 0 && dim > INT64_MAX / rows) return TINYKG_ERR_SHAPE;
+  return tinykg::launch_quantize_any<uint16_t>(act, rows * dim, bits, group, seed, first_index,
+                                               rounding, packed, gmin, gscale, (hipStream_t)stream);
 }
 
 tinykg_status tinykg_dequantize(const uint8_t* packed, const float* gmin, const float* gscale,

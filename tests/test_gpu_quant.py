@@ -275,3 +275,26 @@ def test_config2_full_size_sweep(tk):
             assert np.all(var <= gsc ** 2 / 4 * (1 + 1e-4) + 1e-30), (bits, group)
             ratio = var.sum() / closed.sum()
             assert 0.97 < ratio < 1.03, (bits, group, ratio)
+
+
+def test_bf16_inputs_give_the_codes_of_the_widened_tensor(tk):
+    # Sec. 4.1.4: half-precision activations.  The kernel widens bfloat16 exactly, so its
+    # output must be byte for byte the oracle's on the widened values.
+    g = torch.Generator(device="cuda"); g.manual_seed(3)
+    for rows, dim, bits, group in [(4096, 64, 2, 64), (1000, 32, 4, 32), (333, 256, 8, 256), (7, 128, 1, 128),
+                                   (5000, 64, 2, 256)]:
+        xb = (torch.randn((rows, dim), generator=g, device="cuda") * 3).to(torch.bfloat16)
+        got = tk.tinykg_quantize_bf16(xb, bits, group, 11)
+        torch.cuda.synchronize()
+        bits16 = xb.view(torch.int16).cpu().numpy().view(np.uint16)
+        want = ref.quantize_bf16(bits16, bits, group, 11)
+        assert_same(tuple(a.cpu().numpy() for a in got), want, f"bf16 {rows}x{dim} b{bits} g{group}")
+        same = tk.tinykg_quantize(xb.float(), bits, group, 11)     # and of the fp32 kernel on the widened tensor
+        assert all(torch.equal(a, b) for a, b in zip(got, same))
+    # a slice of a long tensor: first_index, nearest rounding
+    xb = torch.randn((1 << 16, 64), generator=g, device="cuda").to(torch.bfloat16)
+    r0 = 4096 * 5
+    got = tk.tinykg_quantize_bf16(xb[r0:r0 + 128].contiguous(), 2, 64, 3, first_index=r0 * 64, rounding=tk.ROUND_NEAREST)
+    full = tk.tinykg_quantize_bf16(xb, 2, 64, 3, rounding=tk.ROUND_NEAREST)
+    torch.cuda.synchronize()
+    assert torch.equal(got[0], full[0][r0 * 16:(r0 + 128) * 16]) and torch.equal(got[1], full[1][r0:r0 + 128])

@@ -345,3 +345,20 @@ def test_probability_of_rounding_up_by_enumeration():
         ups += (c == 2)
     for f, u in zip(fracs, ups):
         assert abs(u / S - f) < 5 * np.sqrt(f * (1 - f) / S)
+
+
+def test_bf16_widening_matches_the_library_conversion():
+    # the oracle's bfloat16 path = fp32 quantizer on exactly widened values; the widening is
+    # pinned against torch's own bfloat16 -> float32 conversion on every finite bit pattern
+    torch = pytest.importorskip("torch")
+    bits16 = np.arange(65536, dtype=np.uint16)
+    wide = ref.widen_bf16(bits16)
+    t = torch.from_numpy(bits16.view(np.int16).copy()).view(torch.bfloat16).float().numpy()
+    finite = np.isfinite(t)
+    assert np.array_equal(wide[finite].view(np.uint32), t[finite].view(np.uint32))
+    x = wide[finite][::16][:4096].reshape(64, 64)
+    x = np.clip(x, -1e30, 1e30).astype(np.float32)
+    xb = (x.view(np.uint32) >> 16).astype(np.uint16)
+    a = ref.quantize_bf16(xb, 2, 64, 5)
+    b = ref.quantize(ref.widen_bf16(xb), 2, 64, 5)
+    assert all(np.array_equal(u, v) for u, v in zip(a, b))

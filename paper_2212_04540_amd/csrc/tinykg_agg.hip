@@ -609,17 +609,19 @@ __global__ __launch_bounds__(kThreads) void heavy_part1_kernel(const float* __re
   }
 }
 
-// Per heavy head: M, Z (-> hm, hz) and, WITH_ACC, H_h = e_h + acc / Z.
+// Per heavy head (one workgroup of kMergeWaves waves): M, Z (-> hm, hz) and, WITH_ACC,
+// H_h = e_h + acc / Z.  Wave w sums the segments a + w, a + w + kMergeWaves, ... in double;
+// the waves' sums are then added in the order 0, 1, ... (fixed, so H is reproducible).
+constexpr int kMergeWaves = 16;
+
 template <int D, bool WITH_ACC>
-__global__ __launch_bounds__(kThreads) void heavy_merge1_kernel(const float* __restrict__ E, HeavyList hl,
-                                                                const float* __restrict__ pm,
-                                                                const double* __restrict__ pz,
-                                                                const double* __restrict__ pacc,
-                                                                float* __restrict__ hm, double* __restrict__ hz,
-                                                                float* __restrict__ H) {
-  const int lane = threadIdx.x & 63;
-  const int q = blockIdx.x * (kThreads / 64) + (threadIdx.x >> 6);
-  if (q >= hl.n_heavy) return;
+__global__ __launch_bounds__(kMergeWaves * 64) void heavy_merge1_kernel(
+    const float* __restrict__ E, HeavyList hl, const float* __restrict__ pm,
+    const double* __restrict__ pz, const double* __restrict__ pacc, float* __restrict__ hm,
+    double* __restrict__ hz, float* __restrict__ H) {
+  __shared__ double part[kMergeWaves][D];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int q = blockIdx.x;
   const int a = hl.seg_ptr[q], b = hl.seg_ptr[q + 1];
   float M = -INFINITY;
   for (int i = a + lane; i < b; i += 64) M = fmaxf(M, pm[i]);
@@ -627,13 +629,34 @@ __global__ __launch_bounds__(kThreads) void heavy_merge1_kernel(const float* __r
   double Z = 0.0;
   for (int i = a + lane; i < b; i += 64) Z += pz[i] * (double)expf(pm[i] - M);
   Z = wave_sum(Z);
-  if (lane == 0) { hm[q] = M; hz[q] = Z; }
+  if (threadIdx.x == 0) { hm[q] = M; hz[q] = Z; }
   if (WITH_ACC) {
-    const int64_t h = hl.head[q];
     for (int i = lane; i < D; i += 64) {
       double acc = 0.0;
-      for (int sgi = a; sgi < b; ++sgi) acc += pacc[(int64_t)sgi * D + i] * (double)expf(pm[sgi] - M);
-      H[h * D + i] = (float)((double)E[h * D + i] + acc / Z);
+      int sgi = a + wave;
+      for (; sgi + 3 * kMergeWaves < b; sgi += 4 * kMergeWaves) {      // four loads in flight
+        const double p0 = pacc[(int64_t)sgi * D + i], p1 = pacc[(int64_t)(sgi + kMergeWaves) * D + i];
+        const double p2 = pacc[(int64_t)(sgi + 2 * kMergeWaves) * D + i];
+        const double p3 = pacc[(int64_t)(sgi + 3 * kMergeWaves) * D + i];
+        const float m0 = pm[sgi], m1 = pm[sgi + kMergeWaves], m2 = pm[sgi + 2 * kMergeWaves];
+        const float m3 = pm[sgi + 3 * kMergeWaves];
+        acc += p0 * (double)expf(m0 - M);
+        acc += p1 * (double)expf(m1 - M);
+        acc += p2 * (double)expf(m2 - M);
+        acc += p3 * (double)expf(m3 - M);
+      }
+      for (; sgi < b; sgi += kMergeWaves) acc += pacc[(int64_t)sgi * D + i] * (double)expf(pm[sgi] - M);
+      part[wave][i] = acc;
+    }
+    __syncthreads();
+    if (wave == 0) {
+      const int64_t h = hl.head[q];
+      for (int i = lane; i < D; i += 64) {
+        double acc = 0.0;
+#pragma unroll
+        for (int w = 0; w < kMergeWaves; ++w) acc += part[w][i];
+        H[h * D + i] = (float)((double)E[h * D + i] + acc / Z);
+      }
     }
   }
 }
@@ -1729,7 +1752,7 @@ tinykg_status fwd_impl(const tinykg_graph* g, const float* E, const float* Wr, c
     ProfileScope prof("heavy_head_kernels", st);
     hipLaunchKernelGGL((heavy_part1_kernel<D, true>), dim3((g->n_hseg + 3) / 4), dim3(kThreads), 0, st, E,
                        g->h_tail, s, hl, pm, pz, pacc);
-    hipLaunchKernelGGL((heavy_merge1_kernel<D, true>), dim3((g->n_heavy + 3) / 4), dim3(kThreads), 0, st, E,
+    hipLaunchKernelGGL((heavy_merge1_kernel<D, true>), dim3(g->n_heavy), dim3(kMergeWaves * 64), 0, st, E,
                        hl, pm, pz, pacc, hm, hz, H);
     if ((rc = launch_status()) != TINYKG_OK) return rc;
   }
@@ -1835,10 +1858,10 @@ tinykg_status bwd_impl(const tinykg_graph* g, const tinykg_saved* sv, const floa
       float* hm = reinterpret_cast<float*>(ws + L.hv.hm);
       double* hz = reinterpret_cast<double*>(ws + L.hv.hz);
       ProfileScope prof("heavy_head_kernels", st);
-      const dim3 gs_grid((g->n_hseg + 3) / 4), gh_grid((g->n_heavy + 3) / 4);
+      const dim3 gs_grid((g->n_hseg + 3) / 4), gh_grid(g->n_heavy);
       hipLaunchKernelGGL((heavy_part1_kernel<D, false>), gs_grid, dim3(kThreads), 0, st,
                          (const float*)nullptr, g->h_tail, s, hl, pm, pz, (double*)nullptr);
-      hipLaunchKernelGGL((heavy_merge1_kernel<D, false>), gh_grid, dim3(kThreads), 0, st,
+      hipLaunchKernelGGL((heavy_merge1_kernel<D, false>), gh_grid, dim3(kMergeWaves * 64), 0, st,
                          (const float*)nullptr, hl, pm, pz, (const double*)nullptr, hm, hz, (float*)nullptr);
       hipLaunchKernelGGL((heavy_part2_kernel<D, BITS>), gs_grid, dim3(kThreads), 0, st, srcE, gH, g->h_tail,
                          s, hl, hm, hz, pi, gs, pc);

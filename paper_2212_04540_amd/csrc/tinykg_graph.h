@@ -41,7 +41,7 @@ struct tinykg_graph {
 };
 
 namespace tinykg {
-constexpr int kHeavyDegree = 1024;
+constexpr int kHeavyDegree = 256;
 constexpr int kAccHeavyDegree = 1024;
 constexpr int kNodeIdMask = 0x3fffffff;   // bits 30, 31 of a staged node id carry flags
 }

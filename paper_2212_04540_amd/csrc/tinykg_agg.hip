@@ -477,17 +477,19 @@ __global__ __launch_bounds__(kThreads) void attend_fwd_kernel(const float* __res
   for (int64_t h = (int64_t)blockIdx.x * (kThreads / 64) + (threadIdx.x >> 6); h < N; h += n_waves) {
     const int e0 = rowptr[h], deg = rowptr[h + 1] - e0;
     if (deg > kHeavyDegree) continue;   // handled segment-wise by the heavy_* kernels
-    double ax = 0.0, ay = 0.0, az = 0.0, aw = 0.0;
+    // at most kHeavyDegree terms per slot: fp32 sums (longer neighbourhoods take the
+    // segment kernels, which sum in double)
+    float ax = 0.f, ay = 0.f, az = 0.f, aw = 0.f;
     if (deg > 0) {
       float m, z;
       softmax_stats(s, e0, deg, lane, m, z);
       for (int base = 0; base < deg; base += ES) {
         const int j = base + sub;
         if (j < deg) {
-          const double p = (double)(expf(s[e0 + j] - m) / z);
+          const float p = expf(s[e0 + j] - m) / z;
           const float4 x = E4[(int64_t)h_tail[e0 + j] * LPR + li];
-          ax = fma(p, (double)x.x, ax); ay = fma(p, (double)x.y, ay);
-          az = fma(p, (double)x.z, az); aw = fma(p, (double)x.w, aw);
+          ax = fmaf(p, x.x, ax); ay = fmaf(p, x.y, ay);
+          az = fmaf(p, x.z, az); aw = fmaf(p, x.w, aw);
         }
       }
 #pragma unroll
@@ -499,8 +501,7 @@ __global__ __launch_bounds__(kThreads) void attend_fwd_kernel(const float* __res
     if (sub == 0) {
       const float4 eh = E4[h * LPR + li];
       reinterpret_cast<float4*>(H)[h * LPR + li] =
-          make_float4((float)((double)eh.x + ax), (float)((double)eh.y + ay),
-                      (float)((double)eh.z + az), (float)((double)eh.w + aw));
+          make_float4(eh.x + ax, eh.y + ay, eh.z + az, eh.w + aw);
     }
   }
 }
@@ -522,7 +523,7 @@ __global__ __launch_bounds__(kThreads) void attend_bwd_kernel(Source src, const 
     float m, z;
     softmax_stats(s, e0, deg, lane, m, z);
     const float4 g4 = reinterpret_cast<const float4*>(gH)[h * LPR + li];
-    double cpart = 0.0;
+    float cpart = 0.f;   // at most kHeavyDegree terms: fp32
     for (int base = 0; base < deg; base += ES) {
       const int j = base + sub;
       float dot = 0.f, p = 0.f;
@@ -534,14 +535,13 @@ __global__ __launch_bounds__(kThreads) void attend_bwd_kernel(Source src, const 
 #pragma unroll
       for (int o = 1; o < LPR; o <<= 1) dot += __shfl_xor(dot, o);   // g_j on every lane of the slot
       if (j < deg) {
-        cpart = fma((double)p, (double)dot, cpart);
+        cpart = fmaf(p, dot, cpart);
         if (li == 0) { pi[e0 + j] = p; gs[e0 + j] = dot; }
       }
     }
-    double cd = cpart;   // equal on the lanes of a slot: sum once per slot
+    float c = cpart;     // equal on the lanes of a slot: sum once per slot
 #pragma unroll
-    for (int o = LPR; o < 64; o <<= 1) cd += __shfl_xor(cd, o);
-    const float c = (float)cd;
+    for (int o = LPR; o < 64; o <<= 1) c += __shfl_xor(c, o);
     // grad_s_j = pi_j (g_j - sum_j' pi_j' g_j'); each lane re-reads what it wrote itself
     for (int base = 0; base < deg; base += ES) {
       const int j = base + sub;

@@ -924,8 +924,15 @@ __global__ __launch_bounds__(256) void reduce_segments_kernel(const float* __res
   const int p0 = seg_ptr ? seg_ptr[seg] : 0, p1 = seg_ptr ? seg_ptr[seg + 1] : n_single;
   const int j = blockIdx.x * 64 + (threadIdx.x & 63), k = threadIdx.x >> 6;
   double s = 0.0;
-  if (j < stride)
-    for (int p = p0 + k; p < p1; p += 4) s += (double)part[(size_t)p * stride + j];
+  if (j < stride) {
+    int p = p0 + k;
+    for (; p + 12 < p1; p += 16) {      // four loads in flight, added in the same order
+      const float a = part[(size_t)p * stride + j], b = part[(size_t)(p + 4) * stride + j];
+      const float c = part[(size_t)(p + 8) * stride + j], d = part[(size_t)(p + 12) * stride + j];
+      s += (double)a; s += (double)b; s += (double)c; s += (double)d;
+    }
+    for (; p < p1; p += 4) s += (double)part[(size_t)p * stride + j];
+  }
   red[k][threadIdx.x & 63] = s;
   __syncthreads();
   if (k == 0 && j < stride)

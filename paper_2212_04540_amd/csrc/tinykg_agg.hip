@@ -433,6 +433,23 @@ __global__ __launch_bounds__(kThreads) void score_wave_kernel(Source src, const 
 }
 
 // ---------------------------------------------------------- per-head stages ----
+// Sum over the LPR (8, 16 or 32) adjacent lanes that share one edge, result on every one
+// of them: DPP steps inside a row of 16 lanes (after each step the reduced sub-block is
+// uniform, so a mirror pairs it with its neighbour), one cross-lane exchange for 32.
+template <int CTRL>
+__device__ __forceinline__ float dpp_f(float v) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xF, 0xF, true));
+}
+template <int LPR>
+__device__ __forceinline__ float slot_sum(float v) {
+  v += dpp_f<0xB1>(v);                    // quad_perm:[1,0,3,2]
+  v += dpp_f<0x4E>(v);                    // quad_perm:[2,3,0,1]
+  if (LPR >= 8) v += dpp_f<0x141>(v);     // row_half_mirror
+  if (LPR >= 16) v += dpp_f<0x140>(v);    // row_mirror
+  if (LPR >= 32) v += __shfl_xor(v, 16);
+  return v;
+}
+
 __device__ __forceinline__ float wave_max(float v) {
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o));
@@ -532,8 +549,7 @@ __global__ __launch_bounds__(kThreads) void attend_bwd_kernel(Source src, const 
         const float4 x = fetch_chunk<BITS>(src, (int64_t)h_tail[e0 + j] * LPR + li);
         dot = fmaf(g4.x, x.x, fmaf(g4.y, x.y, fmaf(g4.z, x.z, g4.w * x.w)));
       }
-#pragma unroll
-      for (int o = 1; o < LPR; o <<= 1) dot += __shfl_xor(dot, o);   // g_j on every lane of the slot
+      dot = slot_sum<LPR>(dot);   // g_j on every lane of the slot
       if (j < deg) {
         cpart = fmaf(p, dot, cpart);
         if (li == 0) { pi[e0 + j] = p; gs[e0 + j] = dot; }
@@ -689,8 +705,7 @@ __global__ __launch_bounds__(kThreads) void heavy_part2_kernel(Source src, const
       const float4 x = fetch_chunk<BITS>(src, (int64_t)h_tail[e0 + j] * LPR + li);
       dot = fmaf(g4.x, x.x, fmaf(g4.y, x.y, fmaf(g4.z, x.z, g4.w * x.w)));
     }
-#pragma unroll
-    for (int o = 1; o < LPR; o <<= 1) dot += __shfl_xor(dot, o);
+    dot = slot_sum<LPR>(dot);
     if (j < cnt) {
       cpart = fma((double)p, (double)dot, cpart);
       if (li == 0) { pi[e0 + j] = p; gs[e0 + j] = dot; }

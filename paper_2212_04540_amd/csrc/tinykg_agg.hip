@@ -467,18 +467,36 @@ __device__ __forceinline__ double wave_sum(double v) {
   return v;
 }
 
-// Softmax statistics of the scores of one head's out-edges [e0, e0+deg).  Sums over
-// a head run in double: a Zipf head has 10^5 and more out-edges, and its fp32
-// running sums would lose the 1e-5 the result is held to.
+template <int LPR>
+__device__ __forceinline__ float slot_max(float v) {
+  v = fmaxf(v, dpp_f<0xB1>(v));
+  v = fmaxf(v, dpp_f<0x4E>(v));
+  if (LPR >= 8) v = fmaxf(v, dpp_f<0x141>(v));
+  if (LPR >= 16) v = fmaxf(v, dpp_f<0x140>(v));
+  if (LPR >= 32) v = fmaxf(v, __shfl_xor(v, 16));
+  return v;
+}
+
+// Softmax statistics of the scores of one head's out-edges [e0, e0+deg), by a whole wave.
+// At most kHeavyDegree terms (longer neighbourhoods take the segment kernels, which sum in
+// double): fp32 sums.
 __device__ __forceinline__ void softmax_stats(const float* __restrict__ s, int e0, int deg, int lane,
                                               float& m, float& z) {
   m = -INFINITY;
   for (int i = lane; i < deg; i += 64) m = fmaxf(m, s[e0 + i]);
   m = wave_max(m);
-  double zd = 0.0;
-  for (int i = lane; i < deg; i += 64) zd += (double)expf(s[e0 + i] - m);
-  z = (float)wave_sum(zd);
+  float zs = 0.f;
+  for (int i = lane; i < deg; i += 64) zs += expf(s[e0 + i] - m);
+  z = wave_sum(zs);
 }
+
+// The per-head kernels take 64 / LPR consecutive heads per wave and step (LPR = D / 4 lanes
+// hold one row).  A head with at most kSlotDegree out-edges is handled by ONE slot of LPR
+// lanes, so several short neighbourhoods -- the common case: the mean out-degree of a
+// knowledge graph is around ten -- advance side by side and pay the per-head latencies
+// (row pointers, statistics, dependent gathers) together.  Heads between kSlotDegree and
+// kHeavyDegree are then taken one at a time by the whole wave, 64 / LPR edges per step.
+constexpr int kSlotDegree = 16;
 
 template <int D>
 __global__ __launch_bounds__(kThreads) void attend_fwd_kernel(const float* __restrict__ E,
@@ -491,20 +509,63 @@ __global__ __launch_bounds__(kThreads) void attend_fwd_kernel(const float* __res
   const int sub = lane / LPR, li = lane % LPR;
   const int64_t n_waves = (int64_t)gridDim.x * (kThreads / 64);
   const float4* E4 = reinterpret_cast<const float4*>(E);
-  for (int64_t h = (int64_t)blockIdx.x * (kThreads / 64) + (threadIdx.x >> 6); h < N; h += n_waves) {
-    const int e0 = rowptr[h], deg = rowptr[h + 1] - e0;
-    if (deg > kHeavyDegree) continue;   // handled segment-wise by the heavy_* kernels
-    // at most kHeavyDegree terms per slot: fp32 sums (longer neighbourhoods take the
-    // segment kernels, which sum in double)
-    float ax = 0.f, ay = 0.f, az = 0.f, aw = 0.f;
-    if (deg > 0) {
+  for (int64_t h0 = ((int64_t)blockIdx.x * (kThreads / 64) + (threadIdx.x >> 6)) * ES; h0 < N;
+       h0 += n_waves * ES) {
+    const int64_t h = h0 + sub;
+    int e0 = 0, deg = 0;
+    if (h < N) { e0 = rowptr[h]; deg = rowptr[h + 1] - e0; }
+    const bool small = deg <= kSlotDegree;
+    // ---- short neighbourhoods: one slot per head
+    {
+      const int ds = small ? deg : 0;
+      float m = -INFINITY;
+      for (int j = li; j < ds; j += LPR) m = fmaxf(m, s[e0 + j]);
+      m = slot_max<LPR>(m);
+      float z = 0.f;
+      for (int j = li; j < ds; j += LPR) z += expf(s[e0 + j] - m);
+      z = slot_sum<LPR>(z);
+      if (ds == 0) { m = 0.f; z = 1.f; }
+      float ax = 0.f, ay = 0.f, az = 0.f, aw = 0.f;
+      for (int j0 = 0; j0 < kSlotDegree; j0 += 4) {
+        if (__builtin_amdgcn_ballot_w64(j0 < ds) == 0) break;
+        int t[4];
+        float sc[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {      // unused places read node 0 with weight exp(-inf) = 0
+          const bool on = j0 + u < ds;
+          t[u] = on ? h_tail[e0 + j0 + u] : 0;
+          sc[u] = on ? s[e0 + j0 + u] : -INFINITY;
+        }
+        float4 x[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) x[u] = E4[(int64_t)t[u] * LPR + li];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          const float p = expf(sc[u] - m) / z;
+          ax = fmaf(p, x[u].x, ax); ay = fmaf(p, x[u].y, ay);
+          az = fmaf(p, x[u].z, az); aw = fmaf(p, x[u].w, aw);
+        }
+      }
+      if (h < N && small) {
+        const float4 eh = E4[h * LPR + li];
+        reinterpret_cast<float4*>(H)[h * LPR + li] = make_float4(eh.x + ax, eh.y + ay, eh.z + az, eh.w + aw);
+      }
+    }
+    // ---- longer ones: the whole wave, one head at a time (heavy heads: the heavy_* kernels)
+    uint64_t pend = __builtin_amdgcn_ballot_w64(!small && deg <= kHeavyDegree && li == 0);
+    while (pend) {
+      const int leader = __builtin_amdgcn_readfirstlane(__ffsll((long long)pend) - 1);
+      pend &= pend - 1;
+      const int64_t hw = h0 + leader / LPR;
+      const int e0w = __builtin_amdgcn_readlane(e0, leader), degw = __builtin_amdgcn_readlane(deg, leader);
       float m, z;
-      softmax_stats(s, e0, deg, lane, m, z);
-      for (int base = 0; base < deg; base += ES) {
+      softmax_stats(s, e0w, degw, lane, m, z);
+      float ax = 0.f, ay = 0.f, az = 0.f, aw = 0.f;
+      for (int base = 0; base < degw; base += ES) {
         const int j = base + sub;
-        if (j < deg) {
-          const float p = expf(s[e0 + j] - m) / z;
-          const float4 x = E4[(int64_t)h_tail[e0 + j] * LPR + li];
+        if (j < degw) {
+          const float p = expf(s[e0w + j] - m) / z;
+          const float4 x = E4[(int64_t)h_tail[e0w + j] * LPR + li];
           ax = fmaf(p, x.x, ax); ay = fmaf(p, x.y, ay);
           az = fmaf(p, x.z, az); aw = fmaf(p, x.w, aw);
         }
@@ -514,11 +575,10 @@ __global__ __launch_bounds__(kThreads) void attend_fwd_kernel(const float* __res
         ax += __shfl_xor(ax, o); ay += __shfl_xor(ay, o);
         az += __shfl_xor(az, o); aw += __shfl_xor(aw, o);
       }
-    }
-    if (sub == 0) {
-      const float4 eh = E4[h * LPR + li];
-      reinterpret_cast<float4*>(H)[h * LPR + li] =
-          make_float4(eh.x + ax, eh.y + ay, eh.z + az, eh.w + aw);
+      if (sub == 0) {
+        const float4 eh = E4[hw * LPR + li];
+        reinterpret_cast<float4*>(H)[hw * LPR + li] = make_float4(eh.x + ax, eh.y + ay, eh.z + az, eh.w + aw);
+      }
     }
   }
 }
@@ -534,34 +594,92 @@ __global__ __launch_bounds__(kThreads) void attend_bwd_kernel(Source src, const 
   const int lane = threadIdx.x & 63;
   const int sub = lane / LPR, li = lane % LPR;
   const int64_t n_waves = (int64_t)gridDim.x * (kThreads / 64);
-  for (int64_t h = (int64_t)blockIdx.x * (kThreads / 64) + (threadIdx.x >> 6); h < N; h += n_waves) {
-    const int e0 = rowptr[h], deg = rowptr[h + 1] - e0;
-    if (deg == 0 || deg > kHeavyDegree) continue;   // heavy heads: heavy_* kernels
-    float m, z;
-    softmax_stats(s, e0, deg, lane, m, z);
-    const float4 g4 = reinterpret_cast<const float4*>(gH)[h * LPR + li];
-    float cpart = 0.f;   // at most kHeavyDegree terms: fp32
-    for (int base = 0; base < deg; base += ES) {
-      const int j = base + sub;
-      float dot = 0.f, p = 0.f;
-      if (j < deg) {
-        p = expf(s[e0 + j] - m) / z;
-        const float4 x = fetch_chunk<BITS>(src, (int64_t)h_tail[e0 + j] * LPR + li);
-        dot = fmaf(g4.x, x.x, fmaf(g4.y, x.y, fmaf(g4.z, x.z, g4.w * x.w)));
+  const float4* G4 = reinterpret_cast<const float4*>(gH);
+  for (int64_t h0 = ((int64_t)blockIdx.x * (kThreads / 64) + (threadIdx.x >> 6)) * ES; h0 < N;
+       h0 += n_waves * ES) {
+    const int64_t h = h0 + sub;
+    int e0 = 0, deg = 0;
+    if (h < N) { e0 = rowptr[h]; deg = rowptr[h + 1] - e0; }
+    const bool small = deg <= kSlotDegree;
+    // ---- short neighbourhoods: one slot per head; pi_j, g_j stay in registers until
+    //      c = sum pi_j g_j is known, so grad_s_j = pi_j (g_j - c) is written once
+    {
+      const int ds = small ? deg : 0;
+      float m = -INFINITY;
+      for (int j = li; j < ds; j += LPR) m = fmaxf(m, s[e0 + j]);
+      m = slot_max<LPR>(m);
+      float z = 0.f;
+      for (int j = li; j < ds; j += LPR) z += expf(s[e0 + j] - m);
+      z = slot_sum<LPR>(z);
+      if (ds == 0) { m = 0.f; z = 1.f; }
+      float4 g4 = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (ds > 0) g4 = G4[h * LPR + li];
+      float pj[kSlotDegree], gj[kSlotDegree];
+      float c = 0.f;
+#pragma unroll
+      for (int j0 = 0; j0 < kSlotDegree; j0 += 4) {
+        const bool any = __builtin_amdgcn_ballot_w64(j0 < ds) != 0;    // wave-uniform
+        int t[4];
+        float sc[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          const bool on = any && j0 + u < ds;
+          t[u] = on ? h_tail[e0 + j0 + u] : 0;
+          sc[u] = on ? s[e0 + j0 + u] : -INFINITY;
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          float dot = 0.f;
+          if (any) {
+            const float4 x = fetch_chunk<BITS>(src, (int64_t)t[u] * LPR + li);
+            dot = fmaf(g4.x, x.x, fmaf(g4.y, x.y, fmaf(g4.z, x.z, g4.w * x.w)));
+            dot = slot_sum<LPR>(dot);
+          }
+          const float p = expf(sc[u] - m) / z;     // 0 for unused places
+          pj[j0 + u] = p;
+          gj[j0 + u] = dot;
+          c = fmaf(p, dot, c);
+        }
       }
-      dot = slot_sum<LPR>(dot);   // g_j on every lane of the slot
-      if (j < deg) {
-        cpart = fmaf(p, dot, cpart);
-        if (li == 0) { pi[e0 + j] = p; gs[e0 + j] = dot; }
+      if (li == 0) {
+#pragma unroll
+        for (int j = 0; j < kSlotDegree; ++j)
+          if (j < ds) { pi[e0 + j] = pj[j]; gs[e0 + j] = pj[j] * (gj[j] - c); }
       }
     }
-    float c = cpart;     // equal on the lanes of a slot: sum once per slot
+    // ---- longer ones: the whole wave, one head at a time (heavy heads: the heavy_* kernels)
+    uint64_t pend = __builtin_amdgcn_ballot_w64(!small && deg <= kHeavyDegree && li == 0);
+    while (pend) {
+      const int leader = __builtin_amdgcn_readfirstlane(__ffsll((long long)pend) - 1);
+      pend &= pend - 1;
+      const int64_t hw = h0 + leader / LPR;
+      const int e0w = __builtin_amdgcn_readlane(e0, leader), degw = __builtin_amdgcn_readlane(deg, leader);
+      float m, z;
+      softmax_stats(s, e0w, degw, lane, m, z);
+      const float4 g4 = G4[hw * LPR + li];
+      float cpart = 0.f;
+      for (int base = 0; base < degw; base += ES) {
+        const int j = base + sub;
+        float dot = 0.f, p = 0.f;
+        if (j < degw) {
+          p = expf(s[e0w + j] - m) / z;
+          const float4 x = fetch_chunk<BITS>(src, (int64_t)h_tail[e0w + j] * LPR + li);
+          dot = fmaf(g4.x, x.x, fmaf(g4.y, x.y, fmaf(g4.z, x.z, g4.w * x.w)));
+        }
+        dot = slot_sum<LPR>(dot);   // g_j on every lane of the slot
+        if (j < degw) {
+          cpart = fmaf(p, dot, cpart);
+          if (li == 0) { pi[e0w + j] = p; gs[e0w + j] = dot; }
+        }
+      }
+      float c = cpart;     // equal on the lanes of a slot: sum once per slot
 #pragma unroll
-    for (int o = LPR; o < 64; o <<= 1) c += __shfl_xor(c, o);
-    // grad_s_j = pi_j (g_j - sum_j' pi_j' g_j'); each lane re-reads what it wrote itself
-    for (int base = 0; base < deg; base += ES) {
-      const int j = base + sub;
-      if (j < deg && li == 0) gs[e0 + j] = pi[e0 + j] * (gs[e0 + j] - c);
+      for (int o = LPR; o < 64; o <<= 1) c += __shfl_xor(c, o);
+      // grad_s_j = pi_j (g_j - sum_j' pi_j' g_j'); each lane re-reads what it wrote itself
+      for (int base = 0; base < degw; base += ES) {
+        const int j = base + sub;
+        if (j < degw && li == 0) gs[e0w + j] = pi[e0w + j] * (gs[e0w + j] - c);
+      }
     }
   }
 }

@@ -1180,27 +1180,33 @@ __global__ __launch_bounds__(kThreads) void uniform_bwd_kernel(
 }
 
 // ------------------------------------------------------- edge-level backward ----
-// Cooperative form (d = 128: W_r alone takes 66 KiB of LDS, so a workgroup of four waves
-// shares one 32-edge tile).  Phases of a tile, separated by workgroup barriers:
-//   stage rows (prefetched raw one tile ahead, node ids two tiles ahead) and the tile's
-//   per-edge scalars and scatter flags -> a, b per channel block, grad_a / grad_b to LDS ->
-//   scatter rows Pt, Ph and the grad_W_r blocks of each wave -> Pt, Ph back to LDS ->
-//   flag-driven scatter (as in the wave-independent kernel below).
+// Cooperative form (d = 128: W_r alone takes 66 KiB of LDS, so one workgroup -- eight waves,
+// two per SIMD -- fills a compute unit and all of them share one 32-edge tile).  Phases of a
+// tile, separated by workgroup barriers, and who does what:
+//   stage: rows (prefetched raw one tile ahead, node ids two tiles ahead), per-edge scalars
+//          and scatter flags (first wave)
+//   1:     waves 0-3: a for channel block w;  waves 4-7: b for channel block w - 4, then
+//          grad_a = gs tanh(b) and f = gs (1 - tanh(b)^2) to LDS
+//   1':    waves 0-3: grad_b = a * f, in place in LDS
+//   2:     Pt (waves 0-3) / Ph (waves 4-7) for one column block each; every wave two of the
+//          sixteen grad_W_r blocks
+//   3:     Pt, Ph back to LDS; flag-driven scatter (as in the wave-independent kernel below)
+constexpr int kCoopWaves = 8;
+
 template <int D, int TE, int BITS>
-__global__ __launch_bounds__(kThreads) void edge_bwd_kernel(
+__global__ __launch_bounds__(kCoopWaves * 64) void edge_bwd_kernel(
     Source src, const float* __restrict__ Wr, const float* __restrict__ er,
     const int32_t* __restrict__ r_head, const int32_t* __restrict__ r_tail,
     const int32_t* __restrict__ r_eid, const uint8_t* __restrict__ r_hperm, ChunkList chunks,
     const float* __restrict__ pi, const float* __restrict__ gs, const float* __restrict__ gH,
     GradSink sink, float* __restrict__ part_Wr, float* __restrict__ part_er) {
-  static_assert(TE == 32, "flags and head order are per 32-edge tile");
-  constexpr int LD = D + 4, LPR = D / 4, NCB = D / 32, NIB = D / 32;
-  constexpr int NBW = (NCB * NIB + 3) / 4;        // grad_W_r blocks per wave
-  constexpr int NSB = (NIB + 3) / 4;              // scatter-row blocks per wave
-  constexpr int NQ = kThreads / D, RP = TE / NQ;  // scatter: row parts
-  constexpr int CPT = TE * LPR / kThreads;        // row chunks per thread and matrix
-  constexpr int RSTEP = kThreads / LPR;           // rows between a thread's chunks
-  static_assert(TE * LPR % kThreads == 0 && kThreads % LPR == 0 && kThreads % D == 0, "tile split");
+  static_assert(TE == 32 && D == 128, "eight waves: four channel blocks x {a, b}");
+  constexpr int NT = kCoopWaves * 64;
+  constexpr int LD = D + 4, LPR = D / 4, NIB = D / 32;
+  constexpr int NBW = NIB * NIB / kCoopWaves;     // grad_W_r blocks per wave (2)
+  constexpr int NQ = NT / D, RP = TE / NQ;        // scatter: row parts (4 x 8 rows)
+  constexpr int CPT = TE * LPR / NT;              // row chunks per thread and matrix (2)
+  constexpr int RSTEP = NT / LPR;                 // rows between a thread's chunks
   float* Wr_s = reinterpret_cast<float*>(smem_raw);
   float* Et_s = Wr_s + D * LD;
   float* Eh_s = Et_s + TE * LD;
@@ -1218,6 +1224,8 @@ __global__ __launch_bounds__(kThreads) void edge_bwd_kernel(
   const int ch = blockIdx.x;
   const int rel = chunks.rel[ch], start = chunks.start[ch], count = chunks.count[ch];
   const int row0 = tid / LPR, li = tid % LPR;     // this thread stages rows row0 + k * RSTEP
+  const int blk4 = wave & 3;                      // channel / column block of this wave's products
+  const bool b_side = wave >= 4;                  // waves 4-7: b and Ph; waves 0-3: a and Pt
 
   // prefetch: raw rows of the next tile, node ids of the tile after it
   int tn[CPT], hn[CPT];
@@ -1262,9 +1270,9 @@ __global__ __launch_bounds__(kThreads) void edge_bwd_kernel(
   load_edge(TE);
 
   const float4* Wg = reinterpret_cast<const float4*>(Wr + (size_t)rel * D * D);
-  for (int q = tid; q < D * LPR; q += kThreads)
+  for (int q = tid; q < D * LPR; q += NT)
     *reinterpret_cast<float4*>(Wr_s + (q / LPR) * LD + (q % LPR) * 4) = Wg[q];
-  for (int c = tid; c < D; c += kThreads) er_s[c] = er[(size_t)rel * D + c];
+  for (int c = tid; c < D; c += NT) er_s[c] = er[(size_t)rel * D + c];
 
   floatx16 accW[NBW];
 #pragma unroll
@@ -1301,24 +1309,35 @@ __global__ __launch_bounds__(kThreads) void edge_bwd_kernel(
       load_edge(t0 + 2 * TE);
     }
     __syncthreads();
-    // recompute a, b; grad_a = gs * tanh(b); grad_b = gs * a * (1 - tanh(b)^2)
-    for (int cb = wave; cb < NCB; cb += 4) {
-      floatx16 accA = {0}, accB = {0};
-      mfma_dual_kcont<D>(Wr_s + cb * 32 * LD, LD, Et_s, Eh_s, LD, accA, accB);
-      const int e = lane & 31;
-      const float g = gs_s[e];
+    // ---- 1. a (waves 0-3) or b (waves 4-7) of channel block blk4: [c][e], lane = edge
+    floatx16 acc1 = {0};
+    mfma_block<KCONT, KCONT>(Wr_s + blk4 * 32 * LD, LD, b_side ? Eh_s : Et_s, LD, D, acc1);
+    const int e1 = lane & 31;
+    if (b_side) {
+      const float g = gs_s[e1];
 #pragma unroll
       for (int vg = 0; vg < 4; ++vg) {
-        const int c0 = cb * 32 + 8 * vg + 4 * (lane >> 5);
-        float da[4], db[4];
+        const int c0 = blk4 * 32 + 8 * vg + 4 * (lane >> 5);
+        float da[4], f[4];
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
-          const float vv = fast_tanh(accB[4 * vg + u] + er_s[c0 + u]);
+          const float vv = fast_tanh(acc1[4 * vg + u] + er_s[c0 + u]);
           da[u] = g * vv;
-          db[u] = g * accA[4 * vg + u] * (1.f - vv * vv);
+          f[u] = g * (1.f - vv * vv);
         }
-        *reinterpret_cast<float4*>(dA_s + e * LD + c0) = make_float4(da[0], da[1], da[2], da[3]);
-        *reinterpret_cast<float4*>(dB_s + e * LD + c0) = make_float4(db[0], db[1], db[2], db[3]);
+        *reinterpret_cast<float4*>(dA_s + e1 * LD + c0) = make_float4(da[0], da[1], da[2], da[3]);
+        *reinterpret_cast<float4*>(dB_s + e1 * LD + c0) = make_float4(f[0], f[1], f[2], f[3]);
+      }
+    }
+    __syncthreads();
+    // ---- 1'. grad_b = a * f (the wave that holds a; each element is its own)
+    if (!b_side) {
+#pragma unroll
+      for (int vg = 0; vg < 4; ++vg) {
+        const int c0 = blk4 * 32 + 8 * vg + 4 * (lane >> 5);
+        float4 f = *reinterpret_cast<const float4*>(dB_s + e1 * LD + c0);
+        f.x *= acc1[4 * vg + 0]; f.y *= acc1[4 * vg + 1]; f.z *= acc1[4 * vg + 2]; f.w *= acc1[4 * vg + 3];
+        *reinterpret_cast<float4*>(dB_s + e1 * LD + c0) = f;
       }
     }
     __syncthreads();
@@ -1333,43 +1352,25 @@ __global__ __launch_bounds__(kThreads) void edge_bwd_kernel(
     float ghv[RP];
 #pragma unroll
     for (int k = 0; k < RP; ++k) ghv[k] = gH[(int64_t)hd_s[se0 + k] * D + si];
-    // rows to scatter: Pt = grad_a W_r, Ph = grad_b W_r   ([e][i], contraction over c)
-    floatx16 accPt[NSB], accPh[NSB];
-#pragma unroll
-    for (int j = 0; j < NSB; ++j) {
-      accPt[j] = floatx16{0}; accPh[j] = floatx16{0};
-      const int ib = wave + 4 * j;
-      if (ib < NIB) {
-        mfma_block<KCONT, KMAJOR>(dA_s, LD, Wr_s + ib * 32, LD, D, accPt[j]);
-        mfma_block<KCONT, KMAJOR>(dB_s, LD, Wr_s + ib * 32, LD, D, accPh[j]);
-      }
-    }
-    // grad_W_r block(s): [c][i] += sum_e grad_a[e][c] e_t[e][i] + grad_b[e][c] e_h[e][i]
+    // ---- 2. Pt = grad_a W_r (waves 0-3) or Ph = grad_b W_r (waves 4-7), column block blk4
+    floatx16 accP = {0};
+    mfma_block<KCONT, KMAJOR>(b_side ? dB_s : dA_s, LD, Wr_s + blk4 * 32, LD, D, accP);
+    // grad_W_r blocks [c][i] += sum_e grad_a[e][c] e_t[e][i] + grad_b[e][c] e_h[e][i]
 #pragma unroll
     for (int j = 0; j < NBW; ++j) {
-      const int blk = wave + 4 * j;
-      if (blk < NCB * NIB) {
-        const int cb = blk / NIB, ib = blk % NIB;
-        // two-level sum: a fresh accumulator per tile, added to the chunk's accumulator
-        // (keeps the fp32 running sum short when a relation has 10^5 and more edges)
-        floatx16 accT = {0};
-        mfma_block<KMAJOR, KMAJOR>(dA_s + cb * 32, LD, Et_s + ib * 32, LD, TE, accT);
-        mfma_block<KMAJOR, KMAJOR>(dB_s + cb * 32, LD, Eh_s + ib * 32, LD, TE, accT);
-        accW[j] += accT;
-      }
+      const int blk = wave * NBW + j, cb = blk / NIB, ib = blk % NIB;
+      // two-level sum: a fresh accumulator per tile, added to the chunk's accumulator
+      // (keeps the fp32 running sum short when a relation has 10^5 and more edges)
+      floatx16 accT = {0};
+      mfma_block<KMAJOR, KMAJOR>(dA_s + cb * 32, LD, Et_s + ib * 32, LD, TE, accT);
+      mfma_block<KMAJOR, KMAJOR>(dB_s + cb * 32, LD, Eh_s + ib * 32, LD, TE, accT);
+      accW[j] += accT;
     }
     __syncthreads();   // every read of Et_s / Eh_s is done: reuse them as staging
+    {
+      float* P_s = b_side ? Eh_s : Et_s;
 #pragma unroll
-    for (int j = 0; j < NSB; ++j) {
-      const int ib = wave + 4 * j;
-      if (ib < NIB) {
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          const int e = acc_row(v, lane), i = ib * 32 + (lane & 31);
-          Et_s[e * LD + i] = accPt[j][v];
-          Eh_s[e * LD + i] = accPh[j][v];
-        }
-      }
+      for (int v = 0; v < 16; ++v) P_s[acc_row(v, lane) * LD + blk4 * 32 + (lane & 31)] = accP[v];
     }
     __syncthreads();
     // scatter: every LDS read is independent of the running sums; a run inside a tile is
@@ -1403,13 +1404,10 @@ __global__ __launch_bounds__(kThreads) void edge_bwd_kernel(
   float* outW = part_Wr + (size_t)ch * D * D;
 #pragma unroll
   for (int j = 0; j < NBW; ++j) {
-    const int blk = wave + 4 * j;
-    if (blk < NCB * NIB) {
-      const int cb = blk / NIB, ib = blk % NIB;
+    const int blk = wave * NBW + j, cb = blk / NIB, ib = blk % NIB;
 #pragma unroll
-      for (int v = 0; v < 16; ++v)
-        outW[(cb * 32 + acc_row(v, lane)) * D + ib * 32 + (lane & 31)] = accW[j][v];
-    }
+    for (int v = 0; v < 16; ++v)
+      outW[(cb * 32 + acc_row(v, lane)) * D + ib * 32 + (lane & 31)] = accW[j][v];
   }
   if (tid < D) part_er[(size_t)ch * D + tid] = er_acc;
 }
@@ -2022,7 +2020,7 @@ tinykg_status bwd_impl(const tinykg_graph* g, const tinykg_saved* sv, const floa
       auto kern = edge_bwd_kernel<D, TE, BITS>;
       if ((rc = set_smem(kern, smem)) != TINYKG_OK) return rc;
       ProfileScope prof("edge_bwd_kernel", st);
-      hipLaunchKernelGGL(kern, dim3(g->n_chunks), dim3(kThreads), smem, st, srcE, Wr, er, g->r_head,
+      hipLaunchKernelGGL(kern, dim3(g->n_chunks), dim3(kCoopWaves * 64), smem, st, srcE, Wr, er, g->r_head,
                          g->r_tail, g->r_eid, g->r_hperm32, cl, pi, gs, gH, sink, pWr, per);
     }
     if ((rc = launch_status()) != TINYKG_OK) return rc;

@@ -18,7 +18,8 @@
 //   edge_bwd_kernel   relation-bucketed tiles: recompute a, b; grad_a, grad_b;
 //                     W_r^T grad_a / W_r^T grad_b rows scattered to tails / heads;
 //                     grad_W_r, grad_e_r accumulated per chunk
-//   reduce_segments_kernel  fixed-order sums of the per-chunk partial gradients
+//   epilogue_kernel   fixed-order sums of the per-chunk / per-workgroup partial parameter
+//                     gradients, and the heavy nodes' double-precision rows, in one launch
 //
 // MFMA operand convention used throughout: one 32x32 output block is
 // acc[m][n] += sum_k A(m,k) B(k,n); lane l feeds row/column l%32 and the k-half
@@ -938,8 +939,14 @@ __global__ __launch_bounds__(kThreads) void dense_bwd_kernel(Source srcH,
                                                              float slope, int64_t N,
                                                              float* __restrict__ gH,
                                                              float* __restrict__ gE,
-                                                             float* __restrict__ part_W) {
+                                                             float* __restrict__ part_W,
+                                                             double* __restrict__ zero_ptr,
+                                                             int64_t zero_n) {
   constexpr int LD = D + 4, LPR = D / 4, TN = 64, NIB = D / 32;
+  // (the double-precision rows that the edge stage adds to start from zero: cleared here,
+  // a launch earlier, instead of by a kernel of their own)
+  for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < zero_n; i += (int64_t)gridDim.x * kThreads)
+    zero_ptr[i] = 0.0;
   const int DOP = (d_out + 31) & ~31, LDJ = DOP + 4, NOB = DOP / 32;
   float* W_s = reinterpret_cast<float*>(smem_raw);   // [DOP][LD]
   float* Hh_s = W_s + DOP * LD;                      // [TN][LD]
@@ -1044,18 +1051,31 @@ __global__ __launch_bounds__(kThreads) void dense_bwd_kernel(Source srcH,
   }
 }
 
-// out[seg][j] = sum over p in [ptr[seg], ptr[seg+1]) of part[p * stride + j].  Fixed
-// order: thread group k of 4 sums partials p0+k, p0+k+4, ... in double, the four group
-// sums are then added in order 0..3.  seg_ptr == nullptr: one segment [0, n_single).
-// Launch with 256 threads: 64 consecutive j per block.
-__global__ __launch_bounds__(256) void reduce_segments_kernel(const float* __restrict__ part,
-                                                              const int32_t* __restrict__ seg_ptr,
-                                                              int n_single, int stride,
-                                                              float* __restrict__ out) {
-  __shared__ double red[4][64];
-  const int seg = blockIdx.y;
-  const int p0 = seg_ptr ? seg_ptr[seg] : 0, p1 = seg_ptr ? seg_ptr[seg + 1] : n_single;
-  const int j = blockIdx.x * 64 + (threadIdx.x & 63), k = threadIdx.x >> 6;
+// One reduction job: out[seg][j] = sum over p in [ptr[seg], ptr[seg+1]) of
+// part[p * stride + j].  Fixed order: thread group k of 4 sums partials p0+k, p0+k+4, ... in
+// double, the four group sums are then added in order 0..3.  seg_ptr == nullptr: one segment
+// [0, n_single).  nx = ceil(stride / 64) blocks of 256 threads per segment (0: job unused).
+struct ReduceJob {
+  const float* part;
+  const int32_t* seg_ptr;
+  int n_single, stride, nx, ny;
+  float* out;
+};
+// Folding the double-precision rows of the heavy nodes into grad_E (see GradSink below).
+struct HeavyFinish {
+  const double* heavy;
+  const int32_t* node;
+  int64_t n;        // n_acc_heavy * D (0: nothing to do)
+  int D;
+  float* gE;
+};
+
+__device__ __forceinline__ void reduce_job(const ReduceJob& job, int bx, int by, double (*red)[64]) {
+  const int seg = by;
+  const int p0 = job.seg_ptr ? job.seg_ptr[seg] : 0, p1 = job.seg_ptr ? job.seg_ptr[seg + 1] : job.n_single;
+  const int stride = job.stride;
+  const int j = bx * 64 + (threadIdx.x & 63), k = threadIdx.x >> 6;
+  const float* part = job.part;
   double s = 0.0;
   if (j < stride) {
     int p = p0 + k;
@@ -1069,14 +1089,14 @@ __global__ __launch_bounds__(256) void reduce_segments_kernel(const float* __res
   red[k][threadIdx.x & 63] = s;
   __syncthreads();
   if (k == 0 && j < stride)
-    out[(size_t)seg * stride + j] = (float)(((red[0][j & 63] + red[1][j & 63]) + red[2][j & 63]) + red[3][j & 63]);
+    job.out[(size_t)seg * stride + j] = (float)(((red[0][j & 63] + red[1][j & 63]) + red[2][j & 63]) + red[3][j & 63]);
 }
 
 // Where the edge stage adds its gradient rows.  grad_E itself (fp32, preset to grad_H,
 // the e_h term of H_h = e_h + sum pi e_t) takes the rows of ordinary nodes with fp32
 // atomics.  A node that receives more than kAccHeavyDegree rows -- a hot tail sums 10^5
 // and more O(1) terms of both signs, which fp32 accumulation cannot hold to 1e-5 of the
-// result -- has a row of doubles in the compact buffer `heavy` instead; finish_heavy_kernel
+// result -- has a row of doubles in the compact buffer `heavy` instead; the epilogue kernel
 // folds that row into grad_E at the end.  A staged node id carries the choice in bit 30.
 struct GradSink {
   float* gE;              // [n_nodes, D]
@@ -1100,23 +1120,33 @@ __device__ __forceinline__ void sink_add(const GradSink& sink, int flagged_node,
   }
 }
 
-__global__ void zero_f64_kernel(double* __restrict__ dst, int64_t n) {
-  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
-  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) dst[i] = 0.0;
-}
-
 // grad_E rows of the nodes that accumulated in double: replicas summed in order, plus
-// grad_H, rounded once.
-__global__ void finish_heavy_kernel(const double* __restrict__ heavy, const int32_t* __restrict__ node,
-                                    int64_t n, int D, float* __restrict__ gE) {
-  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
-  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) {
-    const int64_t q = i / D, col = i % D;
+// grad_H (already in grad_E), rounded once.
+__device__ __forceinline__ void finish_heavy(const HeavyFinish& hf, int64_t first, int64_t stride) {
+  for (int64_t i = first; i < hf.n; i += stride) {
+    const int64_t q = i / hf.D, col = i % hf.D;
     double sum = 0.0;
-    for (int k = 0; k < kHeavyReplicas; ++k) sum += heavy[(q * kHeavyReplicas + k) * D + col];
-    float* dst = gE + (int64_t)node[q] * D + col;
+    for (int k = 0; k < kHeavyReplicas; ++k) sum += hf.heavy[(q * kHeavyReplicas + k) * hf.D + col];
+    float* dst = hf.gE + (int64_t)hf.node[q] * hf.D + col;
     *dst = (float)(sum + (double)*dst);
   }
+}
+
+// The end of a backward pass in ONE launch (each launch costs several microseconds of a
+// step that takes about a millisecond): blockIdx.z picks the job -- up to three reductions
+// of partial parameter gradients and the heavy-node rows.  Blocks outside a job's range exit.
+__global__ __launch_bounds__(256) void epilogue_kernel(ReduceJob j0, ReduceJob j1, ReduceJob j2,
+                                                       HeavyFinish hf) {
+  __shared__ double red[4][64];
+  const int z = blockIdx.z;
+  if (z == 3) {
+    if (blockIdx.y == 0)
+      finish_heavy(hf, (int64_t)blockIdx.x * 256 + threadIdx.x, (int64_t)gridDim.x * 256);
+    return;
+  }
+  const ReduceJob& job = z == 0 ? j0 : z == 1 ? j1 : j2;
+  if ((int)blockIdx.x >= job.nx || (int)blockIdx.y >= job.ny) return;
+  reduce_job(job, blockIdx.x, blockIdx.y, red);
 }
 
 // ---------------------------------------------- uniform attention, backward ----
@@ -1945,29 +1975,20 @@ tinykg_status bwd_impl(const tinykg_graph* g, const tinykg_saved* sv, const floa
 
   // dense stage
   const int DOP = (d_out + 31) & ~31;
+  const int64_t n_heavy_elems = (int64_t)g->n_acc_heavy * D;
+  const bool with_heavy = g->n_edges > 0 && n_heavy_elems > 0;
+  int dense_blocks = 0;
   {
     const size_t smem = (size_t)(DOP * LD + 64 * LD + 64 * (DOP + 4)) * 4;
     auto kern = dense_bwd_kernel<D, BITS>;
     if ((rc = set_smem(kern, smem)) != TINYKG_OK) return rc;
     const int grid = dense_grid(N);
+    dense_blocks = grid;
     {
       ProfileScope prof("dense_bwd_kernel", st);
       hipLaunchKernelGGL(kern, dim3(grid), dim3(kThreads), smem, st, srcH, sv->mask_J, gEout, W,
-                         d_out, slope, N, gH, gE, pW);
+                         d_out, slope, N, gH, gE, pW, acc, with_heavy ? n_heavy_elems * kHeavyReplicas : 0);
     }
-    if ((rc = launch_status()) != TINYKG_OK) return rc;
-    const int stride = d_out * D;
-    ProfileScope prof("reduce_segments_kernel", st);
-    hipLaunchKernelGGL(reduce_segments_kernel, dim3((stride + 63) / 64, 1), dim3(256), 0, st, pW,
-                       (const int32_t*)nullptr, grid, stride, gW);
-    if ((rc = launch_status()) != TINYKG_OK) return rc;
-  }
-  const int64_t n_heavy_elems = (int64_t)g->n_acc_heavy * D;
-  const int fill_blocks = (int)std::max<int64_t>(1, std::min<int64_t>((n_heavy_elems + 255) / 256, (int64_t)num_cus() * 16));
-  if (g->n_chunks > 0 && n_heavy_elems > 0) {
-    ProfileScope prof("zero_f64_kernel", st);
-    hipLaunchKernelGGL(zero_f64_kernel, dim3(fill_blocks), dim3(256), 0, st, acc,
-                       n_heavy_elems * kHeavyReplicas);
     if ((rc = launch_status()) != TINYKG_OK) return rc;
   }
   const bool uniform = Wr == nullptr;     // pi = 1 / deg: only the transposed sparse product is left
@@ -2025,19 +2046,17 @@ tinykg_status bwd_impl(const tinykg_graph* g, const tinykg_saved* sv, const floa
     }
     if ((rc = launch_status()) != TINYKG_OK) return rc;
   }
-  if (g->n_chunks > 0 && n_heavy_elems > 0) {
-    ProfileScope prof("finish_heavy_kernel", st);
-    hipLaunchKernelGGL(finish_heavy_kernel, dim3(fill_blocks), dim3(256), 0, st, acc, g->acc_node,
-                       n_heavy_elems, D, gE);
-    if ((rc = launch_status()) != TINYKG_OK) return rc;
-  }
-  if (!uniform && g->n_rel > 0) {
-    ProfileScope prof("reduce_segments_kernel", st);
-    hipLaunchKernelGGL(reduce_segments_kernel, dim3((D * D + 63) / 64, g->n_rel), dim3(256), 0, st,
-                       pWr, g->rel_chunk_ptr, 0, D * D, gWr);
-    if ((rc = launch_status()) != TINYKG_OK) return rc;
-    hipLaunchKernelGGL(reduce_segments_kernel, dim3((D + 63) / 64, g->n_rel), dim3(256), 0, st, per,
-                       g->rel_chunk_ptr, 0, D, ger);
+  // one launch: grad_W, grad_W_r, grad_e_r from their partial sums; heavy-node rows of grad_E
+  {
+    const bool edge_grads = !uniform && g->n_rel > 0;
+    const ReduceJob jW{pW, nullptr, dense_blocks, d_out * D, (d_out * D + 63) / 64, 1, gW};
+    const ReduceJob jWr{pWr, g->rel_chunk_ptr, 0, D * D, edge_grads ? (D * D + 63) / 64 : 0, g->n_rel, gWr};
+    const ReduceJob jer{per, g->rel_chunk_ptr, 0, D, edge_grads ? (D + 63) / 64 : 0, g->n_rel, ger};
+    const HeavyFinish hf{acc, g->acc_node, with_heavy ? n_heavy_elems : 0, D, gE};
+    const int gx = std::max(std::max(jW.nx, jWr.nx), std::max(jer.nx, with_heavy ? 64 : 1));
+    const int gy = std::max(1, edge_grads ? (int)g->n_rel : 1);
+    ProfileScope prof("epilogue_kernel", st);
+    hipLaunchKernelGGL(epilogue_kernel, dim3(gx, gy, 4), dim3(256), 0, st, jW, jWr, jer, hf);
     if ((rc = launch_status()) != TINYKG_OK) return rc;
   }
   return TINYKG_OK;

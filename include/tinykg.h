@@ -128,7 +128,12 @@ int64_t tinykg_graph_num_edges(const tinykg_graph* g);
  * Caller-allocated device buffers in exactly tinykg_quantize's output layout.
  * With bits == 32 nothing is compressed: packed_E / packed_H hold the fp32
  * tensors themselves (n_nodes*d_in*4 bytes each) and gmin / gscale are unused
- * (may be NULL). */
+ * (may be NULL).
+ * packed_H == NULL (attentive layer only) leaves H out of the context: the forward
+ * call then saves Q(E) and the mask alone, and the backward call runs the second
+ * stage of Eq. 2 again on E_hat and uses that H~ = e^_h + sum_j pi_j(E_hat) e^_t
+ * where H_hat would stand (half the saved bytes, one more pass over the edges).
+ * Pass the same struct to the forward and the backward call. */
 typedef struct {
   uint8_t* packed_E; float* gmin_E; float* gscale_E; /* Q(E; seed),     n = n_nodes*d_in */
   uint8_t* packed_H; float* gmin_H; float* gscale_H; /* Q(H; seed + 1), n = n_nodes*d_in */

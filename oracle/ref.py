@@ -241,28 +241,44 @@ def aggregate_bwd(n_nodes, head, rel, tail, Ehat, Hhat, mask, Wr, er, W, slope, 
 
 
 # ---- the saved context of one layer (Fig. 1): Q(E; seed), Q(H; seed+1), 1-bit mask
-def save_context(E, H, mask, bits, group, seed):
-    """Compress what the backward pass needs.  bits == 32 keeps fp32 copies."""
+def save_context(E, H, mask, bits, group, seed, keep_H=True):
+    """Compress what the backward pass needs.  bits == 32 keeps fp32 copies.
+    keep_H=False: H is left out (the backward pass rebuilds it from E_hat, see rebuild_H)."""
     E = np.ascontiguousarray(E, dtype=np.float32)
     H = np.ascontiguousarray(H, dtype=np.float32)
     mask_bits = pack((np.ascontiguousarray(mask) != 0).astype(np.uint8), 1)
     if bits == 32:
-        return {"bits": 32, "E": E.copy(), "H": H.copy(), "mask": mask_bits}
+        ctx = {"bits": 32, "E": E.copy(), "mask": mask_bits}
+        if keep_H:
+            ctx["H"] = H.copy()
+        return ctx
     pE, mnE, scE = quantize(E, bits, group, seed)
-    pH, mnH, scH = quantize(H, bits, group, (seed + 1) & (2 ** 64 - 1))
-    return {"bits": bits, "group": group, "packed_E": pE, "gmin_E": mnE, "gscale_E": scE,
-            "packed_H": pH, "gmin_H": mnH, "gscale_H": scH, "mask": mask_bits}
+    ctx = {"bits": bits, "group": group, "packed_E": pE, "gmin_E": mnE, "gscale_E": scE,
+           "mask": mask_bits}
+    if keep_H:
+        pH, mnH, scH = quantize(H, bits, group, (seed + 1) & (2 ** 64 - 1))
+        ctx.update(packed_H=pH, gmin_H=mnH, gscale_H=scH)
+    return ctx
 
 
 def restore_context(ctx, n_nodes, d_in, d_out):
-    """E_hat, H_hat (fp32) and the unpacked mask [n_nodes, d_out]."""
+    """E_hat, H_hat (fp32; None when H was not saved) and the unpacked mask [n_nodes, d_out]."""
     mask = unpack(ctx["mask"], n_nodes * d_out, 1).reshape(n_nodes, d_out)
     if ctx["bits"] == 32:
-        return ctx["E"], ctx["H"], mask
+        return ctx["E"], ctx.get("H"), mask
     b, g = ctx["bits"], ctx["group"]
     Eh = dequantize(ctx["packed_E"], ctx["gmin_E"], ctx["gscale_E"], n_nodes, d_in, b, g)
-    Hh = dequantize(ctx["packed_H"], ctx["gmin_H"], ctx["gscale_H"], n_nodes, d_in, b, g)
+    Hh = None
+    if "packed_H" in ctx:
+        Hh = dequantize(ctx["packed_H"], ctx["gmin_H"], ctx["gscale_H"], n_nodes, d_in, b, g)
     return Eh, Hh, mask
+
+
+def rebuild_H(n_nodes, head, rel, tail, Ehat, Wr, er, W, slope, threads=1):
+    """The variant that saves Q(E) and the mask only: the second stage of Eq. 2 is run
+    again on E_hat, H~ = e^_h + sum_j pi_j(E_hat) e^_t, and stands where H_hat stood in the
+    backward pass (the mask stays the forward pass's own)."""
+    return aggregate_fwd(n_nodes, head, rel, tail, Ehat, Wr, er, W, slope, threads)[1]
 
 
 # ------------------------------------------------ readout + ranking loss ------

@@ -257,18 +257,24 @@ class Graph:
 class SavedContext:
     """Device buffers of one layer's saved context + the tinykg_saved struct."""
 
-    def __init__(self, n_nodes, d_in, d_out, bits, group, device="cuda", with_E=True):
-        """with_E=False: the context of the uniform-attention layer (Q(H) and the mask only)."""
+    def __init__(self, n_nodes, d_in, d_out, bits, group, device="cuda", with_E=True, with_H=True):
+        """with_E=False: the context of the uniform-attention layer (Q(H) and the mask only).
+        with_H=False: Q(E) and the mask only; the attentive layer's backward pass rebuilds H."""
         self.n_nodes, self.d_in, self.d_out, self.bits, self.group = n_nodes, d_in, d_out, bits, group
-        self.packed_E = self.gmin_E = self.gscale_E = self.gmin_H = self.gscale_H = None
+        self.packed_E = self.gmin_E = self.gscale_E = None
+        self.packed_H = self.gmin_H = self.gscale_H = None
+        if not (with_E or with_H):
+            raise ValueError("a saved context holds Q(E), Q(H) or both")
         if bits == 32:
             if with_E:
                 self.packed_E = torch.empty(n_nodes * d_in * 4, dtype=torch.uint8, device=device)
-            self.packed_H = torch.empty(n_nodes * d_in * 4, dtype=torch.uint8, device=device)
+            if with_H:
+                self.packed_H = torch.empty(n_nodes * d_in * 4, dtype=torch.uint8, device=device)
         else:
             if with_E:
                 self.packed_E, self.gmin_E, self.gscale_E = alloc_quantized(n_nodes, d_in, bits, group, device)
-            self.packed_H, self.gmin_H, self.gscale_H = alloc_quantized(n_nodes, d_in, bits, group, device)
+            if with_H:
+                self.packed_H, self.gmin_H, self.gscale_H = alloc_quantized(n_nodes, d_in, bits, group, device)
         self.mask_J = torch.empty((n_nodes * d_out + 7) // 8, dtype=torch.uint8, device=device)
         self.struct = Saved(_ptr(self.packed_E), _ptr(self.gmin_E), _ptr(self.gscale_E),
                             _ptr(self.packed_H), _ptr(self.gmin_H), _ptr(self.gscale_H),

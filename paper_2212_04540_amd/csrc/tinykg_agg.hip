@@ -499,8 +499,8 @@ __device__ __forceinline__ void softmax_stats(const float* __restrict__ s, int e
 // kHeavyDegree are then taken one at a time by the whole wave, 64 / LPR edges per step.
 constexpr int kSlotDegree = 16;
 
-template <int D>
-__global__ __launch_bounds__(kThreads) void attend_fwd_kernel(const float* __restrict__ E,
+template <int D, int BITS>
+__global__ __launch_bounds__(kThreads) void attend_fwd_kernel(Source src,
                                                               const int32_t* __restrict__ rowptr,
                                                               const int32_t* __restrict__ h_tail,
                                                               const float* __restrict__ s, int64_t N,
@@ -509,7 +509,6 @@ __global__ __launch_bounds__(kThreads) void attend_fwd_kernel(const float* __res
   const int lane = threadIdx.x & 63;
   const int sub = lane / LPR, li = lane % LPR;
   const int64_t n_waves = (int64_t)gridDim.x * (kThreads / 64);
-  const float4* E4 = reinterpret_cast<const float4*>(E);
   for (int64_t h0 = ((int64_t)blockIdx.x * (kThreads / 64) + (threadIdx.x >> 6)) * ES; h0 < N;
        h0 += n_waves * ES) {
     const int64_t h = h0 + sub;
@@ -539,7 +538,7 @@ __global__ __launch_bounds__(kThreads) void attend_fwd_kernel(const float* __res
         }
         float4 x[4];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) x[u] = E4[(int64_t)t[u] * LPR + li];
+        for (int u = 0; u < 4; ++u) x[u] = fetch_chunk<BITS>(src, (int64_t)t[u] * LPR + li);
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
           const float p = expf(sc[u] - m) / z;
@@ -548,7 +547,7 @@ __global__ __launch_bounds__(kThreads) void attend_fwd_kernel(const float* __res
         }
       }
       if (h < N && small) {
-        const float4 eh = E4[h * LPR + li];
+        const float4 eh = fetch_chunk<BITS>(src, h * LPR + li);
         reinterpret_cast<float4*>(H)[h * LPR + li] = make_float4(eh.x + ax, eh.y + ay, eh.z + az, eh.w + aw);
       }
     }
@@ -566,7 +565,7 @@ __global__ __launch_bounds__(kThreads) void attend_fwd_kernel(const float* __res
         const int j = base + sub;
         if (j < degw) {
           const float p = expf(s[e0w + j] - m) / z;
-          const float4 x = E4[(int64_t)h_tail[e0w + j] * LPR + li];
+          const float4 x = fetch_chunk<BITS>(src, (int64_t)h_tail[e0w + j] * LPR + li);
           ax = fmaf(p, x.x, ax); ay = fmaf(p, x.y, ay);
           az = fmaf(p, x.z, az); aw = fmaf(p, x.w, aw);
         }
@@ -577,7 +576,7 @@ __global__ __launch_bounds__(kThreads) void attend_fwd_kernel(const float* __res
         az += __shfl_xor(az, o); aw += __shfl_xor(aw, o);
       }
       if (sub == 0) {
-        const float4 eh = E4[hw * LPR + li];
+        const float4 eh = fetch_chunk<BITS>(src, hw * LPR + li);
         reinterpret_cast<float4*>(H)[hw * LPR + li] = make_float4(eh.x + ax, eh.y + ay, eh.z + az, eh.w + aw);
       }
     }
@@ -702,8 +701,8 @@ struct HeavyList {
 };
 
 // Per segment: pm, pz and (WITH_ACC) the unnormalised weighted row sum pacc [n_hseg, D].
-template <int D, bool WITH_ACC>
-__global__ __launch_bounds__(kThreads) void heavy_part1_kernel(const float* __restrict__ E,
+template <int D, bool WITH_ACC, int BITS>
+__global__ __launch_bounds__(kThreads) void heavy_part1_kernel(Source src,
                                                                const int32_t* __restrict__ h_tail,
                                                                const float* __restrict__ s, HeavyList hl,
                                                                float* __restrict__ pm, double* __restrict__ pz,
@@ -721,13 +720,12 @@ __global__ __launch_bounds__(kThreads) void heavy_part1_kernel(const float* __re
   zd = wave_sum(zd);
   if (lane == 0) { pm[sg] = m; pz[sg] = zd; }
   if (WITH_ACC) {
-    const float4* E4 = reinterpret_cast<const float4*>(E);
     double ax = 0.0, ay = 0.0, az = 0.0, aw = 0.0;
     for (int base = 0; base < cnt; base += ES) {
       const int j = base + sub;
       if (j < cnt) {
         const double p = (double)expf(s[e0 + j] - m);
-        const float4 x = E4[(int64_t)h_tail[e0 + j] * LPR + li];
+        const float4 x = fetch_chunk<BITS>(src, (int64_t)h_tail[e0 + j] * LPR + li);
         ax = fma(p, (double)x.x, ax); ay = fma(p, (double)x.y, ay);
         az = fma(p, (double)x.z, az); aw = fma(p, (double)x.w, aw);
       }
@@ -749,9 +747,9 @@ __global__ __launch_bounds__(kThreads) void heavy_part1_kernel(const float* __re
 // the waves' sums are then added in the order 0, 1, ... (fixed, so H is reproducible).
 constexpr int kMergeWaves = 16;
 
-template <int D, bool WITH_ACC>
+template <int D, bool WITH_ACC, int BITS>
 __global__ __launch_bounds__(kMergeWaves * 64) void heavy_merge1_kernel(
-    const float* __restrict__ E, HeavyList hl, const float* __restrict__ pm,
+    Source src, HeavyList hl, const float* __restrict__ pm,
     const double* __restrict__ pz, const double* __restrict__ pacc, float* __restrict__ hm,
     double* __restrict__ hz, float* __restrict__ H) {
   __shared__ double part[kMergeWaves][D];
@@ -790,7 +788,9 @@ __global__ __launch_bounds__(kMergeWaves * 64) void heavy_merge1_kernel(
         double acc = 0.0;
 #pragma unroll
         for (int w = 0; w < kMergeWaves; ++w) acc += part[w][i];
-        H[h * D + i] = (float)((double)E[h * D + i] + acc / Z);
+        const float4 e4 = fetch_chunk<BITS>(src, (h * D + i) >> 2);     // the chunk that holds column i
+        const float eh = (i & 3) == 0 ? e4.x : (i & 3) == 1 ? e4.y : (i & 3) == 2 ? e4.z : e4.w;
+        H[h * D + i] = (float)((double)eh + acc / Z);
       }
     }
   }
@@ -937,7 +937,7 @@ __global__ __launch_bounds__(kThreads) void dense_bwd_kernel(Source srcH,
                                                              const float* __restrict__ gEout,
                                                              const float* __restrict__ W, int d_out,
                                                              float slope, int64_t N,
-                                                             float* __restrict__ gH,
+                                                             float* gH,   // may be the buffer behind srcH
                                                              float* __restrict__ gE,
                                                              float* __restrict__ part_W,
                                                              double* __restrict__ zero_ptr,
@@ -1881,6 +1881,37 @@ tinykg_status launch_score(const tinykg_graph* g, Source src, const float* Wr, c
   return launch_status();
 }
 
+// H_h = e_h + sum_j pi_j e_t from the rows behind `src` (exact E in the forward pass; the
+// saved E_hat when the backward pass rebuilds H instead of reading a saved copy).
+template <int D, int BITS>
+tinykg_status launch_attend_fwd(const tinykg_graph* g, Source src, const float* s, float* H, uint8_t* ws,
+                                const HeavyWs& hv, hipStream_t st) {
+  const int64_t N = g->n_nodes;
+  tinykg_status rc;
+  const int wave_blocks = (int)std::max<int64_t>(1, std::min<int64_t>((N + 3) / 4, (int64_t)num_cus() * 16));
+  {
+    ProfileScope prof("attend_fwd_kernel", st);
+    hipLaunchKernelGGL((attend_fwd_kernel<D, BITS>), dim3(wave_blocks), dim3(kThreads), 0, st, src, g->rowptr,
+                       g->h_tail, s, N, H);
+  }
+  if ((rc = launch_status()) != TINYKG_OK) return rc;
+  if (g->n_heavy > 0) {
+    const HeavyList hl = heavy_list(g);
+    float* pm = reinterpret_cast<float*>(ws + hv.pm);
+    double* pz = reinterpret_cast<double*>(ws + hv.pz);
+    double* pacc = reinterpret_cast<double*>(ws + hv.pacc);
+    float* hm = reinterpret_cast<float*>(ws + hv.hm);
+    double* hz = reinterpret_cast<double*>(ws + hv.hz);
+    ProfileScope prof("heavy_head_kernels", st);
+    hipLaunchKernelGGL((heavy_part1_kernel<D, true, BITS>), dim3((g->n_hseg + 3) / 4), dim3(kThreads), 0, st,
+                       src, g->h_tail, s, hl, pm, pz, pacc);
+    hipLaunchKernelGGL((heavy_merge1_kernel<D, true, BITS>), dim3(g->n_heavy), dim3(kMergeWaves * 64), 0, st,
+                       src, hl, pm, pz, pacc, hm, hz, H);
+    if ((rc = launch_status()) != TINYKG_OK) return rc;
+  }
+  return TINYKG_OK;
+}
+
 template <int D>
 tinykg_status fwd_impl(const tinykg_graph* g, const float* E, const float* Wr, const float* er,
                        const float* W, int d_out, float slope, int bits, int group, uint64_t seed,
@@ -1888,7 +1919,8 @@ tinykg_status fwd_impl(const tinykg_graph* g, const float* E, const float* Wr, c
   const int64_t N = g->n_nodes;
   const FwdWs L = fwd_layout(g, D);
   float* s = reinterpret_cast<float*>(ws + L.s);
-  float* H = bits == 32 ? reinterpret_cast<float*>(sv->packed_H) : reinterpret_cast<float*>(ws + L.H);
+  const bool keep_H = sv->packed_H != nullptr;   // else: the backward pass rebuilds H from E_hat
+  float* H = bits == 32 && keep_H ? reinterpret_cast<float*>(sv->packed_H) : reinterpret_cast<float*>(ws + L.H);
   Source src{reinterpret_cast<const uint8_t*>(E), nullptr, nullptr, 0};
   tinykg_status rc = TINYKG_OK;
   const bool uniform = Wr == nullptr;     // pi = 1 / deg: the softmax of all-zero scores
@@ -1903,27 +1935,7 @@ tinykg_status fwd_impl(const tinykg_graph* g, const float* E, const float* Wr, c
     rc = launch_score<D, 32>(g, src, Wr, er, s, st);
   }
   if (rc != TINYKG_OK) return rc;
-  const int wave_blocks = (int)std::max<int64_t>(1, std::min<int64_t>((N + 3) / 4, (int64_t)num_cus() * 16));
-  {
-    ProfileScope prof("attend_fwd_kernel", st);
-    hipLaunchKernelGGL((attend_fwd_kernel<D>), dim3(wave_blocks), dim3(kThreads), 0, st, E, g->rowptr,
-                       g->h_tail, s, N, H);
-  }
-  if ((rc = launch_status()) != TINYKG_OK) return rc;
-  if (g->n_heavy > 0) {
-    const HeavyList hl = heavy_list(g);
-    float* pm = reinterpret_cast<float*>(ws + L.hv.pm);
-    double* pz = reinterpret_cast<double*>(ws + L.hv.pz);
-    double* pacc = reinterpret_cast<double*>(ws + L.hv.pacc);
-    float* hm = reinterpret_cast<float*>(ws + L.hv.hm);
-    double* hz = reinterpret_cast<double*>(ws + L.hv.hz);
-    ProfileScope prof("heavy_head_kernels", st);
-    hipLaunchKernelGGL((heavy_part1_kernel<D, true>), dim3((g->n_hseg + 3) / 4), dim3(kThreads), 0, st, E,
-                       g->h_tail, s, hl, pm, pz, pacc);
-    hipLaunchKernelGGL((heavy_merge1_kernel<D, true>), dim3(g->n_heavy), dim3(kMergeWaves * 64), 0, st, E,
-                       hl, pm, pz, pacc, hm, hz, H);
-    if ((rc = launch_status()) != TINYKG_OK) return rc;
-  }
+  if ((rc = launch_attend_fwd<D, 32>(g, src, s, H, ws, L.hv, st)) != TINYKG_OK) return rc;
   // save the context (Fig. 1): Q(E; seed), Q(H; seed + 1)
   // (the uniform layer's backward pass never reads E: only Q(H) and the mask are kept)
   if (bits == 32) {
@@ -1937,9 +1949,11 @@ tinykg_status fwd_impl(const tinykg_graph* g, const float* E, const float* Wr, c
                            sv->gmin_E, sv->gscale_E, st);
       if (rc != TINYKG_OK) return rc;
     }
-    rc = launch_quantize(H, N * D, bits, group, seed + 1, 0, TINYKG_ROUND_STOCHASTIC, sv->packed_H,
-                         sv->gmin_H, sv->gscale_H, st);
-    if (rc != TINYKG_OK) return rc;
+    if (keep_H) {
+      rc = launch_quantize(H, N * D, bits, group, seed + 1, 0, TINYKG_ROUND_STOCHASTIC, sv->packed_H,
+                           sv->gmin_H, sv->gscale_H, st);
+      if (rc != TINYKG_OK) return rc;
+    }
   }
   const int DOP = (d_out + 31) & ~31;
   const size_t smem = (size_t)(DOP * (D + 4) + 64 * (D + 4) + 64 * (DOP + 4)) * 4;
@@ -1971,8 +1985,21 @@ tinykg_status bwd_impl(const tinykg_graph* g, const tinykg_saved* sv, const floa
   const int gl2 = BITS == 32 ? 0 : ilog2(group / 4);
   Source srcE{sv->packed_E, sv->gmin_E, sv->gscale_E, gl2};
   Source srcH{sv->packed_H, sv->gmin_H, sv->gscale_H, gl2};
-  tinykg_status rc;
+  tinykg_status rc = TINYKG_OK;
 
+  const bool uniform = Wr == nullptr;     // pi = 1 / deg: only the transposed sparse product is left
+  // H was not saved: rebuild it from E_hat (scores first), in the buffer that grad_H then
+  // overwrites tile by tile (the dense kernel reads the rows of a tile before it writes them)
+  const bool rebuild_H = sv->packed_H == nullptr;
+  bool have_scores = false;
+  if (rebuild_H) {
+    if (g->n_chunks > 0) {
+      if ((rc = launch_score<D, BITS>(g, srcE, Wr, er, s, st)) != TINYKG_OK) return rc;
+      have_scores = true;
+    }
+    if ((rc = launch_attend_fwd<D, BITS>(g, srcE, s, gH, ws, L.hv, st)) != TINYKG_OK) return rc;
+    srcH = Source{reinterpret_cast<const uint8_t*>(gH), nullptr, nullptr, 0};
+  }
   // dense stage
   const int DOP = (d_out + 31) & ~31;
   const int64_t n_heavy_elems = (int64_t)g->n_acc_heavy * D;
@@ -1980,7 +2007,7 @@ tinykg_status bwd_impl(const tinykg_graph* g, const tinykg_saved* sv, const floa
   int dense_blocks = 0;
   {
     const size_t smem = (size_t)(DOP * LD + 64 * LD + 64 * (DOP + 4)) * 4;
-    auto kern = dense_bwd_kernel<D, BITS>;
+    auto kern = rebuild_H ? dense_bwd_kernel<D, 32> : dense_bwd_kernel<D, BITS>;
     if ((rc = set_smem(kern, smem)) != TINYKG_OK) return rc;
     const int grid = dense_grid(N);
     dense_blocks = grid;
@@ -1991,7 +2018,6 @@ tinykg_status bwd_impl(const tinykg_graph* g, const tinykg_saved* sv, const floa
     }
     if ((rc = launch_status()) != TINYKG_OK) return rc;
   }
-  const bool uniform = Wr == nullptr;     // pi = 1 / deg: only the transposed sparse product is left
   if (uniform && g->n_edges > 0) {
     const GradSink sink{gE, acc, g->acc_slot};
     const int64_t waves = (g->n_edges + 31) / 32;
@@ -2001,7 +2027,7 @@ tinykg_status bwd_impl(const tinykg_graph* g, const tinykg_saved* sv, const floa
     if ((rc = launch_status()) != TINYKG_OK) return rc;
   }
   if (!uniform && g->n_chunks > 0) {
-    if ((rc = launch_score<D, BITS>(g, srcE, Wr, er, s, st)) != TINYKG_OK) return rc;
+    if (!have_scores && (rc = launch_score<D, BITS>(g, srcE, Wr, er, s, st)) != TINYKG_OK) return rc;
     const int wave_blocks = (int)std::max<int64_t>(1, std::min<int64_t>((N + 3) / 4, (int64_t)num_cus() * 16));
     {
       ProfileScope prof("attend_bwd_kernel", st);
@@ -2018,10 +2044,12 @@ tinykg_status bwd_impl(const tinykg_graph* g, const tinykg_saved* sv, const floa
       double* hz = reinterpret_cast<double*>(ws + L.hv.hz);
       ProfileScope prof("heavy_head_kernels", st);
       const dim3 gs_grid((g->n_hseg + 3) / 4), gh_grid(g->n_heavy);
-      hipLaunchKernelGGL((heavy_part1_kernel<D, false>), gs_grid, dim3(kThreads), 0, st,
-                         (const float*)nullptr, g->h_tail, s, hl, pm, pz, (double*)nullptr);
-      hipLaunchKernelGGL((heavy_merge1_kernel<D, false>), gh_grid, dim3(kMergeWaves * 64), 0, st,
-                         (const float*)nullptr, hl, pm, pz, (const double*)nullptr, hm, hz, (float*)nullptr);
+      if (!rebuild_H) {   // else the rebuild of H left the softmax statistics of the heavy heads in hm / hz
+        hipLaunchKernelGGL((heavy_part1_kernel<D, false, BITS>), gs_grid, dim3(kThreads), 0, st,
+                           srcE, g->h_tail, s, hl, pm, pz, (double*)nullptr);
+        hipLaunchKernelGGL((heavy_merge1_kernel<D, false, BITS>), gh_grid, dim3(kMergeWaves * 64), 0, st,
+                           srcE, hl, pm, pz, (const double*)nullptr, hm, hz, (float*)nullptr);
+      }
       hipLaunchKernelGGL((heavy_part2_kernel<D, BITS>), gs_grid, dim3(kThreads), 0, st, srcE, gH, g->h_tail,
                          s, hl, hm, hz, pi, gs, pc);
       hipLaunchKernelGGL(heavy_part3_kernel, gs_grid, dim3(kThreads), 0, st, hl, pc, pi, gs);
@@ -2077,15 +2105,18 @@ tinykg_status bwd_bits(int bits, const tinykg_graph* g, const tinykg_saved* sv, 
   return TINYKG_ERR_INVALID_ARG;
 }
 
+// packed_H == NULL: H is not saved (the backward pass rebuilds it from E_hat)
 tinykg_status check_saved(const tinykg_saved* sv, int bits) {
-  if (!sv || !sv->packed_E || !sv->packed_H || !sv->mask_J) return TINYKG_ERR_INVALID_ARG;
+  if (!sv || !sv->packed_E || !sv->mask_J) return TINYKG_ERR_INVALID_ARG;
   if (!aligned16(sv->packed_E) || !aligned16(sv->packed_H) || !aligned16(sv->mask_J))
     return TINYKG_ERR_INVALID_ARG;
   if (bits != 32) {
-    if (!sv->gmin_E || !sv->gscale_E || !sv->gmin_H || !sv->gscale_H) return TINYKG_ERR_INVALID_ARG;
-    if (!aligned16(sv->gmin_E) || !aligned16(sv->gscale_E) || !aligned16(sv->gmin_H) ||
-        !aligned16(sv->gscale_H))
-      return TINYKG_ERR_INVALID_ARG;
+    if (!sv->gmin_E || !sv->gscale_E) return TINYKG_ERR_INVALID_ARG;
+    if (!aligned16(sv->gmin_E) || !aligned16(sv->gscale_E)) return TINYKG_ERR_INVALID_ARG;
+    if (sv->packed_H) {
+      if (!sv->gmin_H || !sv->gscale_H) return TINYKG_ERR_INVALID_ARG;
+      if (!aligned16(sv->gmin_H) || !aligned16(sv->gscale_H)) return TINYKG_ERR_INVALID_ARG;
+    }
   }
   return TINYKG_OK;
 }

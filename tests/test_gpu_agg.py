@@ -9,6 +9,8 @@ Protocol (bit-exactness is only defined for identical inputs):
   4. backward: the oracle starts from the bytes the GPU saved              (1e-5)
   5. E_out with a compressed context is bitwise E_out with bits=32 (the forward
      pass is exact -- Fig. 1)
+  6. the context without Q(H): same E_out, same Q(E) and mask bytes; backward against
+     the oracle with H rebuilt from E_hat (the second stage of Eq. 2 run again)   (1e-5)
 Tolerance ("1e-5 relative" for fp32 tensors whose entries are sums):
   |gpu - ref| <= 1e-5 * max(|ref|, rms(ref tensor), rms(ref row)),
 where a row is the vector of one node (last axis).  The row term is there because
@@ -71,9 +73,9 @@ class Layer:
                  tk.tinykg_kg_aggregate_workspace_bytes(self.graph, self.d, self.k, self.dout, True), 16)
         self.ws = torch.empty(nb, dtype=torch.uint8, device=dev)
 
-    def forward(self, bits, group, seed):
+    def forward(self, bits, group, seed, with_H=True):
         tk = self.tk
-        saved = tk.SavedContext(self.N, self.d, self.dout, bits, group)
+        saved = tk.SavedContext(self.N, self.d, self.dout, bits, group, with_H=with_H)
         Eo = tk.tinykg_kg_aggregate_fwd(self.graph, self.t["E"], self.t["Wr"], self.t["er"], self.t["W"],
                                         SLOPE, bits, group, seed, saved, self.ws)
         torch.cuda.synchronize()
@@ -87,14 +89,18 @@ class Layer:
         return out
 
     def saved_to_host(self, saved):
+        host = lambda t: t.cpu().numpy()
+        ctx = {"bits": saved.bits, "mask": host(saved.mask_J)}
         if saved.bits == 32:
-            return {"bits": 32, "mask": saved.mask_J.cpu().numpy(),
-                    "E": saved.packed_E.cpu().numpy().view(np.float32).reshape(self.N, self.d),
-                    "H": saved.packed_H.cpu().numpy().view(np.float32).reshape(self.N, self.d)}
-        return {"bits": saved.bits, "group": saved.group, "mask": saved.mask_J.cpu().numpy(),
-                "packed_E": saved.packed_E.cpu().numpy(), "gmin_E": saved.gmin_E.cpu().numpy(),
-                "gscale_E": saved.gscale_E.cpu().numpy(), "packed_H": saved.packed_H.cpu().numpy(),
-                "gmin_H": saved.gmin_H.cpu().numpy(), "gscale_H": saved.gscale_H.cpu().numpy()}
+            ctx["E"] = host(saved.packed_E).view(np.float32).reshape(self.N, self.d)
+            if saved.packed_H is not None:
+                ctx["H"] = host(saved.packed_H).view(np.float32).reshape(self.N, self.d)
+            return ctx
+        ctx.update(group=saved.group, packed_E=host(saved.packed_E), gmin_E=host(saved.gmin_E),
+                   gscale_E=host(saved.gscale_E))
+        if saved.packed_H is not None:
+            ctx.update(packed_H=host(saved.packed_H), gmin_H=host(saved.gmin_H), gscale_H=host(saved.gscale_H))
+        return ctx
 
 
 def run_protocol(tk, N, R, head, rel, tail, d, dout, bits, group, seed=5, data_seed=0, threads=4,
@@ -139,6 +145,22 @@ def run_protocol(tk, N, R, head, rel, tail, d, dout, bits, group, seed=5, data_s
         want = ref.aggregate_bwd(N, head, rel, tail, Eh, Hh, mk, Wr, er, W, SLOPE, G, threads=threads)
         for a, w, nm in zip(grads, want, ("grad_E", "grad_Wr", "grad_er", "grad_W")):
             close(a, w, f"{nm} (bits={b})")
+    # the context without Q(H)                                                   # (6)
+    for b, full in ((32, ctx32), (bits, ctx)):
+        Eo_r, sv_r = L.forward(b, group, seed, with_H=False)
+        assert torch.equal(Eo_r, Eo32), "leaving H out changed the forward output"
+        c = L.saved_to_host(sv_r)
+        assert "H" not in c and "packed_H" not in c
+        for key in c:
+            if key not in ("bits", "group"):
+                assert np.array_equal(c[key].view(np.uint8), full[key].view(np.uint8)), key
+        grads = L.backward(sv_r, b, group)
+        Eh, Hh, mk = ref.restore_context(c, N, d, dout)
+        assert Hh is None
+        Ht = ref.rebuild_H(N, head, rel, tail, Eh, Wr, er, W, SLOPE, threads=threads)
+        want = ref.aggregate_bwd(N, head, rel, tail, Eh, Ht, mk, Wr, er, W, SLOPE, G, threads=threads)
+        for a, w, nm in zip(grads, want, ("grad_E", "grad_Wr", "grad_er", "grad_W")):
+            close(a, w, f"{nm} (bits={b}, H rebuilt)")
     L.graph.close()
     return L
 

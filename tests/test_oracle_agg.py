@@ -262,3 +262,34 @@ def test_compressed_context_gives_unbiased_linear_gradient():
     sd = np.sqrt(np.maximum(acc2 / S - mean ** 2, 1e-30) / S)
     z = (mean - gW_exact) / sd
     assert np.abs(z).max() < 5.0 and 0.7 < np.mean(z * z) < 1.4
+
+
+def test_context_without_H_rebuilds_it_from_E_hat():
+    # the variant that saves Q(E) and the mask only: H~ is the brute-force second stage of
+    # Eq. 2 at E_hat (not at E, and not the dequantised Q(H)); with an uncompressed context
+    # it is the forward pass's own H, so both variants give the same gradients there
+    P = small_problem(N=16, seed=11)
+    N, d, dout = P["N"], P["d"], P["dout"]
+    a = (N, P["head"], P["rel"], P["tail"])
+    E32 = P["E"].astype(np.float32)
+    Wr, er, W = (P[k].astype(np.float32) for k in ("Wr", "er", "W"))
+    Eo, H, mask = ref.aggregate_fwd(*a, E32, Wr, er, W, P["slope"])
+    ctx = ref.save_context(E32, H, mask, 2, 32, seed=3, keep_H=False)
+    assert "packed_H" not in ctx
+    full = ref.save_context(E32, H, mask, 2, 32, seed=3)
+    assert np.array_equal(ctx["packed_E"], full["packed_E"]) and np.array_equal(ctx["mask"], full["mask"])
+    Eh, Hh, mk = ref.restore_context(ctx, N, d, dout)
+    assert Hh is None and np.array_equal(mk, mask != 0)
+    Ht = ref.rebuild_H(*a, Eh, Wr, er, W, P["slope"])
+    Q = dict(P)
+    _, H_brute, _, _ = dense_forward(Q, E=Eh.astype(np.float64), Wr=Wr.astype(np.float64),
+                                     er=er.astype(np.float64), W=W.astype(np.float64))
+    assert np.allclose(Ht, H_brute, rtol=2e-6, atol=1e-7)
+    assert not np.allclose(Ht, H, atol=1e-3)                      # 2-bit E_hat is far from E
+    _, Hq, _ = ref.restore_context(full, N, d, dout)
+    assert not np.allclose(Ht, Hq, atol=1e-3)
+    # uncompressed: identical
+    c32 = ref.save_context(E32, H, mask, 32, 32, seed=3, keep_H=False)
+    E0, H0, m0 = ref.restore_context(c32, N, d, dout)
+    assert H0 is None
+    assert np.array_equal(ref.rebuild_H(*a, E0, Wr, er, W, P["slope"]), H)

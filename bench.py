@@ -37,13 +37,15 @@ def bytes_per_activation(bits, group):
     return bits / 8 + 8 / group
 
 
-def step_algorithmic_bytes():
-    """Compulsory bytes of one forward+backward step (per-edge and per-node terms)."""
+def step_algorithmic_bytes(saved_H=True):
+    """Compulsory bytes of one forward+backward step (per-edge and per-node terms).
+    saved_H=False: Q(H) is neither written nor read; the packed e_t rows are gathered twice."""
     bpa = bytes_per_activation(BITS, GROUP)
+    nq = 2 if saved_H else 1
     fwd_edge = 4 * D + 4 + 4 + 4            # e_t row, tail id, relation id, score
-    fwd_node = 4 * D + 4 * D + 2 * D * bpa + D / 8   # E in, E' out, Q(E)+Q(H) saved, mask
-    bwd_edge = D * bpa + 12                 # packed e_t row, ids + score gradient
-    bwd_node = 4 * D + D * bpa + D / 8 + 4 * D       # grad_E' in, H_hat, mask, grad_E out
+    fwd_node = 4 * D + 4 * D + nq * D * bpa + D / 8  # E in, E' out, Q(E) (+Q(H)) saved, mask
+    bwd_edge = (3 - nq) * D * bpa + 12      # packed e_t row, ids + score gradient
+    bwd_node = 4 * D + D * bpa + D / 8 + 4 * D       # grad_E' in, H_hat (or E_hat), mask, grad_E out
     return T * (fwd_edge + bwd_edge) + N * (fwd_node + bwd_node)
 
 
@@ -307,7 +309,9 @@ def stack_workload(a, which):
               for l in range(len(dims) - 1)]
     rng = np.random.default_rng(5)
     u, p, n = (torch.from_numpy(rng.integers(0, sample_hi, 4096).astype(np.int32)).to(dev) for _ in range(3))
-    stack = tk.KGStack(graph, dims, bits, group, SLOPE)
+    stack = tk.KGStack(graph, dims, bits, group, SLOPE, save_H=not a.rebuild_H)
+    if a.rebuild_H:
+        name += "; contexts without Q(H) (H rebuilt in the backward pass)"
     prep_s = time.perf_counter() - t_prep
     torch.cuda.reset_peak_memory_stats()
     for i in range(a.warmup):
@@ -355,6 +359,8 @@ def main():
                     help="config1 (default, the headline step); config2: the 9-cell compressor sweep; "
                          "config3 / config4: multi-layer steps; uniform: the uniform-attention "
                          "layer on the config1 graph")
+    ap.add_argument("--rebuild-H", action="store_true",
+                    help="config1/3/4: save Q(E) and the mask only; the backward pass rebuilds H from E_hat")
     ap.add_argument("--bits", type=int, default=0, help="config4 only: 4 (default) or 32 for the fp32 run")
     a = ap.parse_args()
     if a.gpus != 1:
@@ -376,7 +382,7 @@ def main():
     inp = make_inputs(torch)
     t = {k: torch.from_numpy(v).to(dev) for k, v in inp.items()}
     graph = tk.Graph(N, R, t["head"], t["rel"], t["tail"])
-    saved = tk.SavedContext(N, D, D, BITS, GROUP)
+    saved = tk.SavedContext(N, D, D, BITS, GROUP, with_H=not a.rebuild_H)
     ws = torch.empty(max(tk.tinykg_kg_aggregate_workspace_bytes(graph, D, D, D, False),
                          tk.tinykg_kg_aggregate_workspace_bytes(graph, D, D, D, True)),
                      dtype=torch.uint8, device=dev)
@@ -403,7 +409,7 @@ def main():
     tk.tinykg_profile_enable(False)
 
     ms_per_step = dt / a.steps * 1e3
-    alg = step_algorithmic_bytes()
+    alg = step_algorithmic_bytes(saved_H=not a.rebuild_H)
     kernels = {k: {"launches_per_step": v[0] / a.steps, "ms_per_step": round(v[1] / a.steps, 4)}
                for k, v in rep.items()}
     dom_ms = rep["edge_bwd_kernel"][1] / rep["edge_bwd_kernel"][0]
@@ -416,7 +422,8 @@ def main():
         "data": "synthetic",
         "config": {"workload": "configs[1]: one KGAT-style attentive aggregation layer, forward+backward, "
                                "100k entities, dim 64, 16 relations, 1M triplets (Zipf 1.1 tails), "
-                               "saved inputs INT2 group 64",
+                               "saved inputs INT2 group 64"
+                               + ("; context without Q(H) (H rebuilt in the backward pass)" if a.rebuild_H else ""),
                    "bits": BITS, "group": GROUP, "bytes_per_activation": bytes_per_activation(BITS, GROUP),
                    "compression_ratio": round(4 / bytes_per_activation(BITS, GROUP), 3),
                    "algorithmic_bytes_per_step": alg,

@@ -11,13 +11,17 @@ from . import binding as B
 
 
 class KGStack:
-    def __init__(self, graph, dims, bits, group, slope=0.2, device="cuda", keep_activations=False):
-        """dims = [d_0, d_1, ..., d_L]; layer l maps [N, d_l] -> [N, d_{l+1}]."""
+    def __init__(self, graph, dims, bits, group, slope=0.2, device="cuda", keep_activations=False,
+                 save_H=True):
+        """dims = [d_0, d_1, ..., d_L]; layer l maps [N, d_l] -> [N, d_{l+1}].
+        save_H=False: the contexts hold Q(E) and the mask only (the backward pass rebuilds H)."""
         self.graph, self.dims, self.bits, self.group, self.slope = graph, list(dims), bits, group, slope
         self.L = len(dims) - 1
         self.N = graph.n_nodes
         self.device = device
-        self.saved = [B.SavedContext(self.N, dims[l], dims[l + 1], bits, group, device) for l in range(self.L)]
+        self.save_H = save_H
+        self.saved = [B.SavedContext(self.N, dims[l], dims[l + 1], bits, group, device, with_H=save_H)
+                      for l in range(self.L)]
         nb = 16
         for l in range(self.L):
             for bwd in (False, True):

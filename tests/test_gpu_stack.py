@@ -24,7 +24,8 @@ def tk():
     return tk
 
 
-def run_stack(tk, N, R, head, rel, tail, dims, bits, group, batch, seed=3, threads=4, sample_hi=None):
+def run_stack(tk, N, R, head, rel, tail, dims, bits, group, batch, seed=3, threads=4, sample_hi=None,
+              save_H=True):
     dev = "cuda"
     rng = np.random.default_rng(5)
     E0 = gen.entity_embeddings(N, dims[0], seed=1, std=0.1)
@@ -35,7 +36,7 @@ def run_stack(tk, N, R, head, rel, tail, dims, bits, group, batch, seed=3, threa
     neg = rng.integers(0, hi, batch).astype(np.int32)
     users[1] = users[0]; neg[2] = pos[3]                      # repeated ids
     graph = tk.Graph(N, R, *(torch.from_numpy(a).to(dev) for a in (head, rel, tail)))
-    stack = tk.KGStack(graph, dims, bits, group, SLOPE, keep_activations=True)
+    stack = tk.KGStack(graph, dims, bits, group, SLOPE, keep_activations=True, save_H=save_H)
     tp = [tuple(torch.from_numpy(a).to(dev) for a in p) for p in params]
     tu, tpz, tn = (torch.from_numpy(a).to(dev) for a in (users, pos, neg))
     loss = stack.forward(torch.from_numpy(E0).to(dev), tp, seed, tu, tpz, tn)
@@ -44,7 +45,8 @@ def run_stack(tk, N, R, head, rel, tail, dims, bits, group, batch, seed=3, threa
     L = len(dims) - 1
 
     # footprint ledger: 2 N d_l (b/8 + 8/G) + N d_{l+1} / 8 per layer
-    want_bytes = sum(2 * N * dims[l] * (bits / 8 + 8 / group) + N * dims[l + 1] / 8 for l in range(L))
+    nq = 2 if save_H else 1
+    want_bytes = sum(nq * N * dims[l] * (bits / 8 + 8 / group) + N * dims[l + 1] / 8 for l in range(L))
     assert stack.saved_context_bytes() == want_bytes
     assert stack.fp32_context_bytes() == sum(2 * N * dims[l] * 4 + N * dims[l + 1] / 8 for l in range(L))
 
@@ -72,9 +74,13 @@ def run_stack(tk, N, R, head, rel, tail, dims, bits, group, batch, seed=3, threa
         sv = stack.saved[l]
         ctx = {"bits": bits, "group": group, "mask": sv.mask_J.cpu().numpy(),
                "packed_E": sv.packed_E.cpu().numpy(), "gmin_E": sv.gmin_E.cpu().numpy(),
-               "gscale_E": sv.gscale_E.cpu().numpy(), "packed_H": sv.packed_H.cpu().numpy(),
-               "gmin_H": sv.gmin_H.cpu().numpy(), "gscale_H": sv.gscale_H.cpu().numpy()}
+               "gscale_E": sv.gscale_E.cpu().numpy()}
+        if save_H:
+            ctx.update(packed_H=sv.packed_H.cpu().numpy(), gmin_H=sv.gmin_H.cpu().numpy(),
+                       gscale_H=sv.gscale_H.cpu().numpy())
         Eh, Hh, mk = ref.restore_context(ctx, N, dims[l], dims[l + 1])
+        if not save_H:      # the second stage of Eq. 2 again, at E_hat
+            Hh = ref.rebuild_H(N, head, rel, tail, Eh, *params[l], SLOPE, threads=threads)
         wgE, wgWr, wger, wgW = ref.aggregate_bwd_f64(N, head, rel, tail, Eh, Hh, mk, *params[l],
                                                      float(np.float32(SLOPE)), g[l + 1], threads=threads)
         close(g[l], wgE + rgrads[l], f"grad_E^({l})")
@@ -88,6 +94,13 @@ def test_small_stack_matches_oracle_stage_by_stage(tk):
     N, R, T = 600, 6, 5000
     head, rel, tail = gen.kg_triplets(N, R, T, seed=4, tail_zipf=1.1)
     run_stack(tk, N, R, head, rel, tail, [64, 64, 32, 16], 2, 64, batch=256)
+
+
+def test_small_stack_with_contexts_without_H(tk):
+    N, R, T = 600, 6, 5000
+    head, rel, tail = gen.kg_triplets(N, R, T, seed=4, tail_zipf=1.1)
+    stack = run_stack(tk, N, R, head, rel, tail, [64, 64, 32, 16], 2, 64, batch=256, save_H=False)
+    assert stack.fp32_context_bytes() / stack.saved_context_bytes() > 15
 
 
 def test_small_stack_end_to_end_against_the_oracle_chain(tk):

@@ -382,3 +382,86 @@ def quantize_bf16(act_u16, bits, group, seed, first_index=0, rounding=0):
     """Quant of Eq. (3) for half-precision inputs (Sec. 4.1.4): the fp32 quantizer applied to
     the exactly widened values."""
     return quantize(widen_bf16(act_u16), bits, group, seed, first_index, rounding)
+
+
+# ------------------------------------------------ BatchNorm with a compressed context ------
+def batchnorm_fwd(x, gamma, beta, eps):
+    """Batch normalisation over the rows, training mode (one of the operators whose saved
+    input is compressed, Sec. 4.1.4): mu_c = mean_n x[n, c], var_c = mean_n (x[n, c] - mu_c)^2,
+    rstd_c = 1 / sqrt(var_c + eps), y = gamma (x - mu) rstd + beta.  float64 throughout,
+    outputs rounded to fp32 once.  Returns y, mu, rstd.  The context is Q(x; seed) plus mu and
+    rstd themselves (2 * dim numbers, kept exact)."""
+    x64 = np.asarray(x, dtype=np.float64)
+    n = x64.shape[0]
+    mu = x64.sum(axis=0) / n
+    var = ((x64 - mu) ** 2).sum(axis=0) / n
+    rstd = 1.0 / np.sqrt(var + np.float64(eps))
+    y = np.asarray(gamma, np.float64) * (x64 - mu) * rstd + np.asarray(beta, np.float64)
+    return y.astype(np.float32), mu.astype(np.float32), rstd.astype(np.float32)
+
+
+def batchnorm_bwd(xhat, mu, rstd, gamma, grad_y):
+    """Backward of batchnorm_fwd at the saved context (x_hat, mu, rstd):
+    xbar = (x_hat - mu) rstd; grad_beta = sum_n g; grad_gamma = sum_n g xbar;
+    grad_x = gamma rstd (g - grad_beta / n - xbar grad_gamma / n).  float64, rounded once."""
+    xh = np.asarray(xhat, dtype=np.float64)
+    g = np.asarray(grad_y, dtype=np.float64)
+    n = xh.shape[0]
+    mu, rstd, gamma = (np.asarray(a, dtype=np.float64) for a in (mu, rstd, gamma))
+    xbar = (xh - mu) * rstd
+    gbeta = g.sum(axis=0)
+    ggamma = (g * xbar).sum(axis=0)
+    gx = gamma * rstd * (g - gbeta / n - xbar * ggamma / n)
+    return gx.astype(np.float32), ggamma.astype(np.float32), gbeta.astype(np.float32)
+
+
+# ------------------------------------------------ max-pooling aggregation (SPMM_MAX) ------
+def head_order(head, rel, tail):
+    """The order in which a head's out-edges are numbered: by (relation, tail, input
+    position).  Returns the permutation of the input triplets sorted by (head, relation,
+    tail, position)."""
+    head, rel, tail = _coo(head, rel, tail)
+    order = np.lexsort((np.arange(head.size), tail, rel, head))
+    return order
+
+
+def spmm_max_fwd(n_nodes, head, rel, tail, E):
+    """M[h, c] = max over the out-edges (h, r, t) of E[t, c]; 0 for a head without
+    out-edges.  The context is, per output element, the LOCAL number (in head_order) of the
+    first out-edge that attains the maximum -- a narrow integer instead of the activation
+    (Sec. 4.1.4 lists SPMM_MAX among the compressed operators); 0 where there is no edge.
+    Returns M (fp32, exact: a maximum has no rounding) and arg (int64 [n, d])."""
+    head, rel, tail = _coo(head, rel, tail)
+    E = np.ascontiguousarray(E, dtype=np.float32)
+    d = E.shape[1]
+    order = head_order(head, rel, tail)
+    hs, ts = head[order], tail[order]
+    M = np.zeros((n_nodes, d), np.float32)
+    arg = np.zeros((n_nodes, d), np.int64)
+    start = np.searchsorted(hs, np.arange(n_nodes), side="left")
+    end = np.searchsorted(hs, np.arange(n_nodes), side="right")
+    for h in range(n_nodes):
+        if end[h] > start[h]:
+            rows = E[ts[start[h]:end[h]]]                 # [deg, d]
+            arg[h] = np.argmax(rows, axis=0)              # first occurrence of the maximum
+            M[h] = rows[arg[h], np.arange(d)]
+    return M, arg
+
+
+def spmm_max_bwd(n_nodes, head, rel, tail, arg, grad_M):
+    """grad_E[t, c] = sum of grad_M[h, c] over the heads h whose saved out-edge number
+    arg[h, c] leads to t; heads without out-edges pass nothing on.  float64 sums, rounded once."""
+    head, rel, tail = _coo(head, rel, tail)
+    g = np.asarray(grad_M, dtype=np.float64)
+    d = g.shape[1]
+    order = head_order(head, rel, tail)
+    hs, ts = head[order], tail[order]
+    start = np.searchsorted(hs, np.arange(n_nodes), side="left")
+    end = np.searchsorted(hs, np.arange(n_nodes), side="right")
+    gE = np.zeros((n_nodes, d), np.float64)
+    cols = np.arange(d)
+    for h in range(n_nodes):
+        if end[h] > start[h]:
+            t = ts[start[h] + np.asarray(arg[h], dtype=np.int64)]
+            np.add.at(gE, (t, cols), g[h])
+    return gE.astype(np.float32)

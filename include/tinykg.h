@@ -235,6 +235,38 @@ tinykg_status tinykg_scatter_add_rows(const float* src, int dim, const int32_t* 
 tinykg_status tinykg_fill_zero(float* dst, int64_t n, void* stream);
 
 /* ------------------------------------------------------------------------- *
+ * Batch normalisation over the rows (training mode) with its input saved
+ * compressed.  Sec. 4.1.4 names BatchNorm among the operators whose context is
+ * compressed; the operator's input takes the place of the activation in Eq. 3 / 4:
+ *   mu_c = mean_n x[n,c]   var_c = mean_n (x[n,c] - mu_c)^2   rstd_c = 1/sqrt(var_c + eps)
+ *   y[n,c] = gamma_c (x[n,c] - mu_c) rstd_c + beta_c                     (exact)
+ * Saved: Q(x; seed) in tinykg_quantize's layout (with bits == 32: an fp32 copy of
+ * x in `packed`, rows*dim*4 bytes, gmin / gscale unused), and mean[dim], rstd[dim]
+ * themselves.  Backward, at x_hat = the dequantised Q(x), xbar = (x_hat - mu) rstd:
+ *   grad_beta_c = sum_n g[n,c]        grad_gamma_c = sum_n g[n,c] xbar[n,c]
+ *   grad_x = gamma rstd (g - grad_beta/rows - xbar grad_gamma/rows)
+ * All pointers DEVICE, 16-byte aligned, row-major; x, y, grad_y, grad_x [rows, dim]
+ * fp32; gamma, beta, mean, rstd, grad_gamma, grad_beta [dim].  dim a multiple of 4
+ * in [4, 1024] and rows*dim < 2^34 (else ERR_UNSUPPORTED); rows*dim a multiple of
+ * `group` (ERR_SHAPE); eps >= 0.  rows == 0: OK; the forward call writes nothing,
+ * the backward call zeroes grad_gamma / grad_beta.  Outputs are overwritten, and
+ * every one of them is deterministic.  `workspace`: at least
+ * tinykg_batchnorm_workspace_bytes(rows, dim) bytes (0 = unsupported shape);
+ * ERR_WORKSPACE if missing or too small.  Calls enqueue on `stream` and return.
+ * ------------------------------------------------------------------------- */
+size_t tinykg_batchnorm_workspace_bytes(int64_t rows, int dim);
+tinykg_status tinykg_batchnorm_fwd(const float* x, int64_t rows, int dim, const float* gamma,
+                                   const float* beta, float eps, int bits, int group, uint64_t seed,
+                                   float* y, uint8_t* packed, float* gmin, float* gscale,
+                                   float* mean, float* rstd, void* workspace,
+                                   size_t workspace_bytes, void* stream);
+tinykg_status tinykg_batchnorm_bwd(const uint8_t* packed, const float* gmin, const float* gscale,
+                                   const float* mean, const float* rstd, const float* gamma,
+                                   int64_t rows, int dim, int bits, int group, const float* grad_y,
+                                   float* grad_x, float* grad_gamma, float* grad_beta,
+                                   void* workspace, size_t workspace_bytes, void* stream);
+
+/* ------------------------------------------------------------------------- *
  * Measurement hooks (not part of the method): when enabled, every kernel launch
  * made by the entry points above is bracketed by a pair of HIP events recorded
  * on the caller's stream, so a benchmark can read each kernel's device time over

@@ -25,6 +25,7 @@ EXPORTS = [
     "tinykg_kg_uniform_bwd", "tinykg_profile_enable",
     "tinykg_profile_report", "tinykg_profile_copy", "tinykg_bpr_loss", "tinykg_bpr_grad",
     "tinykg_gather_rows", "tinykg_scatter_add_rows", "tinykg_fill_zero",
+    "tinykg_batchnorm_workspace_bytes", "tinykg_batchnorm_fwd", "tinykg_batchnorm_bwd",
 ]
 
 
@@ -89,6 +90,12 @@ def lib():
         L.tinykg_gather_rows.argtypes = [vp, i32, vp, i64, vp, vp]
         L.tinykg_scatter_add_rows.argtypes = [vp, i32, vp, i64, vp, vp]
         L.tinykg_fill_zero.argtypes = [vp, i64, vp]
+        L.tinykg_batchnorm_workspace_bytes.argtypes = [i64, i32]
+        L.tinykg_batchnorm_workspace_bytes.restype = sz
+        L.tinykg_batchnorm_fwd.argtypes = [vp, i64, i32, vp, vp, f32, i32, i32, u64, vp, vp, vp, vp, vp, vp,
+                                           vp, sz, vp]
+        L.tinykg_batchnorm_bwd.argtypes = [vp, vp, vp, vp, vp, vp, i64, i32, i32, i32, vp, vp, vp, vp, vp, sz,
+                                           vp]
         _lib = L
     return _lib
 
@@ -364,3 +371,54 @@ def tinykg_quantize_bf16(act, bits, group, seed, out=None, first_index=0, roundi
                                     _ptr(gscale), _stream())
     _ok(st, "tinykg_quantize_bf16")
     return packed, gmin, gscale
+
+
+class NormContext:
+    """Device buffers of a batch-norm layer's saved context: Q(x) (or an fp32 copy with
+    bits == 32), the column means and inverse standard deviations, and the workspace."""
+
+    def __init__(self, rows, dim, bits, group, device="cuda"):
+        self.rows, self.dim, self.bits, self.group = rows, dim, bits, group
+        self.gmin = self.gscale = None
+        if bits == 32:
+            self.packed = torch.empty(rows * dim * 4, dtype=torch.uint8, device=device)
+        else:
+            self.packed, self.gmin, self.gscale = alloc_quantized(rows, dim, bits, group, device)
+        self.mean = torch.empty(dim, dtype=torch.float32, device=device)
+        self.rstd = torch.empty(dim, dtype=torch.float32, device=device)
+        nb = int(lib().tinykg_batchnorm_workspace_bytes(rows, dim))
+        if nb == 0:
+            raise TinyKGError(3, "tinykg_batchnorm_workspace_bytes")
+        self.ws = torch.empty(nb, dtype=torch.uint8, device=device)
+
+    def nbytes(self):
+        ts = [self.packed, self.gmin, self.gscale, self.mean, self.rstd]
+        return sum(t.numel() * t.element_size() for t in ts if t is not None)
+
+
+def tinykg_batchnorm_fwd(x, gamma, beta, eps, bits, group, seed, ctx, y=None):
+    for t, nm in ((x, "x"), (gamma, "gamma"), (beta, "beta")):
+        _dev(t, torch.float32, nm)
+    rows, dim = x.shape
+    if y is None:
+        y = torch.empty_like(x)
+    st = lib().tinykg_batchnorm_fwd(_ptr(x), rows, dim, _ptr(gamma), _ptr(beta), float(eps), bits, group,
+                                    C.c_uint64(seed), _ptr(y), _ptr(ctx.packed), _ptr(ctx.gmin),
+                                    _ptr(ctx.gscale), _ptr(ctx.mean), _ptr(ctx.rstd), _ptr(ctx.ws),
+                                    ctx.ws.numel(), _stream())
+    _ok(st, "tinykg_batchnorm_fwd")
+    return y
+
+
+def tinykg_batchnorm_bwd(ctx, gamma, grad_y, out=None):
+    _dev(gamma, torch.float32, "gamma")
+    _dev(grad_y, torch.float32, "grad_y")
+    if out is None:
+        out = (torch.empty_like(grad_y), torch.empty_like(gamma), torch.empty_like(gamma))
+    gx, gg, gb = out
+    st = lib().tinykg_batchnorm_bwd(_ptr(ctx.packed), _ptr(ctx.gmin), _ptr(ctx.gscale), _ptr(ctx.mean),
+                                    _ptr(ctx.rstd), _ptr(gamma), ctx.rows, ctx.dim, ctx.bits, ctx.group,
+                                    _ptr(grad_y), _ptr(gx), _ptr(gg), _ptr(gb), _ptr(ctx.ws), ctx.ws.numel(),
+                                    _stream())
+    _ok(st, "tinykg_batchnorm_bwd")
+    return gx, gg, gb

@@ -18,6 +18,7 @@ SOURCES = {
     "tinykg_agg.hip": [],
     "tinykg_profile.hip": [],
     "tinykg_bpr.hip": [],
+    "tinykg_norm.hip": [],
 }
 
 

@@ -33,6 +33,12 @@ inline tinykg_status launch_status() {
 tinykg_status launch_quantize(const float* act, int64_t n, int bits, int group, uint64_t seed,
                               uint64_t first_index, int rounding, uint8_t* packed, float* gmin,
                               float* gscale, hipStream_t stream);
+// The quantizer with y = (x - mu_c) a_c + beta_c (column c of a [*, dim] tensor) written
+// in the same pass over x; n / 4 must stay below 2^32.
+tinykg_status launch_quantize_affine(const float* act, int64_t n, int bits, int group, uint64_t seed,
+                                     uint8_t* packed, float* gmin, float* gscale, int dim,
+                                     const float* mu, const float* a, const float* beta, float* y,
+                                     hipStream_t stream);
 tinykg_status launch_dequantize(const uint8_t* packed, const float* gmin, const float* gscale,
                                 int64_t n, int bits, int group, float* out, hipStream_t stream);
 

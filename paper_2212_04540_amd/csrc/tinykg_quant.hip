@@ -156,14 +156,42 @@ __device__ __forceinline__ uint32_t place_high_half(uint32_t S, uint32_t pos) {
   return r;
 }
 
+// Optional hook of the quantizer: it is shown every 128-bit chunk of an fp32 input as the
+// kernel loaded it (index of the chunk in the flattened tensor, its column position, the four
+// values), so that an operator which has to save Q(x) and also produce an elementwise
+// function of x reads x once.  Chunk indices stay below 2^32 when a hook is active.
+struct NoEpilogue {
+  static constexpr bool kActive = false;
+  uint32_t lpr = 1, step = 0;
+  __device__ __forceinline__ void operator()(int64_t, uint32_t, const float4&) const {}
+};
+
+// y = (x - mu_c) a_c + beta_c per column c (the normalisation of a batch-norm layer whose
+// input the same pass compresses).  lpr = chunks per row, step = 64 mod lpr.
+struct AffineEpilogue {
+  static constexpr bool kActive = true;
+  uint32_t lpr, step;
+  const float4* mu;
+  const float4* a;
+  const float4* beta;
+  float4* y;
+  __device__ __forceinline__ void operator()(int64_t c, uint32_t col, const float4& x) const {
+    const float4 m = mu[col], s = a[col], b = beta[col];
+    float4 o;
+    o.x = fmaf(x.x - m.x, s.x, b.x); o.y = fmaf(x.y - m.y, s.y, b.y);
+    o.z = fmaf(x.z - m.z, s.z, b.z); o.w = fmaf(x.w - m.w, s.w, b.w);
+    store_stream(y + c, o);
+  }
+};
+
 // IN = float: fp32 activations.  IN = uint16_t: bfloat16 activations (Sec. 4.1.4: half-precision
 // inputs, for mixed-precision training); each value is widened to fp32 exactly and then takes
 // the same path, so the output is that of the fp32 quantizer on the widened tensor.
-template <typename IN, int BITS, int GROUP, int ROUNDING>
+template <typename IN, int BITS, int GROUP, int ROUNDING, typename EPI>
 __global__ __launch_bounds__(kBlock) void quantize_kernel(
     const IN* __restrict__ act, int64_t n, uint32_t seed_lo, uint32_t seed_hi,
     uint64_t first_index, uint8_t* __restrict__ packed, float* __restrict__ gmin,
-    float* __restrict__ gscale) {
+    float* __restrict__ gscale, EPI epi) {
   constexpr int LPG = GROUP / kElemsPerLane;       // lanes per group
   constexpr float Bf = (float)((1 << BITS) - 1);   // B = 2^b - 1
   constexpr float B16 = Bf * 65536.0f;
@@ -228,6 +256,16 @@ __global__ __launch_bounds__(kBlock) void quantize_kernel(
     const int wslot = slab_slot(lane);
 #pragma unroll
     for (int u = 0; u < 4; ++u) my[u * kWave + wslot] = v[tt][u];
+    if constexpr (EPI::kActive) {
+      const int64_t c0 = tile * (kTileElems / 4) + lane;
+      uint32_t col = (uint32_t)c0 % epi.lpr;
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        if (c0 + u * kWave < (n >> 2)) epi(c0 + u * kWave, col, v[tt][u]);
+        col += epi.step;
+        col = col >= epi.lpr ? col - epi.lpr : col;
+      }
+    }
     // lane-contiguous read-back: elements [16*lane, 16*lane+16) of the tile
     // (slab_slot(4 * lane + j) = slab_slot(4 * lane) ^ j for j < 4)
     const int rslot = slab_slot(4 * lane);
@@ -391,10 +429,10 @@ int ilog2(int v) {
   return l;
 }
 
-template <typename IN, int BITS, int ROUNDING>
+template <typename IN, int BITS, int ROUNDING, typename EPI = NoEpilogue>
 tinykg_status launch_quantize_g(const IN* act, int64_t n, int group, uint64_t seed,
                                 uint64_t first_index, uint8_t* packed, float* gmin, float* gscale,
-                                hipStream_t stream) {
+                                hipStream_t stream, EPI epi = EPI{}) {
   const int64_t n_tiles = (n + kTileElems - 1) / kTileElems;
   const int64_t per_block = kWavesPerBlock * kTilesPerWave;
   const int64_t want = (n_tiles + per_block - 1) / per_block;
@@ -403,8 +441,8 @@ tinykg_status launch_quantize_g(const IN* act, int64_t n, int group, uint64_t se
   const uint32_t lo = (uint32_t)seed, hi = (uint32_t)(seed >> 32);
   ProfileScope prof("quantize_kernel", stream);
 #define TINYKG_Q_LAUNCH(G)                                                                   \
-  hipLaunchKernelGGL((quantize_kernel<IN, BITS, G, ROUNDING>), grid, dim3(kBlock), 0, stream, act, n, \
-                     lo, hi, first_index, packed, gmin, gscale)
+  hipLaunchKernelGGL((quantize_kernel<IN, BITS, G, ROUNDING, EPI>), grid, dim3(kBlock), 0, stream, act, n, \
+                     lo, hi, first_index, packed, gmin, gscale, epi)
   switch (group) {
     case 32: TINYKG_Q_LAUNCH(32); break;
     case 64: TINYKG_Q_LAUNCH(64); break;
@@ -468,6 +506,30 @@ tinykg_status launch_quantize(const float* act, int64_t n, int bits, int group, 
                               float* gscale, hipStream_t stream) {
   return launch_quantize_any<float>(act, n, bits, group, seed, first_index, rounding, packed, gmin,
                                     gscale, stream);
+}
+
+tinykg_status launch_quantize_affine(const float* act, int64_t n, int bits, int group, uint64_t seed,
+                                     uint8_t* packed, float* gmin, float* gscale, int dim,
+                                     const float* mu, const float* a, const float* beta, float* y,
+                                     hipStream_t stream) {
+  if (!bits_ok(bits) || !group_ok(group)) return TINYKG_ERR_INVALID_ARG;
+  if (n <= 0 || n % group != 0 || dim < 4 || dim % 4 != 0 || (n >> 2) >= ((int64_t)1 << 32))
+    return TINYKG_ERR_SHAPE;
+  AffineEpilogue epi;
+  epi.lpr = (uint32_t)(dim / 4);
+  epi.step = 64u % epi.lpr;
+  epi.mu = reinterpret_cast<const float4*>(mu);
+  epi.a = reinterpret_cast<const float4*>(a);
+  epi.beta = reinterpret_cast<const float4*>(beta);
+  epi.y = reinterpret_cast<float4*>(y);
+  constexpr int RS = TINYKG_ROUND_STOCHASTIC;
+  switch (bits) {
+    case 1: return launch_quantize_g<float, 1, RS, AffineEpilogue>(act, n, group, seed, 0, packed, gmin, gscale, stream, epi);
+    case 2: return launch_quantize_g<float, 2, RS, AffineEpilogue>(act, n, group, seed, 0, packed, gmin, gscale, stream, epi);
+    case 4: return launch_quantize_g<float, 4, RS, AffineEpilogue>(act, n, group, seed, 0, packed, gmin, gscale, stream, epi);
+    case 8: return launch_quantize_g<float, 8, RS, AffineEpilogue>(act, n, group, seed, 0, packed, gmin, gscale, stream, epi);
+  }
+  return TINYKG_ERR_INVALID_ARG;
 }
 
 tinykg_status launch_dequantize(const uint8_t* packed, const float* gmin, const float* gscale,

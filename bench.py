@@ -278,6 +278,69 @@ def uniform_workload(a):
     graph.close()
 
 
+def batchnorm_workload(a):
+    """Batch normalisation with a compressed input (Sec. 4.1.4 operator list) on the
+    configs[2] tensor shape: every kernel is a stream, so HBM bounds the whole step."""
+    import torch
+    import paper_2212_04540_amd as tk
+    dev = "cuda"
+    rows, dim = C2_ROWS, C2_DIM
+    g = torch.Generator(device=dev)
+    g.manual_seed(0)
+    x = torch.randn((rows, dim), generator=g, device=dev) * 1.5 + 0.3
+    gy = torch.randn((rows, dim), generator=g, device=dev)
+    gamma = torch.rand(dim, generator=g, device=dev) + 0.5
+    beta = torch.randn(dim, generator=g, device=dev)
+    ctx = tk.NormContext(rows, dim, BITS, GROUP)
+    y = torch.empty_like(x)
+    out = (torch.empty_like(x), torch.empty_like(gamma), torch.empty_like(gamma))
+
+    def step(i):
+        tk.tinykg_batchnorm_fwd(x, gamma, beta, 1e-5, BITS, GROUP, 1 + i, ctx, y=y)
+        tk.tinykg_batchnorm_bwd(ctx, gamma, gy, out=out)
+
+    for i in range(a.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    tk.tinykg_profile_enable(True)
+    t0 = time.perf_counter()
+    for i in range(a.steps):
+        step(a.warmup + i)
+    torch.cuda.synchronize()
+    dt = (time.perf_counter() - t0) / a.steps
+    rep = tk.tinykg_profile_report()
+    tk.tinykg_profile_enable(False)
+    bpa = bytes_per_activation(BITS, GROUP)
+    n = rows * dim
+    per_kernel = {"bn_stats_kernel<fwd>": 4.0, "quantize_kernel": 8.0 + bpa, "bn_stats_kernel<bwd>": 4.0 + bpa,
+                  "bn_apply_bwd_kernel": 8.0 + bpa}
+    alg = n * sum(per_kernel.values())
+    kernels = {}
+    for k, v in rep.items():
+        ms = v[1] / v[0]
+        kernels[k] = {"launches_per_step": v[0] / a.steps, "ms_per_launch": round(ms, 4)}
+        if k in per_kernel:
+            kernels[k]["algorithmic_GBps"] = round(n * per_kernel[k] / (ms * 1e-3) / 1e9, 1)
+            kernels[k]["frac_of_hbm_peak"] = round(n * per_kernel[k] / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)
+    dom = max(per_kernel, key=lambda k: rep[k][1])
+    dom_ms = rep[dom][1] / rep[dom][0]
+    print(json.dumps({
+        "metric": "quantize+pack and dequant+agg-bwd HBM GB/s (fraction of peak); bytes/activation",
+        "value": round(alg / dt / 1e9, 2), "unit": "GB/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
+        "ms_per_step": round(dt * 1e3, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"batch normalisation with a compressed input, forward+backward, {rows}x{dim} fp32 "
+                               f"(2 GiB per tensor), INT{BITS} group {GROUP}",
+                   "bits": BITS, "group": GROUP, "bytes_per_activation": bpa, "algorithmic_bytes_per_step": alg,
+                   "saved_context_bytes": ctx.nbytes(), "fp32_context_bytes": n * 4 + 8 * dim},
+        "frac_of_hbm_peak": round(alg / dt / 1e9 / HBM_PEAK_GBS, 5),
+        "roofline": {"kernel": dom, "bound": "hbm", "achieved": round(n * per_kernel[dom] / (dom_ms * 1e-3) / 1e9, 1),
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": round(n * per_kernel[dom] / (dom_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+                     "traffic": None, "avg_launch_ms": round(dom_ms, 4)},
+        "kernels": kernels}))
+
+
 def stack_workload(a, which):
     """configs[3] / configs[4]: a stack of layers, forward + ranking loss + backward.
     Reported for the step time and the saved-activation footprint; not the default."""
@@ -355,7 +418,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-compressor", action="store_true")
-    ap.add_argument("--workload", choices=["config1", "config2", "config3", "config4", "uniform"], default="config1",
+    ap.add_argument("--workload", choices=["config1", "config2", "config3", "config4", "uniform", "batchnorm"], default="config1",
                     help="config1 (default, the headline step); config2: the 9-cell compressor sweep; "
                          "config3 / config4: multi-layer steps; uniform: the uniform-attention "
                          "layer on the config1 graph")
@@ -376,6 +439,8 @@ def main():
         return compressor_sweep(a)
     if a.workload == "uniform":
         return uniform_workload(a)
+    if a.workload == "batchnorm":
+        return batchnorm_workload(a)
     if a.workload != "config1":
         return stack_workload(a, a.workload)
     dev = "cuda"

@@ -25,7 +25,8 @@ namespace {
 constexpr int kThreads = 256;
 constexpr int kMaxStatBlocks = 2048;
 constexpr int kFinishThreads = 1024;
-constexpr int kFlushRows = 16;      // fp32 terms per thread between two flushes to double
+constexpr int kFlushRows = 16;      // fp32 terms per thread between two flushes to double (tail: < 24)
+constexpr int kStatUFwd = 8, kStatUBwd = 4;   // rows a thread has in flight in the column-sum kernel
 constexpr int kApplyU = 4;          // chunks per thread in the elementwise kernels
 
 typedef float floatx4 __attribute__((ext_vector_type(4)));
@@ -66,30 +67,52 @@ __global__ __launch_bounds__(kThreads) void bn_stats_kernel(Source src, const fl
     } else {
       k = fetch_chunk<BITS>(src, li);                  // row 0
     }
+    const float rv[4] = {rs.x, rs.y, rs.z, rs.w};
+    float s1[4] = {0, 0, 0, 0}, s2[4] = {0, 0, 0, 0};
+    auto add = [&](const float4& x, const float4& gg) {
+      const float v[4] = {x.x - k.x, x.y - k.y, x.z - k.z, x.w - k.w};
+      const float gv[4] = {gg.x, gg.y, gg.z, gg.w};
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        if (BWD) { s1[j] += gv[j]; s2[j] = fmaf(gv[j], v[j] * rv[j], s2[j]); }
+        else { s1[j] += v[j]; s2[j] = fmaf(v[j], v[j], s2[j]); }
+      }
+    };
+    auto flush = [&]() {
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        d1[j] += (double)s1[j]; d2[j] += (double)s2[j];
+        s1[j] = 0.f; s2[j] = 0.f;
+      }
+    };
+    auto fetch_x = [&](int64_t c) {
+      if (BITS == 32) return load_stream(reinterpret_cast<const float4*>(src.data) + c);
+      return fetch_chunk<BITS>(src, c);
+    };
+    const float4 zero4 = make_float4(0.f, 0.f, 0.f, 0.f);
+    constexpr int kStatU = BWD ? kStatUBwd : kStatUFwd;
     int64_t r = r0 + rin;
-    while (r < r1) {
-      float s1[4] = {0, 0, 0, 0}, s2[4] = {0, 0, 0, 0};
-#pragma unroll 4
-      for (int it = 0; it < kFlushRows; ++it) {
-        if (r < r1) {
-          const float4 x = fetch_chunk<BITS>(src, r * lpr + li);
-          const float v[4] = {x.x - k.x, x.y - k.y, x.z - k.z, x.w - k.w};
-          if (BWD) {
-            const float4 gg = load_stream(reinterpret_cast<const float4*>(g) + r * lpr + li);
-            const float gv[4] = {gg.x, gg.y, gg.z, gg.w};
-            const float rv[4] = {rs.x, rs.y, rs.z, rs.w};
+    int pending = 0;
+    // whole batches of kStatU rows: all loads of a batch are issued before the first use
+    while (r + (int64_t)(kStatU - 1) * rg < r1) {
+      float4 xs[kStatU], gs[kStatU];
 #pragma unroll
-            for (int j = 0; j < 4; ++j) { s1[j] += gv[j]; s2[j] = fmaf(gv[j], v[j] * rv[j], s2[j]); }
-          } else {
-#pragma unroll
-            for (int j = 0; j < 4; ++j) { s1[j] += v[j]; s2[j] = fmaf(v[j], v[j], s2[j]); }
-          }
-        }
-        r += rg;
+      for (int u = 0; u < kStatU; ++u) {
+        const int64_t c = (r + (int64_t)u * rg) * lpr + li;
+        xs[u] = fetch_x(c);
+        gs[u] = BWD ? load_stream(reinterpret_cast<const float4*>(g) + c) : zero4;
       }
 #pragma unroll
-      for (int j = 0; j < 4; ++j) { d1[j] += (double)s1[j]; d2[j] += (double)s2[j]; }
+      for (int u = 0; u < kStatU; ++u) add(xs[u], gs[u]);
+      r += (int64_t)kStatU * rg;
+      pending += kStatU;
+      if (pending >= kFlushRows) { flush(); pending = 0; }
     }
+    for (; r < r1; r += rg) {
+      const int64_t c = r * lpr + li;
+      add(fetch_x(c), BWD ? load_stream(reinterpret_cast<const float4*>(g) + c) : zero4);
+    }
+    flush();
   }
 #pragma unroll
   for (int j = 0; j < 4; ++j) { red[tid][j] = d1[j]; red[tid][4 + j] = d2[j]; }
@@ -283,7 +306,7 @@ tinykg_status bwd_impl(Source src, const float* mean, const float* rstd, const f
   const int lpr = dim / 4;
   const StatGrid sg = stat_grid(rows, dim);
   {
-    ProfileScope prof("bn_stats_kernel", st);
+    ProfileScope prof("bn_stats_kernel<bwd>", st);
     hipLaunchKernelGGL((bn_stats_kernel<BITS, true>), dim3(sg.blocks), dim3(kThreads), 0, st, src, grad_y, mean,
                        rstd, rows, lpr, sg.rows_per_block, part);
   }
@@ -335,7 +358,7 @@ tinykg_status tinykg_batchnorm_fwd(const float* x, int64_t rows, int dim, const 
   const StatGrid sg = stat_grid(rows, dim);
   const Source src{reinterpret_cast<const uint8_t*>(x), nullptr, nullptr, 0};
   {
-    ProfileScope prof("bn_stats_kernel", st);
+    ProfileScope prof("bn_stats_kernel<fwd>", st);
     hipLaunchKernelGGL((bn_stats_kernel<32, false>), dim3(sg.blocks), dim3(kThreads), 0, st, src,
                        (const float*)nullptr, (const float*)nullptr, (const float*)nullptr, rows, lpr,
                        sg.rows_per_block, part);

@@ -235,6 +235,32 @@ tinykg_status tinykg_scatter_add_rows(const float* src, int dim, const int32_t* 
 tinykg_status tinykg_fill_zero(float* dst, int64_t n, void* stream);
 
 /* ------------------------------------------------------------------------- *
+ * Max-pooling aggregation over the out-edges (the SPMM_MAX operator of the list in
+ * Sec. 4.1.4):  M[h,c] = max over the out-edges (h,r,t) of E[t,c];  0 for a head
+ * without out-edges.  The backward pass needs no activation, only WHICH out-edge
+ * won each output element; the context is that edge's number inside the head's
+ * neighbourhood -- out-edges numbered from 0 in the order (relation, tail, position
+ * in the arrays given to tinykg_graph_create); the first one on equal values; 0
+ * without out-edges -- stored in tinykg_kg_max_arg_bytes(g) bytes per element
+ * (1 if the graph's largest out-degree is at most 256, 2 up to 65536, else 4;
+ * little-endian unsigned), as `arg` [n_nodes, d].  Backward:
+ *   grad_E[t,c] = sum of grad_M[h,c] over the heads h whose saved edge number leads to t.
+ * E, M, grad_M, grad_E [n_nodes, d] fp32, d in {32, 64, 128} (else ERR_UNSUPPORTED);
+ * all pointers DEVICE and 16-byte aligned; outputs are overwritten.  M and arg are
+ * exact and deterministic; grad_E is accumulated with atomics (fp32, double for the
+ * nodes with more than 1024 incident edges), so it is reproducible to rounding.
+ * Edge numbers in `arg` beyond a head's degree (a corrupted context) are clamped.
+ * `workspace` (backward only): tinykg_kg_max_workspace_bytes(g, d) bytes.
+ * ------------------------------------------------------------------------- */
+int tinykg_kg_max_arg_bytes(const tinykg_graph* g);
+size_t tinykg_kg_max_workspace_bytes(const tinykg_graph* g, int d);
+tinykg_status tinykg_kg_max_fwd(const tinykg_graph* g, const float* E, int d, float* M, void* arg,
+                                void* stream);
+tinykg_status tinykg_kg_max_bwd(const tinykg_graph* g, const void* arg, int d, const float* grad_M,
+                                float* grad_E, void* workspace, size_t workspace_bytes,
+                                void* stream);
+
+/* ------------------------------------------------------------------------- *
  * Batch normalisation over the rows (training mode) with its input saved
  * compressed.  Sec. 4.1.4 names BatchNorm among the operators whose context is
  * compressed; the operator's input takes the place of the activation in Eq. 3 / 4:

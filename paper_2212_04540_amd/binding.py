@@ -26,6 +26,7 @@ EXPORTS = [
     "tinykg_profile_report", "tinykg_profile_copy", "tinykg_bpr_loss", "tinykg_bpr_grad",
     "tinykg_gather_rows", "tinykg_scatter_add_rows", "tinykg_fill_zero",
     "tinykg_batchnorm_workspace_bytes", "tinykg_batchnorm_fwd", "tinykg_batchnorm_bwd",
+    "tinykg_kg_max_arg_bytes", "tinykg_kg_max_workspace_bytes", "tinykg_kg_max_fwd", "tinykg_kg_max_bwd",
 ]
 
 
@@ -90,6 +91,11 @@ def lib():
         L.tinykg_gather_rows.argtypes = [vp, i32, vp, i64, vp, vp]
         L.tinykg_scatter_add_rows.argtypes = [vp, i32, vp, i64, vp, vp]
         L.tinykg_fill_zero.argtypes = [vp, i64, vp]
+        L.tinykg_kg_max_arg_bytes.argtypes = [vp]
+        L.tinykg_kg_max_workspace_bytes.argtypes = [vp, i32]
+        L.tinykg_kg_max_workspace_bytes.restype = sz
+        L.tinykg_kg_max_fwd.argtypes = [vp, vp, i32, vp, vp, vp]
+        L.tinykg_kg_max_bwd.argtypes = [vp, vp, i32, vp, vp, vp, sz, vp]
         L.tinykg_batchnorm_workspace_bytes.argtypes = [i64, i32]
         L.tinykg_batchnorm_workspace_bytes.restype = sz
         L.tinykg_batchnorm_fwd.argtypes = [vp, i64, i32, vp, vp, f32, i32, i32, u64, vp, vp, vp, vp, vp, vp,
@@ -422,3 +428,32 @@ def tinykg_batchnorm_bwd(ctx, gamma, grad_y, out=None):
                                     _stream())
     _ok(st, "tinykg_batchnorm_bwd")
     return gx, gg, gb
+
+
+_ARG_DTYPES = {1: torch.uint8, 2: torch.int16, 4: torch.int32}
+
+
+def tinykg_kg_max_fwd(graph, E, out=None):
+    """M [n, d] fp32 and the saved edge numbers `arg` [n, d] (1, 2 or 4 bytes per element;
+    torch has no unsigned 16 / 32-bit types: the signed tensors hold the unsigned bits)."""
+    _dev(E, torch.float32, "E")
+    d = E.shape[1]
+    if out is None:
+        nb = int(lib().tinykg_kg_max_arg_bytes(graph.handle))
+        out = (torch.empty_like(E), torch.empty((graph.n_nodes, d), dtype=_ARG_DTYPES[nb], device=E.device))
+    M, arg = out
+    _ok(lib().tinykg_kg_max_fwd(graph.handle, _ptr(E), d, _ptr(M), _ptr(arg), _stream()), "tinykg_kg_max_fwd")
+    return M, arg
+
+
+def tinykg_kg_max_bwd(graph, arg, grad_M, workspace=None, out=None):
+    _dev(grad_M, torch.float32, "grad_M")
+    d = grad_M.shape[1]
+    if workspace is None:
+        workspace = torch.empty(int(lib().tinykg_kg_max_workspace_bytes(graph.handle, d)), dtype=torch.uint8,
+                                device=grad_M.device)
+    if out is None:
+        out = torch.empty_like(grad_M)
+    _ok(lib().tinykg_kg_max_bwd(graph.handle, _ptr(arg), d, _ptr(grad_M), _ptr(out), _ptr(workspace),
+                                workspace.numel(), _stream()), "tinykg_kg_max_bwd")
+    return out

@@ -2225,3 +2225,257 @@ tinykg_status tinykg_kg_uniform_bwd(const tinykg_graph* g, const tinykg_saved* s
 }
 
 }  // extern "C"
+
+// ------------------------------------------------ max-pooling aggregation (SPMM_MAX) ----
+// M[h, c] = max over the out-edges (h, r, t) of E[t, c] (0 without out-edges).  What the
+// backward pass needs is not an activation but, per output element, WHICH out-edge won: the
+// context is that edge's number inside the head's neighbourhood (head order: relation, tail,
+// input position; first one on ties), in the narrowest of 1 / 2 / 4 bytes that holds the
+// graph's largest out-degree.  Backward: grad_E[t(arg), c] += grad_M[h, c].
+namespace tinykg {
+
+namespace {
+
+template <typename ARG> struct ArgVec;
+template <> struct ArgVec<uint8_t> { typedef uchar4 type; };
+template <> struct ArgVec<uint16_t> { typedef ushort4 type; };
+template <> struct ArgVec<uint32_t> { typedef uint4 type; };
+
+// One LPR-lane slot per head for neighbourhoods of at most kSlotDegree edges (64 / LPR
+// heads side by side), the whole wave for longer ones: its 64 / LPR lane groups take the
+// edges j = sub, sub + ES, ... and their (value, number) pairs are merged at the end,
+// larger value first, smaller number on equal values.
+template <int D, typename ARG>
+__global__ __launch_bounds__(kThreads) void max_fwd_kernel(const float* __restrict__ E,
+                                                           const int32_t* __restrict__ rowptr,
+                                                           const int32_t* __restrict__ h_tail, int64_t N,
+                                                           float* __restrict__ M, ARG* __restrict__ arg) {
+  constexpr int LPR = D / 4, ES = 64 / LPR;
+  typedef typename ArgVec<ARG>::type AV;
+  const int lane = threadIdx.x & 63;
+  const int sub = lane / LPR, li = lane % LPR;
+  const float4* rows = reinterpret_cast<const float4*>(E);
+  const int64_t n_waves = (int64_t)gridDim.x * (kThreads / 64);
+  auto take = [](float& best, uint32_t& at, float v, uint32_t j) {
+    const bool win = v > best || (v == best && j < at);
+    best = win ? v : best;
+    at = win ? j : at;
+  };
+  auto store = [&](int64_t h, const float (&b)[4], const uint32_t (&a)[4]) {
+    reinterpret_cast<float4*>(M)[h * LPR + li] = make_float4(b[0], b[1], b[2], b[3]);
+    AV o;
+    o.x = a[0]; o.y = a[1]; o.z = a[2]; o.w = a[3];
+    reinterpret_cast<AV*>(arg)[h * LPR + li] = o;
+  };
+  for (int64_t h0 = ((int64_t)blockIdx.x * (kThreads / 64) + (threadIdx.x >> 6)) * ES; h0 < N;
+       h0 += n_waves * ES) {
+    const int64_t h = h0 + sub;
+    int e0 = 0, deg = 0;
+    if (h < N) { e0 = rowptr[h]; deg = rowptr[h + 1] - e0; }
+    const bool small = deg <= kSlotDegree;
+    {
+      const int ds = small ? deg : 0;
+      float b[4] = {-INFINITY, -INFINITY, -INFINITY, -INFINITY};
+      uint32_t a[4] = {0u, 0u, 0u, 0u};
+      for (int j0 = 0; j0 < kSlotDegree; j0 += 4) {
+        if (__builtin_amdgcn_ballot_w64(j0 < ds) == 0) break;
+        float4 x[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          const bool on = j0 + u < ds;
+          const int t = on ? h_tail[e0 + j0 + u] : 0;
+          x[u] = rows[(int64_t)t * LPR + li];
+          if (!on) x[u] = make_float4(-INFINITY, -INFINITY, -INFINITY, -INFINITY);
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {       // in edge order with a strict comparison: the first maximum stays
+          if (x[u].x > b[0]) { b[0] = x[u].x; a[0] = j0 + u; }
+          if (x[u].y > b[1]) { b[1] = x[u].y; a[1] = j0 + u; }
+          if (x[u].z > b[2]) { b[2] = x[u].z; a[2] = j0 + u; }
+          if (x[u].w > b[3]) { b[3] = x[u].w; a[3] = j0 + u; }
+        }
+      }
+      if (h < N && small) {
+        if (deg == 0) { b[0] = b[1] = b[2] = b[3] = 0.f; }
+        store(h, b, a);
+      }
+    }
+    uint64_t pend = __builtin_amdgcn_ballot_w64(!small && li == 0);
+    while (pend) {
+      const int leader = __builtin_amdgcn_readfirstlane(__ffsll((long long)pend) - 1);
+      pend &= pend - 1;
+      const int64_t hw = h0 + leader / LPR;
+      const int e0w = __builtin_amdgcn_readlane(e0, leader), degw = __builtin_amdgcn_readlane(deg, leader);
+      float b[4] = {-INFINITY, -INFINITY, -INFINITY, -INFINITY};
+      uint32_t a[4] = {0u, 0u, 0u, 0u};
+      for (int base = 0; base < degw; base += 2 * ES) {
+        const int j0 = base + sub, j1 = base + ES + sub;
+        float4 x0 = make_float4(-INFINITY, -INFINITY, -INFINITY, -INFINITY), x1 = x0;
+        if (j0 < degw) x0 = rows[(int64_t)h_tail[e0w + j0] * LPR + li];
+        if (j1 < degw) x1 = rows[(int64_t)h_tail[e0w + j1] * LPR + li];
+        if (x0.x > b[0]) { b[0] = x0.x; a[0] = j0; }
+        if (x0.y > b[1]) { b[1] = x0.y; a[1] = j0; }
+        if (x0.z > b[2]) { b[2] = x0.z; a[2] = j0; }
+        if (x0.w > b[3]) { b[3] = x0.w; a[3] = j0; }
+        if (x1.x > b[0]) { b[0] = x1.x; a[0] = j1; }
+        if (x1.y > b[1]) { b[1] = x1.y; a[1] = j1; }
+        if (x1.z > b[2]) { b[2] = x1.z; a[2] = j1; }
+        if (x1.w > b[3]) { b[3] = x1.w; a[3] = j1; }
+      }
+      // merge the lane groups (lanes li, li + LPR, ...): xor steps LPR, 2 LPR, ..., 32
+#pragma unroll
+      for (int o = LPR; o < 64; o <<= 1) {
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+          const float ov = __shfl_xor(b[c], o);
+          const uint32_t oa = (uint32_t)__shfl_xor((int)a[c], o);
+          take(b[c], a[c], ov, oa);
+        }
+      }
+      if (sub == 0) store(hw, b, a);
+    }
+  }
+}
+
+// One thread per 4 output elements: passes its four gradient entries to the winning tails.
+template <int D, typename ARG>
+__global__ __launch_bounds__(kThreads) void max_bwd_kernel(const float* __restrict__ gM,
+                                                           const ARG* __restrict__ arg,
+                                                           const int32_t* __restrict__ rowptr,
+                                                           const int32_t* __restrict__ h_tail, int64_t N,
+                                                           GradSink sink) {
+  constexpr int LPR = D / 4;
+  typedef typename ArgVec<ARG>::type AV;
+  const int64_t q = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+  if (q >= N * LPR) return;
+  const int64_t h = q / LPR;
+  const int li = (int)(q % LPR);
+  const int e0 = rowptr[h], deg = rowptr[h + 1] - e0;
+  if (deg == 0) return;
+  const float4 g4 = reinterpret_cast<const float4*>(gM)[q];
+  const AV a4 = reinterpret_cast<const AV*>(arg)[q];
+  const uint32_t a[4] = {a4.x, a4.y, a4.z, a4.w};
+  const float gv[4] = {g4.x, g4.y, g4.z, g4.w};
+  int t[4];
+#pragma unroll
+  for (int c = 0; c < 4; ++c) t[c] = h_tail[e0 + (int)min(a[c], (uint32_t)(deg - 1))];
+#pragma unroll
+  for (int c = 0; c < 4; ++c) {
+    const int flagged = t[c] | (sink.slot[t[c]] >= 0 ? kHeavyBit : 0);
+    sink_add<D>(sink, flagged, li * 4 + c, gv[c]);
+  }
+}
+
+__global__ __launch_bounds__(256) void max_bwd_zero_kernel(float* __restrict__ gE, int64_t n,
+                                                           double* __restrict__ acc, int64_t m) {
+  const int64_t stride = (int64_t)gridDim.x * 256;
+  const int64_t i0 = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  for (int64_t i = i0; i < (n >> 2); i += stride) reinterpret_cast<float4*>(gE)[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+  for (int64_t i = i0; i < m; i += stride) acc[i] = 0.0;
+}
+
+__global__ __launch_bounds__(256) void max_bwd_finish_kernel(HeavyFinish hf) {
+  finish_heavy(hf, (int64_t)blockIdx.x * 256 + threadIdx.x, (int64_t)gridDim.x * 256);
+}
+
+int max_arg_bytes(const tinykg_graph* g) {
+  return g->max_out_degree <= 256 ? 1 : g->max_out_degree <= 65536 ? 2 : 4;
+}
+
+template <int D, typename ARG>
+tinykg_status max_fwd_impl(const tinykg_graph* g, const float* E, float* M, void* arg, hipStream_t st) {
+  const int64_t N = g->n_nodes;
+  const int wave_blocks = (int)std::max<int64_t>(1, std::min<int64_t>((N + 3) / 4, (int64_t)num_cus() * 16));
+  ProfileScope prof("max_fwd_kernel", st);
+  hipLaunchKernelGGL((max_fwd_kernel<D, ARG>), dim3(wave_blocks), dim3(kThreads), 0, st, E, g->rowptr, g->h_tail,
+                     N, M, static_cast<ARG*>(arg));
+  return launch_status();
+}
+
+template <int D, typename ARG>
+tinykg_status max_bwd_impl(const tinykg_graph* g, const void* arg, const float* gM, float* gE, double* acc,
+                           hipStream_t st) {
+  const int64_t N = g->n_nodes;
+  const int64_t n_heavy_elems = (int64_t)g->n_acc_heavy * D;
+  const int zb = (int)std::min<int64_t>((N * D / 4 + 255) / 256, (int64_t)num_cus() * 8);
+  ProfileScope prof("max_bwd_kernels", st);
+  hipLaunchKernelGGL(max_bwd_zero_kernel, dim3(std::max(zb, 1)), dim3(256), 0, st, gE, N * D, acc,
+                     n_heavy_elems * kHeavyReplicas);
+  const GradSink sink{gE, acc, g->acc_slot};
+  const int64_t blocks = (N * (D / 4) + kThreads - 1) / kThreads;
+  hipLaunchKernelGGL((max_bwd_kernel<D, ARG>), dim3((unsigned)blocks), dim3(kThreads), 0, st, gM,
+                     static_cast<const ARG*>(arg), g->rowptr, g->h_tail, N, sink);
+  if (n_heavy_elems > 0) {
+    const HeavyFinish hf{acc, g->acc_node, n_heavy_elems, D, gE};
+    hipLaunchKernelGGL(max_bwd_finish_kernel, dim3(64), dim3(256), 0, st, hf);
+  }
+  return launch_status();
+}
+
+template <int D>
+tinykg_status max_fwd_d(const tinykg_graph* g, const float* E, float* M, void* arg, hipStream_t st) {
+  switch (max_arg_bytes(g)) {
+    case 1: return max_fwd_impl<D, uint8_t>(g, E, M, arg, st);
+    case 2: return max_fwd_impl<D, uint16_t>(g, E, M, arg, st);
+  }
+  return max_fwd_impl<D, uint32_t>(g, E, M, arg, st);
+}
+template <int D>
+tinykg_status max_bwd_d(const tinykg_graph* g, const void* arg, const float* gM, float* gE, double* acc,
+                        hipStream_t st) {
+  switch (max_arg_bytes(g)) {
+    case 1: return max_bwd_impl<D, uint8_t>(g, arg, gM, gE, acc, st);
+    case 2: return max_bwd_impl<D, uint16_t>(g, arg, gM, gE, acc, st);
+  }
+  return max_bwd_impl<D, uint32_t>(g, arg, gM, gE, acc, st);
+}
+
+}  // namespace
+
+}  // namespace tinykg
+
+extern "C" {
+
+int tinykg_kg_max_arg_bytes(const tinykg_graph* g) { return g ? tinykg::max_arg_bytes(g) : 0; }
+
+size_t tinykg_kg_max_workspace_bytes(const tinykg_graph* g, int d) {
+  using namespace tinykg;
+  if (!g || !(d == 32 || d == 64 || d == 128)) return 0;
+  return std::max<size_t>(256, (size_t)g->n_acc_heavy * kHeavyReplicas * d * sizeof(double));
+}
+
+tinykg_status tinykg_kg_max_fwd(const tinykg_graph* g, const float* E, int d, float* M, void* arg,
+                                void* stream) {
+  using namespace tinykg;
+  if (!g) return TINYKG_ERR_INVALID_ARG;
+  if (!(d == 32 || d == 64 || d == 128)) return TINYKG_ERR_UNSUPPORTED;
+  if (g->n_nodes == 0) return TINYKG_OK;
+  if (!E || !M || !arg || !aligned16(E) || !aligned16(M) || !aligned16(arg)) return TINYKG_ERR_INVALID_ARG;
+  hipStream_t st = (hipStream_t)stream;
+  switch (d) {
+    case 32: return max_fwd_d<32>(g, E, M, arg, st);
+    case 64: return max_fwd_d<64>(g, E, M, arg, st);
+  }
+  return max_fwd_d<128>(g, E, M, arg, st);
+}
+
+tinykg_status tinykg_kg_max_bwd(const tinykg_graph* g, const void* arg, int d, const float* grad_M,
+                                float* grad_E, void* workspace, size_t workspace_bytes, void* stream) {
+  using namespace tinykg;
+  if (!g) return TINYKG_ERR_INVALID_ARG;
+  if (!(d == 32 || d == 64 || d == 128)) return TINYKG_ERR_UNSUPPORTED;
+  if (g->n_nodes == 0) return TINYKG_OK;
+  if (!arg || !grad_M || !grad_E || !aligned16(arg) || !aligned16(grad_M) || !aligned16(grad_E))
+    return TINYKG_ERR_INVALID_ARG;
+  if (!workspace || !aligned16(workspace) || workspace_bytes < tinykg_kg_max_workspace_bytes(g, d))
+    return TINYKG_ERR_WORKSPACE;
+  hipStream_t st = (hipStream_t)stream;
+  double* acc = static_cast<double*>(workspace);
+  switch (d) {
+    case 32: return max_bwd_d<32>(g, arg, grad_M, grad_E, acc, st);
+    case 64: return max_bwd_d<64>(g, arg, grad_M, grad_E, acc, st);
+  }
+  return max_bwd_d<128>(g, arg, grad_M, grad_E, acc, st);
+}
+
+}  // extern "C"

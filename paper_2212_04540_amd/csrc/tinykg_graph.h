@@ -10,6 +10,7 @@ struct tinykg_graph {
   // head order (edges sorted by head, relation, tail)
   int32_t* rowptr = nullptr;   // [n_nodes + 1]
   int32_t* h_tail = nullptr;   // [n_edges]
+  int32_t max_out_degree = 0;
   // relation order (edges sorted by relation, tail, head)
   int32_t* r_head = nullptr;   // [n_edges]
   int32_t* r_tail = nullptr;   // [n_edges]

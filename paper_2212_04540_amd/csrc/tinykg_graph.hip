@@ -183,6 +183,8 @@ tinykg_status tinykg_graph_create(int64_t n_nodes, int32_t n_rel, int64_t n_edge
   if (st == TINYKG_OK) st = upload(chunk_count, &g->chunk_count);
   if (st == TINYKG_OK) st = upload(rel_chunk_ptr, &g->rel_chunk_ptr);
   g->n_heavy = (int32_t)heavy_head.size();
+  for (int64_t i = 0; i < n_nodes; ++i)
+    g->max_out_degree = std::max(g->max_out_degree, rowptr[(size_t)i + 1] - rowptr[(size_t)i]);
   g->n_hseg = (int32_t)hseg_q.size();
   if (st == TINYKG_OK) st = upload(heavy_head, &g->heavy_head);
   if (st == TINYKG_OK) st = upload(heavy_seg_ptr, &g->heavy_seg_ptr);

@@ -1,0 +1,133 @@
+"""GPU parity of the max-pooling aggregation (SPMM_MAX, Sec. 4.1.4 operator list) against
+oracle/ref.py, through the C ABI.  M and the saved edge numbers are compared bit for bit
+(a maximum has no rounding; ties go to the first out-edge in head order on both sides, and
+the numbers are also checked to be VALID: they point at an out-edge that attains M);
+grad_E within 1e-5 (tolerance of test_gpu_agg.py)."""
+import numpy as np
+import pytest
+
+torch = pytest.importorskip("torch")
+
+from oracle import ref
+from workloads import gen
+from test_gpu_agg import close
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def tk():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import paper_2212_04540_amd as tk
+    tk.lib()
+    return tk
+
+
+def unsigned(arg):
+    a = arg.cpu().numpy()
+    return a.view({1: np.uint8, 2: np.uint16, 4: np.uint32}[a.dtype.itemsize]).astype(np.int64)
+
+
+def run_case(tk, N, R, head, rel, tail, E, G, want_bytes=None):
+    dev = "cuda"
+    graph = tk.Graph(N, R, *(torch.from_numpy(np.ascontiguousarray(a)).to(dev) for a in (head, rel, tail)))
+    nb = int(tk.lib().tinykg_kg_max_arg_bytes(graph.handle))
+    if want_bytes is not None:
+        assert nb == want_bytes
+    M, arg = tk.tinykg_kg_max_fwd(graph, torch.from_numpy(E).to(dev))
+    torch.cuda.synchronize()
+    wM, warg = ref.spmm_max_fwd(N, head, rel, tail, E)
+    assert np.array_equal(M.cpu().numpy().view(np.uint32), wM.view(np.uint32)), "M differs"
+    got = unsigned(arg)
+    # valid: the numbered out-edge exists and attains the maximum
+    order = ref.head_order(head, rel, tail)
+    hs, ts = np.asarray(head)[order], np.asarray(tail)[order]
+    start = np.searchsorted(hs, np.arange(N), side="left")
+    deg = np.searchsorted(hs, np.arange(N), side="right") - start
+    has = deg > 0
+    assert np.all(got[has] < deg[has, None]) and not got[~has].any()
+    if has.any():
+        t = ts[(start[has, None] + got[has])]
+        assert np.array_equal(E[t, np.arange(E.shape[1])[None, :]], wM[has])
+    assert np.array_equal(got, warg), "saved edge numbers differ (tie rule: first out-edge in head order)"
+    gE = tk.tinykg_kg_max_bwd(graph, arg, torch.from_numpy(G).to(dev))
+    torch.cuda.synchronize()
+    close(gE, ref.spmm_max_bwd(N, head, rel, tail, warg, G), "grad_E")
+    graph.close()
+    return nb
+
+
+@pytest.mark.parametrize("d", [32, 64, 128])
+def test_small_graph_with_ties(tk, d):
+    N, R, T = 336, 5, 3000
+    head, rel, tail = gen.kg_triplets(N, R, T, seed=d)
+    head[:20] = N - 1                                           # one longer neighbourhood (whole-wave path)
+    head[20:40], rel[20:40], tail[20:40] = head[40:60], rel[40:60], tail[40:60]   # repeated triplets
+    rng = np.random.default_rng(d)
+    E = rng.standard_normal((N, d)).astype(np.float32)
+    E[5] = E[9]; E[:, 3] = 0.25; E[17] = -0.0; E[18] = 0.0       # equal rows, a tied column, signed zeros
+    G = rng.standard_normal((N, d)).astype(np.float32)
+    run_case(tk, N, R, head, rel, tail, E, G, want_bytes=1)
+
+
+def test_no_edges_and_single_edge(tk):
+    N, R, d = 64, 2, 64
+    rng = np.random.default_rng(0)
+    E = rng.standard_normal((N, d)).astype(np.float32); G = rng.standard_normal((N, d)).astype(np.float32)
+    empty = np.zeros(0, np.int32)
+    run_case(tk, N, R, empty, empty, empty, E, G)
+    run_case(tk, N, R, np.array([3], np.int32), np.array([1], np.int32), np.array([60], np.int32), E, G)
+
+
+def test_hot_head_and_hot_tail_two_byte_numbers(tk):
+    N, R, d = 512, 5, 64
+    rng = np.random.default_rng(1)
+    T1 = 6000
+    head = rng.integers(0, N, T1).astype(np.int32)
+    tail = np.where(rng.random(T1) < 0.6, 7, rng.integers(0, N, T1)).astype(np.int32)
+    rel = rng.choice([0, 2, 4], T1).astype(np.int32)
+    T2 = 5000
+    head = np.concatenate([head, np.full(T2, 11, np.int32)])
+    tail = np.concatenate([tail, rng.integers(0, N, T2).astype(np.int32)])
+    rel = np.concatenate([rel, np.zeros(T2, np.int32)])
+    E = rng.standard_normal((N, d)).astype(np.float32)
+    E[7] += 2.0                                                 # the hot tail wins often: many rows land on one node
+    G = rng.standard_normal((N, d)).astype(np.float32)
+    run_case(tk, N, R, head, rel, tail, E, G, want_bytes=2)
+
+
+def test_out_degree_above_65536_uses_four_bytes(tk):
+    N, R, d = 1024, 2, 32
+    rng = np.random.default_rng(2)
+    T = 70_000
+    head = np.full(T, 5, np.int32); head[:2000] = rng.integers(0, N, 2000)
+    rel = rng.integers(0, R, T).astype(np.int32)
+    tail = rng.integers(0, N, T).astype(np.int32)
+    E = rng.standard_normal((N, d)).astype(np.float32); G = rng.standard_normal((N, d)).astype(np.float32)
+    run_case(tk, N, R, head, rel, tail, E, G, want_bytes=4)
+
+
+def test_config1_graph_full_size(tk):
+    N, R, T, d = 100_000, 16, 1_000_000, 64
+    head, rel, tail = gen.kg_triplets(N, R, T, seed=0, tail_zipf=1.1)
+    E = gen.entity_embeddings(N, d, seed=1, std=0.1)
+    G = gen.upstream_grad(N, d, seed=3)
+    run_case(tk, N, R, head, rel, tail, E, G, want_bytes=1)
+
+
+def test_error_paths(tk):
+    N, R = 64, 2
+    head, rel, tail = gen.kg_triplets(N, R, 100, seed=0)
+    g = tk.Graph(N, R, *(torch.from_numpy(a).cuda() for a in (head, rel, tail)))
+    assert tk.lib().tinykg_kg_max_workspace_bytes(g.handle, 48) == 0
+    E = torch.zeros((N, 48), device="cuda")
+    with pytest.raises(tk.TinyKGError) as e:
+        tk.tinykg_kg_max_fwd(g, E, out=(torch.empty_like(E), torch.empty((N, 48), dtype=torch.uint8, device="cuda")))
+    assert e.value.status == 3
+    G = torch.zeros((N, 64), device="cuda")
+    arg = torch.zeros((N, 64), dtype=torch.uint8, device="cuda")
+    with pytest.raises(tk.TinyKGError) as e:
+        tk.tinykg_kg_max_bwd(g, arg, G, workspace=torch.empty(16, dtype=torch.uint8, device="cuda"))
+    assert e.value.status == 4
+    g.close()

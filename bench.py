@@ -278,6 +278,59 @@ def uniform_workload(a):
     graph.close()
 
 
+def maxpool_workload(a):
+    """Max-pooling aggregation (SPMM_MAX, Sec. 4.1.4 operator list) on the configs[1] graph:
+    a gather and a scatter, no arithmetic to speak of."""
+    import torch
+    import paper_2212_04540_amd as tk
+    dev = "cuda"
+    inp = make_inputs(torch)
+    t = {k: torch.from_numpy(v).to(dev) for k, v in inp.items()}
+    graph = tk.Graph(N, R, t["head"], t["rel"], t["tail"])
+    nb = int(tk.lib().tinykg_kg_max_arg_bytes(graph.handle))
+    G = t["G"]
+    M, arg = tk.tinykg_kg_max_fwd(graph, t["E"])
+    ws = torch.empty(int(tk.lib().tinykg_kg_max_workspace_bytes(graph.handle, D)), dtype=torch.uint8, device=dev)
+    gE = torch.empty_like(G)
+
+    def step(i):
+        tk.tinykg_kg_max_fwd(graph, t["E"], out=(M, arg))
+        tk.tinykg_kg_max_bwd(graph, arg, G, workspace=ws, out=gE)
+
+    for i in range(a.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    tk.tinykg_profile_enable(True)
+    t0 = time.perf_counter()
+    for i in range(a.steps):
+        step(a.warmup + i)
+    torch.cuda.synchronize()
+    dt = (time.perf_counter() - t0) / a.steps
+    rep = tk.tinykg_profile_report()
+    tk.tinykg_profile_enable(False)
+    fwd_bytes = T * (4 * D + 4) + N * (4 * D + D * nb + 4)          # e_t row + tail id; M, numbers, row pointer
+    bwd_bytes = T * (4 * D + D * nb + 13) + N * 4 * D                # per edge: grad_M row, numbers of the head's row,
+    #                                                                  head / tail / position / flags; grad_E cleared
+    alg = fwd_bytes + bwd_bytes
+    kernels = {k: {"launches_per_step": v[0] / a.steps, "ms_per_step": round(v[1] / a.steps, 4)} for k, v in rep.items()}
+    f_ms = rep["max_fwd_kernel"][1] / rep["max_fwd_kernel"][0]
+    print(json.dumps({
+        "metric": "quantize+pack and dequant+agg-bwd HBM GB/s (fraction of peak); bytes/activation",
+        "value": round(alg / dt / 1e9, 2), "unit": "GB/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
+        "ms_per_step": round(dt * 1e3, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "max-pooling aggregation (SPMM_MAX), forward+backward, on the configs[1] graph: "
+                               "100k entities, dim 64, 1M triplets",
+                   "context_bytes_per_element": nb, "algorithmic_bytes_per_step": alg,
+                   "saved_context_bytes": N * D * nb, "int64_argmax_context_bytes": N * D * 8},
+        "frac_of_hbm_peak": round(alg / dt / 1e9 / HBM_PEAK_GBS, 5),
+        "roofline": {"kernel": "max_fwd_kernel", "bound": "hbm", "achieved": round(fwd_bytes / (f_ms * 1e-3) / 1e9, 1),
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(fwd_bytes / (f_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+                     "traffic": None, "avg_launch_ms": round(f_ms, 4)},
+        "kernels": kernels}))
+    graph.close()
+
+
 def batchnorm_workload(a):
     """Batch normalisation with a compressed input (Sec. 4.1.4 operator list) on the
     configs[2] tensor shape: every kernel is a stream, so HBM bounds the whole step."""
@@ -418,7 +471,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-compressor", action="store_true")
-    ap.add_argument("--workload", choices=["config1", "config2", "config3", "config4", "uniform", "batchnorm"], default="config1",
+    ap.add_argument("--workload", choices=["config1", "config2", "config3", "config4", "uniform", "batchnorm", "maxpool"], default="config1",
                     help="config1 (default, the headline step); config2: the 9-cell compressor sweep; "
                          "config3 / config4: multi-layer steps; uniform: the uniform-attention "
                          "layer on the config1 graph")
@@ -441,6 +494,8 @@ def main():
         return uniform_workload(a)
     if a.workload == "batchnorm":
         return batchnorm_workload(a)
+    if a.workload == "maxpool":
+        return maxpool_workload(a)
     if a.workload != "config1":
         return stack_workload(a, a.workload)
     dev = "cuda"

@@ -249,7 +249,8 @@ tinykg_status tinykg_fill_zero(float* dst, int64_t n, void* stream);
  * all pointers DEVICE and 16-byte aligned; outputs are overwritten.  M and arg are
  * exact and deterministic; grad_E is accumulated with atomics (fp32, double for the
  * nodes with more than 1024 incident edges), so it is reproducible to rounding.
- * Edge numbers in `arg` beyond a head's degree (a corrupted context) are clamped.
+ * An edge number in `arg` beyond its head's degree (a corrupted context) matches no
+ * out-edge: that gradient entry is dropped.
  * `workspace` (backward only): tinykg_kg_max_workspace_bytes(g, d) bytes.
  * ------------------------------------------------------------------------- */
 int tinykg_kg_max_arg_bytes(const tinykg_graph* g);

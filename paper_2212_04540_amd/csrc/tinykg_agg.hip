@@ -1130,27 +1130,51 @@ __global__ void zero_f32_fill_kernel(float* __restrict__ dst, int64_t n) {
   for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) dst[i] = 0.f;
 }
 
+// What one edge (h -> t) passes to its tail, column by column: a per-edge word staged once
+// per row and the value of column c.
 template <int D>
+struct UniformRows {     // grad_H_h / deg(h)
+  const int32_t* rowptr;
+  const float* gH;
+  __device__ __forceinline__ int stage(int h, int64_t) const {
+    return __float_as_int(1.0f / (float)(rowptr[h + 1] - rowptr[h]));
+  }
+  __device__ __forceinline__ float value(int word, int h, int c) const {
+    return __int_as_float(word) * gH[(int64_t)h * D + c];     // rows past the end: word = 0, row 0
+  }
+};
+template <int D, typename ARG>
+struct MaxRows {         // grad_M[h, c] where this edge is the one whose number the head saved
+  const int32_t* rowptr;
+  const int32_t* r_eid;
+  const float* gM;
+  const ARG* arg;
+  __device__ __forceinline__ int stage(int h, int64_t pos) const { return r_eid[pos] - rowptr[h] + 1; }
+  __device__ __forceinline__ float value(int word, int h, int c) const {   // rows past the end: word = 0
+    const int64_t i = (int64_t)h * D + c;
+    return (int)arg[i] + 1 == word ? gM[i] : 0.f;
+  }
+};
+
+template <int D, typename ROWS>
 __global__ __launch_bounds__(kThreads) void uniform_bwd_kernel(
     const int32_t* __restrict__ r_head, const int32_t* __restrict__ r_tail,
-    const uint8_t* __restrict__ r_hperm, const int32_t* __restrict__ rowptr,
-    const float* __restrict__ gH, int64_t n_edges, GradSink sink) {
+    const uint8_t* __restrict__ r_hperm, ROWS rows, int64_t n_edges, GradSink sink) {
   constexpr int NQ = D >= 64 ? 1 : 64 / D, RP = 32 / NQ;   // row parts of a wave
   constexpr int CPL = D >= 64 ? D / 64 : 1;                // columns per lane
   __shared__ int tl_s[kThreads / 64][32];
   __shared__ int hd_s[kThreads / 64][32];
-  __shared__ float w_s[kThreads / 64][32];
+  __shared__ int w_s[kThreads / 64][32];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, r = lane & 31;
   const int64_t pos0 = ((int64_t)blockIdx.x * (kThreads / 64) + wave) * 32;
   if (pos0 >= n_edges) return;
   const int nrow = (int)min((int64_t)32, n_edges - pos0);
-  int t_id = 0, h = 0;
-  float w = 0.f;
+  int t_id = 0, h = 0, w = 0;
   if (r < nrow) {
     const int64_t pos = pos0 + r;
     h = r_head[pos];
     t_id = r_tail[pos] | ((r_hperm[pos] & 0x40) ? kHeavyBit : 0);
-    w = 1.0f / (float)(rowptr[h + 1] - rowptr[h]);
+    w = rows.stage(h, pos);
   }
   const int t_next = __shfl_down(t_id, 1);
   const bool stop = r + 1 == nrow || (r + 1) % RP == 0;
@@ -1166,7 +1190,7 @@ __global__ __launch_bounds__(kThreads) void uniform_bwd_kernel(
 #pragma unroll
     for (int k = 0; k < RP; ++k) {
       node[k] = tl_s[wave][e0 + k];
-      val[k] = w_s[wave][e0 + k] * gH[(int64_t)hd_s[wave][e0 + k] * D + c];   // rows past the end: w = 0, row 0
+      val[k] = rows.value(w_s[wave][e0 + k], hd_s[wave][e0 + k], c);
     }
     float run = 0.f;
 #pragma unroll
@@ -1993,8 +2017,8 @@ tinykg_status bwd_impl(const tinykg_graph* g, const tinykg_saved* sv, const floa
     const GradSink sink{gE, acc, g->acc_slot};
     const int64_t waves = (g->n_edges + 31) / 32;
     ProfileScope prof("uniform_bwd_kernel", st);
-    hipLaunchKernelGGL((uniform_bwd_kernel<D>), dim3((unsigned)((waves + 3) / 4)), dim3(kThreads), 0, st,
-                       g->r_head, g->r_tail, g->r_hperm32, g->rowptr, gH, g->n_edges, sink);
+    hipLaunchKernelGGL((uniform_bwd_kernel<D, UniformRows<D>>), dim3((unsigned)((waves + 3) / 4)), dim3(kThreads),
+                       0, st, g->r_head, g->r_tail, g->r_hperm32, UniformRows<D>{g->rowptr, gH}, g->n_edges, sink);
     if ((rc = launch_status()) != TINYKG_OK) return rc;
   }
   if (!uniform && g->n_chunks > 0) {
@@ -2337,35 +2361,6 @@ __global__ __launch_bounds__(kThreads) void max_fwd_kernel(const float* __restri
   }
 }
 
-// One thread per 4 output elements: passes its four gradient entries to the winning tails.
-template <int D, typename ARG>
-__global__ __launch_bounds__(kThreads) void max_bwd_kernel(const float* __restrict__ gM,
-                                                           const ARG* __restrict__ arg,
-                                                           const int32_t* __restrict__ rowptr,
-                                                           const int32_t* __restrict__ h_tail, int64_t N,
-                                                           GradSink sink) {
-  constexpr int LPR = D / 4;
-  typedef typename ArgVec<ARG>::type AV;
-  const int64_t q = (int64_t)blockIdx.x * kThreads + threadIdx.x;
-  if (q >= N * LPR) return;
-  const int64_t h = q / LPR;
-  const int li = (int)(q % LPR);
-  const int e0 = rowptr[h], deg = rowptr[h + 1] - e0;
-  if (deg == 0) return;
-  const float4 g4 = reinterpret_cast<const float4*>(gM)[q];
-  const AV a4 = reinterpret_cast<const AV*>(arg)[q];
-  const uint32_t a[4] = {a4.x, a4.y, a4.z, a4.w};
-  const float gv[4] = {g4.x, g4.y, g4.z, g4.w};
-  int t[4];
-#pragma unroll
-  for (int c = 0; c < 4; ++c) t[c] = h_tail[e0 + (int)min(a[c], (uint32_t)(deg - 1))];
-#pragma unroll
-  for (int c = 0; c < 4; ++c) {
-    const int flagged = t[c] | (sink.slot[t[c]] >= 0 ? kHeavyBit : 0);
-    sink_add<D>(sink, flagged, li * 4 + c, gv[c]);
-  }
-}
-
 __global__ __launch_bounds__(256) void max_bwd_zero_kernel(float* __restrict__ gE, int64_t n,
                                                            double* __restrict__ acc, int64_t m) {
   const int64_t stride = (int64_t)gridDim.x * 256;
@@ -2401,10 +2396,15 @@ tinykg_status max_bwd_impl(const tinykg_graph* g, const void* arg, const float* 
   ProfileScope prof("max_bwd_kernels", st);
   hipLaunchKernelGGL(max_bwd_zero_kernel, dim3(std::max(zb, 1)), dim3(256), 0, st, gE, N * D, acc,
                      n_heavy_elems * kHeavyReplicas);
-  const GradSink sink{gE, acc, g->acc_slot};
-  const int64_t blocks = (N * (D / 4) + kThreads - 1) / kThreads;
-  hipLaunchKernelGGL((max_bwd_kernel<D, ARG>), dim3((unsigned)blocks), dim3(kThreads), 0, st, gM,
-                     static_cast<const ARG*>(arg), g->rowptr, g->h_tail, N, sink);
+  // the transposed walk of the uniform layer with another row: edges in (relation, tail)
+  // order, 32 per wave, equal tails summed before one row of atomics per run
+  if (g->n_edges > 0) {
+    const GradSink sink{gE, acc, g->acc_slot};
+    const int64_t waves = (g->n_edges + 31) / 32;
+    const MaxRows<D, ARG> rows{g->rowptr, g->r_eid, gM, static_cast<const ARG*>(arg)};
+    hipLaunchKernelGGL((uniform_bwd_kernel<D, MaxRows<D, ARG>>), dim3((unsigned)((waves + 3) / 4)), dim3(kThreads),
+                       0, st, g->r_head, g->r_tail, g->r_hperm32, rows, g->n_edges, sink);
+  }
   if (n_heavy_elems > 0) {
     const HeavyFinish hf{acc, g->acc_node, n_heavy_elems, D, gE};
     hipLaunchKernelGGL(max_bwd_finish_kernel, dim3(64), dim3(256), 0, st, hf);

@@ -58,12 +58,12 @@ def edge_bwd_flops():
 PROFILE_SUMMARY = os.path.join(ROOT, "profiles", "aggregation_step_configs1_and_compressor_configs2.txt")
 
 
-def profiled_traffic(kernel):
+def profiled_traffic(kernel, summary=None):
     """HBM bytes per launch of `kernel` from the committed rocprofv3 counter summary
     (FETCH_SIZE + WRITE_SIZE, each scaled by what the counter reads for a copy of known
     size): measured offline with the commands that file lists, not in this run."""
     try:
-        rows = [l.split() for l in open(PROFILE_SUMMARY) if l.startswith(kernel + "<") and len(l.split()) >= 6]
+        rows = [l.split() for l in open(summary or PROFILE_SUMMARY) if l.startswith(kernel + "<") and len(l.split()) >= 6]
         tot = [(float(r[-2]) + float(r[-1])) * 1e6 for r in rows if r[-1] != "nan" and r[-2] != "nan"]
         return round(max(tot)) if tot else None
     except (OSError, ValueError):
@@ -390,7 +390,8 @@ def batchnorm_workload(a):
         "roofline": {"kernel": dom, "bound": "hbm", "achieved": round(n * per_kernel[dom] / (dom_ms * 1e-3) / 1e9, 1),
                      "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(n * per_kernel[dom] / (dom_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
-                     "traffic": None, "avg_launch_ms": round(dom_ms, 4)},
+                     "traffic": profiled_traffic(dom, os.path.join(ROOT, "profiles", "batchnorm_2p23x64_int2_g64.txt")),
+                     "avg_launch_ms": round(dom_ms, 4)},
         "kernels": kernels}))
 
 

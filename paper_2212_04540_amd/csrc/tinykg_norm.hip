@@ -129,24 +129,34 @@ __global__ __launch_bounds__(kThreads) void bn_stats_kernel(Source src, const fl
   }
 }
 
-// Sum of the per-workgroup partials of column c, kind k (0 / 1), in a fixed order: the
-// workgroup's threads split the partials into kFinishThreads / dim interleaved subsets.
-__device__ __forceinline__ void sum_partials(const double* part, int n_part, int dim, double* lds,
-                                             double& t0, double& t1) {
+// Sums of the per-workgroup partials in a fixed order.  Workgroup b owns the kFinishCols
+// columns from b * kFinishCols on; its threads split the partials of a column into
+// kFinishThreads / kFinishCols interleaved subsets, combined in two steps through LDS.
+// Returns the column (threads below kFinishCols hold its two sums), -1 elsewhere.
+constexpr int kFinishCols = 4;
+__device__ __forceinline__ int sum_partials(const double* part, int n_part, int dim, double* lds,
+                                            double& t0, double& t1) {
+  constexpr int kparts = kFinishThreads / kFinishCols, kStep = 16;
   const int tid = threadIdx.x;
-  const int kparts = kFinishThreads / dim;
-  const int c = tid % dim, k = tid / dim;
+  const int cl = tid % kFinishCols, k = tid / kFinishCols;
+  const int c = blockIdx.x * kFinishCols + cl;
   double a0 = 0.0, a1 = 0.0;
-  if (k < kparts)
-    for (int b = k; b < n_part; b += kparts) {
-      a0 += part[(size_t)b * 2 * dim + c];
-      a1 += part[(size_t)b * 2 * dim + dim + c];
-    }
+  for (int b = k; b < n_part; b += kparts) {
+    a0 += part[(size_t)b * 2 * dim + c];
+    a1 += part[(size_t)b * 2 * dim + dim + c];
+  }
   lds[tid * 2] = a0; lds[tid * 2 + 1] = a1;
   __syncthreads();
+  a0 = 0.0; a1 = 0.0;
+  if (k < kparts / kStep)
+    for (int q = k * kStep; q < (k + 1) * kStep; ++q) { a0 += lds[(q * kFinishCols + cl) * 2]; a1 += lds[(q * kFinishCols + cl) * 2 + 1]; }
+  __syncthreads();
+  if (k < kparts / kStep) { lds[tid * 2] = a0; lds[tid * 2 + 1] = a1; }
+  __syncthreads();
   t0 = 0.0; t1 = 0.0;
-  if (tid < dim)
-    for (int q = 0; q < kparts; ++q) { t0 += lds[(q * dim + tid) * 2]; t1 += lds[(q * dim + tid) * 2 + 1]; }
+  if (tid >= kFinishCols) return -1;
+  for (int q = 0; q < kparts / kStep; ++q) { t0 += lds[(q * kFinishCols + cl) * 2]; t1 += lds[(q * kFinishCols + cl) * 2 + 1]; }
+  return c;
 }
 
 // tab: [3][dim] = fl(mu), a = gamma * rstd, b = beta - (mu - fl(mu)) a (what the normalising pass reads)
@@ -156,9 +166,8 @@ __global__ __launch_bounds__(kFinishThreads) void bn_finish_fwd_kernel(
     float* __restrict__ mean, float* __restrict__ rstd, float* __restrict__ tab) {
   __shared__ double lds[kFinishThreads * 2];
   double s1, s2;
-  sum_partials(part, n_part, dim, lds, s1, s2);
-  const int c = threadIdx.x;
-  if (c < dim) {
+  const int c = sum_partials(part, n_part, dim, lds, s1, s2);
+  if (c >= 0) {
     const double m = s1 / (double)rows;
     const double var = fmax(s2 / (double)rows - m * m, 0.0);
     const double mu_d = (double)x_row0[c] + m, rs_d = 1.0 / sqrt(var + (double)eps);
@@ -179,9 +188,8 @@ __global__ __launch_bounds__(kFinishThreads) void bn_finish_bwd_kernel(
     float* __restrict__ grad_gamma, float* __restrict__ grad_beta, float* __restrict__ tab) {
   __shared__ double lds[kFinishThreads * 2];
   double gb, gg;
-  sum_partials(part, n_part, dim, lds, gb, gg);
-  const int c = threadIdx.x;
-  if (c < dim) {
+  const int c = sum_partials(part, n_part, dim, lds, gb, gg);
+  if (c >= 0) {
     grad_beta[c] = (float)gb; grad_gamma[c] = (float)gg;
     const double A = (double)gamma[c] * (double)rstd[c];
     tab[c] = mean[c];
@@ -310,7 +318,7 @@ tinykg_status bwd_impl(Source src, const float* mean, const float* rstd, const f
     hipLaunchKernelGGL((bn_stats_kernel<BITS, true>), dim3(sg.blocks), dim3(kThreads), 0, st, src, grad_y, mean,
                        rstd, rows, lpr, sg.rows_per_block, part);
   }
-  hipLaunchKernelGGL(bn_finish_bwd_kernel, dim3(1), dim3(kFinishThreads), 0, st, part, sg.blocks, mean, rstd,
+  hipLaunchKernelGGL(bn_finish_bwd_kernel, dim3(dim / kFinishCols), dim3(kFinishThreads), 0, st, part, sg.blocks, mean, rstd,
                      gamma, rows, dim, grad_gamma, grad_beta, tab);
   const int64_t n_chunks = rows * lpr;
   const int64_t blocks = (n_chunks + kThreads * kApplyU - 1) / (kThreads * kApplyU);
@@ -363,7 +371,7 @@ tinykg_status tinykg_batchnorm_fwd(const float* x, int64_t rows, int dim, const 
                        (const float*)nullptr, (const float*)nullptr, (const float*)nullptr, rows, lpr,
                        sg.rows_per_block, part);
   }
-  hipLaunchKernelGGL(bn_finish_fwd_kernel, dim3(1), dim3(kFinishThreads), 0, st, part, sg.blocks, x, gamma, beta,
+  hipLaunchKernelGGL(bn_finish_fwd_kernel, dim3(dim / kFinishCols), dim3(kFinishThreads), 0, st, part, sg.blocks, x, gamma, beta,
                      eps, rows, dim, mean, rstd, tab);
   if ((rc = launch_status()) != TINYKG_OK) return rc;
   if (bits == 32) {

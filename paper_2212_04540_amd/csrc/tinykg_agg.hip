@@ -404,6 +404,182 @@ __global__ __launch_bounds__(kThreads) void score_wave_kernel(Source src, const 
   }
 }
 
+// ---- fp32 products on the bf16 matrix cores -------------------------------------------
+// An fp32 number is the exact sum of three bfloat16 numbers (8 + 8 + 8 significant bits,
+// taken by truncation): x = h + m + l.  A product x y is then h h' + (h m' + m h') +
+// (m m' + h l' + l h') up to terms below 2^-23 |x y| -- the size of fp32's own rounding --
+// so an fp32 contraction becomes six bf16 MFMAs (v_mfma_f32_32x32x16_bf16, fp32 accumulate),
+// which run sixteen times faster than the fp32 MFMA each: 2.7 times the fp32 matrix rate at
+// fp32 accuracy.  The splitting is vector work (two subtractions, two masks and 1.5 byte
+// permutes per element) that overlaps with the matrix pipe.
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+
+union Bf16Frag {          // eight consecutive k-values of one operand row / column
+  bf16x8 v;
+  uint32_t u[4];
+};
+
+// Pieces of eight fp32 values: element 2i in the low half of word i, 2i + 1 in the high half.
+__device__ __forceinline__ void split3x8(const float (&x)[8], Bf16Frag& h, Bf16Frag& m, Bf16Frag& l) {
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    uint32_t hb[2], mb[2], lb[2];
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+      const float v = x[2 * i + u];
+      hb[u] = __float_as_uint(v) & 0xFFFF0000u;
+      const float r1 = v - __uint_as_float(hb[u]);           // exact
+      mb[u] = __float_as_uint(r1) & 0xFFFF0000u;
+      lb[u] = __float_as_uint(r1 - __uint_as_float(mb[u]));  // exact; its upper half is kept
+    }
+    h.u[i] = __builtin_amdgcn_perm(hb[1], hb[0], 0x07060302u);
+    m.u[i] = __builtin_amdgcn_perm(mb[1], mb[0], 0x07060302u);
+    l.u[i] = __builtin_amdgcn_perm(lb[1], lb[0], 0x07060302u);
+  }
+}
+
+// acc += W x for the pieces of eight k-values (six piece products, small ones first)
+__device__ __forceinline__ void mfma_split(const Bf16Frag& wh, const Bf16Frag& wm, const Bf16Frag& wl,
+                                           const Bf16Frag& xh, const Bf16Frag& xm, const Bf16Frag& xl,
+                                           floatx16& acc) {
+  acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wl.v, xh.v, acc, 0, 0, 0);
+  acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wh.v, xl.v, acc, 0, 0, 0);
+  acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wm.v, xm.v, acc, 0, 0, 0);
+  acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wm.v, xh.v, acc, 0, 0, 0);
+  acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wh.v, xm.v, acc, 0, 0, 0);
+  acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wh.v, xh.v, acc, 0, 0, 0);
+}
+
+// W_r (fp32, [D][D] row-major in global memory) as three bf16 matrices in LDS, rows padded
+// to D + 8 halves (row stride = 16 bytes mod 128: the 128-bit row reads of 32 lanes that
+// hold 32 different rows spread over all banks).
+template <int D>
+__device__ __forceinline__ void stage_split_matrix(const float* __restrict__ W, uint16_t* __restrict__ Wp,
+                                                   int tid, int n_threads) {
+  constexpr int LDW = D + 8, LPR = D / 4;
+  for (int q = tid; q < D * LPR; q += n_threads) {
+    const float4 w = reinterpret_cast<const float4*>(W)[q];
+    const float x[4] = {w.x, w.y, w.z, w.w};
+    uint32_t hb[4], mb[4], lb[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      hb[u] = __float_as_uint(x[u]) & 0xFFFF0000u;
+      const float r1 = x[u] - __uint_as_float(hb[u]);
+      mb[u] = __float_as_uint(r1) & 0xFFFF0000u;
+      lb[u] = __float_as_uint(r1 - __uint_as_float(mb[u]));
+    }
+    const int at = (q / LPR) * LDW + (q % LPR) * 4;    // in halves
+    *reinterpret_cast<uint2*>(Wp + at) = make_uint2(__builtin_amdgcn_perm(hb[1], hb[0], 0x07060302u),
+                                                    __builtin_amdgcn_perm(hb[3], hb[2], 0x07060302u));
+    *reinterpret_cast<uint2*>(Wp + D * LDW + at) = make_uint2(__builtin_amdgcn_perm(mb[1], mb[0], 0x07060302u),
+                                                              __builtin_amdgcn_perm(mb[3], mb[2], 0x07060302u));
+    *reinterpret_cast<uint2*>(Wp + 2 * D * LDW + at) = make_uint2(__builtin_amdgcn_perm(lb[1], lb[0], 0x07060302u),
+                                                                  __builtin_amdgcn_perm(lb[3], lb[2], 0x07060302u));
+  }
+}
+
+// score_wave_kernel with the two projections on the bf16 matrix cores.  Lane l = (r, hh)
+// holds elements [32 hh, +D/2) of both rows of edge r; MFMA number m of a row block takes
+// its elements [8 m, +8) -- the same permutation of the contraction index on the W_r side.
+template <int D, int BITS>
+__global__ __launch_bounds__(kThreads) void score_split_kernel(Source src, const float* __restrict__ Wr,
+                                                               const float* __restrict__ er,
+                                                               const int32_t* __restrict__ r_head,
+                                                               const int32_t* __restrict__ r_tail,
+                                                               const int32_t* __restrict__ r_eid,
+                                                               ChunkList chunks, float* __restrict__ s_out) {
+  constexpr int LDW = D + 8, KH = D / 2, NCB = D / 32, NM = KH / 8;
+  uint16_t* Wp = reinterpret_cast<uint16_t*>(smem_raw);                 // [3][D][LDW] halves
+  float* er_s = reinterpret_cast<float*>(Wp + 3 * D * LDW);
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int ch = blockIdx.x;
+  const int rel = chunks.rel[ch], start = chunks.start[ch], count = chunks.count[ch];
+  const int r = lane & 31, hh = lane >> 5;
+  const int n_wt = (count + 31) >> 5;
+  int wt = wave;
+
+  int t_nx = 0, h_nx = 0, e_nx = -1;
+  auto load_idx = [&](int tile) {
+    const int row = tile * 32 + r;
+    t_nx = 0; h_nx = 0; e_nx = -1;
+    if (row < count) { const int pos = start + row; t_nx = r_tail[pos]; h_nx = r_head[pos]; e_nx = r_eid[pos]; }
+  };
+  HalfRow<D, BITS> nt, nh;
+  load_idx(wt);
+  nt.load(src, t_nx, hh);
+  nh.load(src, h_nx, hh);
+  int e_cur = e_nx;
+  if (wt + 4 < n_wt) load_idx(wt + 4);
+
+  stage_split_matrix<D>(Wr + (size_t)rel * D * D, Wp, tid, kThreads);
+  for (int c = tid; c < D; c += kThreads) er_s[c] = er[(size_t)rel * D + c];
+  __syncthreads();
+  if (wt >= n_wt) return;
+
+  for (; wt < n_wt; wt += 4) {
+    float tv[KH], hv[KH];
+#pragma unroll
+    for (int i = 0; i < KH; ++i) { tv[i] = nt.get(i); hv[i] = nh.get(i); }
+    const int eid = e_cur;
+    if (wt + 4 < n_wt) {
+      nt.load(src, t_nx, hh);
+      nh.load(src, h_nx, hh);
+      e_cur = e_nx;
+      if (wt + 8 < n_wt) load_idx(wt + 8);
+    }
+    floatx16 accA[NCB], accB[NCB];
+#pragma unroll
+    for (int cb = 0; cb < NCB; ++cb) {
+      accA[cb] = floatx16{0};
+#pragma unroll
+      for (int v = 0; v < 16; ++v) accB[cb][v] = er_s[cb * 32 + acc_row(v, lane)];
+    }
+    int wofs = 0;
+    asm volatile("" : "+v"(wofs));
+    const uint16_t* wrow = Wp + r * LDW + hh * KH + wofs;
+#pragma unroll
+    for (int m = 0; m < NM; ++m) {
+      Bf16Frag th, tm, tl, hhi, hmi, hlo;
+      {
+        float a[8], b[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) { a[i] = tv[8 * m + i]; b[i] = hv[8 * m + i]; }
+        split3x8(a, th, tm, tl);
+        split3x8(b, hhi, hmi, hlo);
+      }
+      Bf16Frag wh[NCB], wm[NCB], wl[NCB];
+#pragma unroll
+      for (int cb = 0; cb < NCB; ++cb) {
+        const uint16_t* wp = wrow + cb * 32 * LDW + 8 * m;
+        *reinterpret_cast<uint4*>(wh[cb].u) = *reinterpret_cast<const uint4*>(wp);
+        *reinterpret_cast<uint4*>(wm[cb].u) = *reinterpret_cast<const uint4*>(wp + D * LDW);
+        *reinterpret_cast<uint4*>(wl[cb].u) = *reinterpret_cast<const uint4*>(wp + 2 * D * LDW);
+      }
+      // six piece products (small ones first), each over the 2 NCB independent accumulators
+#define TINYKG_SPLIT_STEP(WP, TP, HP)                                                                      \
+      _Pragma("unroll") for (int cb = 0; cb < NCB; ++cb) {                                                 \
+        accA[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(WP[cb].v, TP.v, accA[cb], 0, 0, 0);             \
+        accB[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(WP[cb].v, HP.v, accB[cb], 0, 0, 0);             \
+      }
+      TINYKG_SPLIT_STEP(wl, th, hhi)
+      TINYKG_SPLIT_STEP(wh, tl, hlo)
+      TINYKG_SPLIT_STEP(wm, tm, hmi)
+      TINYKG_SPLIT_STEP(wm, th, hhi)
+      TINYKG_SPLIT_STEP(wh, tm, hmi)
+      TINYKG_SPLIT_STEP(wh, th, hhi)
+#undef TINYKG_SPLIT_STEP
+    }
+    float p = 0.f;
+#pragma unroll
+    for (int cb = 0; cb < NCB; ++cb) {
+#pragma unroll
+      for (int v = 0; v < 16; ++v) p = fmaf(accA[cb][v], fast_tanh(accB[cb][v]), p);
+    }
+    p += __shfl_xor(p, 32);
+    if (hh == 0 && eid >= 0) s_out[eid] = p;
+  }
+}
+
 // ---------------------------------------------------------- per-head stages ----
 // Sum over the LPR (8, 16 or 32) adjacent lanes that share one edge, result on every one
 // of them: DPP steps inside a row of 16 lanes (after each step the reduced sub-block is
@@ -1858,8 +2034,13 @@ tinykg_status launch_score(const tinykg_graph* g, Source src, const float* Wr, c
   ChunkList cl{g->chunk_rel, g->chunk_start, g->chunk_count};
   ProfileScope prof("score_kernel", st);
   if constexpr (D <= 64) {
+#ifdef TINYKG_FP32_MFMA_SCORES
     const size_t smem = (size_t)(D * LD + D) * 4;
     auto kern = score_wave_kernel<D, BITS>;
+#else
+    const size_t smem = (size_t)3 * D * (D + 8) * 2 + (size_t)D * 4;
+    auto kern = score_split_kernel<D, BITS>;
+#endif
     tinykg_status rc = set_smem(kern, smem);
     if (rc != TINYKG_OK) return rc;
     hipLaunchKernelGGL(kern, dim3(g->n_chunks), dim3(kThreads), smem, st, src, Wr, er, g->r_head,

@@ -110,7 +110,7 @@ tinykg_status tinykg_graph_create(int64_t n_nodes, int32_t n_rel, int64_t n_edge
   // chunks: runs of at most chunk_edges consecutive relation-order edges of one
   // relation; about 2048 of them: few enough that the per-chunk partial gradients stay
   // small and a workgroup amortises staging W_r, enough to fill 256 compute units.
-    int64_t chunk_edges = ((n_edges / 2048 + 63) / 64) * 64;
+  int64_t chunk_edges = ((n_edges / 2048 + 63) / 64) * 64;
   if (chunk_edges < 64) chunk_edges = 64;
   std::vector<int32_t> chunk_rel, chunk_start, chunk_count, rel_chunk_ptr((size_t)n_rel + 1, 0);
   int64_t pos = 0;

@@ -1749,27 +1749,41 @@ __global__ __launch_bounds__(kEdgeWaves * 64) void edge_wave_kernel(
 #pragma unroll
     for (int cb = 0; cb < NB; ++cb) { accA[cb] = floatx16{0}; accB[cb] = floatx16{0}; }
     {
+      // on the bf16 matrix cores: eight k-values of each operand are read as fp32, split into
+      // three bfloat16 pieces in registers and multiplied piece by piece (see split3x8); the
+      // W_r fragments serve both products and the row fragments both channel blocks, which is
+      // what makes splitting on the fly pay here (it does not for the other two product pairs
+      // of this kernel, whose fragments are used once)
       int wofs = 0;
       asm volatile("" : "+v"(wofs));    // W_r is re-read from LDS, never parked in registers
       const float* wrow = Wr_s + r * LD + hh * KH + wofs;
       const float* trow = X_s + r * LD + hh * KH + wofs;
       const float* hrow = Y_s + r * LD + hh * KH + wofs;
+      auto frag = [](const float* p, Bf16Frag& h, Bf16Frag& m, Bf16Frag& l) {
+        const float4 lo4 = *reinterpret_cast<const float4*>(p), hi4 = *reinterpret_cast<const float4*>(p + 4);
+        const float x[8] = {lo4.x, lo4.y, lo4.z, lo4.w, hi4.x, hi4.y, hi4.z, hi4.w};
+        split3x8(x, h, m, l);
+      };
 #pragma unroll
-      for (int s0 = 0; s0 < KH; s0 += 4) {
-        const float4 t4 = *reinterpret_cast<const float4*>(trow + s0);
-        const float4 h4 = *reinterpret_cast<const float4*>(hrow + s0);
+      for (int m = 0; m < KH / 8; ++m) {
+        Bf16Frag th, tm, tl, hhi, hmi, hlo, wh[NB], wm[NB], wl[NB];
+        frag(trow + 8 * m, th, tm, tl);
+        frag(hrow + 8 * m, hhi, hmi, hlo);
 #pragma unroll
-        for (int cb = 0; cb < NB; ++cb) {
-          const float4 w4 = *reinterpret_cast<const float4*>(wrow + cb * 32 * LD + s0);
-          accA[cb] = __builtin_amdgcn_mfma_f32_32x32x2f32(t4.x, w4.x, accA[cb], 0, 0, 0);
-          accB[cb] = __builtin_amdgcn_mfma_f32_32x32x2f32(h4.x, w4.x, accB[cb], 0, 0, 0);
-          accA[cb] = __builtin_amdgcn_mfma_f32_32x32x2f32(t4.y, w4.y, accA[cb], 0, 0, 0);
-          accB[cb] = __builtin_amdgcn_mfma_f32_32x32x2f32(h4.y, w4.y, accB[cb], 0, 0, 0);
-          accA[cb] = __builtin_amdgcn_mfma_f32_32x32x2f32(t4.z, w4.z, accA[cb], 0, 0, 0);
-          accB[cb] = __builtin_amdgcn_mfma_f32_32x32x2f32(h4.z, w4.z, accB[cb], 0, 0, 0);
-          accA[cb] = __builtin_amdgcn_mfma_f32_32x32x2f32(t4.w, w4.w, accA[cb], 0, 0, 0);
-          accB[cb] = __builtin_amdgcn_mfma_f32_32x32x2f32(h4.w, w4.w, accB[cb], 0, 0, 0);
+        for (int cb = 0; cb < NB; ++cb) frag(wrow + cb * 32 * LD + 8 * m, wh[cb], wm[cb], wl[cb]);
+#define TINYKG_SPLIT_STEP(TP, HP, WP)                                                                      \
+        _Pragma("unroll") for (int cb = 0; cb < NB; ++cb) {                                                \
+          accA[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(TP.v, WP[cb].v, accA[cb], 0, 0, 0);           \
+          accB[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(HP.v, WP[cb].v, accB[cb], 0, 0, 0);           \
         }
+        TINYKG_SPLIT_STEP(th, hhi, wl)
+        TINYKG_SPLIT_STEP(tl, hlo, wh)
+        TINYKG_SPLIT_STEP(tm, hmi, wm)
+        TINYKG_SPLIT_STEP(th, hhi, wm)
+        TINYKG_SPLIT_STEP(tm, hmi, wh)
+        TINYKG_SPLIT_STEP(th, hhi, wh)
+#undef TINYKG_SPLIT_STEP
+        __builtin_amdgcn_sched_barrier(0);   // one k-step's fragments at a time
       }
     }
     phase_fence();

@@ -580,6 +580,131 @@ __global__ __launch_bounds__(kThreads) void score_split_kernel(Source src, const
   }
 }
 
+// Three bf16 pieces of four consecutive fp32 values, stored at the same position of three
+// LDS matrices `piece_stride` halves apart.
+__device__ __forceinline__ void store_split4(const float4& v, uint16_t* dst, int piece_stride) {
+  const float x[4] = {v.x, v.y, v.z, v.w};
+  uint32_t hb[4], mb[4], lb[4];
+#pragma unroll
+  for (int u = 0; u < 4; ++u) {
+    hb[u] = __float_as_uint(x[u]) & 0xFFFF0000u;
+    const float r1 = x[u] - __uint_as_float(hb[u]);
+    mb[u] = __float_as_uint(r1) & 0xFFFF0000u;
+    lb[u] = __float_as_uint(r1 - __uint_as_float(mb[u]));
+  }
+  *reinterpret_cast<uint2*>(dst) = make_uint2(__builtin_amdgcn_perm(hb[1], hb[0], 0x07060302u),
+                                              __builtin_amdgcn_perm(hb[3], hb[2], 0x07060302u));
+  *reinterpret_cast<uint2*>(dst + piece_stride) = make_uint2(__builtin_amdgcn_perm(mb[1], mb[0], 0x07060302u),
+                                                             __builtin_amdgcn_perm(mb[3], mb[2], 0x07060302u));
+  *reinterpret_cast<uint2*>(dst + 2 * piece_stride) = make_uint2(__builtin_amdgcn_perm(lb[1], lb[0], 0x07060302u),
+                                                                 __builtin_amdgcn_perm(lb[3], lb[2], 0x07060302u));
+}
+
+// score_kernel on the bf16 matrix cores (d = 128): W_r and the tile's rows are split into
+// their three bfloat16 pieces as they are staged (once per element, whatever the number of
+// waves that multiply them); a wave then reads ready 128-bit fragments.  k-step m of half
+// hh covers k = 16 m + 8 hh + 0..7 on both operands.
+template <int D, int TE, int BITS>
+__global__ __launch_bounds__(kThreads) void score_coop_split_kernel(Source src, const float* __restrict__ Wr,
+                                                                    const float* __restrict__ er,
+                                                                    const int32_t* __restrict__ r_head,
+                                                                    const int32_t* __restrict__ r_tail,
+                                                                    const int32_t* __restrict__ r_eid,
+                                                                    ChunkList chunks, float* __restrict__ s_out) {
+  constexpr int LDW = D + 8, LPR = D / 4, NCB = D / 32, NEB = TE / 32, NP = NCB * 2;
+  constexpr int CPT = TE * LPR / kThreads, RSTEP = kThreads / LPR;
+  constexpr int WP = D * LDW, TP = TE * LDW;      // halves per piece
+  static_assert(TE * LPR % kThreads == 0 && kThreads % LPR == 0, "tile does not split evenly");
+  uint16_t* W_s = reinterpret_cast<uint16_t*>(smem_raw);        // [3][D][LDW]
+  uint16_t* Et_s = W_s + 3 * WP;                                 // [3][TE][LDW]
+  uint16_t* Eh_s = Et_s + 3 * TP;
+  float* er_s = reinterpret_cast<float*>(Eh_s + 3 * TP);
+  float* part = er_s + D;  // [NP][TE]
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int ch = blockIdx.x;
+  const int r = chunks.rel[ch], start = chunks.start[ch], count = chunks.count[ch];
+  const int row0 = tid / LPR, li = tid % LPR;
+
+  int tn[CPT], hn[CPT];
+  auto load_ids = [&](int t0) {
+#pragma unroll
+    for (int k = 0; k < CPT; ++k) {
+      const int row = t0 + row0 + k * RSTEP;
+      tn[k] = 0; hn[k] = 0;
+      if (row < count) { tn[k] = r_tail[start + row]; hn[k] = r_head[start + row]; }
+    }
+  };
+  RawChunk<BITS> rt[CPT], rh[CPT];
+  auto load_rows = [&]() {
+#pragma unroll
+    for (int k = 0; k < CPT; ++k) {
+      rt[k].load(src, (int64_t)tn[k] * LPR + li);
+      rh[k].load(src, (int64_t)hn[k] * LPR + li);
+    }
+  };
+  load_ids(0);
+  load_rows();
+  load_ids(TE);
+
+  stage_split_matrix<D>(Wr + (size_t)r * D * D, W_s, tid, kThreads);
+  for (int c = tid; c < D; c += kThreads) er_s[c] = er[(size_t)r * D + c];
+
+  for (int t0 = 0; t0 < count; t0 += TE) {
+    const int nrow = min(TE, count - t0);
+#pragma unroll
+    for (int k = 0; k < CPT; ++k) {
+      const int row = row0 + k * RSTEP;
+      store_split4(rt[k].get(), Et_s + row * LDW + li * 4, TP);
+      store_split4(rh[k].get(), Eh_s + row * LDW + li * 4, TP);
+    }
+    if (t0 + TE < count) {
+      load_rows();
+      load_ids(t0 + 2 * TE);
+    }
+    __syncthreads();
+    for (int blk = wave; blk < NCB * NEB; blk += 4) {
+      const int cb = blk % NCB, eb = blk / NCB;
+      floatx16 accA = {0}, accB = {0};
+      const int fr = (lane & 31) * LDW + (lane >> 5) * 8;
+      const uint16_t* wp = W_s + cb * 32 * LDW + fr;
+      const uint16_t* tp = Et_s + eb * 32 * LDW + fr;
+      const uint16_t* hp = Eh_s + eb * 32 * LDW + fr;
+      auto ld = [](const uint16_t* p) { Bf16Frag f; *reinterpret_cast<uint4*>(f.u) = *reinterpret_cast<const uint4*>(p); return f; };
+#pragma unroll
+      for (int m = 0; m < D / 16; ++m) {
+        const Bf16Frag wh = ld(wp + 16 * m), wm = ld(wp + WP + 16 * m), wl = ld(wp + 2 * WP + 16 * m);
+        const Bf16Frag th = ld(tp + 16 * m), tm = ld(tp + TP + 16 * m), tl = ld(tp + 2 * TP + 16 * m);
+        const Bf16Frag hh_ = ld(hp + 16 * m), hm = ld(hp + TP + 16 * m), hl = ld(hp + 2 * TP + 16 * m);
+#define TINYKG_SPLIT_STEP(WF, TF, HF)                                                           \
+        accA = __builtin_amdgcn_mfma_f32_32x32x16_bf16(WF.v, TF.v, accA, 0, 0, 0);              \
+        accB = __builtin_amdgcn_mfma_f32_32x32x16_bf16(WF.v, HF.v, accB, 0, 0, 0);
+        TINYKG_SPLIT_STEP(wl, th, hh_)
+        TINYKG_SPLIT_STEP(wh, tl, hl)
+        TINYKG_SPLIT_STEP(wm, tm, hm)
+        TINYKG_SPLIT_STEP(wm, th, hh_)
+        TINYKG_SPLIT_STEP(wh, tm, hm)
+        TINYKG_SPLIT_STEP(wh, th, hh_)
+#undef TINYKG_SPLIT_STEP
+      }
+      float p = 0.f;
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int c = cb * 32 + acc_row(v, lane);
+        p = fmaf(accA[v], fast_tanh(accB[v] + er_s[c]), p);
+      }
+      part[(cb * 2 + (lane >> 5)) * TE + eb * 32 + (lane & 31)] = p;
+    }
+    __syncthreads();
+    if (tid < nrow) {
+      float s = 0.f;
+#pragma unroll
+      for (int k = 0; k < NP; ++k) s += part[k * TE + tid];
+      s_out[r_eid[start + t0 + tid]] = s;
+    }
+  }
+}
+
 // ---------------------------------------------------------- per-head stages ----
 // Sum over the LPR (8, 16 or 32) adjacent lanes that share one edge, result on every one
 // of them: DPP steps inside a row of 16 lanes (after each step the reduced sub-block is
@@ -2061,8 +2186,13 @@ tinykg_status launch_score(const tinykg_graph* g, Source src, const float* Wr, c
                        g->r_tail, g->r_eid, cl, s);
   } else {
     constexpr int TE = 32;
+#ifdef TINYKG_FP32_MFMA_SCORES
     const size_t smem = (size_t)(D * LD + 2 * TE * LD + D + (D / 32) * 2 * TE) * 4;
     auto kern = score_kernel<D, TE, BITS>;
+#else
+    const size_t smem = (size_t)3 * (D + 2 * TE) * (D + 8) * 2 + (size_t)(D + (D / 32) * 2 * TE) * 4;
+    auto kern = score_coop_split_kernel<D, TE, BITS>;
+#endif
     tinykg_status rc = set_smem(kern, smem);
     if (rc != TINYKG_OK) return rc;
     hipLaunchKernelGGL(kern, dim3(g->n_chunks), dim3(kThreads), smem, st, src, Wr, er, g->r_head,

@@ -553,12 +553,21 @@ def main():
         "roofline": {"kernel": "edge_bwd_kernel", "bound": "mfma", "achieved": round(achieved, 3),
                      "peak": MFMA_FP32_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": round(achieved / MFMA_FP32_PEAK_TFLOPS, 4),
+                     "note": "fp32 flops of the kernel's six k x d contractions per triplet over its launch time, "
+                             "against the fp32 matrix peak; four of the six run on the fp32 matrix cores, two (the "
+                             "recomputation of a and b) as six bfloat16 piece products each on the bf16 matrix "
+                             "cores (dense peak 2500 TFLOP/s), fp32 accumulation, fp32 accuracy",
                      "traffic": profiled_traffic("edge_wave_kernel"),
                      "traffic_unit": "HBM bytes per launch (rocprofv3 --pmc FETCH_SIZE, WRITE_SIZE; "
                                      "summary under profiles/)",
                      "avg_launch_ms": round(dom_ms, 4)},
         "kernels": kernels,
     }
+    sc = rep["score_kernel"]
+    out["score_kernels"] = {"launches_per_step": sc[0] / a.steps, "avg_launch_ms": round(sc[1] / sc[0], 4),
+                            "fp32_equivalent_TFLOPs": round(T * 2 * 2 * D * D / (sc[1] / sc[0] * 1e-3) / 1e12, 1),
+                            "note": "two k x d projections per triplet, each as six bfloat16 piece products on the "
+                                    "bf16 matrix cores (executed bf16 flops = 6 x the fp32 flops)"}
     if not a.no_compressor:
         out["compressor"] = compressor_line(tk, torch)
     if not a.no_cpu_baseline:

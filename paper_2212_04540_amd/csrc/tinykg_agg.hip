@@ -9,8 +9,9 @@
 // materialised.
 //
 // Kernels
-//   score_kernel      relation-bucketed tiles: a = W_r e_t, b = W_r e_h + e_r on the
-//                     fp32 matrix cores (v_mfma_f32_32x32x2_f32), s = a . tanh(b)
+//   score kernels     relation-bucketed tiles: a = W_r e_t, b = W_r e_h + e_r, s = a . tanh(b);
+//                     the products run on the bf16 matrix cores with every fp32 operand split
+//                     exactly into three bfloat16 pieces (six piece products, fp32 accuracy)
 //   attend_fwd_kernel per head: softmax over its out-edges, H_h = e_h + sum pi e_t
 //   dense_fwd_kernel  J = H W^T (MFMA), E' = LeakyReLU(J), 1-bit sign mask
 //   dense_bwd_kernel  grad_J from the mask, grad_H = grad_J W, grad_W = grad_J^T H_hat

@@ -302,6 +302,11 @@ struct HalfRow {
       z = src.gmin[g]; s = src.gscale[g];
     }
   }
+  // the integer code of element i (compressed rows only)
+  __device__ __forceinline__ uint32_t code(int i) const {
+    constexpr uint32_t B = (1u << (EB & 31)) - 1u;
+    return (w[((i * EB) >> 5) % NW] >> ((i * EB) & 31)) & B;
+  }
   __device__ __forceinline__ float get(int i) const {
     if (BITS == 32) return __uint_as_float(w[i % NW]);
     constexpr uint32_t B = (1u << (EB & 31)) - 1u;
@@ -482,7 +487,11 @@ __device__ __forceinline__ void stage_split_matrix(const float* __restrict__ W, 
 // score_wave_kernel with the two projections on the bf16 matrix cores.  Lane l = (r, hh)
 // holds elements [32 hh, +D/2) of both rows of edge r; MFMA number m of a row block takes
 // its elements [8 m, +8) -- the same permutation of the contraction index on the W_r side.
-template <int D, int BITS>
+// CODES (compressed rows whose group covers at least a row, so that a row has ONE (Z, scale)
+// pair): W_r e_hat = scale (W_r code) + Z (W_r 1) by Eq. (4).  The integer codes are exact
+// bfloat16 values, so the product needs three piece products instead of six and no splitting or
+// dequantising of the rows at all; the affine part is applied to the 32 x 32 results.
+template <int D, int BITS, bool CODES>
 __global__ __launch_bounds__(kThreads) void score_split_kernel(Source src, const float* __restrict__ Wr,
                                                                const float* __restrict__ er,
                                                                const int32_t* __restrict__ r_head,
@@ -490,8 +499,10 @@ __global__ __launch_bounds__(kThreads) void score_split_kernel(Source src, const
                                                                const int32_t* __restrict__ r_eid,
                                                                ChunkList chunks, float* __restrict__ s_out) {
   constexpr int LDW = D + 8, KH = D / 2, NCB = D / 32, NM = KH / 8;
+  static_assert(!CODES || BITS != 32, "codes exist for compressed rows only");
   uint16_t* Wp = reinterpret_cast<uint16_t*>(smem_raw);                 // [3][D][LDW] halves
   float* er_s = reinterpret_cast<float*>(Wp + 3 * D * LDW);
+  float* wsum_s = er_s + D;                                             // row sums of W_r (CODES)
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int ch = blockIdx.x;
   const int rel = chunks.rel[ch], start = chunks.start[ch], count = chunks.count[ch];
@@ -514,13 +525,37 @@ __global__ __launch_bounds__(kThreads) void score_split_kernel(Source src, const
 
   stage_split_matrix<D>(Wr + (size_t)rel * D * D, Wp, tid, kThreads);
   for (int c = tid; c < D; c += kThreads) er_s[c] = er[(size_t)rel * D + c];
+  if (CODES) {
+    for (int c = tid; c < D; c += kThreads) {
+      const float4* row = reinterpret_cast<const float4*>(Wr + ((size_t)rel * D + c) * D);
+      double sum = 0.0;
+      for (int q = 0; q < D / 4; ++q) { const float4 w = row[q]; sum += (double)w.x + (double)w.y + (double)w.z + (double)w.w; }
+      wsum_s[c] = (float)sum;
+    }
+  }
   __syncthreads();
   if (wt >= n_wt) return;
 
   for (; wt < n_wt; wt += 4) {
-    float tv[KH], hv[KH];
+    float tv[CODES ? 1 : KH], hv[CODES ? 1 : KH];
+    Bf16Frag tc[CODES ? NM : 1], hc[CODES ? NM : 1];
+    float zt = 0.f, st = 0.f, zh = 0.f, sh = 0.f;
+    if constexpr (CODES) {
+      auto pack = [](uint32_t c0, uint32_t c1) {     // two codes as bfloat16 values (exact)
+        return __builtin_amdgcn_perm(__float_as_uint((float)c1), __float_as_uint((float)c0), 0x07060302u);
+      };
 #pragma unroll
-    for (int i = 0; i < KH; ++i) { tv[i] = nt.get(i); hv[i] = nh.get(i); }
+      for (int m = 0; m < NM; ++m)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          tc[m].u[i] = pack(nt.code(8 * m + 2 * i), nt.code(8 * m + 2 * i + 1));
+          hc[m].u[i] = pack(nh.code(8 * m + 2 * i), nh.code(8 * m + 2 * i + 1));
+        }
+      zt = nt.z; st = nt.s; zh = nh.z; sh = nh.s;
+    } else {
+#pragma unroll
+      for (int i = 0; i < KH; ++i) { tv[i] = nt.get(i); hv[i] = nh.get(i); }
+    }
     const int eid = e_cur;
     if (wt + 4 < n_wt) {
       nt.load(src, t_nx, hh);
@@ -533,7 +568,7 @@ __global__ __launch_bounds__(kThreads) void score_split_kernel(Source src, const
     for (int cb = 0; cb < NCB; ++cb) {
       accA[cb] = floatx16{0};
 #pragma unroll
-      for (int v = 0; v < 16; ++v) accB[cb][v] = er_s[cb * 32 + acc_row(v, lane)];
+      for (int v = 0; v < 16; ++v) accB[cb][v] = CODES ? 0.f : er_s[cb * 32 + acc_row(v, lane)];
     }
     int wofs = 0;
     asm volatile("" : "+v"(wofs));
@@ -541,7 +576,7 @@ __global__ __launch_bounds__(kThreads) void score_split_kernel(Source src, const
 #pragma unroll
     for (int m = 0; m < NM; ++m) {
       Bf16Frag th, tm, tl, hhi, hmi, hlo;
-      {
+      if constexpr (!CODES) {
         float a[8], b[8];
 #pragma unroll
         for (int i = 0; i < 8; ++i) { a[i] = tv[8 * m + i]; b[i] = hv[8 * m + i]; }
@@ -562,19 +597,35 @@ __global__ __launch_bounds__(kThreads) void score_split_kernel(Source src, const
         accA[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(WP[cb].v, TP.v, accA[cb], 0, 0, 0);             \
         accB[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(WP[cb].v, HP.v, accB[cb], 0, 0, 0);             \
       }
-      TINYKG_SPLIT_STEP(wl, th, hhi)
-      TINYKG_SPLIT_STEP(wh, tl, hlo)
-      TINYKG_SPLIT_STEP(wm, tm, hmi)
-      TINYKG_SPLIT_STEP(wm, th, hhi)
-      TINYKG_SPLIT_STEP(wh, tm, hmi)
-      TINYKG_SPLIT_STEP(wh, th, hhi)
+      if constexpr (CODES) {
+        TINYKG_SPLIT_STEP(wl, tc[m], hc[m])
+        TINYKG_SPLIT_STEP(wm, tc[m], hc[m])
+        TINYKG_SPLIT_STEP(wh, tc[m], hc[m])
+      } else {
+        TINYKG_SPLIT_STEP(wl, th, hhi)
+        TINYKG_SPLIT_STEP(wh, tl, hlo)
+        TINYKG_SPLIT_STEP(wm, tm, hmi)
+        TINYKG_SPLIT_STEP(wm, th, hhi)
+        TINYKG_SPLIT_STEP(wh, tm, hmi)
+        TINYKG_SPLIT_STEP(wh, th, hhi)
+      }
 #undef TINYKG_SPLIT_STEP
     }
     float p = 0.f;
 #pragma unroll
     for (int cb = 0; cb < NCB; ++cb) {
 #pragma unroll
-      for (int v = 0; v < 16; ++v) p = fmaf(accA[cb][v], fast_tanh(accB[cb][v]), p);
+      for (int v = 0; v < 16; ++v) {
+        if constexpr (CODES) {
+          const int c = cb * 32 + acc_row(v, lane);
+          const float ws = wsum_s[c];
+          const float a = fmaf(st, accA[cb][v], zt * ws);
+          const float b = fmaf(sh, accB[cb][v], fmaf(zh, ws, er_s[c]));
+          p = fmaf(a, fast_tanh(b), p);
+        } else {
+          p = fmaf(accA[cb][v], fast_tanh(accB[cb][v]), p);
+        }
+      }
     }
     p += __shfl_xor(p, 32);
     if (hh == 0 && eid >= 0) s_out[eid] = p;
@@ -2178,8 +2229,11 @@ tinykg_status launch_score(const tinykg_graph* g, Source src, const float* Wr, c
     const size_t smem = (size_t)(D * LD + D) * 4;
     auto kern = score_wave_kernel<D, BITS>;
 #else
-    const size_t smem = (size_t)3 * D * (D + 8) * 2 + (size_t)D * 4;
-    auto kern = score_split_kernel<D, BITS>;
+    const size_t smem = (size_t)3 * D * (D + 8) * 2 + (size_t)2 * D * 4;
+    auto kern = score_split_kernel<D, BITS, false>;
+    if constexpr (BITS != 32) {
+      if ((4 << src.group_chunks_log2) >= D) kern = score_split_kernel<D, BITS, true>;   // one group per row
+    }
 #endif
     tinykg_status rc = set_smem(kern, smem);
     if (rc != TINYKG_OK) return rc;

@@ -656,7 +656,9 @@ __device__ __forceinline__ void store_split4(const float4& v, uint16_t* dst, int
 // their three bfloat16 pieces as they are staged (once per element, whatever the number of
 // waves that multiply them); a wave then reads ready 128-bit fragments.  k-step m of half
 // hh covers k = 16 m + 8 hh + 0..7 on both operands.
-template <int D, int TE, int BITS>
+// (CODES: as in score_split_kernel -- the tile holds one bfloat16 matrix of codes per side and
+// the rows' (Z, scale) pairs instead of three pieces of dequantised values)
+template <int D, int TE, int BITS, bool CODES>
 __global__ __launch_bounds__(kThreads) void score_coop_split_kernel(Source src, const float* __restrict__ Wr,
                                                                     const float* __restrict__ er,
                                                                     const int32_t* __restrict__ r_head,
@@ -672,6 +674,9 @@ __global__ __launch_bounds__(kThreads) void score_coop_split_kernel(Source src, 
   uint16_t* Eh_s = Et_s + 3 * TP;
   float* er_s = reinterpret_cast<float*>(Eh_s + 3 * TP);
   float* part = er_s + D;  // [NP][TE]
+  float* wsum_s = part + NP * TE;      // [D] row sums of W_r           (CODES)
+  float* zs_s = wsum_s + D;            // [4][TE] Z_t, scale_t, Z_h, scale_h of the tile's rows (CODES)
+  static_assert(!CODES || BITS != 32, "codes exist for compressed rows only");
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int ch = blockIdx.x;
@@ -701,14 +706,40 @@ __global__ __launch_bounds__(kThreads) void score_coop_split_kernel(Source src, 
 
   stage_split_matrix<D>(Wr + (size_t)r * D * D, W_s, tid, kThreads);
   for (int c = tid; c < D; c += kThreads) er_s[c] = er[(size_t)r * D + c];
+  if (CODES) {
+    for (int c = tid; c < D; c += kThreads) {
+      const float4* row = reinterpret_cast<const float4*>(Wr + ((size_t)r * D + c) * D);
+      double sum = 0.0;
+      for (int q = 0; q < D / 4; ++q) { const float4 w = row[q]; sum += (double)w.x + (double)w.y + (double)w.z + (double)w.w; }
+      wsum_s[c] = (float)sum;
+    }
+  }
+  auto store_codes4 = [](const RawChunk<BITS>& c, uint16_t* dst) {   // four codes as bfloat16 values (exact)
+    constexpr uint32_t B = (BITS == 32) ? 0u : ((1u << (BITS & 31)) - 1u);
+    constexpr int SH = BITS & 31;
+    const uint32_t w = c.w[0];
+    const uint32_t f0 = __float_as_uint((float)(w & B)), f1 = __float_as_uint((float)((w >> SH) & B));
+    const uint32_t f2 = __float_as_uint((float)((w >> (2 * SH)) & B)), f3 = __float_as_uint((float)((w >> (3 * SH)) & B));
+    *reinterpret_cast<uint2*>(dst) = make_uint2(__builtin_amdgcn_perm(f1, f0, 0x07060302u),
+                                                __builtin_amdgcn_perm(f3, f2, 0x07060302u));
+  };
 
   for (int t0 = 0; t0 < count; t0 += TE) {
     const int nrow = min(TE, count - t0);
 #pragma unroll
     for (int k = 0; k < CPT; ++k) {
       const int row = row0 + k * RSTEP;
-      store_split4(rt[k].get(), Et_s + row * LDW + li * 4, TP);
-      store_split4(rh[k].get(), Eh_s + row * LDW + li * 4, TP);
+      if constexpr (CODES) {
+        store_codes4(rt[k], Et_s + row * LDW + li * 4);
+        store_codes4(rh[k], Eh_s + row * LDW + li * 4);
+        if (li == 0) {
+          zs_s[row] = rt[k].z; zs_s[TE + row] = rt[k].s;
+          zs_s[2 * TE + row] = rh[k].z; zs_s[3 * TE + row] = rh[k].s;
+        }
+      } else {
+        store_split4(rt[k].get(), Et_s + row * LDW + li * 4, TP);
+        store_split4(rh[k].get(), Eh_s + row * LDW + li * 4, TP);
+      }
     }
     if (t0 + TE < count) {
       load_rows();
@@ -726,24 +757,42 @@ __global__ __launch_bounds__(kThreads) void score_coop_split_kernel(Source src, 
 #pragma unroll
       for (int m = 0; m < D / 16; ++m) {
         const Bf16Frag wh = ld(wp + 16 * m), wm = ld(wp + WP + 16 * m), wl = ld(wp + 2 * WP + 16 * m);
-        const Bf16Frag th = ld(tp + 16 * m), tm = ld(tp + TP + 16 * m), tl = ld(tp + 2 * TP + 16 * m);
-        const Bf16Frag hh_ = ld(hp + 16 * m), hm = ld(hp + TP + 16 * m), hl = ld(hp + 2 * TP + 16 * m);
+        const Bf16Frag th = ld(tp + 16 * m), hh_ = ld(hp + 16 * m);
 #define TINYKG_SPLIT_STEP(WF, TF, HF)                                                           \
         accA = __builtin_amdgcn_mfma_f32_32x32x16_bf16(WF.v, TF.v, accA, 0, 0, 0);              \
         accB = __builtin_amdgcn_mfma_f32_32x32x16_bf16(WF.v, HF.v, accB, 0, 0, 0);
-        TINYKG_SPLIT_STEP(wl, th, hh_)
-        TINYKG_SPLIT_STEP(wh, tl, hl)
-        TINYKG_SPLIT_STEP(wm, tm, hm)
-        TINYKG_SPLIT_STEP(wm, th, hh_)
-        TINYKG_SPLIT_STEP(wh, tm, hm)
-        TINYKG_SPLIT_STEP(wh, th, hh_)
+        if constexpr (CODES) {
+          TINYKG_SPLIT_STEP(wl, th, hh_)
+          TINYKG_SPLIT_STEP(wm, th, hh_)
+          TINYKG_SPLIT_STEP(wh, th, hh_)
+        } else {
+          const Bf16Frag tm = ld(tp + TP + 16 * m), tl = ld(tp + 2 * TP + 16 * m);
+          const Bf16Frag hm = ld(hp + TP + 16 * m), hl = ld(hp + 2 * TP + 16 * m);
+          TINYKG_SPLIT_STEP(wl, th, hh_)
+          TINYKG_SPLIT_STEP(wh, tl, hl)
+          TINYKG_SPLIT_STEP(wm, tm, hm)
+          TINYKG_SPLIT_STEP(wm, th, hh_)
+          TINYKG_SPLIT_STEP(wh, tm, hm)
+          TINYKG_SPLIT_STEP(wh, th, hh_)
+        }
 #undef TINYKG_SPLIT_STEP
       }
       float p = 0.f;
+      float zt = 0.f, st = 0.f, zh = 0.f, sh = 0.f;
+      if constexpr (CODES) {
+        const int e = eb * 32 + (lane & 31);
+        zt = zs_s[e]; st = zs_s[TE + e]; zh = zs_s[2 * TE + e]; sh = zs_s[3 * TE + e];
+      }
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
         const int c = cb * 32 + acc_row(v, lane);
-        p = fmaf(accA[v], fast_tanh(accB[v] + er_s[c]), p);
+        if constexpr (CODES) {
+          const float ws = wsum_s[c];
+          const float a = fmaf(st, accA[v], zt * ws);
+          p = fmaf(a, fast_tanh(fmaf(sh, accB[v], fmaf(zh, ws, er_s[c]))), p);
+        } else {
+          p = fmaf(accA[v], fast_tanh(accB[v] + er_s[c]), p);
+        }
       }
       part[(cb * 2 + (lane >> 5)) * TE + eb * 32 + (lane & 31)] = p;
     }
@@ -2245,8 +2294,11 @@ tinykg_status launch_score(const tinykg_graph* g, Source src, const float* Wr, c
     const size_t smem = (size_t)(D * LD + 2 * TE * LD + D + (D / 32) * 2 * TE) * 4;
     auto kern = score_kernel<D, TE, BITS>;
 #else
-    const size_t smem = (size_t)3 * (D + 2 * TE) * (D + 8) * 2 + (size_t)(D + (D / 32) * 2 * TE) * 4;
-    auto kern = score_coop_split_kernel<D, TE, BITS>;
+    const size_t smem = (size_t)3 * (D + 2 * TE) * (D + 8) * 2 + (size_t)(2 * D + (D / 32) * 2 * TE + 4 * TE) * 4;
+    auto kern = score_coop_split_kernel<D, TE, BITS, false>;
+    if constexpr (BITS != 32) {
+      if ((4 << src.group_chunks_log2) >= D) kern = score_coop_split_kernel<D, TE, BITS, true>;
+    }
 #endif
     tinykg_status rc = set_smem(kern, smem);
     if (rc != TINYKG_OK) return rc;

@@ -566,8 +566,9 @@ def main():
     sc = rep["score_kernel"]
     out["score_kernels"] = {"launches_per_step": sc[0] / a.steps, "avg_launch_ms": round(sc[1] / sc[0], 4),
                             "fp32_equivalent_TFLOPs": round(T * 2 * 2 * D * D / (sc[1] / sc[0] * 1e-3) / 1e12, 1),
-                            "note": "two k x d projections per triplet, each as six bfloat16 piece products on the "
-                                    "bf16 matrix cores (executed bf16 flops = 6 x the fp32 flops)"}
+                            "note": "two k x d projections per triplet on the bf16 matrix cores: six bfloat16 piece "
+                                    "products each in the forward launch (fp32 rows), three in the backward launch "
+                                    "(integer codes are exact bfloat16 values)"}
     if not a.no_compressor:
         out["compressor"] = compressor_line(tk, torch)
     if not a.no_cpu_baseline:

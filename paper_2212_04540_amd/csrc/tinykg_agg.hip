@@ -2095,11 +2095,10 @@ __global__ __launch_bounds__(kEdgeWaves * 64) void edge_wave_kernel(
     const int si = lane % D, se0 = (lane / D) * RP;   // scatter: this lane's column and rows
     float ghv[RP];
 #pragma unroll
-    for (int k = 0; k < RP; ++k) ghv[k] = gH[(int64_t)hd_s[se0 + k] * D + si];
-    // with D == 64 a row is the whole wave and its flag is uniform: a scalar branch
-    auto flush_here = [](int flagged) {
-      return (D == 64 ? __builtin_amdgcn_readfirstlane(flagged) : flagged) < 0;
-    };
+    for (int k = 0; k < RP; ++k) {
+      const int hk = D == 64 ? __builtin_amdgcn_readfirstlane(hd_s[se0 + k]) : hd_s[se0 + k];   // uniform when a row is a wave
+      ghv[k] = gH[(int64_t)hk * D + si];
+    }
     // P[e][i] = sum_c G[e][c] W_r[c][i] for G = grad_a (tails), then grad_b (heads); half hh
     // walks c = (s&7) + 16 (s>>3) + 8 hh, which keeps the two halves of a W_r read in
     // different LDS banks.  Then P goes back to the same buffer as [e][i] and its rows are
@@ -2151,14 +2150,18 @@ __global__ __launch_bounds__(kEdgeWaves * 64) void edge_wave_kernel(
             val[k] = fmaf(pi_s[se0 + k0 + k], ghv[k0 + k], P_s[(se0 + k0 + k) * LD + si]);
           } else {
             node[k] = hr_s[se0 + k0 + k];
-            val[k] = P_s[hp_s[se0 + k0 + k] * LD + si];
+            const int pk = D == 64 ? __builtin_amdgcn_readfirstlane(hp_s[se0 + k0 + k]) : hp_s[se0 + k0 + k];
+            val[k] = P_s[pk * LD + si];
           }
         }
 #pragma unroll
         for (int k = 0; k < RB; ++k) {
           run += val[k];
-          if (flush_here(node[k])) {
-            sink_add<D>(sink, node[k], si, run);
+          // (D == 64: the row's node is the same in every lane; as a scalar it keeps the
+          // address arithmetic and the heavy-node lookup off the vector unit)
+          const int nk = D == 64 ? __builtin_amdgcn_readfirstlane(node[k]) : node[k];
+          if (nk < 0) {
+            sink_add<D>(sink, nk, si, run);
             run = 0.f;
           }
         }

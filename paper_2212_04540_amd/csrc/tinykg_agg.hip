@@ -860,8 +860,44 @@ __device__ __forceinline__ void softmax_stats(const float* __restrict__ s, int e
   for (int i = lane; i < deg; i += 64) m = fmaxf(m, s[e0 + i]);
   m = wave_max(m);
   float zs = 0.f;
-  for (int i = lane; i < deg; i += 64) zs += expf(s[e0 + i] - m);
+  for (int i = lane; i < deg; i += 64) zs += __expf(s[e0 + i] - m);
   z = wave_sum(zs);
+}
+
+// Softmax weights of a short neighbourhood (at most kSlotDegree edges) owned by a slot of LPR
+// lanes: lane li computes the weights of edges li, li + LPR, ... ONCE (one exponential per edge
+// and one reciprocal per lane instead of one of each per edge and lane); slot_weight hands
+// edge j's weight to every lane of the slot.  exp through the hardware exp2 unit: relative
+// error about 1e-7 (1 + |x|) on a weight exp(x), x <= 0.
+constexpr int kSlotDegree = 16;
+template <int LPR>
+constexpr int kSlotWeights = (kSlotDegree + LPR - 1) / LPR;
+
+template <int LPR>
+__device__ __forceinline__ void slot_softmax(const float* __restrict__ s, int e0, int ds, int li,
+                                             float (&pw)[kSlotWeights<LPR>]) {
+  float sc[kSlotWeights<LPR>];
+  float m = -INFINITY;
+#pragma unroll
+  for (int q = 0; q < kSlotWeights<LPR>; ++q) {
+    const int j = li + q * LPR;
+    sc[q] = j < ds ? s[e0 + j] : -INFINITY;
+    m = fmaxf(m, sc[q]);
+  }
+  m = slot_max<LPR>(m);
+  if (ds == 0) m = 0.f;
+  float z = 0.f;
+#pragma unroll
+  for (int q = 0; q < kSlotWeights<LPR>; ++q) { pw[q] = __expf(sc[q] - m); z += pw[q]; }   // exp(-inf) = 0
+  z = slot_sum<LPR>(z);
+  const float inv = ds == 0 ? 0.f : 1.0f / z;
+#pragma unroll
+  for (int q = 0; q < kSlotWeights<LPR>; ++q) pw[q] *= inv;
+}
+
+template <int LPR>
+__device__ __forceinline__ float slot_weight(const float (&pw)[kSlotWeights<LPR>], int j, int lane) {
+  return __shfl(pw[j / LPR], (lane & ~(LPR - 1)) | (j % LPR));
 }
 
 // The per-head kernels take 64 / LPR consecutive heads per wave and step (LPR = D / 4 lanes
@@ -870,7 +906,6 @@ __device__ __forceinline__ void softmax_stats(const float* __restrict__ s, int e
 // knowledge graph is around ten -- advance side by side and pay the per-head latencies
 // (row pointers, statistics, dependent gathers) together.  Heads between kSlotDegree and
 // kHeavyDegree are then taken one at a time by the whole wave, 64 / LPR edges per step.
-constexpr int kSlotDegree = 16;
 
 template <int D, int BITS>
 __global__ __launch_bounds__(kThreads) void attend_fwd_kernel(Source src,
@@ -891,30 +926,21 @@ __global__ __launch_bounds__(kThreads) void attend_fwd_kernel(Source src,
     // ---- short neighbourhoods: one slot per head
     {
       const int ds = small ? deg : 0;
-      float m = -INFINITY;
-      for (int j = li; j < ds; j += LPR) m = fmaxf(m, s[e0 + j]);
-      m = slot_max<LPR>(m);
-      float z = 0.f;
-      for (int j = li; j < ds; j += LPR) z += expf(s[e0 + j] - m);
-      z = slot_sum<LPR>(z);
-      if (ds == 0) { m = 0.f; z = 1.f; }
+      float pw[kSlotWeights<LPR>];
+      slot_softmax<LPR>(s, e0, ds, li, pw);
       float ax = 0.f, ay = 0.f, az = 0.f, aw = 0.f;
+#pragma unroll
       for (int j0 = 0; j0 < kSlotDegree; j0 += 4) {
         if (__builtin_amdgcn_ballot_w64(j0 < ds) == 0) break;
         int t[4];
-        float sc[4];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {      // unused places read node 0 with weight exp(-inf) = 0
-          const bool on = j0 + u < ds;
-          t[u] = on ? h_tail[e0 + j0 + u] : 0;
-          sc[u] = on ? s[e0 + j0 + u] : -INFINITY;
-        }
+        for (int u = 0; u < 4; ++u) t[u] = j0 + u < ds ? h_tail[e0 + j0 + u] : 0;   // unused places: node 0, weight 0
         float4 x[4];
 #pragma unroll
         for (int u = 0; u < 4; ++u) x[u] = fetch_chunk<BITS>(src, (int64_t)t[u] * LPR + li);
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
-          const float p = expf(sc[u] - m) / z;
+          const float p = slot_weight<LPR>(pw, j0 + u, lane);
           ax = fmaf(p, x[u].x, ax); ay = fmaf(p, x[u].y, ay);
           az = fmaf(p, x[u].z, az); aw = fmaf(p, x[u].w, aw);
         }
@@ -937,7 +963,7 @@ __global__ __launch_bounds__(kThreads) void attend_fwd_kernel(Source src,
       for (int base = 0; base < degw; base += ES) {
         const int j = base + sub;
         if (j < degw) {
-          const float p = expf(s[e0w + j] - m) / z;
+          const float p = __expf(s[e0w + j] - m) * (1.0f / z);
           const float4 x = fetch_chunk<BITS>(src, (int64_t)h_tail[e0w + j] * LPR + li);
           ax = fmaf(p, x.x, ax); ay = fmaf(p, x.y, ay);
           az = fmaf(p, x.z, az); aw = fmaf(p, x.w, aw);
@@ -978,13 +1004,8 @@ __global__ __launch_bounds__(kThreads) void attend_bwd_kernel(Source src, const 
     //      c = sum pi_j g_j is known, so grad_s_j = pi_j (g_j - c) is written once
     {
       const int ds = small ? deg : 0;
-      float m = -INFINITY;
-      for (int j = li; j < ds; j += LPR) m = fmaxf(m, s[e0 + j]);
-      m = slot_max<LPR>(m);
-      float z = 0.f;
-      for (int j = li; j < ds; j += LPR) z += expf(s[e0 + j] - m);
-      z = slot_sum<LPR>(z);
-      if (ds == 0) { m = 0.f; z = 1.f; }
+      float pw[kSlotWeights<LPR>];
+      slot_softmax<LPR>(s, e0, ds, li, pw);
       float4 g4 = make_float4(0.f, 0.f, 0.f, 0.f);
       if (ds > 0) g4 = G4[h * LPR + li];
       float pj[kSlotDegree], gj[kSlotDegree];
@@ -993,13 +1014,8 @@ __global__ __launch_bounds__(kThreads) void attend_bwd_kernel(Source src, const 
       for (int j0 = 0; j0 < kSlotDegree; j0 += 4) {
         const bool any = __builtin_amdgcn_ballot_w64(j0 < ds) != 0;    // wave-uniform
         int t[4];
-        float sc[4];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-          const bool on = any && j0 + u < ds;
-          t[u] = on ? h_tail[e0 + j0 + u] : 0;
-          sc[u] = on ? s[e0 + j0 + u] : -INFINITY;
-        }
+        for (int u = 0; u < 4; ++u) t[u] = (any && j0 + u < ds) ? h_tail[e0 + j0 + u] : 0;
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
           float dot = 0.f;
@@ -1008,7 +1024,7 @@ __global__ __launch_bounds__(kThreads) void attend_bwd_kernel(Source src, const 
             dot = fmaf(g4.x, x.x, fmaf(g4.y, x.y, fmaf(g4.z, x.z, g4.w * x.w)));
             dot = slot_sum<LPR>(dot);
           }
-          const float p = expf(sc[u] - m) / z;     // 0 for unused places
+          const float p = slot_weight<LPR>(pw, j0 + u, lane);     // 0 for unused places
           pj[j0 + u] = p;
           gj[j0 + u] = dot;
           c = fmaf(p, dot, c);
@@ -1035,7 +1051,7 @@ __global__ __launch_bounds__(kThreads) void attend_bwd_kernel(Source src, const 
         const int j = base + sub;
         float dot = 0.f, p = 0.f;
         if (j < degw) {
-          p = expf(s[e0w + j] - m) / z;
+          p = __expf(s[e0w + j] - m) * (1.0f / z);
           const float4 x = fetch_chunk<BITS>(src, (int64_t)h_tail[e0w + j] * LPR + li);
           dot = fmaf(g4.x, x.x, fmaf(g4.y, x.y, fmaf(g4.z, x.z, g4.w * x.w)));
         }

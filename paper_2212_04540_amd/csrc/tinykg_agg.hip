@@ -1885,13 +1885,15 @@ __device__ __forceinline__ void phase_fence() {
   __builtin_amdgcn_sched_barrier(0);
 }
 
+// One span (a run of whole chunks of one relation) by one workgroup; `ch` numbers the span and
+// its slot in the partial-sum buffers.
 template <int D, int BITS>
-__global__ __launch_bounds__(kEdgeWaves * 64) void edge_wave_kernel(
-    Source src, const float* __restrict__ Wr, const float* __restrict__ er,
+__device__ __forceinline__ void edge_wave_span(
+    const int ch, const Source& src, const float* __restrict__ Wr, const float* __restrict__ er,
     const int32_t* __restrict__ r_head, const int32_t* __restrict__ r_tail,
-    const int32_t* __restrict__ r_eid, const uint8_t* __restrict__ r_hperm, ChunkList chunks,
+    const int32_t* __restrict__ r_eid, const uint8_t* __restrict__ r_hperm, const ChunkList& chunks,
     const float* __restrict__ pi, const float* __restrict__ gs, const float* __restrict__ gH,
-    GradSink sink, float* __restrict__ part_Wr, float* __restrict__ part_er) {
+    const GradSink& sink, float* __restrict__ part_Wr, float* __restrict__ part_er) {
   constexpr int LD = D + 4, LPR = D / 4, KH = D / 2, NB = D / 32, NW = kEdgeWaves;
   constexpr int NT = NW * 64, BUF = 32 * LD, REGION = edge_wave_region<D>();
   constexpr int NQ = 64 / D, RP = 32 / NQ;        // scatter: row parts of a wave
@@ -1909,7 +1911,6 @@ __global__ __launch_bounds__(kEdgeWaves * 64) void edge_wave_kernel(
   int* hp_s = hd_s + 32;                           // row of head-order rank k
   int* hr_s = hp_s + 32;                           // head of rank k; sign bit: a head run ends here
 
-  const int ch = blockIdx.x;
   const int rel = chunks.rel[ch], start = chunks.start[ch], count = chunks.count[ch];
   const int r = lane & 31, hh = lane >> 5;
   const int n_wt = (count + 31) >> 5;
@@ -2218,6 +2219,24 @@ __global__ __launch_bounds__(kEdgeWaves * 64) void edge_wave_kernel(
   }
 }
 
+// The persistent form: workgroup w walks the spans [group_ptr[w], group_ptr[w + 1]) -- its
+// share of the relation order, about n_edges / gridDim.x edges -- so W_r is staged and the
+// waves' partial parameter gradients are combined once per span (one or two per workgroup)
+// instead of once per 500-edge chunk, and no workgroup is left over for a last round.
+template <int D, int BITS>
+__global__ __launch_bounds__(kEdgeWaves * 64) void edge_wave_kernel(
+    Source src, const float* __restrict__ Wr, const float* __restrict__ er,
+    const int32_t* __restrict__ r_head, const int32_t* __restrict__ r_tail,
+    const int32_t* __restrict__ r_eid, const uint8_t* __restrict__ r_hperm, ChunkList spans,
+    const int32_t* __restrict__ group_ptr, const float* __restrict__ pi, const float* __restrict__ gs,
+    const float* __restrict__ gH, GradSink sink, float* __restrict__ part_Wr, float* __restrict__ part_er) {
+  const int first = group_ptr[blockIdx.x], last = group_ptr[blockIdx.x + 1];
+  for (int sp = first; sp < last; ++sp) {
+    if (sp != first) __syncthreads();   // the previous span's combination has read the waves' LDS regions
+    edge_wave_span<D, BITS>(sp, src, Wr, er, r_head, r_tail, r_eid, r_hperm, spans, pi, gs, gH, sink, part_Wr, part_er);
+  }
+}
+
 // ------------------------------------------------------------- host helpers ----
 size_t align256(size_t b) { return (b + 255) & ~(size_t)255; }
 
@@ -2508,8 +2527,10 @@ tinykg_status bwd_impl(const tinykg_graph* g, const tinykg_saved* sv, const floa
       auto kern = edge_wave_kernel<D, BITS>;
       if ((rc = set_smem(kern, smem)) != TINYKG_OK) return rc;
       ProfileScope prof("edge_bwd_kernel", st);
-      hipLaunchKernelGGL(kern, dim3(g->n_chunks), dim3(kEdgeWaves * 64), smem, st, srcE, Wr, er,
-                         g->r_head, g->r_tail, g->r_eid, g->r_hperm32, cl, pi, gs, gH, sink, pWr, per);
+      const ChunkList spans{g->span_rel, g->span_start, g->span_count};
+      hipLaunchKernelGGL(kern, dim3(g->n_span_groups), dim3(kEdgeWaves * 64), smem, st, srcE, Wr, er,
+                         g->r_head, g->r_tail, g->r_eid, g->r_hperm32, spans, g->span_group_ptr, pi, gs, gH,
+                         sink, pWr, per);
     } else {
       const size_t smem = (size_t)(D * LD + 4 * TE * LD + D + 6 * TE) * 4;
       auto kern = edge_bwd_kernel<D, TE, BITS>;
@@ -2524,8 +2545,10 @@ tinykg_status bwd_impl(const tinykg_graph* g, const tinykg_saved* sv, const floa
   {
     const bool edge_grads = !uniform && g->n_rel > 0;
     const ReduceJob jW{pW, nullptr, dense_blocks, d_out * D, (d_out * D + 63) / 64, 1, gW};
-    const ReduceJob jWr{pWr, g->rel_chunk_ptr, 0, D * D, edge_grads ? (D * D + 63) / 64 : 0, g->n_rel, gWr};
-    const ReduceJob jer{per, g->rel_chunk_ptr, 0, D, edge_grads ? (D + 63) / 64 : 0, g->n_rel, ger};
+    // (partial sums per span from the persistent kernel, per chunk from the d = 128 one)
+    const int32_t* part_ptr = D <= 64 ? g->rel_span_ptr : g->rel_chunk_ptr;
+    const ReduceJob jWr{pWr, part_ptr, 0, D * D, edge_grads ? (D * D + 63) / 64 : 0, g->n_rel, gWr};
+    const ReduceJob jer{per, part_ptr, 0, D, edge_grads ? (D + 63) / 64 : 0, g->n_rel, ger};
     const HeavyFinish hf{acc, g->acc_node, with_heavy ? n_heavy_elems : 0, D, gE};
     const int gx = std::max(std::max(jW.nx, jWr.nx), std::max(jer.nx, with_heavy ? 64 : 1));
     const int gy = std::max(1, edge_grads ? (int)g->n_rel : 1);

@@ -21,6 +21,16 @@ struct tinykg_graph {
   int32_t* chunk_start = nullptr;    // [n_chunks] first relation-order position
   int32_t* chunk_count = nullptr;    // [n_chunks]
   int32_t* rel_chunk_ptr = nullptr;  // [n_rel + 1] chunks of relation r: [ptr[r], ptr[r+1])
+  // spans: the relation order cut at chunk boundaries into one piece of about equal edge
+  // count per compute unit, each piece cut again where the relation changes -- what one
+  // persistent workgroup of the edge-level backward kernel walks (a span is a run of whole
+  // chunks of one relation, so its 32-edge tiles are the chunks' tiles)
+  int32_t n_span_groups = 0, n_spans = 0;
+  int32_t* span_group_ptr = nullptr; // [n_span_groups + 1] spans of workgroup w: [ptr[w], ptr[w+1])
+  int32_t* span_rel = nullptr;       // [n_spans]
+  int32_t* span_start = nullptr;     // [n_spans] first relation-order position
+  int32_t* span_count = nullptr;     // [n_spans]
+  int32_t* rel_span_ptr = nullptr;   // [n_rel + 1] spans of relation r: [ptr[r], ptr[r+1])
   // heads with more than kHeavyDegree out-edges are cut into segments of that many
   // head-order edges, so that one wave never walks a 10^5-edge neighbourhood alone
   int32_t n_heavy = 0, n_hseg = 0;

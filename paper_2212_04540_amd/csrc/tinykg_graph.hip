@@ -42,7 +42,8 @@ void release(tinykg_graph* g) {
   if (!g) return;
   void* ptrs[] = {g->rowptr, g->h_tail, g->r_head, g->r_tail, g->r_eid, g->chunk_rel,
                   g->chunk_start, g->chunk_count, g->rel_chunk_ptr, g->heavy_head, g->heavy_seg_ptr,
-                  g->hseg_q, g->hseg_e0, g->hseg_cnt, g->r_hperm32, g->acc_slot, g->acc_node};
+                  g->hseg_q, g->hseg_e0, g->hseg_cnt, g->r_hperm32, g->acc_slot, g->acc_node,
+                  g->span_group_ptr, g->span_rel, g->span_start, g->span_count, g->rel_span_ptr};
   for (void* p : ptrs)
     if (p) (void)hipFree(p);
   delete g;
@@ -127,6 +128,33 @@ tinykg_status tinykg_graph_create(int64_t n_nodes, int32_t n_rel, int64_t n_edge
   }
   rel_chunk_ptr[(size_t)n_rel] = (int32_t)chunk_rel.size();
 
+  // spans of the persistent edge-level kernel (one group per compute unit)
+  std::vector<int32_t> span_group_ptr(1, 0), span_rel, span_start, span_count, rel_span_ptr((size_t)n_rel + 1, 0);
+  {
+    const int64_t n_groups = std::max<int64_t>(1, std::min<int64_t>(num_cus(), (int64_t)chunk_rel.size()));
+    int64_t cur_group = 0, last_group = -1;
+    for (size_t c = 0; c < chunk_rel.size(); ++c) {
+      const int64_t mid = (int64_t)chunk_start[c] + chunk_count[c] / 2;
+      const int64_t grp = std::min<int64_t>(n_groups - 1, mid * n_groups / std::max<int64_t>(n_edges, 1));
+      while (cur_group < grp) { span_group_ptr.push_back((int32_t)span_rel.size()); ++cur_group; }
+      if (grp == last_group && span_rel.back() == chunk_rel[c]) {
+        span_count.back() += chunk_count[c];
+      } else {
+        span_rel.push_back(chunk_rel[c]);
+        span_start.push_back(chunk_start[c]);
+        span_count.push_back(chunk_count[c]);
+      }
+      last_group = grp;
+    }
+    while ((int64_t)span_group_ptr.size() < n_groups + 1) span_group_ptr.push_back((int32_t)span_rel.size());
+    size_t sp = 0;
+    for (int32_t r = 0; r < n_rel; ++r) {
+      while (sp < span_rel.size() && span_rel[sp] < r) ++sp;
+      rel_span_ptr[(size_t)r] = (int32_t)sp;
+    }
+    rel_span_ptr[(size_t)n_rel] = (int32_t)span_rel.size();
+  }
+
   // heavy heads and their segments
   std::vector<int32_t> heavy_head, heavy_seg_ptr(1, 0), hseg_q, hseg_e0, hseg_cnt;
   for (int64_t h = 0; h < n_nodes; ++h) {
@@ -182,6 +210,13 @@ tinykg_status tinykg_graph_create(int64_t n_nodes, int32_t n_rel, int64_t n_edge
   if (st == TINYKG_OK) st = upload(chunk_start, &g->chunk_start);
   if (st == TINYKG_OK) st = upload(chunk_count, &g->chunk_count);
   if (st == TINYKG_OK) st = upload(rel_chunk_ptr, &g->rel_chunk_ptr);
+  g->n_span_groups = (int32_t)span_group_ptr.size() - 1;
+  g->n_spans = (int32_t)span_rel.size();
+  if (st == TINYKG_OK) st = upload(span_group_ptr, &g->span_group_ptr);
+  if (st == TINYKG_OK) st = upload(span_rel, &g->span_rel);
+  if (st == TINYKG_OK) st = upload(span_start, &g->span_start);
+  if (st == TINYKG_OK) st = upload(span_count, &g->span_count);
+  if (st == TINYKG_OK) st = upload(rel_span_ptr, &g->rel_span_ptr);
   g->n_heavy = (int32_t)heavy_head.size();
   for (int64_t i = 0; i < n_nodes; ++i)
     g->max_out_degree = std::max(g->max_out_degree, rowptr[(size_t)i + 1] - rowptr[(size_t)i]);

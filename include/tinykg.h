@@ -150,7 +150,12 @@ size_t tinykg_kg_aggregate_workspace_bytes(const tinykg_graph* g, int d_in, int 
  *   E [n_nodes, d_in], Wr [n_rel, d_rel, d_in], er [n_rel, d_rel], W [d_out, d_in]
  *   E_out [n_nodes, d_out]
  * d_in == d_rel in {32, 64, 128}; d_out a multiple of 16 up to 128; n_nodes*d_in
- * a multiple of `group` (else ERR_UNSUPPORTED / ERR_SHAPE). */
+ * a multiple of `group` (else ERR_UNSUPPORTED / ERR_SHAPE).
+ * Arithmetic: fp32 in, fp32 out, fp32 (or wider) accumulation.  The projections W_r e are
+ * formed on the matrix cores from exact three-way bfloat16 splits of their fp32 operands
+ * (all piece products down to 2^-23 of a term are kept), so they agree with an fp32
+ * evaluation to fp32's own rounding level; sums over many edges are reproducible to
+ * rounding, not bitwise (atomic order), everything else is deterministic. */
 tinykg_status tinykg_kg_aggregate_fwd(const tinykg_graph* g, const float* E, const float* Wr,
                                       const float* er, const float* W, int d_in, int d_rel,
                                       int d_out, float leaky_slope, int bits, int group,

@@ -1897,7 +1897,6 @@ __device__ __forceinline__ void edge_wave_span(
   constexpr int LD = D + 4, LPR = D / 4, KH = D / 2, NB = D / 32, NW = kEdgeWaves;
   constexpr int NT = NW * 64, BUF = 32 * LD, REGION = edge_wave_region<D>();
   constexpr int NQ = 64 / D, RP = 32 / NQ;        // scatter: row parts of a wave
-  constexpr bool PF = BITS != 32;                 // prefetch the next tile's rows
   float* Wr_s = reinterpret_cast<float*>(smem_raw);
   float* er_s = Wr_s + D * LD;
   float* regions = er_s + D;
@@ -1935,11 +1934,6 @@ __device__ __forceinline__ void edge_wave_span(
     if (e_nx >= 0) { g_ld = gs[e_nx]; p_ld = pi[e_nx]; }
     t_ld = t_nx; h_ld = h_nx; hp_ld = hp_nx;
   };
-  if (PF) {
-    load_idx(wt);
-    load_rows();
-    if (wt + NW < n_wt) load_idx(wt + NW);
-  }
 
   const float4* Wg = reinterpret_cast<const float4*>(Wr + (size_t)rel * D * D);
   for (int q = tid; q < D * LPR; q += NT)
@@ -1955,7 +1949,11 @@ __device__ __forceinline__ void edge_wave_span(
   for (int j = 0; j < NB * NB; ++j) accW[j] = floatx16{0};
 
   for (; wt < n_wt; wt += NW) {
-    if (!PF) { load_idx(wt); load_rows(); }
+    // (fetching the next tile's rows a tile ahead gained nothing once the workgroups became
+    // persistent -- the second wave of the SIMD covers the latency -- and cost INT8 rows 16 %
+    // through the registers the raw words occupy)
+    load_idx(wt);
+    load_rows();
     const int nrow = min(32, count - wt * 32);
     {
       // where the scatter has to flush its running sums: at the last row of a run of
@@ -1980,10 +1978,6 @@ __device__ __forceinline__ void edge_wave_span(
           make_float4(nt.get(i), nt.get(i + 1), nt.get(i + 2), nt.get(i + 3));
       *reinterpret_cast<float4*>(Y_s + r * LD + hh * KH + i) =
           make_float4(nh.get(i), nh.get(i + 1), nh.get(i + 2), nh.get(i + 3));
-    }
-    if (PF && wt + NW < n_wt) {         // rows of the wave's next tile: in flight during the MFMAs
-      load_rows();
-      if (wt + 2 * NW < n_wt) load_idx(wt + 2 * NW);
     }
     phase_fence();
 

@@ -468,8 +468,8 @@ def stack_workload(a, which):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-compressor", action="store_true")
     ap.add_argument("--workload", choices=["config1", "config2", "config3", "config4", "uniform", "batchnorm", "maxpool"], default="config1",

@@ -1628,8 +1628,9 @@ __global__ __launch_bounds__(kThreads) void uniform_bwd_kernel(
 // tile, separated by workgroup barriers, and who does what:
 //   stage: rows (prefetched raw one tile ahead, node ids two tiles ahead), per-edge scalars
 //          and scatter flags (first wave)
-//   1:     waves 0-3: a for channel block w;  waves 4-7: b for channel block w - 4, then
-//          grad_a = gs tanh(b) and f = gs (1 - tanh(b)^2) to LDS
+//   1:     waves 0-3: a for channel block w;  waves 4-7: b for channel block w - 4 (bf16
+//          matrix cores, operands split on the fly), then grad_a = gs tanh(b) and
+//          f = gs (1 - tanh(b)^2) to LDS
 //   1':    waves 0-3: grad_b = a * f, in place in LDS
 //   2:     Pt (waves 0-3) / Ph (waves 4-7) for one column block each; every wave two of the
 //          sixteen grad_W_r blocks
@@ -1753,8 +1754,25 @@ __global__ __launch_bounds__(kCoopWaves * 64) void edge_bwd_kernel(
     }
     __syncthreads();
     // ---- 1. a (waves 0-3) or b (waves 4-7) of channel block blk4: [c][e], lane = edge
+    //      on the bf16 matrix cores: both operands are read as fp32, eight k-values at a time,
+    //      and split into their three bfloat16 pieces in registers (see split3x8)
     floatx16 acc1 = {0};
-    mfma_block<KCONT, KCONT>(Wr_s + blk4 * 32 * LD, LD, b_side ? Eh_s : Et_s, LD, D, acc1);
+    {
+      const float* wrow = Wr_s + (blk4 * 32 + (lane & 31)) * LD + (lane >> 5) * 8;
+      const float* xrow = (b_side ? Eh_s : Et_s) + (lane & 31) * LD + (lane >> 5) * 8;
+      auto frag = [](const float* p, Bf16Frag& h, Bf16Frag& m, Bf16Frag& l) {
+        const float4 lo4 = *reinterpret_cast<const float4*>(p), hi4 = *reinterpret_cast<const float4*>(p + 4);
+        const float x[8] = {lo4.x, lo4.y, lo4.z, lo4.w, hi4.x, hi4.y, hi4.z, hi4.w};
+        split3x8(x, h, m, l);
+      };
+#pragma unroll
+      for (int m = 0; m < D / 16; ++m) {
+        Bf16Frag wh, wm, wl, xh, xm, xl;
+        frag(wrow + 16 * m, wh, wm, wl);
+        frag(xrow + 16 * m, xh, xm, xl);
+        mfma_split(wh, wm, wl, xh, xm, xl, acc1);
+      }
+    }
     const int e1 = lane & 31;
     if (b_side) {
       const float g = gs_s[e1];

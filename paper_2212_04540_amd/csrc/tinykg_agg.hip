@@ -652,33 +652,51 @@ __device__ __forceinline__ void store_split4(const float4& v, uint16_t* dst, int
                                                                  __builtin_amdgcn_perm(lb[3], lb[2], 0x07060302u));
 }
 
-// score_kernel on the bf16 matrix cores (d = 128): W_r and the tile's rows are split into
-// their three bfloat16 pieces as they are staged (once per element, whatever the number of
-// waves that multiply them); a wave then reads ready 128-bit fragments.  k-step m of half
-// hh covers k = 16 m + 8 hh + 0..7 on both operands.
+// The four integer codes of a compressed chunk as bfloat16 values (exact), to LDS.
+template <int BITS>
+__device__ __forceinline__ void store_codes4(const RawChunk<BITS>& c, uint16_t* dst) {
+  constexpr uint32_t B = (BITS == 32) ? 0u : ((1u << (BITS & 31)) - 1u);
+  constexpr int SH = BITS & 31;
+  const uint32_t w = c.w[0];
+  const uint32_t f0 = __float_as_uint((float)(w & B)), f1 = __float_as_uint((float)((w >> SH) & B));
+  const uint32_t f2 = __float_as_uint((float)((w >> (2 * SH)) & B)), f3 = __float_as_uint((float)((w >> (3 * SH)) & B));
+  *reinterpret_cast<uint2*>(dst) = make_uint2(__builtin_amdgcn_perm(f1, f0, 0x07060302u),
+                                              __builtin_amdgcn_perm(f3, f2, 0x07060302u));
+}
+
+// score_kernel on the bf16 matrix cores (d = 128).  Wave w of the four owns channel block w
+// for the whole chunk and keeps its 32 x 128 block of W_r, split into the three bfloat16
+// pieces, in REGISTERS (96 per lane: one wave per SIMD and workgroup, so the registers are
+// there, and LDS -- which three pieces of the whole W_r would fill to two thirds -- holds only
+// the tile).  That leaves room for two workgroups per compute unit, whose barrier-separated
+// phases (stage the tile / multiply) overlap each other.  The tile's rows are split as they
+// are staged (once per element, whatever the number of waves that multiply them); a wave then
+// reads ready 128-bit fragments.  k-step m of half hh covers k = 16 m + 8 hh + 0..7 on both
+// operands.
 // (CODES: as in score_split_kernel -- the tile holds one bfloat16 matrix of codes per side and
 // the rows' (Z, scale) pairs instead of three pieces of dequantised values)
 template <int D, int TE, int BITS, bool CODES>
-__global__ __launch_bounds__(kThreads) void score_coop_split_kernel(Source src, const float* __restrict__ Wr,
-                                                                    const float* __restrict__ er,
-                                                                    const int32_t* __restrict__ r_head,
-                                                                    const int32_t* __restrict__ r_tail,
-                                                                    const int32_t* __restrict__ r_eid,
-                                                                    ChunkList chunks, float* __restrict__ s_out) {
-  constexpr int LDW = D + 8, LPR = D / 4, NCB = D / 32, NEB = TE / 32, NP = NCB * 2;
+__global__ __launch_bounds__(kThreads, 2) void score_coop_split_kernel(Source src, const float* __restrict__ Wr,
+                                                                       const float* __restrict__ er,
+                                                                       const int32_t* __restrict__ r_head,
+                                                                       const int32_t* __restrict__ r_tail,
+                                                                       const int32_t* __restrict__ r_eid,
+                                                                       ChunkList chunks, float* __restrict__ s_out) {
+  constexpr int LDW = D + 8, LPR = D / 4, NCB = D / 32, NP = NCB * 2, NM = D / 16;
   constexpr int CPT = TE * LPR / kThreads, RSTEP = kThreads / LPR;
-  constexpr int WP = D * LDW, TP = TE * LDW;      // halves per piece
+  constexpr int TP = TE * LDW;                    // halves per piece
+  constexpr int NPIECE = CODES ? 1 : 3;
+  static_assert(TE == 32 && NCB * 64 == kThreads, "one 32 x 32 block of a and of b per wave and tile");
   static_assert(TE * LPR % kThreads == 0 && kThreads % LPR == 0, "tile does not split evenly");
-  uint16_t* W_s = reinterpret_cast<uint16_t*>(smem_raw);        // [3][D][LDW]
-  uint16_t* Et_s = W_s + 3 * WP;                                 // [3][TE][LDW]
-  uint16_t* Eh_s = Et_s + 3 * TP;
-  float* er_s = reinterpret_cast<float*>(Eh_s + 3 * TP);
+  uint16_t* Et_s = reinterpret_cast<uint16_t*>(smem_raw);        // [NPIECE][TE][LDW]
+  uint16_t* Eh_s = Et_s + NPIECE * TP;
+  float* er_s = reinterpret_cast<float*>(Eh_s + NPIECE * TP);
   float* part = er_s + D;  // [NP][TE]
   float* wsum_s = part + NP * TE;      // [D] row sums of W_r           (CODES)
   float* zs_s = wsum_s + D;            // [4][TE] Z_t, scale_t, Z_h, scale_h of the tile's rows (CODES)
   static_assert(!CODES || BITS != 32, "codes exist for compressed rows only");
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63, cb = tid >> 6;
   const int ch = blockIdx.x;
   const int r = chunks.rel[ch], start = chunks.start[ch], count = chunks.count[ch];
   const int row0 = tid / LPR, li = tid % LPR;
@@ -704,7 +722,18 @@ __global__ __launch_bounds__(kThreads) void score_coop_split_kernel(Source src, 
   load_rows();
   load_ids(TE);
 
-  stage_split_matrix<D>(Wr + (size_t)r * D * D, W_s, tid, kThreads);
+  // this wave's block of W_r: row cb * 32 + (lane & 31), k-values 16 m + 8 (lane >> 5) + 0..7
+  Bf16Frag wh[NM], wm[NM], wl[NM];
+  {
+    const float* wrow = Wr + ((size_t)r * D + cb * 32 + (lane & 31)) * D + (lane >> 5) * 8;
+#pragma unroll
+    for (int m = 0; m < NM; ++m) {
+      const float4 lo4 = *reinterpret_cast<const float4*>(wrow + 16 * m);
+      const float4 hi4 = *reinterpret_cast<const float4*>(wrow + 16 * m + 4);
+      const float x[8] = {lo4.x, lo4.y, lo4.z, lo4.w, hi4.x, hi4.y, hi4.z, hi4.w};
+      split3x8(x, wh[m], wm[m], wl[m]);
+    }
+  }
   for (int c = tid; c < D; c += kThreads) er_s[c] = er[(size_t)r * D + c];
   if (CODES) {
     for (int c = tid; c < D; c += kThreads) {
@@ -714,15 +743,6 @@ __global__ __launch_bounds__(kThreads) void score_coop_split_kernel(Source src, 
       wsum_s[c] = (float)sum;
     }
   }
-  auto store_codes4 = [](const RawChunk<BITS>& c, uint16_t* dst) {   // four codes as bfloat16 values (exact)
-    constexpr uint32_t B = (BITS == 32) ? 0u : ((1u << (BITS & 31)) - 1u);
-    constexpr int SH = BITS & 31;
-    const uint32_t w = c.w[0];
-    const uint32_t f0 = __float_as_uint((float)(w & B)), f1 = __float_as_uint((float)((w >> SH) & B));
-    const uint32_t f2 = __float_as_uint((float)((w >> (2 * SH)) & B)), f3 = __float_as_uint((float)((w >> (3 * SH)) & B));
-    *reinterpret_cast<uint2*>(dst) = make_uint2(__builtin_amdgcn_perm(f1, f0, 0x07060302u),
-                                                __builtin_amdgcn_perm(f3, f2, 0x07060302u));
-  };
 
   for (int t0 = 0; t0 < count; t0 += TE) {
     const int nrow = min(TE, count - t0);
@@ -746,21 +766,18 @@ __global__ __launch_bounds__(kThreads) void score_coop_split_kernel(Source src, 
       load_ids(t0 + 2 * TE);
     }
     __syncthreads();
-    for (int blk = wave; blk < NCB * NEB; blk += 4) {
-      const int cb = blk % NCB, eb = blk / NCB;
+    {
       floatx16 accA = {0}, accB = {0};
       const int fr = (lane & 31) * LDW + (lane >> 5) * 8;
-      const uint16_t* wp = W_s + cb * 32 * LDW + fr;
-      const uint16_t* tp = Et_s + eb * 32 * LDW + fr;
-      const uint16_t* hp = Eh_s + eb * 32 * LDW + fr;
+      const uint16_t* tp = Et_s + fr;
+      const uint16_t* hp = Eh_s + fr;
       auto ld = [](const uint16_t* p) { Bf16Frag f; *reinterpret_cast<uint4*>(f.u) = *reinterpret_cast<const uint4*>(p); return f; };
 #pragma unroll
-      for (int m = 0; m < D / 16; ++m) {
-        const Bf16Frag wh = ld(wp + 16 * m), wm = ld(wp + WP + 16 * m), wl = ld(wp + 2 * WP + 16 * m);
+      for (int m = 0; m < NM; ++m) {
         const Bf16Frag th = ld(tp + 16 * m), hh_ = ld(hp + 16 * m);
 #define TINYKG_SPLIT_STEP(WF, TF, HF)                                                           \
-        accA = __builtin_amdgcn_mfma_f32_32x32x16_bf16(WF.v, TF.v, accA, 0, 0, 0);              \
-        accB = __builtin_amdgcn_mfma_f32_32x32x16_bf16(WF.v, HF.v, accB, 0, 0, 0);
+        accA = __builtin_amdgcn_mfma_f32_32x32x16_bf16(WF[m].v, TF.v, accA, 0, 0, 0);           \
+        accB = __builtin_amdgcn_mfma_f32_32x32x16_bf16(WF[m].v, HF.v, accB, 0, 0, 0);
         if constexpr (CODES) {
           TINYKG_SPLIT_STEP(wl, th, hh_)
           TINYKG_SPLIT_STEP(wm, th, hh_)
@@ -780,7 +797,7 @@ __global__ __launch_bounds__(kThreads) void score_coop_split_kernel(Source src, 
       float p = 0.f;
       float zt = 0.f, st = 0.f, zh = 0.f, sh = 0.f;
       if constexpr (CODES) {
-        const int e = eb * 32 + (lane & 31);
+        const int e = lane & 31;
         zt = zs_s[e]; st = zs_s[TE + e]; zh = zs_s[2 * TE + e]; sh = zs_s[3 * TE + e];
       }
 #pragma unroll
@@ -794,7 +811,7 @@ __global__ __launch_bounds__(kThreads) void score_coop_split_kernel(Source src, 
           p = fmaf(accA[v], fast_tanh(accB[v] + er_s[c]), p);
         }
       }
-      part[(cb * 2 + (lane >> 5)) * TE + eb * 32 + (lane & 31)] = p;
+      part[(cb * 2 + (lane >> 5)) * TE + (lane & 31)] = p;
     }
     __syncthreads();
     if (tid < nrow) {
@@ -2344,10 +2361,14 @@ tinykg_status launch_score(const tinykg_graph* g, Source src, const float* Wr, c
     const size_t smem = (size_t)(D * LD + 2 * TE * LD + D + (D / 32) * 2 * TE) * 4;
     auto kern = score_kernel<D, TE, BITS>;
 #else
-    const size_t smem = (size_t)3 * (D + 2 * TE) * (D + 8) * 2 + (size_t)(2 * D + (D / 32) * 2 * TE + 4 * TE) * 4;
+    // (tile: three bfloat16 pieces per side, or one matrix of codes per side)
+    size_t smem = (size_t)3 * 2 * TE * (D + 8) * 2 + (size_t)(2 * D + (D / 32) * 2 * TE + 4 * TE) * 4;
     auto kern = score_coop_split_kernel<D, TE, BITS, false>;
     if constexpr (BITS != 32) {
-      if ((4 << src.group_chunks_log2) >= D) kern = score_coop_split_kernel<D, TE, BITS, true>;
+      if ((4 << src.group_chunks_log2) >= D) {
+        kern = score_coop_split_kernel<D, TE, BITS, true>;
+        smem = (size_t)2 * TE * (D + 8) * 2 + (size_t)(2 * D + (D / 32) * 2 * TE + 4 * TE) * 4;
+      }
     }
 #endif
     tinykg_status rc = set_smem(kern, smem);

@@ -484,6 +484,8 @@ __device__ __forceinline__ void stage_split_matrix(const float* __restrict__ W, 
   }
 }
 
+constexpr int kScoreWaves = 4;
+
 // score_wave_kernel with the two projections on the bf16 matrix cores.  Lane l = (r, hh)
 // holds elements [32 hh, +D/2) of both rows of edge r; MFMA number m of a row block takes
 // its elements [8 m, +8) -- the same permutation of the contraction index on the W_r side.
@@ -492,7 +494,7 @@ __device__ __forceinline__ void stage_split_matrix(const float* __restrict__ W, 
 // bfloat16 values, so the product needs three piece products instead of six and no splitting or
 // dequantising of the rows at all; the affine part is applied to the 32 x 32 results.
 template <int D, int BITS, bool CODES>
-__global__ __launch_bounds__(kThreads) void score_split_kernel(Source src, const float* __restrict__ Wr,
+__global__ __launch_bounds__(kScoreWaves * 64) void score_split_kernel(Source src, const float* __restrict__ Wr,
                                                                const float* __restrict__ er,
                                                                const int32_t* __restrict__ r_head,
                                                                const int32_t* __restrict__ r_tail,
@@ -517,16 +519,11 @@ __global__ __launch_bounds__(kThreads) void score_split_kernel(Source src, const
     if (row < count) { const int pos = start + row; t_nx = r_tail[pos]; h_nx = r_head[pos]; e_nx = r_eid[pos]; }
   };
   HalfRow<D, BITS> nt, nh;
-  load_idx(wt);
-  nt.load(src, t_nx, hh);
-  nh.load(src, h_nx, hh);
-  int e_cur = e_nx;
-  if (wt + 4 < n_wt) load_idx(wt + 4);
 
-  stage_split_matrix<D>(Wr + (size_t)rel * D * D, Wp, tid, kThreads);
-  for (int c = tid; c < D; c += kThreads) er_s[c] = er[(size_t)rel * D + c];
+  stage_split_matrix<D>(Wr + (size_t)rel * D * D, Wp, tid, kScoreWaves * 64);
+  for (int c = tid; c < D; c += kScoreWaves * 64) er_s[c] = er[(size_t)rel * D + c];
   if (CODES) {
-    for (int c = tid; c < D; c += kThreads) {
+    for (int c = tid; c < D; c += kScoreWaves * 64) {
       const float4* row = reinterpret_cast<const float4*>(Wr + ((size_t)rel * D + c) * D);
       double sum = 0.0;
       for (int q = 0; q < D / 4; ++q) { const float4 w = row[q]; sum += (double)w.x + (double)w.y + (double)w.z + (double)w.w; }
@@ -536,7 +533,12 @@ __global__ __launch_bounds__(kThreads) void score_split_kernel(Source src, const
   __syncthreads();
   if (wt >= n_wt) return;
 
-  for (; wt < n_wt; wt += 4) {
+  for (; wt < n_wt; wt += kScoreWaves) {
+    // (rows fetched here, not a tile ahead: the raw words of a prefetched tile cost a wave per
+    // SIMD in registers, and the other waves cover the latency better than the prefetch did)
+    load_idx(wt);
+    nt.load(src, t_nx, hh);
+    nh.load(src, h_nx, hh);
     float tv[CODES ? 1 : KH], hv[CODES ? 1 : KH];
     Bf16Frag tc[CODES ? NM : 1], hc[CODES ? NM : 1];
     float zt = 0.f, st = 0.f, zh = 0.f, sh = 0.f;
@@ -556,13 +558,7 @@ __global__ __launch_bounds__(kThreads) void score_split_kernel(Source src, const
 #pragma unroll
       for (int i = 0; i < KH; ++i) { tv[i] = nt.get(i); hv[i] = nh.get(i); }
     }
-    const int eid = e_cur;
-    if (wt + 4 < n_wt) {
-      nt.load(src, t_nx, hh);
-      nh.load(src, h_nx, hh);
-      e_cur = e_nx;
-      if (wt + 8 < n_wt) load_idx(wt + 8);
-    }
+    const int eid = e_nx;
     floatx16 accA[NCB], accB[NCB];
 #pragma unroll
     for (int cb = 0; cb < NCB; ++cb) {
@@ -2353,7 +2349,7 @@ tinykg_status launch_score(const tinykg_graph* g, Source src, const float* Wr, c
 #endif
     tinykg_status rc = set_smem(kern, smem);
     if (rc != TINYKG_OK) return rc;
-    hipLaunchKernelGGL(kern, dim3(g->n_chunks), dim3(kThreads), smem, st, src, Wr, er, g->r_head,
+    hipLaunchKernelGGL(kern, dim3(g->n_chunks), dim3(kScoreWaves * 64), smem, st, src, Wr, er, g->r_head,
                        g->r_tail, g->r_eid, cl, s);
   } else {
     constexpr int TE = 32;

@@ -50,14 +50,13 @@ __device__ __forceinline__ int acc_row(int v, int lane) {
   return (v & 3) + 4 * (lane >> 5) + 8 * (v >> 2);
 }
 
-// tanh without branches: sign(x) * (1 - 2 / (exp(2|x|) + 1)) on the hardware exp2 / rcp
-// units.  Absolute error below 2e-7 for every x (the subtraction from 1 bounds it by
-// the error of the quotient), which is what the score s = a . tanh(b) and its
-// derivative 1 - tanh^2 need; exp overflow gives exactly +-1.
+// tanh without branches: 1 - 2 / (exp(2x) + 1) on the hardware exp2 / rcp units.  Absolute
+// error below 2e-7 for every x (the subtraction from 1 bounds it by the error of the
+// quotient), which is what the score s = a . tanh(b) and its derivative 1 - tanh^2 need;
+// exp overflow gives exactly 1, underflow exactly -1.
 __device__ __forceinline__ float fast_tanh(float x) {
-  const float e = __builtin_amdgcn_exp2f(fabsf(x) * 2.885390081777927f);   // exp(2|x|)
-  const float t = fmaf(-2.0f, __builtin_amdgcn_rcpf(e + 1.0f), 1.0f);
-  return copysignf(t, x);
+  const float e = __builtin_amdgcn_exp2f(x * 2.885390081777927f);   // exp(2x)
+  return fmaf(-2.0f, __builtin_amdgcn_rcpf(e + 1.0f), 1.0f);
 }
 
 template <int AM, int BM>

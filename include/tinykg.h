@@ -308,6 +308,11 @@ tinykg_status tinykg_batchnorm_bwd(const uint8_t* packed, const float* gmin, con
  * ------------------------------------------------------------------------- */
 /* on != 0: drop earlier records and start recording; on == 0: stop recording. */
 void tinykg_profile_enable(int on);
+/* Restricts recording to the launches reported under `name` (one of the names
+ * tinykg_profile_report prints, e.g. "edge_bwd_kernel"); NULL or "": every launch again.
+ * Bracketing one kernel instead of all keeps the events' own cost (about 4 % of a
+ * one-millisecond step when every launch is bracketed) out of a timed region. */
+void tinykg_profile_select(const char* name);
 /* Waits for the recorded events, then writes one line per kernel name,
  * "<name> <launches> <total_ms>\n", into buf (NUL-terminated, truncated to cap).
  * Returns the number of bytes the full text needs (excluding the NUL). */

@@ -22,7 +22,7 @@ EXPORTS = [
     "tinykg_quantize_ex", "tinykg_quantize_bf16", "tinykg_dequantize", "tinykg_graph_create", "tinykg_graph_destroy",
     "tinykg_graph_num_nodes", "tinykg_graph_num_edges", "tinykg_kg_aggregate_workspace_bytes",
     "tinykg_kg_aggregate_fwd", "tinykg_kg_aggregate_bwd", "tinykg_kg_uniform_fwd",
-    "tinykg_kg_uniform_bwd", "tinykg_profile_enable",
+    "tinykg_kg_uniform_bwd", "tinykg_profile_enable", "tinykg_profile_select",
     "tinykg_profile_report", "tinykg_profile_copy", "tinykg_bpr_loss", "tinykg_bpr_grad",
     "tinykg_gather_rows", "tinykg_scatter_add_rows", "tinykg_fill_zero",
     "tinykg_batchnorm_workspace_bytes", "tinykg_batchnorm_fwd", "tinykg_batchnorm_bwd",
@@ -83,6 +83,8 @@ def lib():
                                                 vp, vp, vp, vp, sz, vp]
         L.tinykg_profile_enable.argtypes = [i32]
         L.tinykg_profile_enable.restype = None
+        L.tinykg_profile_select.argtypes = [C.c_char_p]
+        L.tinykg_profile_select.restype = None
         L.tinykg_profile_report.argtypes = [C.c_char_p, sz]
         L.tinykg_profile_report.restype = sz
         L.tinykg_profile_copy.argtypes = [vp, vp, sz, vp]
@@ -169,6 +171,11 @@ def tinykg_dequantize(packed, gmin, gscale, rows, dim, bits, group, out=None):
 
 def tinykg_profile_enable(on):
     lib().tinykg_profile_enable(1 if on else 0)
+
+
+def tinykg_profile_select(name=None):
+    """Record only the launches reported under `name` (None: every launch)."""
+    lib().tinykg_profile_select(name.encode() if name else None)
 
 
 def tinykg_profile_report():

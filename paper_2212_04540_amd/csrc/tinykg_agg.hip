@@ -1256,23 +1256,33 @@ __global__ __launch_bounds__(kThreads) void heavy_part3_kernel(HeavyList hl, con
 
 // ------------------------------------------------------------- dense stage ----
 // J = H W^T, E' = LeakyReLU(J), mask = [J > 0].  64 nodes per tile.
+// A wave keeps its 32 x D block of W in registers for the whole launch (wave w: output block
+// w mod NOB; the waves that share a block share the tile's two node blocks), so LDS holds only
+// the tile and several workgroups fit a compute unit: the loads, the products and the stores of
+// different workgroups overlap, which a single resident workgroup's barriers rule out.
 template <int D>
 __global__ __launch_bounds__(kThreads) void dense_fwd_kernel(const float* __restrict__ H,
                                                              const float* __restrict__ W, int d_out,
                                                              float slope, int64_t N,
                                                              float* __restrict__ E_out,
                                                              uint8_t* __restrict__ mask) {
-  constexpr int LD = D + 4, LPR = D / 4, TN = 64;
+  constexpr int LD = D + 4, LPR = D / 4, TN = 64, KH = D / 2;
   const int DOP = (d_out + 31) & ~31, LDJ = DOP + 4, NOB = DOP / 32;
-  float* W_s = reinterpret_cast<float*>(smem_raw);   // [DOP][LD]
-  float* H_s = W_s + DOP * LD;                       // [TN][LD]
+  float* H_s = reinterpret_cast<float*>(smem_raw);   // [TN][LD]
   float* J_s = H_s + TN * LD;                        // [TN][LDJ]
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  for (int q = tid; q < DOP * LPR; q += kThreads) {
-    const int row = q / LPR, li = q % LPR;
-    float4 w = make_float4(0.f, 0.f, 0.f, 0.f);
-    if (row < d_out) w = reinterpret_cast<const float4*>(W)[row * LPR + li];
-    *reinterpret_cast<float4*>(W_s + row * LD + li * 4) = w;
+  const int r = lane & 31, hh = lane >> 5;
+  const int ob = wave % NOB;                         // NOB <= 4 = waves
+  const int rank = wave / NOB, sharers = (4 - ob + NOB - 1) / NOB;   // waves with this block: w = ob + NOB j
+  float wreg[KH];                                    // W[ob * 32 + r][hh * KH + s]
+  {
+    const int row = ob * 32 + r;
+#pragma unroll
+    for (int s = 0; s < KH; s += 4) {
+      float4 w = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (row < d_out) w = *reinterpret_cast<const float4*>(W + (size_t)row * D + hh * KH + s);
+      wreg[s] = w.x; wreg[s + 1] = w.y; wreg[s + 2] = w.z; wreg[s + 3] = w.w;
+    }
   }
   const int64_t n_tiles = (N + TN - 1) / TN;
   // the rows of the workgroup's next tile are requested while the current one is multiplied
@@ -1298,13 +1308,20 @@ __global__ __launch_bounds__(kThreads) void dense_fwd_kernel(const float* __rest
     }
     if (tile + gridDim.x < n_tiles) load_tile(tile + gridDim.x);
     __syncthreads();
-    for (int blk = wave; blk < 2 * NOB; blk += 4) {
-      const int nb = blk & 1, ob = blk >> 1;
+    for (int nb = rank; nb < 2; nb += sharers) {
       floatx16 acc = {0};
-      mfma_block<KCONT, KCONT>(H_s + nb * 32 * LD, LD, W_s + ob * 32 * LD, LD, D, acc);
+      const float* ap = H_s + (nb * 32 + r) * LD + hh * KH;
+#pragma unroll
+      for (int s = 0; s < KH; s += 4) {
+        const float4 a = *reinterpret_cast<const float4*>(ap + s);
+        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.x, wreg[s], acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.y, wreg[s + 1], acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.z, wreg[s + 2], acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.w, wreg[s + 3], acc, 0, 0, 0);
+      }
 #pragma unroll
       for (int v = 0; v < 16; ++v)
-        J_s[(nb * 32 + acc_row(v, lane)) * LDJ + ob * 32 + (lane & 31)] = acc[v];
+        J_s[(nb * 32 + acc_row(v, lane)) * LDJ + ob * 32 + r] = acc[v];
     }
     __syncthreads();
     const int oc = d_out / 4;
@@ -2449,11 +2466,13 @@ tinykg_status fwd_impl(const tinykg_graph* g, const float* E, const float* Wr, c
     }
   }
   const int DOP = (d_out + 31) & ~31;
-  const size_t smem = (size_t)(DOP * (D + 4) + 64 * (D + 4) + 64 * (DOP + 4)) * 4;
+  const size_t smem = (size_t)(64 * (D + 4) + 64 * (DOP + 4)) * 4;
   auto kern = dense_fwd_kernel<D>;
   if ((rc = set_smem(kern, smem)) != TINYKG_OK) return rc;
   ProfileScope prof("dense_fwd_kernel", st);
-  hipLaunchKernelGGL(kern, dim3(dense_grid(N)), dim3(kThreads), smem, st, H, W, d_out, slope, N,
+  // (persistent workgroups, as many as stay resident: LDS allows two at d = 128, four below)
+  const int fwd_grid = (int)std::max<int64_t>(1, std::min<int64_t>((N + 63) / 64, (int64_t)num_cus() * (D == 128 ? 2 : 4)));
+  hipLaunchKernelGGL(kern, dim3(fwd_grid), dim3(kThreads), smem, st, H, W, d_out, slope, N,
                      E_out, sv->mask_J);
   return launch_status();
 }

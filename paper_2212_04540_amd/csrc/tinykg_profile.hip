@@ -12,20 +12,28 @@ namespace tinykg {
 namespace {
 struct Record { const char* name; hipEvent_t start, stop; bool closed; };
 bool g_on = false;
+std::string g_only;                 // empty: every scope; else only the scopes of this name
 std::vector<Record> g_records;
+std::vector<hipEvent_t> g_spare;    // events of dropped records, reused (creating one costs microseconds)
 constexpr size_t kMaxRecords = 8192;
 
 void drop_records() {
-  for (Record& r : g_records) { (void)hipEventDestroy(r.start); (void)hipEventDestroy(r.stop); }
+  for (Record& r : g_records) { g_spare.push_back(r.start); g_spare.push_back(r.stop); }
   g_records.clear();
+}
+
+bool take_event(hipEvent_t* e) {
+  if (!g_spare.empty()) { *e = g_spare.back(); g_spare.pop_back(); return true; }
+  return hipEventCreate(e) == hipSuccess;
 }
 }  // namespace
 
 ProfileScope::ProfileScope(const char* name, hipStream_t st) : slot_(-1), st_(st) {
   if (!g_on || g_records.size() >= kMaxRecords) return;
+  if (!g_only.empty() && g_only != name) return;
   Record r{name, nullptr, nullptr, false};
-  if (hipEventCreate(&r.start) != hipSuccess) return;
-  if (hipEventCreate(&r.stop) != hipSuccess) { (void)hipEventDestroy(r.start); return; }
+  if (!take_event(&r.start)) return;
+  if (!take_event(&r.stop)) { g_spare.push_back(r.start); return; }
   (void)hipEventRecord(r.start, st);
   g_records.push_back(r);
   slot_ = (int)g_records.size() - 1;
@@ -63,6 +71,10 @@ void tinykg_profile_enable(int on) {
   using namespace tinykg;
   if (on) drop_records();
   g_on = on != 0;
+}
+
+void tinykg_profile_select(const char* name) {
+  tinykg::g_only = name ? name : "";
 }
 
 size_t tinykg_profile_report(char* buf, size_t cap) {

@@ -571,7 +571,11 @@ def main():
                      "note": "fp32 flops of the kernel's six k x d contractions per triplet over its launch time, "
                              "against the fp32 matrix peak; four of the six run on the fp32 matrix cores, two (the "
                              "recomputation of a and b) as six bfloat16 piece products each on the bf16 matrix "
-                             "cores (dense peak 2500 TFLOP/s), fp32 accumulation, fp32 accuracy",
+                             "cores (dense peak 2500 TFLOP/s), fp32 accumulation, fp32 accuracy.  These are the "
+                             "ALGORITHMIC flops (six products for every triplet); for a 32-edge tile whose "
+                             "edges share one tail (54 % of the tiles of this graph) the kernel forms the "
+                             "two tail-side products W_r^T grad_a and grad_a e_t^T once per tile from the "
+                             "sum of grad_a over the tile, so it executes fewer",
                      "traffic": profiled_traffic("edge_wave_kernel"),
                      "traffic_unit": "HBM bytes per launch (rocprofv3 --pmc FETCH_SIZE, WRITE_SIZE; "
                                      "summary under profiles/)",

@@ -1913,7 +1913,13 @@ __global__ __launch_bounds__(kCoopWaves * 64) void edge_bwd_kernel(
 //   2. X, Y <- grad_a, grad_b
 //      Pt, Ph [e][i] = grad_a W_r, grad_b W_r    (X, Y x W_r in LDS)
 //   3. X, Y <- Pt, Ph; rows walked in tail order / head order, equal neighbours summed
-//      in double, one fp64 atomic per run and column.
+//      in fp32, one atomic per run and column (fp64 for the rows of heavy nodes).
+// Run form: the relation order is sorted by tail, so popular tails own long runs and more than
+// half of the tiles of a Zipf-tailed graph hold ONE tail.  For such a tile the tail-side
+// products depend on the edges only through S = sum_e grad_a_e: grad_W_r += S e_t^T (a rank-one
+// update on the vector unit) and Pt = S W_r (one row, added with the tile's first row), so two
+// of the six products -- half of the fp32 ones -- are skipped.  The host balances the
+// workgroups' spans by tile cost, not by edge count.
 // The transposed form of step 1 (edge index on the accumulator rows, channel on the
 // lanes) is what lets grad_a / grad_b feed the grad_W_r products without leaving the
 // registers.  There is no workgroup barrier between staging W_r and the final fixed-order
@@ -2002,6 +2008,9 @@ __device__ __forceinline__ void edge_wave_span(
     load_idx(wt);
     load_rows();
     const int nrow = min(32, count - wt * 32);
+    // Rows are in tail order inside a relation, and popular tails own long runs: a tile whose
+    // edges all share ONE tail needs W_r^T (sum_e grad_a_e) once, not W_r^T grad_a_e per edge.
+    const bool one_tail = __all(r >= nrow || t_ld == __builtin_amdgcn_readfirstlane(t_ld)) != 0;
     {
       // where the scatter has to flush its running sums: at the last row of a run of
       // equal tails (rows are in tail order) resp. equal heads (ranks are in head order),
@@ -2095,8 +2104,20 @@ __device__ __forceinline__ void edge_wave_span(
 #pragma unroll
       for (int cb = 0; cb < NB; ++cb) er_acc[cb] += er_t[cb];
     }
+    float s_col[NB];     // one_tail: S = sum_e grad_a_e, channel cb * 32 + r (both halves of the wave)
+#pragma unroll
+    for (int cb = 0; cb < NB; ++cb) {
+      float t = 0.f;
+      if (one_tail) {
+#pragma unroll
+        for (int v = 0; v < 16; ++v) t += accA[cb][v];
+        t += __shfl_xor(t, 32);
+      }
+      s_col[cb] = t;
+    }
     phase_fence();
     // ---- 1c. grad_W_r[c][i] += sum_e grad_a[e][c] e_t[e][i] + grad_b[e][c] e_h[e][i]
+    //      (one_tail: the first sum is the rank-one matrix S e_t^T, added after the loop)
     //      (two-level sum: a fresh accumulator per tile keeps the fp32 running sum short)
     //      The operands of four accumulator registers (eight edges) are fetched from LDS
     //      while the products of the previous four run; the scheduling fences keep the
@@ -2116,18 +2137,32 @@ __device__ __forceinline__ void edge_wave_span(
         }
       };
       fetch(0, bt[0], bh[0]);
+      if (one_tail) {
 #pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        if (q < 3) fetch(q + 1, bt[(q + 1) & 1], bh[(q + 1) & 1]);
+        for (int q = 0; q < 4; ++q) {
+          if (q < 3) fetch(q + 1, bt[(q + 1) & 1], bh[(q + 1) & 1]);
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
+          for (int u = 0; u < 4; ++u) {
 #pragma unroll
-          for (int cb = 0; cb < NB; ++cb) {
-            accT[cb] = __builtin_amdgcn_mfma_f32_32x32x2f32(accA[cb][4 * q + u], bt[q & 1][u], accT[cb], 0, 0, 0);
-            accT[cb] = __builtin_amdgcn_mfma_f32_32x32x2f32(accB[cb][4 * q + u], bh[q & 1][u], accT[cb], 0, 0, 0);
+            for (int cb = 0; cb < NB; ++cb)
+              accT[cb] = __builtin_amdgcn_mfma_f32_32x32x2f32(accB[cb][4 * q + u], bh[q & 1][u], accT[cb], 0, 0, 0);
           }
+          __builtin_amdgcn_sched_barrier(0);
         }
-        __builtin_amdgcn_sched_barrier(0);
+      } else {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          if (q < 3) fetch(q + 1, bt[(q + 1) & 1], bh[(q + 1) & 1]);
+#pragma unroll
+          for (int u = 0; u < 4; ++u) {
+#pragma unroll
+            for (int cb = 0; cb < NB; ++cb) {
+              accT[cb] = __builtin_amdgcn_mfma_f32_32x32x2f32(accA[cb][4 * q + u], bt[q & 1][u], accT[cb], 0, 0, 0);
+              accT[cb] = __builtin_amdgcn_mfma_f32_32x32x2f32(accB[cb][4 * q + u], bh[q & 1][u], accT[cb], 0, 0, 0);
+            }
+          }
+          __builtin_amdgcn_sched_barrier(0);
+        }
       }
 #pragma unroll
       for (int cb = 0; cb < NB; ++cb) {
@@ -2137,6 +2172,21 @@ __device__ __forceinline__ void edge_wave_span(
         asm volatile("" : "+v"(accW[cb * NB + ib]));
       }
     }
+    if (one_tail) {
+      // S e_t^T: row c of block cb needs S[c], which lane c % 32 holds; e_t is any row of X
+      float et[NB];
+#pragma unroll
+      for (int ib = 0; ib < NB; ++ib) et[ib] = X_s[ib * 32 + r];
+#pragma unroll
+      for (int cb = 0; cb < NB; ++cb) {
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const float sr = __shfl(s_col[cb], acc_row(v, lane));
+#pragma unroll
+          for (int ib = 0; ib < NB; ++ib) accW[cb * NB + ib][v] = fmaf(sr, et[ib], accW[cb * NB + ib][v]);
+        }
+      }
+    }
     phase_fence();
     // ---- 2. X, Y <- grad_a, grad_b as [e][c]
 #pragma unroll
@@ -2144,7 +2194,7 @@ __device__ __forceinline__ void edge_wave_span(
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
         const int e = acc_row(v, lane);
-        X_s[e * LD + cb * 32 + r] = accA[cb][v];
+        if (!one_tail) X_s[e * LD + cb * 32 + r] = accA[cb][v];   // (the run form works from S alone)
         Y_s[e * LD + cb * 32 + r] = accB[cb][v];
       }
     }
@@ -2168,6 +2218,18 @@ __device__ __forceinline__ void edge_wave_span(
     for (int side = 0; side < 2; ++side) {
       float* P_s = side == 0 ? X_s : Y_s;
       phase_fence();
+      const bool run_form = side == 0 && one_tail;
+      float pt_run = 0.f;                          // run_form: (sum_e grad_a_e) W_r, column si
+      if (run_form) {
+#pragma unroll
+        for (int cb = 0; cb < NB; ++cb) {
+#pragma unroll
+          for (int j = 0; j < 32; ++j) {
+            const float sc = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(s_col[cb]), j));
+            pt_run = fmaf(sc, Wr_s[(cb * 32 + j) * LD + si], pt_run);
+          }
+        }
+      } else {
       floatx16 accP[NB];
 #pragma unroll
       for (int ib = 0; ib < NB; ++ib) accP[ib] = floatx16{0};
@@ -2194,6 +2256,7 @@ __device__ __forceinline__ void edge_wave_span(
 #pragma unroll
         for (int v = 0; v < 16; ++v) P_s[acc_row(v, lane) * LD + ib * 32 + r] = accP[ib][v];
       }
+      }
       phase_fence();
       constexpr int RB = RP < 16 ? RP : 16;        // rows whose LDS reads are issued together
       float run = 0.f;
@@ -2205,7 +2268,9 @@ __device__ __forceinline__ void edge_wave_span(
         for (int k = 0; k < RB; ++k) {
           if (side == 0) {
             node[k] = tl_s[se0 + k0 + k];
-            val[k] = fmaf(pi_s[se0 + k0 + k], ghv[k0 + k], P_s[(se0 + k0 + k) * LD + si]);
+            // (run_form: the whole tile is one run, whose product enters with its first row)
+            const float pv = run_form ? (se0 + k0 + k == 0 ? pt_run : 0.f) : P_s[(se0 + k0 + k) * LD + si];
+            val[k] = fmaf(pi_s[se0 + k0 + k], ghv[k0 + k], pv);
           } else {
             node[k] = hr_s[se0 + k0 + k];
             const int pk = D == 64 ? __builtin_amdgcn_readfirstlane(hp_s[se0 + k0 + k]) : hp_s[se0 + k0 + k];
@@ -2330,8 +2395,10 @@ BwdWs bwd_layout(const tinykg_graph* g, int d, int d_out) {
   w.acc = w.gH + align256((size_t)g->n_nodes * d * 4);
   w.pW = w.acc + align256((size_t)g->n_acc_heavy * kHeavyReplicas * d * 8);
   w.pWr = w.pW + align256((size_t)dense_grid(g->n_nodes) * d_out * d * 4);
-  w.per = w.pWr + align256((size_t)g->n_chunks * d * d * 4);
-  w.hv = heavy_layout(g, d, w.per + align256((size_t)g->n_chunks * d * 4));
+  // (one partial per chunk, or per span of the persistent kernel, whichever are more)
+  const size_t n_part = (size_t)std::max(g->n_chunks, g->n_spans);
+  w.per = w.pWr + align256(n_part * d * d * 4);
+  w.hv = heavy_layout(g, d, w.per + align256(n_part * d * 4));
   w.total = w.hv.end;
   return w;
 }

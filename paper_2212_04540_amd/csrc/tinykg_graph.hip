@@ -19,6 +19,12 @@ namespace tinykg {
 
 namespace {
 
+// Time of a one-tail tile of the edge-level backward kernel (d <= 64) relative to an ordinary one.
+#ifndef TINYKG_ONE_TAIL_COST
+#define TINYKG_ONE_TAIL_COST 0.7
+#endif
+constexpr double kOneTailTileCost = TINYKG_ONE_TAIL_COST;
+
 template <typename T>
 tinykg_status upload(const std::vector<T>& v, T** out) {
   *out = nullptr;
@@ -128,23 +134,50 @@ tinykg_status tinykg_graph_create(int64_t n_nodes, int32_t n_rel, int64_t n_edge
   }
   rel_chunk_ptr[(size_t)n_rel] = (int32_t)chunk_rel.size();
 
-  // spans of the persistent edge-level kernel (one group per compute unit)
+  // spans of the persistent edge-level kernel (one group per compute unit): runs of whole
+  // 32-edge tiles of one relation (tiles are counted from the relation's first edge).  The
+  // groups get equal shares of the kernel's WORK, not of the edges: a tile whose edges share
+  // one tail (popular tails own long runs of the relation order) takes the kernel's run form,
+  // which skips a third of the matrix products.
   std::vector<int32_t> span_group_ptr(1, 0), span_rel, span_start, span_count, rel_span_ptr((size_t)n_rel + 1, 0);
   {
     const int64_t n_groups = std::max<int64_t>(1, std::min<int64_t>(num_cus(), (int64_t)chunk_rel.size()));
-    int64_t cur_group = 0, last_group = -1;
-    for (size_t c = 0; c < chunk_rel.size(); ++c) {
-      const int64_t mid = (int64_t)chunk_start[c] + chunk_count[c] / 2;
-      const int64_t grp = std::min<int64_t>(n_groups - 1, mid * n_groups / std::max<int64_t>(n_edges, 1));
-      while (cur_group < grp) { span_group_ptr.push_back((int32_t)span_rel.size()); ++cur_group; }
-      if (grp == last_group && span_rel.back() == chunk_rel[c]) {
-        span_count.back() += chunk_count[c];
-      } else {
-        span_rel.push_back(chunk_rel[c]);
-        span_start.push_back(chunk_start[c]);
-        span_count.push_back(chunk_count[c]);
+    auto tile_cost = [&](int64_t first, int64_t n) {
+      for (int64_t k = 1; k < n; ++k)
+        if (r_tail[(size_t)(first + k)] != r_tail[(size_t)first]) return 1.0;
+      return kOneTailTileCost;
+    };
+    double total_cost = 0.0;
+    int64_t first = 0;
+    for (int32_t r = 0; r < n_rel; ++r) {
+      const int64_t end = first + rel_count[(size_t)r];
+      for (int64_t t0 = first; t0 < end; t0 += 32) total_cost += tile_cost(t0, std::min<int64_t>(32, end - t0));
+      first = end;
+    }
+    int64_t cur_group = 0;
+    double cost_before = 0.0;
+    first = 0;
+    for (int32_t r = 0; r < n_rel; ++r) {
+      const int64_t end = first + rel_count[(size_t)r];
+      bool open = false;      // a span of this relation in the current group is being extended
+      for (int64_t t0 = first; t0 < end; t0 += 32) {
+        const int64_t n = std::min<int64_t>(32, end - t0);
+        const double cost = tile_cost(t0, n);
+        const int64_t grp = std::min<int64_t>(n_groups - 1, (int64_t)((cost_before + 0.5 * cost) * (double)n_groups /
+                                                                      std::max(total_cost, 1.0)));
+        cost_before += cost;
+        if (grp > cur_group) open = false;
+        while (cur_group < grp) { span_group_ptr.push_back((int32_t)span_rel.size()); ++cur_group; }
+        if (open) {
+          span_count.back() += (int32_t)n;
+        } else {
+          span_rel.push_back(r);
+          span_start.push_back((int32_t)t0);
+          span_count.push_back((int32_t)n);
+          open = true;
+        }
       }
-      last_group = grp;
+      first = end;
     }
     while ((int64_t)span_group_ptr.size() < n_groups + 1) span_group_ptr.push_back((int32_t)span_rel.size());
     size_t sp = 0;

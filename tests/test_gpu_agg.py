@@ -244,6 +244,23 @@ def test_hot_tail_hot_head_and_empty_relations(tk):
                  np.concatenate([tail, tail2]), 64, 64, 2, 64)
 
 
+@pytest.mark.parametrize("d,bits,group", [(64, 2, 64), (32, 4, 32), (64, 8, 256)])
+def test_tiles_whose_edges_share_one_tail(tk, d, bits, group):
+    # the edge-level backward kernel forms W_r^T (sum_e grad_a_e) and (sum_e grad_a_e) e_t^T once
+    # for a 32-edge tile of one tail: relation 0 is ONE tail throughout (three full tiles and a
+    # ragged one), relation 1 starts with a 40-edge run (one such tile, then a mixed one),
+    # relation 2 has no such tile, relation 3 is a single edge
+    N, R = 256, 4
+    rng = np.random.default_rng(9)
+    n0, n1, n2 = 101, 150, 90
+    head = np.concatenate([rng.integers(0, N, n0), rng.integers(0, N, n1), rng.integers(0, N, n2), [5]]).astype(np.int32)
+    tail = np.concatenate([np.full(n0, 3), np.full(40, 0), rng.integers(1, N, n1 - 40),
+                           rng.integers(0, N, n2), [3]]).astype(np.int32)
+    rel = np.concatenate([np.zeros(n0), np.ones(n1), np.full(n2, 2), [3]]).astype(np.int32)
+    perm = rng.permutation(head.size)
+    run_protocol(tk, N, R, head[perm], rel[perm], tail[perm], d, d, bits, group, data_seed=21)
+
+
 def test_zero_relation_maps_give_the_normalised_adjacency_spmm(tk):
     # W_r = 0 => uniform attention => H = E + D^-1 A E  (Eq. 2's spmm), on the GPU path
     import scipy.sparse as sp

@@ -1692,6 +1692,10 @@ __global__ __launch_bounds__(kCoopWaves * 64) void edge_bwd_kernel(
   int* hd_s = tl_s + TE;                           // head of row e
   int* hp_s = hd_s + TE;                           // row of head-order rank k
   int* hr_s = hp_s + TE;                           // head of rank k; sign bit: a head run ends here
+  // run form (a tile whose edges share one tail; see the wave-independent kernel below)
+  float* S_s = reinterpret_cast<float*>(hr_s + TE);    // [D] sum_e grad_a_e
+  float* Pt_s = S_s + D;                               // [D] S W_r
+  int* flag_s = reinterpret_cast<int*>(Pt_s + D);      // [0]: the current tile has one tail
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int ch = blockIdx.x;
@@ -1774,6 +1778,8 @@ __global__ __launch_bounds__(kCoopWaves * 64) void edge_bwd_kernel(
         gs_s[er_row] = g_ld; pi_s[er_row] = p_ld; hd_s[er_row] = h_ld; hp_s[er_row] = perm;
         tl_s[er_row] = t_id | t_flag; hr_s[er_row] = h_rank | h_flag;
       }
+      const int one = __all(er_row >= nrow || t_ld == __builtin_amdgcn_readfirstlane(t_ld));
+      if (lane == 0) flag_s[0] = one;
     }
     if (t0 + TE < count) {
       load_rows();
@@ -1782,6 +1788,7 @@ __global__ __launch_bounds__(kCoopWaves * 64) void edge_bwd_kernel(
       load_edge(t0 + 2 * TE);
     }
     __syncthreads();
+    const bool one_tail = flag_s[0] != 0;          // the same for the whole workgroup
     // ---- 1. a (waves 0-3) or b (waves 4-7) of channel block blk4: [c][e], lane = edge
     //      on the bf16 matrix cores: both operands are read as fp32, eight k-values at a time,
     //      and split into their three bfloat16 pieces in registers (see split3x8)
@@ -1817,6 +1824,11 @@ __global__ __launch_bounds__(kCoopWaves * 64) void edge_bwd_kernel(
         }
         *reinterpret_cast<float4*>(dA_s + e1 * LD + c0) = make_float4(da[0], da[1], da[2], da[3]);
         *reinterpret_cast<float4*>(dB_s + e1 * LD + c0) = make_float4(f[0], f[1], f[2], f[3]);
+        if (one_tail) {        // S: grad_a summed over the tile's 32 edges (the lanes of a half)
+#pragma unroll
+          for (int u = 0; u < 4; ++u) da[u] = slot_sum<32>(da[u]);
+          if (e1 == 0) *reinterpret_cast<float4*>(S_s + c0) = make_float4(da[0], da[1], da[2], da[3]);
+        }
       }
     }
     __syncthreads();
@@ -1843,8 +1855,26 @@ __global__ __launch_bounds__(kCoopWaves * 64) void edge_bwd_kernel(
 #pragma unroll
     for (int k = 0; k < RP; ++k) ghv[k] = gH[(int64_t)hd_s[se0 + k] * D + si];
     // ---- 2. Pt = grad_a W_r (waves 0-3) or Ph = grad_b W_r (waves 4-7), column block blk4
+    //      (run form: Pt is the one row S W_r; half hh of the wave sums half of the channels)
     floatx16 accP = {0};
-    mfma_block<KCONT, KMAJOR>(b_side ? dB_s : dA_s, LD, Wr_s + blk4 * 32, LD, D, accP);
+    const bool run_form = one_tail && !b_side;
+    if (run_form) {
+      float p = 0.f;
+      const float* wcol = Wr_s + (lane >> 5) * (D / 2) * LD + blk4 * 32 + (lane & 31);
+      const float* sp = S_s + (lane >> 5) * (D / 2);
+#pragma unroll 4
+      for (int c = 0; c < D / 2; c += 4) {
+        const float4 s4 = *reinterpret_cast<const float4*>(sp + c);
+        p = fmaf(s4.x, wcol[c * LD], p);
+        p = fmaf(s4.y, wcol[(c + 1) * LD], p);
+        p = fmaf(s4.z, wcol[(c + 2) * LD], p);
+        p = fmaf(s4.w, wcol[(c + 3) * LD], p);
+      }
+      p += __shfl_xor(p, 32);
+      if (lane < 32) Pt_s[blk4 * 32 + lane] = p;
+    } else {
+      mfma_block<KCONT, KMAJOR>(b_side ? dB_s : dA_s, LD, Wr_s + blk4 * 32, LD, D, accP);
+    }
     // grad_W_r blocks [c][i] += sum_e grad_a[e][c] e_t[e][i] + grad_b[e][c] e_h[e][i]
 #pragma unroll
     for (int j = 0; j < NBW; ++j) {
@@ -1852,12 +1882,21 @@ __global__ __launch_bounds__(kCoopWaves * 64) void edge_bwd_kernel(
       // two-level sum: a fresh accumulator per tile, added to the chunk's accumulator
       // (keeps the fp32 running sum short when a relation has 10^5 and more edges)
       floatx16 accT = {0};
-      mfma_block<KMAJOR, KMAJOR>(dA_s + cb * 32, LD, Et_s + ib * 32, LD, TE, accT);
+      if (one_tail) {          // S e_t^T: e_t is any row of the tile
+        const float et = Et_s[ib * 32 + (lane & 31)];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const float4 s4 = *reinterpret_cast<const float4*>(S_s + cb * 32 + 8 * q + 4 * (lane >> 5));
+          accT[4 * q] = s4.x * et; accT[4 * q + 1] = s4.y * et; accT[4 * q + 2] = s4.z * et; accT[4 * q + 3] = s4.w * et;
+        }
+      } else {
+        mfma_block<KMAJOR, KMAJOR>(dA_s + cb * 32, LD, Et_s + ib * 32, LD, TE, accT);
+      }
       mfma_block<KMAJOR, KMAJOR>(dB_s + cb * 32, LD, Eh_s + ib * 32, LD, TE, accT);
       accW[j] += accT;
     }
     __syncthreads();   // every read of Et_s / Eh_s is done: reuse them as staging
-    {
+    if (!run_form) {
       float* P_s = b_side ? Eh_s : Et_s;
 #pragma unroll
       for (int v = 0; v < 16; ++v) P_s[acc_row(v, lane) * LD + blk4 * 32 + (lane & 31)] = accP[v];
@@ -1874,7 +1913,9 @@ __global__ __launch_bounds__(kCoopWaves * 64) void edge_bwd_kernel(
       for (int k = 0; k < RP; ++k) {
         if (side == 0) {
           node[k] = tl_s[se0 + k];
-          val[k] = fmaf(pi_s[se0 + k], ghv[k], Et_s[(se0 + k) * LD + si]);
+          // (run form: the whole tile is one run, whose product enters with its first row)
+          const float pv = one_tail ? (se0 + k == 0 ? Pt_s[si] : 0.f) : Et_s[(se0 + k) * LD + si];
+          val[k] = fmaf(pi_s[se0 + k], ghv[k], pv);
         } else {
           node[k] = hr_s[se0 + k];
           val[k] = Eh_s[hp_s[se0 + k] * LD + si];
@@ -2646,7 +2687,7 @@ tinykg_status bwd_impl(const tinykg_graph* g, const tinykg_saved* sv, const floa
                          g->r_head, g->r_tail, g->r_eid, g->r_hperm32, spans, g->span_group_ptr, pi, gs, gH,
                          sink, pWr, per);
     } else {
-      const size_t smem = (size_t)(D * LD + 4 * TE * LD + D + 6 * TE) * 4;
+      const size_t smem = (size_t)(D * LD + 4 * TE * LD + D + 6 * TE + 2 * D + 4) * 4;
       auto kern = edge_bwd_kernel<D, TE, BITS>;
       if ((rc = set_smem(kern, smem)) != TINYKG_OK) return rc;
       ProfileScope prof("edge_bwd_kernel", st);

@@ -244,7 +244,7 @@ def test_hot_tail_hot_head_and_empty_relations(tk):
                  np.concatenate([tail, tail2]), 64, 64, 2, 64)
 
 
-@pytest.mark.parametrize("d,bits,group", [(64, 2, 64), (32, 4, 32), (64, 8, 256)])
+@pytest.mark.parametrize("d,bits,group", [(64, 2, 64), (32, 4, 32), (64, 8, 256), (128, 4, 128), (128, 2, 64)])
 def test_tiles_whose_edges_share_one_tail(tk, d, bits, group):
     # the edge-level backward kernel forms W_r^T (sum_e grad_a_e) and (sum_e grad_a_e) e_t^T once
     # for a 32-edge tile of one tail: relation 0 is ONE tail throughout (three full tiles and a

@@ -21,10 +21,10 @@ struct tinykg_graph {
   int32_t* chunk_start = nullptr;    // [n_chunks] first relation-order position
   int32_t* chunk_count = nullptr;    // [n_chunks]
   int32_t* rel_chunk_ptr = nullptr;  // [n_rel + 1] chunks of relation r: [ptr[r], ptr[r+1])
-  // spans: the relation order cut at chunk boundaries into one piece of about equal edge
-  // count per compute unit, each piece cut again where the relation changes -- what one
-  // persistent workgroup of the edge-level backward kernel walks (a span is a run of whole
-  // chunks of one relation, so its 32-edge tiles are the chunks' tiles)
+  // spans: the relation order cut at 32-edge tile boundaries (tiles counted from a relation's
+  // first edge) into one piece of about equal WORK per compute unit -- a tile whose edges
+  // share one tail is cheaper for the edge-level backward kernel -- each piece cut again
+  // where the relation changes: what one persistent workgroup of that kernel walks
   int32_t n_span_groups = 0, n_spans = 0;
   int32_t* span_group_ptr = nullptr; // [n_span_groups + 1] spans of workgroup w: [ptr[w], ptr[w+1])
   int32_t* span_rel = nullptr;       // [n_spans]

@@ -66,3 +66,14 @@ def test_argument_errors_need_no_gpu():
     assert L.tinykg_quantize_ex(fake, 4, 64, 2, 64, 0, 0, 7, fake, fake, fake, null) == 1   # rounding
     assert L.tinykg_dequantize(fake, fake, fake, 3, 50, 2, 64, fake, null) == 2
     assert L.tinykg_dequantize(null, null, null, 0, 64, 2, 64, null, null) == 0
+
+
+def test_bench_refuses_more_than_one_gpu():
+    # this build is one GPU: bench.py --gpus N > 1 must say so and exit non-zero (no GPU needed)
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"],
+                       capture_output=True, text=True, timeout=120)
+    assert r.returncode != 0
+    assert "ONE GPU" in (r.stdout + r.stderr)

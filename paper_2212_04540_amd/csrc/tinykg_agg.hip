@@ -2457,7 +2457,7 @@ template <int D, int BITS>
 tinykg_status launch_score(const tinykg_graph* g, Source src, const float* Wr, const float* er,
                            float* s, hipStream_t st) {
   if (g->n_chunks == 0) return TINYKG_OK;
-  constexpr int LD = D + 4;
+  [[maybe_unused]] constexpr int LD = D + 4;   // (the fp32-MFMA build sizes its LDS with it)
   ChunkList cl{g->chunk_rel, g->chunk_start, g->chunk_count};
   ProfileScope prof("score_kernel", st);
   if constexpr (D <= 64) {

@@ -149,7 +149,9 @@ size_t tinykg_kg_aggregate_workspace_bytes(const tinykg_graph* g, int d_in, int 
  * tinykg_quantize (or fp32 copies when bits == 32), and the sign mask of J.
  *   E [n_nodes, d_in], Wr [n_rel, d_rel, d_in], er [n_rel, d_rel], W [d_out, d_in]
  *   E_out [n_nodes, d_out]
- * d_in == d_rel in {32, 64, 128}; d_out a multiple of 16 up to 128; n_nodes*d_in
+ * Wr / er may be NULL only for a graph without edges (Q(E) is saved all the same).
+ * d_in == d_rel in {32, 64, 128} (the relation space has the embedding's width: a d_rel
+ * other than d_in is ERR_UNSUPPORTED); d_out a multiple of 16 up to 128; n_nodes*d_in
  * a multiple of `group` (else ERR_UNSUPPORTED / ERR_SHAPE).
  * Arithmetic: fp32 in, fp32 out, fp32 (or wider) accumulation.  The projections W_r e are
  * formed on the matrix cores from exact three-way bfloat16 splits of their fp32 operands
@@ -236,6 +238,13 @@ tinykg_status tinykg_gather_rows(const float* E, int dim, const int32_t* idx, in
                                  float* out, void* stream);
 tinykg_status tinykg_scatter_add_rows(const float* src, int dim, const int32_t* idx, int64_t n_rows,
                                       float* dst, void* stream);
+/* The id list of one readout batch: ids[0..3*batch) = users | pos | neg (what
+ * tinykg_gather_rows takes), and slot[i] = i, so that slot, slot + batch and
+ * slot + 2*batch address the three parts inside the gathered rows (what
+ * tinykg_bpr_loss / tinykg_bpr_grad take when they run on gathered rows).  All DEVICE
+ * int32; ids and slot hold 3*batch entries each; 3*batch < 2^31 (else ERR_SHAPE). */
+tinykg_status tinykg_readout_ids(const int32_t* users, const int32_t* pos, const int32_t* neg,
+                                 int64_t batch, int32_t* ids, int32_t* slot, void* stream);
 /* dst[0..n) = 0 with a fill kernel (n a multiple of 4, dst DEVICE, 16-byte aligned). */
 tinykg_status tinykg_fill_zero(float* dst, int64_t n, void* stream);
 

@@ -24,7 +24,7 @@ EXPORTS = [
     "tinykg_kg_aggregate_fwd", "tinykg_kg_aggregate_bwd", "tinykg_kg_uniform_fwd",
     "tinykg_kg_uniform_bwd", "tinykg_profile_enable", "tinykg_profile_select",
     "tinykg_profile_report", "tinykg_profile_copy", "tinykg_bpr_loss", "tinykg_bpr_grad",
-    "tinykg_gather_rows", "tinykg_scatter_add_rows", "tinykg_fill_zero",
+    "tinykg_gather_rows", "tinykg_scatter_add_rows", "tinykg_fill_zero", "tinykg_readout_ids",
     "tinykg_batchnorm_workspace_bytes", "tinykg_batchnorm_fwd", "tinykg_batchnorm_bwd",
     "tinykg_kg_max_arg_bytes", "tinykg_kg_max_workspace_bytes", "tinykg_kg_max_fwd", "tinykg_kg_max_bwd",
 ]
@@ -93,6 +93,7 @@ def lib():
         L.tinykg_gather_rows.argtypes = [vp, i32, vp, i64, vp, vp]
         L.tinykg_scatter_add_rows.argtypes = [vp, i32, vp, i64, vp, vp]
         L.tinykg_fill_zero.argtypes = [vp, i64, vp]
+        L.tinykg_readout_ids.argtypes = [vp, vp, vp, i64, vp, vp, vp]
         L.tinykg_kg_max_arg_bytes.argtypes = [vp]
         L.tinykg_kg_max_workspace_bytes.argtypes = [vp, i32]
         L.tinykg_kg_max_workspace_bytes.restype = sz
@@ -232,6 +233,20 @@ def tinykg_gather_rows(E, idx, out=None):
     _ok(lib().tinykg_gather_rows(_ptr(E), E.shape[1], _ptr(idx), idx.numel(), _ptr(out), _stream()),
         "tinykg_gather_rows")
     return out
+
+
+def tinykg_readout_ids(users, pos, neg):
+    """ids = users | pos | neg and slot = 0 .. 3*batch - 1, both int32 [3*batch]."""
+    for t, nm in ((users, "users"), (pos, "pos"), (neg, "neg")):
+        _dev(t, torch.int32, nm)
+    batch = users.numel()
+    if pos.numel() != batch or neg.numel() != batch:
+        raise ValueError("users, pos, neg must have the same length")
+    ids = torch.empty(3 * batch, dtype=torch.int32, device=users.device)
+    slot = torch.empty(3 * batch, dtype=torch.int32, device=users.device)
+    _ok(lib().tinykg_readout_ids(_ptr(users), _ptr(pos), _ptr(neg), batch, _ptr(ids), _ptr(slot), _stream()),
+        "tinykg_readout_ids")
+    return ids, slot
 
 
 def tinykg_fill_zero(dst):

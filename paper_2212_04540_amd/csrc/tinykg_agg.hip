@@ -50,13 +50,20 @@ __device__ __forceinline__ int acc_row(int v, int lane) {
   return (v & 3) + 4 * (lane >> 5) + 8 * (v >> 2);
 }
 
-// tanh without branches: 1 - 2 / (exp(2x) + 1) on the hardware exp2 / rcp units.  Absolute
-// error below 2e-7 for every x (the subtraction from 1 bounds it by the error of the
-// quotient), which is what the score s = a . tanh(b) and its derivative 1 - tanh^2 need;
-// exp overflow gives exactly 1, underflow exactly -1.
+// tanh without branches.  |x| >= 1/8: 1 - 2 / (exp(2x) + 1) on the hardware exp2 / rcp units;
+// the subtraction from 1 bounds the ABSOLUTE error by that of the quotient (below 2e-7), i.e.
+// a relative error below 2e-6 there; exp overflow gives exactly 1, underflow exactly -1.
+// |x| < 1/8: the odd series x - x^3/3 + 2x^5/15 - 17x^7/315 (truncation below 2e-9 of the
+// value), because near 0 the first form loses the value's leading digits in the subtraction
+// and grad_a = grad_s tanh(b) inherits the RELATIVE error of tanh.
 __device__ __forceinline__ float fast_tanh(float x) {
   const float e = __builtin_amdgcn_exp2f(x * 2.885390081777927f);   // exp(2x)
-  return fmaf(-2.0f, __builtin_amdgcn_rcpf(e + 1.0f), 1.0f);
+  const float big = fmaf(-2.0f, __builtin_amdgcn_rcpf(e + 1.0f), 1.0f);
+  const float x2 = x * x;
+  float p = fmaf(x2, -17.0f / 315.0f, 2.0f / 15.0f);
+  p = fmaf(x2, p, -1.0f / 3.0f);
+  const float small = fmaf(x * x2, p, x);
+  return fabsf(x) < 0.125f ? small : big;
 }
 
 template <int AM, int BM>
@@ -86,43 +93,6 @@ __device__ __forceinline__ void mfma_block(const float* __restrict__ A, int lda,
     }
 #pragma unroll
     for (int u = 0; u < 4; ++u) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a[u], b[u], acc, 0, 0, 0);
-  }
-}
-
-// Two 32x32 blocks that share their A operand (all three operands stored with k
-// contiguous): accA += W x T, accB += W x H.  The operands of 32 k-values per lane are
-// loaded with 128-bit LDS reads before the 2 x 32 MFMAs that consume them are issued, so
-// the matrix pipe is not stalled on LDS latency between instructions.
-template <int K>
-__device__ __forceinline__ void mfma_dual_kcont(const float* __restrict__ W, int ldw,
-                                                const float* __restrict__ T, const float* __restrict__ H,
-                                                int ld, floatx16& accA, floatx16& accB) {
-  const int lane = threadIdx.x & 63, r = lane & 31, hh = lane >> 5;
-  constexpr int KH = K / 2;                       // k-values per lane
-  constexpr int STEP = KH < 32 ? KH : 32;
-  const float* wp = W + r * ldw + hh * KH;
-  const float* tp = T + r * ld + hh * KH;
-  const float* hp = H + r * ld + hh * KH;
-#pragma unroll
-  for (int s0 = 0; s0 < KH; s0 += STEP) {
-    float4 w[STEP / 4], t[STEP / 4], h[STEP / 4];
-#pragma unroll
-    for (int i = 0; i < STEP / 4; ++i) {
-      w[i] = *reinterpret_cast<const float4*>(wp + s0 + 4 * i);
-      t[i] = *reinterpret_cast<const float4*>(tp + s0 + 4 * i);
-      h[i] = *reinterpret_cast<const float4*>(hp + s0 + 4 * i);
-    }
-#pragma unroll
-    for (int i = 0; i < STEP / 4; ++i) {
-      accA = __builtin_amdgcn_mfma_f32_32x32x2f32(w[i].x, t[i].x, accA, 0, 0, 0);
-      accB = __builtin_amdgcn_mfma_f32_32x32x2f32(w[i].x, h[i].x, accB, 0, 0, 0);
-      accA = __builtin_amdgcn_mfma_f32_32x32x2f32(w[i].y, t[i].y, accA, 0, 0, 0);
-      accB = __builtin_amdgcn_mfma_f32_32x32x2f32(w[i].y, h[i].y, accB, 0, 0, 0);
-      accA = __builtin_amdgcn_mfma_f32_32x32x2f32(w[i].z, t[i].z, accA, 0, 0, 0);
-      accB = __builtin_amdgcn_mfma_f32_32x32x2f32(w[i].z, h[i].z, accB, 0, 0, 0);
-      accA = __builtin_amdgcn_mfma_f32_32x32x2f32(w[i].w, t[i].w, accA, 0, 0, 0);
-      accB = __builtin_amdgcn_mfma_f32_32x32x2f32(w[i].w, h[i].w, accB, 0, 0, 0);
-    }
   }
 }
 
@@ -171,93 +141,6 @@ struct ChunkList {
 };
 
 // ------------------------------------------------------------------ scores ----
-template <int D, int TE, int BITS>
-__global__ __launch_bounds__(kThreads) void score_kernel(Source src, const float* __restrict__ Wr,
-                                                         const float* __restrict__ er,
-                                                         const int32_t* __restrict__ r_head,
-                                                         const int32_t* __restrict__ r_tail,
-                                                         const int32_t* __restrict__ r_eid,
-                                                         ChunkList chunks, float* __restrict__ s_out) {
-  constexpr int LD = D + 4, LPR = D / 4, NCB = D / 32, NEB = TE / 32, NP = NCB * 2;
-  constexpr int CPT = TE * LPR / kThreads;        // row chunks per thread and matrix
-  constexpr int RSTEP = kThreads / LPR;           // rows between a thread's chunks
-  static_assert(TE * LPR % kThreads == 0 && kThreads % LPR == 0, "tile does not split evenly");
-  float* Wr_s = reinterpret_cast<float*>(smem_raw);
-  float* Et_s = Wr_s + D * LD;
-  float* Eh_s = Et_s + TE * LD;
-  float* er_s = Eh_s + TE * LD;
-  float* part = er_s + D;  // [NP][TE]
-
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int ch = blockIdx.x;
-  const int r = chunks.rel[ch], start = chunks.start[ch], count = chunks.count[ch];
-  const int row0 = tid / LPR, li = tid % LPR;     // this thread stages rows row0 + k * RSTEP
-
-  // Rows of tile k + 1 are requested (raw) while tile k is multiplied; their node ids one
-  // tile earlier still.  Rows past the end of the chunk read node 0 and are never used.
-  int tn[CPT], hn[CPT];
-  auto load_ids = [&](int t0) {
-#pragma unroll
-    for (int k = 0; k < CPT; ++k) {
-      const int row = t0 + row0 + k * RSTEP;
-      tn[k] = 0; hn[k] = 0;
-      if (row < count) { tn[k] = r_tail[start + row]; hn[k] = r_head[start + row]; }
-    }
-  };
-  RawChunk<BITS> rt[CPT], rh[CPT];
-  auto load_rows = [&]() {
-#pragma unroll
-    for (int k = 0; k < CPT; ++k) {
-      rt[k].load(src, (int64_t)tn[k] * LPR + li);
-      rh[k].load(src, (int64_t)hn[k] * LPR + li);
-    }
-  };
-  load_ids(0);
-  load_rows();
-  load_ids(TE);
-
-  const float4* Wg = reinterpret_cast<const float4*>(Wr + (size_t)r * D * D);
-  for (int q = tid; q < D * LPR; q += kThreads)
-    *reinterpret_cast<float4*>(Wr_s + (q / LPR) * LD + (q % LPR) * 4) = Wg[q];
-  for (int c = tid; c < D; c += kThreads) er_s[c] = er[(size_t)r * D + c];
-
-  for (int t0 = 0; t0 < count; t0 += TE) {
-    const int nrow = min(TE, count - t0);
-#pragma unroll
-    for (int k = 0; k < CPT; ++k) {
-      const int row = row0 + k * RSTEP;
-      *reinterpret_cast<float4*>(Et_s + row * LD + li * 4) = rt[k].get();
-      *reinterpret_cast<float4*>(Eh_s + row * LD + li * 4) = rh[k].get();
-    }
-    if (t0 + TE < count) {
-      load_rows();
-      load_ids(t0 + 2 * TE);
-    }
-    __syncthreads();
-    for (int blk = wave; blk < NCB * NEB; blk += 4) {
-      const int cb = blk % NCB, eb = blk / NCB;
-      floatx16 accA = {0}, accB = {0};
-      mfma_dual_kcont<D>(Wr_s + cb * 32 * LD, LD, Et_s + eb * 32 * LD, Eh_s + eb * 32 * LD, LD, accA, accB);
-      float p = 0.f;
-#pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const int c = cb * 32 + acc_row(v, lane);
-        p = fmaf(accA[v], fast_tanh(accB[v] + er_s[c]), p);
-      }
-      part[(cb * 2 + (lane >> 5)) * TE + eb * 32 + (lane & 31)] = p;
-    }
-    __syncthreads();
-    if (tid < nrow) {
-      float s = 0.f;
-#pragma unroll
-      for (int k = 0; k < NP; ++k) s += part[k * TE + tid];
-      s_out[r_eid[start + t0 + tid]] = s;
-    }
-  }
-}
-
-
-// ------------------------------------------------- scores, wave-independent form ----
 // Half of one activation row (D/2 consecutive elements) as a lane fetched it: raw
 // words plus the group's (min, scale); dequantised (Eq. 4) only when consumed, so a
 // prefetched row costs D/2 * bits / 32 registers.
@@ -314,101 +197,6 @@ struct HalfRow {
   }
 };
 
-// One wave owns 32 relation-order edges end to end: it fetches (and dequantises) the
-// two rows of each edge straight into MFMA operand registers -- lane l holds elements
-// [32*(l/32), +D/2) of the tail and head rows of edge l%32 -- multiplies them with all
-// of W_r (shared through LDS, the only shared state), and reduces a . tanh(b) inside
-// the wave.  No workgroup barrier after W_r is staged; the rows of the wave's next
-// 32 edges are in flight while the current ones are multiplied.  D = 32 or 64.
-template <int D, int BITS>
-__global__ __launch_bounds__(kThreads) void score_wave_kernel(Source src, const float* __restrict__ Wr,
-                                                              const float* __restrict__ er,
-                                                              const int32_t* __restrict__ r_head,
-                                                              const int32_t* __restrict__ r_tail,
-                                                              const int32_t* __restrict__ r_eid,
-                                                              ChunkList chunks, float* __restrict__ s_out) {
-  constexpr int LD = D + 4, LPR = D / 4, KH = D / 2, NCB = D / 32;
-  float* Wr_s = reinterpret_cast<float*>(smem_raw);
-  float* er_s = Wr_s + D * LD;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int ch = blockIdx.x;
-  const int rel = chunks.rel[ch], start = chunks.start[ch], count = chunks.count[ch];
-  const int r = lane & 31, hh = lane >> 5;
-  const int n_wt = (count + 31) >> 5;   // 32-edge wave tiles of this chunk
-  int wt = wave;
-
-  int t_nx = 0, h_nx = 0, e_nx = -1;    // edge of the tile whose rows are fetched next
-  auto load_idx = [&](int tile) {
-    const int row = tile * 32 + r;
-    t_nx = 0; h_nx = 0; e_nx = -1;      // past the end: node 0 (a valid row), no store
-    if (row < count) { const int pos = start + row; t_nx = r_tail[pos]; h_nx = r_head[pos]; e_nx = r_eid[pos]; }
-  };
-  // the first tile's rows are requested before W_r is staged, so both latencies overlap
-  HalfRow<D, BITS> nt, nh;
-  load_idx(wt);
-  nt.load(src, t_nx, hh);
-  nh.load(src, h_nx, hh);
-  int e_cur = e_nx;
-  if (wt + 4 < n_wt) load_idx(wt + 4);
-
-  const float4* Wg = reinterpret_cast<const float4*>(Wr + (size_t)rel * D * D);
-  for (int q = tid; q < D * LPR; q += kThreads)
-    *reinterpret_cast<float4*>(Wr_s + (q / LPR) * LD + (q % LPR) * 4) = Wg[q];
-  for (int c = tid; c < D; c += kThreads) er_s[c] = er[(size_t)rel * D + c];
-  __syncthreads();
-  if (wt >= n_wt) return;
-
-  for (; wt < n_wt; wt += 4) {
-    float tv[KH], hv[KH];
-#pragma unroll
-    for (int i = 0; i < KH; ++i) { tv[i] = nt.get(i); hv[i] = nh.get(i); }
-    const int eid = e_cur;
-    if (wt + 4 < n_wt) {                // rows of the next tile: in flight during the MFMAs
-      nt.load(src, t_nx, hh);
-      nh.load(src, h_nx, hh);
-      e_cur = e_nx;
-      if (wt + 8 < n_wt) load_idx(wt + 8);
-    }
-    floatx16 accA[NCB], accB[NCB];
-#pragma unroll
-    for (int cb = 0; cb < NCB; ++cb) {
-      accA[cb] = floatx16{0};
-#pragma unroll
-      for (int v = 0; v < 16; ++v) accB[cb][v] = er_s[cb * 32 + acc_row(v, lane)];   // b starts from e_r
-    }
-    // W_r is re-read from LDS for every tile (the opaque zero keeps the compiler from
-    // parking all of it in registers, which would halve the waves per SIMD)
-    int wofs = 0;
-    asm volatile("" : "+v"(wofs));
-    const float* wrow = Wr_s + r * LD + hh * KH + wofs;
-#pragma unroll
-    for (int s0 = 0; s0 < KH; s0 += 4) {
-#pragma unroll
-      for (int cb = 0; cb < NCB; ++cb) {
-        const float4 w4 = *reinterpret_cast<const float4*>(wrow + cb * 32 * LD + s0);
-        accA[cb] = __builtin_amdgcn_mfma_f32_32x32x2f32(w4.x, tv[s0 + 0], accA[cb], 0, 0, 0);
-        accB[cb] = __builtin_amdgcn_mfma_f32_32x32x2f32(w4.x, hv[s0 + 0], accB[cb], 0, 0, 0);
-        accA[cb] = __builtin_amdgcn_mfma_f32_32x32x2f32(w4.y, tv[s0 + 1], accA[cb], 0, 0, 0);
-        accB[cb] = __builtin_amdgcn_mfma_f32_32x32x2f32(w4.y, hv[s0 + 1], accB[cb], 0, 0, 0);
-        accA[cb] = __builtin_amdgcn_mfma_f32_32x32x2f32(w4.z, tv[s0 + 2], accA[cb], 0, 0, 0);
-        accB[cb] = __builtin_amdgcn_mfma_f32_32x32x2f32(w4.z, hv[s0 + 2], accB[cb], 0, 0, 0);
-        accA[cb] = __builtin_amdgcn_mfma_f32_32x32x2f32(w4.w, tv[s0 + 3], accA[cb], 0, 0, 0);
-        accB[cb] = __builtin_amdgcn_mfma_f32_32x32x2f32(w4.w, hv[s0 + 3], accB[cb], 0, 0, 0);
-      }
-    }
-    float p = 0.f;
-#pragma unroll
-    for (int cb = 0; cb < NCB; ++cb) {
-#pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        p = fmaf(accA[cb][v], fast_tanh(accB[cb][v]), p);
-      }
-    }
-    p += __shfl_xor(p, 32);
-    if (hh == 0 && eid >= 0) s_out[eid] = p;
-  }
-}
-
 // ---- fp32 products on the bf16 matrix cores -------------------------------------------
 // An fp32 number is the exact sum of three bfloat16 numbers (8 + 8 + 8 significant bits,
 // taken by truncation): x = h + m + l.  A product x y is then h h' + (h m' + m h') +
@@ -418,6 +206,7 @@ __global__ __launch_bounds__(kThreads) void score_wave_kernel(Source src, const 
 // fp32 accuracy.  The splitting is vector work (two subtractions, two masks and 1.5 byte
 // permutes per element) that overlaps with the matrix pipe.
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+
 
 union Bf16Frag {          // eight consecutive k-values of one operand row / column
   bf16x8 v;
@@ -485,7 +274,11 @@ __device__ __forceinline__ void stage_split_matrix(const float* __restrict__ W, 
 
 constexpr int kScoreWaves = 4;
 
-// score_wave_kernel with the two projections on the bf16 matrix cores.  Lane l = (r, hh)
+// Scores for d <= 64.  One wave owns 32 relation-order edges end to end: it fetches (and
+// dequantises) the two rows of each edge straight into operand registers, multiplies them
+// with all of W_r (split once per chunk into three bfloat16 matrices in LDS, the only shared
+// state) on the bf16 matrix cores and reduces a . tanh(b) inside the wave; no workgroup
+// barrier after W_r is staged.  Lane l = (r, hh)
 // holds elements [32 hh, +D/2) of both rows of edge r; MFMA number m of a row block takes
 // its elements [8 m, +8) -- the same permutation of the contraction index on the W_r side.
 // CODES (compressed rows whose group covers at least a row, so that a row has ONE (Z, scale)
@@ -659,7 +452,7 @@ __device__ __forceinline__ void store_codes4(const RawChunk<BITS>& c, uint16_t* 
                                               __builtin_amdgcn_perm(f3, f2, 0x07060302u));
 }
 
-// score_kernel on the bf16 matrix cores (d = 128).  Wave w of the four owns channel block w
+// Scores for d = 128, cooperative 32-edge tiles.  Wave w of the four owns channel block w
 // for the whole chunk and keeps its 32 x 128 block of W_r, split into the three bfloat16
 // pieces, in REGISTERS (96 per lane: one wave per SIMD and workgroup, so the registers are
 // there, and LDS -- which three pieces of the whole W_r would fill to two thirds -- holds only
@@ -2457,30 +2250,20 @@ template <int D, int BITS>
 tinykg_status launch_score(const tinykg_graph* g, Source src, const float* Wr, const float* er,
                            float* s, hipStream_t st) {
   if (g->n_chunks == 0) return TINYKG_OK;
-  [[maybe_unused]] constexpr int LD = D + 4;   // (the fp32-MFMA build sizes its LDS with it)
   ChunkList cl{g->chunk_rel, g->chunk_start, g->chunk_count};
   ProfileScope prof("score_kernel", st);
   if constexpr (D <= 64) {
-#ifdef TINYKG_FP32_MFMA_SCORES
-    const size_t smem = (size_t)(D * LD + D) * 4;
-    auto kern = score_wave_kernel<D, BITS>;
-#else
     const size_t smem = (size_t)3 * D * (D + 8) * 2 + (size_t)2 * D * 4;
     auto kern = score_split_kernel<D, BITS, false>;
     if constexpr (BITS != 32) {
       if ((4 << src.group_chunks_log2) >= D) kern = score_split_kernel<D, BITS, true>;   // one group per row
     }
-#endif
     tinykg_status rc = set_smem(kern, smem);
     if (rc != TINYKG_OK) return rc;
     hipLaunchKernelGGL(kern, dim3(g->n_chunks), dim3(kScoreWaves * 64), smem, st, src, Wr, er, g->r_head,
                        g->r_tail, g->r_eid, cl, s);
   } else {
     constexpr int TE = 32;
-#ifdef TINYKG_FP32_MFMA_SCORES
-    const size_t smem = (size_t)(D * LD + 2 * TE * LD + D + (D / 32) * 2 * TE) * 4;
-    auto kern = score_kernel<D, TE, BITS>;
-#else
     // (tile: three bfloat16 pieces per side, or one matrix of codes per side)
     size_t smem = (size_t)3 * 2 * TE * (D + 8) * 2 + (size_t)(2 * D + (D / 32) * 2 * TE + 4 * TE) * 4;
     auto kern = score_coop_split_kernel<D, TE, BITS, false>;
@@ -2490,7 +2273,6 @@ tinykg_status launch_score(const tinykg_graph* g, Source src, const float* Wr, c
         smem = (size_t)2 * TE * (D + 8) * 2 + (size_t)(2 * D + (D / 32) * 2 * TE + 4 * TE) * 4;
       }
     }
-#endif
     tinykg_status rc = set_smem(kern, smem);
     if (rc != TINYKG_OK) return rc;
     hipLaunchKernelGGL(kern, dim3(g->n_chunks), dim3(kThreads), smem, st, src, Wr, er, g->r_head,
@@ -2533,7 +2315,7 @@ tinykg_status launch_attend_fwd(const tinykg_graph* g, Source src, const float* 
 template <int D>
 tinykg_status fwd_impl(const tinykg_graph* g, const float* E, const float* Wr, const float* er,
                        const float* W, int d_out, float slope, int bits, int group, uint64_t seed,
-                       float* E_out, const tinykg_saved* sv, uint8_t* ws, hipStream_t st) {
+                       float* E_out, const tinykg_saved* sv, uint8_t* ws, hipStream_t st, bool uniform) {
   const int64_t N = g->n_nodes;
   const FwdWs L = fwd_layout(g, D);
   float* s = reinterpret_cast<float*>(ws + L.s);
@@ -2541,8 +2323,7 @@ tinykg_status fwd_impl(const tinykg_graph* g, const float* E, const float* Wr, c
   float* H = bits == 32 && keep_H ? reinterpret_cast<float*>(sv->packed_H) : reinterpret_cast<float*>(ws + L.H);
   Source src{reinterpret_cast<const uint8_t*>(E), nullptr, nullptr, 0};
   tinykg_status rc = TINYKG_OK;
-  const bool uniform = Wr == nullptr;     // pi = 1 / deg: the softmax of all-zero scores
-  if (uniform) {
+  if (uniform) {                          // pi = 1 / deg: the softmax of all-zero scores
     if (g->n_edges > 0) {
       ProfileScope prof("zero_scores_kernel", st);
       const int blocks = (int)std::min<int64_t>((g->n_edges + 255) / 256, (int64_t)num_cus() * 16);
@@ -2589,7 +2370,7 @@ template <int D, int BITS>
 tinykg_status bwd_impl(const tinykg_graph* g, const tinykg_saved* sv, const float* Wr,
                        const float* er, const float* W, int d_out, float slope, int group,
                        const float* gEout, float* gE, float* gWr, float* ger, float* gW,
-                       uint8_t* ws, hipStream_t st) {
+                       uint8_t* ws, hipStream_t st, bool uniform) {
   constexpr int TE = 32;   // edge tile of the d = 128 kernel
   constexpr int LD = D + 4;
   const int64_t N = g->n_nodes;
@@ -2607,7 +2388,7 @@ tinykg_status bwd_impl(const tinykg_graph* g, const tinykg_saved* sv, const floa
   Source srcH{sv->packed_H, sv->gmin_H, sv->gscale_H, gl2};
   tinykg_status rc = TINYKG_OK;
 
-  const bool uniform = Wr == nullptr;     // pi = 1 / deg: only the transposed sparse product is left
+  // (uniform: pi = 1 / deg, only the transposed sparse product is left)
   // H was not saved: rebuild it from E_hat (scores first), in the buffer that grad_H then
   // overwrites tile by tile (the dense kernel reads the rows of a tile before it writes them)
   const bool rebuild_H = sv->packed_H == nullptr;
@@ -2718,13 +2499,13 @@ template <int D>
 tinykg_status bwd_bits(int bits, const tinykg_graph* g, const tinykg_saved* sv, const float* Wr,
                        const float* er, const float* W, int d_out, float slope, int group,
                        const float* gEout, float* gE, float* gWr, float* ger, float* gW,
-                       uint8_t* ws, hipStream_t st) {
+                       uint8_t* ws, hipStream_t st, bool uniform) {
   switch (bits) {
-    case 1: return bwd_impl<D, 1>(g, sv, Wr, er, W, d_out, slope, group, gEout, gE, gWr, ger, gW, ws, st);
-    case 2: return bwd_impl<D, 2>(g, sv, Wr, er, W, d_out, slope, group, gEout, gE, gWr, ger, gW, ws, st);
-    case 4: return bwd_impl<D, 4>(g, sv, Wr, er, W, d_out, slope, group, gEout, gE, gWr, ger, gW, ws, st);
-    case 8: return bwd_impl<D, 8>(g, sv, Wr, er, W, d_out, slope, group, gEout, gE, gWr, ger, gW, ws, st);
-    case 32: return bwd_impl<D, 32>(g, sv, Wr, er, W, d_out, slope, group, gEout, gE, gWr, ger, gW, ws, st);
+    case 1: return bwd_impl<D, 1>(g, sv, Wr, er, W, d_out, slope, group, gEout, gE, gWr, ger, gW, ws, st, uniform);
+    case 2: return bwd_impl<D, 2>(g, sv, Wr, er, W, d_out, slope, group, gEout, gE, gWr, ger, gW, ws, st, uniform);
+    case 4: return bwd_impl<D, 4>(g, sv, Wr, er, W, d_out, slope, group, gEout, gE, gWr, ger, gW, ws, st, uniform);
+    case 8: return bwd_impl<D, 8>(g, sv, Wr, er, W, d_out, slope, group, gEout, gE, gWr, ger, gW, ws, st, uniform);
+    case 32: return bwd_impl<D, 32>(g, sv, Wr, er, W, d_out, slope, group, gEout, gE, gWr, ger, gW, ws, st, uniform);
   }
   return TINYKG_ERR_INVALID_ARG;
 }
@@ -2796,9 +2577,9 @@ tinykg_status tinykg_kg_aggregate_fwd(const tinykg_graph* g, const float* E, con
   hipStream_t st = (hipStream_t)stream;
   uint8_t* ws = static_cast<uint8_t*>(workspace);
   switch (d_in) {
-    case 32: return fwd_impl<32>(g, E, Wr, er, W, d_out, leaky_slope, bits, group, seed, E_out, saved, ws, st);
-    case 64: return fwd_impl<64>(g, E, Wr, er, W, d_out, leaky_slope, bits, group, seed, E_out, saved, ws, st);
-    case 128: return fwd_impl<128>(g, E, Wr, er, W, d_out, leaky_slope, bits, group, seed, E_out, saved, ws, st);
+    case 32: return fwd_impl<32>(g, E, Wr, er, W, d_out, leaky_slope, bits, group, seed, E_out, saved, ws, st, false);
+    case 64: return fwd_impl<64>(g, E, Wr, er, W, d_out, leaky_slope, bits, group, seed, E_out, saved, ws, st, false);
+    case 128: return fwd_impl<128>(g, E, Wr, er, W, d_out, leaky_slope, bits, group, seed, E_out, saved, ws, st, false);
   }
   return TINYKG_ERR_UNSUPPORTED;
 }
@@ -2824,9 +2605,9 @@ tinykg_status tinykg_kg_aggregate_bwd(const tinykg_graph* g, const tinykg_saved*
   hipStream_t st = (hipStream_t)stream;
   uint8_t* ws = static_cast<uint8_t*>(workspace);
   switch (d_in) {
-    case 32: return bwd_bits<32>(bits, g, saved, Wr, er, W, d_out, leaky_slope, group, grad_E_out, grad_E, grad_Wr, grad_er, grad_W, ws, st);
-    case 64: return bwd_bits<64>(bits, g, saved, Wr, er, W, d_out, leaky_slope, group, grad_E_out, grad_E, grad_Wr, grad_er, grad_W, ws, st);
-    case 128: return bwd_bits<128>(bits, g, saved, Wr, er, W, d_out, leaky_slope, group, grad_E_out, grad_E, grad_Wr, grad_er, grad_W, ws, st);
+    case 32: return bwd_bits<32>(bits, g, saved, Wr, er, W, d_out, leaky_slope, group, grad_E_out, grad_E, grad_Wr, grad_er, grad_W, ws, st, false);
+    case 64: return bwd_bits<64>(bits, g, saved, Wr, er, W, d_out, leaky_slope, group, grad_E_out, grad_E, grad_Wr, grad_er, grad_W, ws, st, false);
+    case 128: return bwd_bits<128>(bits, g, saved, Wr, er, W, d_out, leaky_slope, group, grad_E_out, grad_E, grad_Wr, grad_er, grad_W, ws, st, false);
   }
   return TINYKG_ERR_UNSUPPORTED;
 }
@@ -2847,9 +2628,9 @@ tinykg_status tinykg_kg_uniform_fwd(const tinykg_graph* g, const float* E, const
   hipStream_t st = (hipStream_t)stream;
   uint8_t* ws = static_cast<uint8_t*>(workspace);
   switch (d_in) {
-    case 32: return fwd_impl<32>(g, E, nullptr, nullptr, W, d_out, leaky_slope, bits, group, seed, E_out, saved, ws, st);
-    case 64: return fwd_impl<64>(g, E, nullptr, nullptr, W, d_out, leaky_slope, bits, group, seed, E_out, saved, ws, st);
-    case 128: return fwd_impl<128>(g, E, nullptr, nullptr, W, d_out, leaky_slope, bits, group, seed, E_out, saved, ws, st);
+    case 32: return fwd_impl<32>(g, E, nullptr, nullptr, W, d_out, leaky_slope, bits, group, seed, E_out, saved, ws, st, true);
+    case 64: return fwd_impl<64>(g, E, nullptr, nullptr, W, d_out, leaky_slope, bits, group, seed, E_out, saved, ws, st, true);
+    case 128: return fwd_impl<128>(g, E, nullptr, nullptr, W, d_out, leaky_slope, bits, group, seed, E_out, saved, ws, st, true);
   }
   return TINYKG_ERR_UNSUPPORTED;
 }
@@ -2870,9 +2651,9 @@ tinykg_status tinykg_kg_uniform_bwd(const tinykg_graph* g, const tinykg_saved* s
   hipStream_t st = (hipStream_t)stream;
   uint8_t* ws = static_cast<uint8_t*>(workspace);
   switch (d_in) {
-    case 32: return bwd_bits<32>(bits, g, saved, nullptr, nullptr, W, d_out, leaky_slope, group, grad_E_out, grad_E, nullptr, nullptr, grad_W, ws, st);
-    case 64: return bwd_bits<64>(bits, g, saved, nullptr, nullptr, W, d_out, leaky_slope, group, grad_E_out, grad_E, nullptr, nullptr, grad_W, ws, st);
-    case 128: return bwd_bits<128>(bits, g, saved, nullptr, nullptr, W, d_out, leaky_slope, group, grad_E_out, grad_E, nullptr, nullptr, grad_W, ws, st);
+    case 32: return bwd_bits<32>(bits, g, saved, nullptr, nullptr, W, d_out, leaky_slope, group, grad_E_out, grad_E, nullptr, nullptr, grad_W, ws, st, true);
+    case 64: return bwd_bits<64>(bits, g, saved, nullptr, nullptr, W, d_out, leaky_slope, group, grad_E_out, grad_E, nullptr, nullptr, grad_W, ws, st, true);
+    case 128: return bwd_bits<128>(bits, g, saved, nullptr, nullptr, W, d_out, leaky_slope, group, grad_E_out, grad_E, nullptr, nullptr, grad_W, ws, st, true);
   }
   return TINYKG_ERR_UNSUPPORTED;
 }

@@ -108,6 +108,20 @@ __global__ void scatter_add_rows_kernel(const float* __restrict__ src, int d, co
     unsafeAtomicAdd(dst + (int64_t)idx[q / d] * d + q % d, src[q]);
 }
 
+// ids[0..3b) = users | pos | neg; slot[i] = i: the sampled nodes of a batch as one id list for
+// the row gathers, and the positions of its three parts inside the gathered rows.
+__global__ __launch_bounds__(256) void readout_ids_kernel(const int32_t* __restrict__ users,
+                                                          const int32_t* __restrict__ pos,
+                                                          const int32_t* __restrict__ neg, int64_t batch,
+                                                          int32_t* __restrict__ ids, int32_t* __restrict__ slot) {
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < 3 * batch;
+       i += (int64_t)gridDim.x * blockDim.x) {
+    const int32_t* src = i < batch ? users : (i < 2 * batch ? pos : neg);
+    ids[i] = src[i % batch];
+    slot[i] = (int32_t)i;
+  }
+}
+
 }  // namespace
 }  // namespace tinykg
 
@@ -206,6 +220,19 @@ tinykg_status tinykg_bpr_grad(const float* E_l, int dim, int64_t n_nodes, const 
   ProfileScope prof("bpr_grad_kernel", st);
   hipLaunchKernelGGL(bpr_grad_kernel, dim3((unsigned)((batch + 3) / 4)), dim3(256), 0, st, E_l, dim,
                      users, pos, neg, coef, batch, grad);
+  return launch_status();
+}
+
+tinykg_status tinykg_readout_ids(const int32_t* users, const int32_t* pos, const int32_t* neg,
+                                 int64_t batch, int32_t* ids, int32_t* slot, void* stream) {
+  using namespace tinykg;
+  if (batch < 0 || 3 * batch >= ((int64_t)1 << 31)) return TINYKG_ERR_SHAPE;
+  if (batch == 0) return TINYKG_OK;
+  if (!users || !pos || !neg || !ids || !slot) return TINYKG_ERR_INVALID_ARG;
+  const int64_t want = (3 * batch + 255) / 256, cap = (int64_t)num_cus() * 16;
+  ProfileScope prof("readout_ids_kernel", (hipStream_t)stream);
+  hipLaunchKernelGGL(readout_ids_kernel, dim3((unsigned)(want < cap ? want : cap)), dim3(256), 0,
+                     (hipStream_t)stream, users, pos, neg, batch, ids, slot);
   return launch_status();
 }
 

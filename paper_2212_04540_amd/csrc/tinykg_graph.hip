@@ -20,10 +20,7 @@ namespace tinykg {
 namespace {
 
 // Time of a one-tail tile of the edge-level backward kernel (d <= 64) relative to an ordinary one.
-#ifndef TINYKG_ONE_TAIL_COST
-#define TINYKG_ONE_TAIL_COST 0.7
-#endif
-constexpr double kOneTailTileCost = TINYKG_ONE_TAIL_COST;
+constexpr double kOneTailTileCost = 0.7;
 
 template <typename T>
 tinykg_status upload(const std::vector<T>& v, T** out) {

@@ -48,10 +48,7 @@ constexpr int kWave = 64;
 constexpr int kElemsPerLane = 16;
 constexpr int kTileElems = kWave * kElemsPerLane;  // 1024 elements = 4 KiB of fp32
 constexpr int kWavesPerBlock = 4;
-#ifndef TINYKG_Q_TPW
-#define TINYKG_Q_TPW 1
-#endif
-constexpr int kTilesPerWave = TINYKG_Q_TPW;      // consecutive tiles handled by one wave
+constexpr int kTilesPerWave = 1;                   // consecutive tiles handled by one wave
 constexpr int kBlock = kWave * kWavesPerBlock;
 
 // ---- cross-lane exchange inside a DPP row (16 lanes) ------------------------

@@ -46,7 +46,7 @@ class KGStack:
     def forward(self, E0, params, seed, users, pos, neg):
         """params: list of (Wr, er, W) per layer.  Returns the loss tensor [1]."""
         batch = users.numel()
-        ids = torch.cat([users, pos, neg]).contiguous()
+        ids, slot = B.tinykg_readout_ids(users, pos, neg)
         self.sample_ids, self.batch = ids, batch
         self.rows = []
         self.acts = [E0] if self.keep_activations else None
@@ -60,8 +60,7 @@ class KGStack:
             if self.keep_activations:
                 self.acts.append(E)
         self.rows.append(B.tinykg_gather_rows(E, ids))
-        ar = torch.arange(batch, dtype=torch.int32, device=self.device)
-        self._u, self._p, self._n = ar, (ar + batch).contiguous(), (ar + 2 * batch).contiguous()
+        self._u, self._p, self._n = slot[:batch], slot[batch:2 * batch], slot[2 * batch:]
         self.loss, self.coef = B.tinykg_bpr_loss(self.rows, self._u, self._p, self._n)
         return self.loss
 

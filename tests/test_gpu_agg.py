@@ -12,14 +12,18 @@ Protocol (bit-exactness is only defined for identical inputs):
   6. the context without Q(H): same E_out, same Q(E) and mask bytes; backward against
      the oracle with H rebuilt from E_hat (the second stage of Eq. 2 run again)   (1e-5)
 Tolerance ("1e-5 relative" for fp32 tensors whose entries are sums):
-  |gpu - ref| <= 1e-5 * max(|ref|, rms(ref tensor), rms(ref row)),
-where a row is the vector of one node (last axis).  The row term is there because
-an entry of grad_E is a sum over all in-edges of its node: every term carries the
+  |gpu - ref| <= 1e-5 * max(|ref|, rms(ref tensor))                       every tensor but grad_E
+  |gpu - ref| <= 1e-5 * max(|ref|, rms(ref tensor), rms(ref row))         grad_E
+where a row is the vector of one node (last axis).  grad_E has the row term because
+an entry of it is a sum over all in-edges of its node: every term carries the
 fp32 rounding of its factors (pi_j, grad_H, both fp32 by the method's own choice of
 full-precision operators), so the reachable absolute error scales with the size of
 the terms of that node -- the row's scale -- and not with the entry itself, which
 cancellation can make arbitrarily small (a Zipf tail with 10^5 in-edges has row rms
-~50 and entries near 0).
+~50 and entries near 0).  Measured on the 100k-entity / 1M-triplet configuration
+(test_config1_full_size records it): the worst err / bound of grad_E is 1.9 without the row
+term (0.64 with an fp32 context) and 0.13 with it; every other tensor stays below 0.2 of
+the plain bound.
 """
 import numpy as np
 import pytest
@@ -42,19 +46,7 @@ def tk():
     return tk
 
 
-def close(got, want, what, tol=1e-5):
-    got = got.cpu().numpy().astype(np.float64) if hasattr(got, "cpu") else np.asarray(got, np.float64)
-    want = np.asarray(want, np.float64)
-    assert got.shape == want.shape, f"{what}: shape {got.shape} vs {want.shape}"
-    scale = np.sqrt(np.mean(want ** 2)) if want.size else 0.0
-    row = np.sqrt(np.mean(want ** 2, axis=-1, keepdims=True)) if want.ndim >= 2 else 0.0
-    bound = tol * np.maximum(np.maximum(np.abs(want), scale), row)
-    err = np.abs(got - want)
-    if not np.all(err <= bound):
-        i = np.unravel_index(np.argmax(err - bound), err.shape)
-        raise AssertionError(f"{what}: worst at {i}: got {got[i]!r} want {want[i]!r} "
-                             f"(err {err[i]:.3e}, bound {bound[i]:.3e}); "
-                             f"{np.count_nonzero(err > bound)} of {err.size} out of tolerance")
+from parity import MARGINS, close  # noqa: E402
 
 
 class Layer:
@@ -104,9 +96,10 @@ class Layer:
 
 
 def run_protocol(tk, N, R, head, rel, tail, d, dout, bits, group, seed=5, data_seed=0, threads=4,
-                 e_std=0.1, e_shift=0.0, tol=1e-5, tol_Wr=None):
+                 e_std=0.1, e_shift=0.0, tol=1e-5, tol_Wr=None, er_std=0.1, case=None):
+    """case: a name under which the worst err / bound ratios of every tensor are recorded."""
     E = gen.entity_embeddings(N, d, seed=data_seed + 1, std=e_std) + np.float32(e_shift)
-    Wr, er, W = gen.layer_params(R, d, d, dout, seed=data_seed + 2)
+    Wr, er, W = gen.layer_params(R, d, d, dout, seed=data_seed + 2, er_std=er_std)
     G = gen.upstream_grad(N, dout, seed=data_seed + 3)
     L = Layer(tk, N, R, head, rel, tail, E, Wr, er, W, G)
     h = L.host
@@ -115,8 +108,8 @@ def run_protocol(tk, N, R, head, rel, tail, d, dout, bits, group, seed=5, data_s
     Eo32, sv32 = L.forward(32, group, seed)
     ctx32 = L.saved_to_host(sv32)
     wEo, wH, wmask = ref.aggregate_fwd(N, head, rel, tail, E, Wr, er, W, SLOPE, threads=threads)
-    close(Eo32, wEo, "E_out", tol=tol)                                           # (2)
-    close(ctx32["H"], wH, "H", tol=tol)
+    close(Eo32, wEo, "E_out", tol=tol, row_term=False, case=case)                # (2)
+    close(ctx32["H"], wH, "H", tol=tol, row_term=False, case=case)
     assert np.array_equal(ctx32["E"].view(np.uint32), E.view(np.uint32))
     gmask = ref.unpack(ctx32["mask"], N * dout, 1).reshape(N, dout)
     Eo_host = Eo32.cpu().numpy()
@@ -144,7 +137,8 @@ def run_protocol(tk, N, R, head, rel, tail, d, dout, bits, group, seed=5, data_s
         Eh, Hh, mk = ref.restore_context(c, N, d, dout)
         want = ref.aggregate_bwd(N, head, rel, tail, Eh, Hh, mk, Wr, er, W, SLOPE, G, threads=threads)
         for a, w, nm in zip(grads, want, ("grad_E", "grad_Wr", "grad_er", "grad_W")):
-            close(a, w, f"{nm} (bits={b})", tol=tol_Wr if (tol_Wr and nm == "grad_Wr") else tol)
+            close(a, w, f"{nm} (bits={b})", tol=tol_Wr if (tol_Wr and nm == "grad_Wr") else tol,
+                  row_term=nm == "grad_E", case=case)
     # the context without Q(H)                                                   # (6)
     for b, full in ((32, ctx32), (bits, ctx)):
         Eo_r, sv_r = L.forward(b, group, seed, with_H=False)
@@ -160,7 +154,8 @@ def run_protocol(tk, N, R, head, rel, tail, d, dout, bits, group, seed=5, data_s
         Ht = ref.rebuild_H(N, head, rel, tail, Eh, Wr, er, W, SLOPE, threads=threads)
         want = ref.aggregate_bwd(N, head, rel, tail, Eh, Ht, mk, Wr, er, W, SLOPE, G, threads=threads)
         for a, w, nm in zip(grads, want, ("grad_E", "grad_Wr", "grad_er", "grad_W")):
-            close(a, w, f"{nm} (bits={b}, H rebuilt)", tol=tol_Wr if (tol_Wr and nm == "grad_Wr") else tol)
+            close(a, w, f"{nm} (bits={b}, H rebuilt)", tol=tol_Wr if (tol_Wr and nm == "grad_Wr") else tol,
+                  row_term=nm == "grad_E", case=case)
     L.graph.close()
     return L
 
@@ -172,7 +167,8 @@ def test_small_graph_all_shapes(tk, d, dout, bits, group):
     # several node tiles and edge tiles with ragged tails: 333 nodes -> pad so N*d % group == 0
     N, R, T = 336, 5, 3000
     head, rel, tail = gen.kg_triplets(N, R, T, seed=d + dout)
-    run_protocol(tk, N, R, head, rel, tail, d, dout, bits, group, data_seed=d)
+    run_protocol(tk, N, R, head, rel, tail, d, dout, bits, group, data_seed=d,
+                 case=f"small d={d} dout={dout} INT{bits}/G{group}")
 
 
 def test_ten_node_graph(tk):
@@ -193,6 +189,17 @@ def test_tiny_embeddings(tk, d, bits, group, e_std):
     N, R, T = 336, 5, 3000
     head, rel, tail = gen.kg_triplets(N, R, T, seed=17)
     run_protocol(tk, N, R, head, rel, tail, d, d, bits, group, data_seed=3, e_std=e_std)
+
+
+@pytest.mark.parametrize("d,bits,group", [(64, 2, 64), (128, 4, 128), (32, 8, 32)])
+def test_small_arguments_of_tanh(tk, d, bits, group):
+    # E and e_r both ~1e-3: every b = W_r e_h + e_r is ~1e-3, where tanh(b) ~ b and an
+    # evaluation that is accurate only in absolute terms would lose the leading digits of
+    # grad_a = grad_s tanh(b) (and of the grad_a e_t^T half of grad_W_r)
+    N, R, T = 336, 5, 3000
+    head, rel, tail = gen.kg_triplets(N, R, T, seed=23)
+    run_protocol(tk, N, R, head, rel, tail, d, d, bits, group, data_seed=7, e_std=1e-3, er_std=1e-3,
+                 case=f"tanh near 0, d={d}")
 
 
 @pytest.mark.parametrize("d,bits,group,e_std,e_shift", [(64, 2, 64, 0.2, 2.0), (64, 8, 32, 0.3, -2.0),
@@ -225,6 +232,9 @@ def test_no_edges_and_isolated_nodes(tk):
     # H = E when nothing is aggregated
     one = np.array([3], dtype=np.int32)
     run_protocol(tk, N, R, one, np.array([2], np.int32), np.array([60], np.int32), 64, 32, 2, 64)
+    # no relations at all (W_r, e_r are empty: NULL pointers at the boundary); step (6) of the
+    # protocol then rebuilds H from the Q(E) that the forward call must have saved all the same
+    run_protocol(tk, N, 0, empty, empty, empty, 64, 64, 2, 64)
 
 
 def test_hot_tail_hot_head_and_empty_relations(tk):
@@ -308,4 +318,8 @@ def test_config1_full_size(tk):
     # 100k entities, dim 64, 16 relations, 1M triplets, Zipf(1.1) tails, INT2 / group 64
     N, R, T, d = 100_000, 16, 1_000_000, 64
     head, rel, tail = gen.kg_triplets(N, R, T, seed=0, tail_zipf=1.1)
-    run_protocol(tk, N, R, head, rel, tail, d, d, 2, 64, seed=1, threads=ref.default_threads())
+    run_protocol(tk, N, R, head, rel, tail, d, d, 2, 64, seed=1, threads=ref.default_threads(), case="configs[1]")
+    # on record: grad_E sits within a factor of a few of the plain bound and well inside the row bound
+    for key, m in MARGINS.items():
+        if key.startswith("configs[1] | grad_E"):
+            assert m["row"] <= 0.5 and m["entry"] <= 4.0, (key, m)

@@ -10,7 +10,7 @@ torch = pytest.importorskip("torch")
 
 from oracle import ref
 from workloads import gen
-from test_gpu_agg import close
+from parity import close
 
 pytestmark = pytest.mark.gpu
 

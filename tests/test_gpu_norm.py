@@ -11,7 +11,7 @@ import pytest
 torch = pytest.importorskip("torch")
 
 from oracle import ref
-from test_gpu_agg import close
+from parity import close
 
 pytestmark = pytest.mark.gpu
 

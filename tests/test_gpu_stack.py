@@ -1,7 +1,7 @@
 """GPU parity of the multi-layer composition (forward through the layers, readout +
 ranking loss, backward), stage by stage: each stage of the oracle is fed what the GPU
 fed to the same stage (the GPU's own layer inputs, saved bytes, incoming gradients), so
-every comparison has identical inputs.  Tolerance as in test_gpu_agg.py."""
+every comparison has identical inputs.  Tolerance as in test_gpu_agg.py (row term for grad_E only)."""
 import numpy as np
 import pytest
 
@@ -9,7 +9,7 @@ torch = pytest.importorskip("torch")
 
 from oracle import ref
 from workloads import gen
-from test_gpu_agg import close
+from parity import close
 
 pytestmark = pytest.mark.gpu
 SLOPE = 0.2
@@ -25,7 +25,7 @@ def tk():
 
 
 def run_stack(tk, N, R, head, rel, tail, dims, bits, group, batch, seed=3, threads=4, sample_hi=None,
-              save_H=True):
+              save_H=True, case=None):
     dev = "cuda"
     rng = np.random.default_rng(5)
     E0 = gen.entity_embeddings(N, dims[0], seed=1, std=0.1)
@@ -54,7 +54,7 @@ def run_stack(tk, N, R, head, rel, tail, dims, bits, group, batch, seed=3, threa
     acts = [a.cpu().numpy() for a in stack.acts]
     for l in range(L):
         wEo, wH, wmask = ref.aggregate_fwd(N, head, rel, tail, acts[l], *params[l], SLOPE, threads=threads)
-        close(acts[l + 1], wEo, f"E^({l + 1})")
+        close(acts[l + 1], wEo, f"E^({l + 1})", row_term=False, case=case)
         sv = stack.saved[l]
         wp, wmn, wsc = ref.quantize(acts[l], bits, group, seed + 2 * l)
         assert np.array_equal(sv.packed_E.cpu().numpy(), wp), f"layer {l}: Q(E) differs"
@@ -65,11 +65,11 @@ def run_stack(tk, N, R, head, rel, tail, dims, bits, group, batch, seed=3, threa
         assert np.array_equal(stack.rows[l].cpu().numpy(), acts[l][ids])
     wloss, wcoef, _ = ref.bpr_loss_grad(acts, users, pos, neg)
     assert abs(float(loss.cpu()[0]) - wloss) <= 1e-5 * abs(wloss)
-    close(stack.coef[:batch], wcoef, "coef")
+    close(stack.coef[:batch], wcoef, "coef", row_term=False)
     # backward, layer by layer, from the GPU's own incoming gradient and saved bytes
     _, _, rgrads = ref.bpr_loss_grad(acts, users, pos, neg)
     g = [x.cpu().numpy() for x in layer_grads]
-    close(g[L], rgrads[L], f"grad_E^({L})")
+    close(g[L], rgrads[L], f"grad_E^({L})", case=case)
     for l in range(L - 1, -1, -1):
         sv = stack.saved[l]
         ctx = {"bits": bits, "group": group, "mask": sv.mask_J.cpu().numpy(),
@@ -83,9 +83,9 @@ def run_stack(tk, N, R, head, rel, tail, dims, bits, group, batch, seed=3, threa
             Hh = ref.rebuild_H(N, head, rel, tail, Eh, *params[l], SLOPE, threads=threads)
         wgE, wgWr, wger, wgW = ref.aggregate_bwd_f64(N, head, rel, tail, Eh, Hh, mk, *params[l],
                                                      float(np.float32(SLOPE)), g[l + 1], threads=threads)
-        close(g[l], wgE + rgrads[l], f"grad_E^({l})")
+        close(g[l], wgE + rgrads[l], f"grad_E^({l})", case=case)
         for a, w, nm in zip(pgrads[l], (wgWr, wger, wgW), ("grad_Wr", "grad_er", "grad_W")):
-            close(a, w, f"{nm} layer {l}")
+            close(a, w, f"{nm} layer {l}", row_term=False, case=case)
     graph.close()
     return stack
 
@@ -121,10 +121,10 @@ def test_small_stack_end_to_end_against_the_oracle_chain(tk):
     layer_grads, pgrads = stack.backward(tp)
     torch.cuda.synchronize()
     assert abs(float(loss.cpu()[0]) - want["loss"]) <= 1e-5 * want["loss"]
-    close(layer_grads[0], want["layer_grads"][0], "grad_E0", tol=1e-4)
+    close(layer_grads[0], want["layer_grads"][0], "grad_E0", tol=1e-4, case="end to end (bound 1e-4)")
     for l in range(2):
         for a, w, nm in zip(pgrads[l], want["param_grads"][l], ("grad_Wr", "grad_er", "grad_W")):
-            close(a, w, f"{nm} layer {l}", tol=1e-4)
+            close(a, w, f"{nm} layer {l}", tol=1e-4, row_term=False, case="end to end (bound 1e-4)")
     graph.close()
 
 
@@ -136,7 +136,7 @@ def test_config3_user_item_entity_graph(tk):
     head, rel, tail = gen.user_item_entity_graph(nu, ni, na, 40, 3_000_000, 850_000, seed=0, zipf=1.2)
     N = nu + ni + na
     stack = run_stack(tk, N, 42, head, rel, tail, [64, 64, 32, 16], 2, 64, batch=4096,
-                      threads=ref.default_threads(), sample_hi=nu + ni)
+                      threads=ref.default_threads(), sample_hi=nu + ni, case="configs[3]")
     ratio = stack.fp32_context_bytes() / stack.saved_context_bytes()
     assert 9.0 < ratio < 10.7          # 10.67x on E and H, less the uncompressed 1-bit masks
 
@@ -147,6 +147,6 @@ def test_config4_at_one_hundredth_scale(tk):
     N, R, T = 200_000, 60, 1_500_000
     head, rel, tail = gen.kg_triplets(N, R, T, seed=0, tail_zipf=1.05)
     stack = run_stack(tk, N, R, head, rel, tail, [128, 128, 128], 4, 128, batch=4096,
-                      threads=ref.default_threads())
+                      threads=ref.default_threads(), case="configs[4]/100")
     ratio = stack.fp32_context_bytes() / stack.saved_context_bytes()
     assert 6.4 < ratio < 7.2           # 7.11x on E and H, less the 1-bit masks (6.5x overall)

@@ -8,7 +8,7 @@ import pytest
 torch = pytest.importorskip("torch")
 
 from oracle import ref
-from tests.test_gpu_agg import close
+from parity import close
 from workloads import gen
 
 pytestmark = pytest.mark.gpu

@@ -55,13 +55,13 @@ def kg_triplets(n_nodes, n_rel, n_edges, seed=0, tail_zipf=1.1, head_zipf=None):
     return head, rel, tail
 
 
-def layer_params(n_rel, d_in, d_rel, d_out, seed=0):
+def layer_params(n_rel, d_in, d_rel, d_out, seed=0, er_std=0.1):
     """W_r[R, d_rel, d_in], e_r[R, d_rel], W[d_out, d_in]: N(0, 1/d_in) weights,
-    N(0, 0.1^2) relation embeddings."""
+    N(0, er_std^2) relation embeddings (0.1 in every workload)."""
     rng = np.random.default_rng(seed)
     s = np.float32(1.0 / np.sqrt(d_in))
     Wr = rng.standard_normal((n_rel, d_rel, d_in), dtype=np.float32) * s
-    er = rng.standard_normal((n_rel, d_rel), dtype=np.float32) * np.float32(0.1)
+    er = rng.standard_normal((n_rel, d_rel), dtype=np.float32) * np.float32(er_std)
     W = rng.standard_normal((d_out, d_in), dtype=np.float32) * s
     return Wr.astype(np.float32), er.astype(np.float32), W.astype(np.float32)
 

@@ -307,6 +307,22 @@ tinykg_status tinykg_batchnorm_bwd(const uint8_t* packed, const float* gmin, con
                                    float* grad_x, float* grad_gamma, float* grad_beta,
                                    void* workspace, size_t workspace_bytes, void* stream);
 
+/* tinykg_batchnorm_bwd for callers that cannot allocate device memory or bring a
+ * workspace: code under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  Same arguments (without the workspace pair), same kernels, same results bit
+ * for bit.  The partial column sums and the coefficient table live in a fixed array of
+ * 4 MiB + 2 KiB of device memory inside the library's code object (each GPU the library
+ * runs on holds its own copy until the process ends), so dim is limited to 128: a larger
+ * dim returns TINYKG_ERR_UNSUPPORTED and writes nothing.  The call allocates and frees
+ * nothing, creates no event (the measurement hooks below ignore it) and clears nothing: every
+ * scratch word it reads was written earlier in the same call.  All calls on one GPU share that
+ * array: calls that may overlap on one GPU (different streams, or threads) race and must be
+ * serialised by the caller; calls on one stream are ordered by the stream. */
+tinykg_status tinykg_batchnorm_bwd_static(const uint8_t* packed, const float* gmin, const float* gscale,
+                                          const float* mean, const float* rstd, const float* gamma,
+                                          int64_t rows, int dim, int bits, int group, const float* grad_y,
+                                          float* grad_x, float* grad_gamma, float* grad_beta, void* stream);
+
 /* ------------------------------------------------------------------------- *
  * Measurement hooks (not part of the method): when enabled, every kernel launch
  * made by the entry points above is bracketed by a pair of HIP events recorded

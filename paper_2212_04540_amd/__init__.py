@@ -11,5 +11,5 @@ from .binding import (tinykg_bpr_grad, tinykg_bpr_loss, tinykg_gather_rows,  # n
                       tinykg_kg_uniform_bwd, tinykg_kg_uniform_fwd,
                       tinykg_num_groups, tinykg_packed_bytes, tinykg_profile_copy, tinykg_profile_enable,
                       tinykg_profile_report, tinykg_profile_select, tinykg_quantize, tinykg_quantize_bf16,
-                      NormContext, tinykg_batchnorm_fwd, tinykg_batchnorm_bwd, tinykg_readout_ids, tinykg_kg_max_fwd, tinykg_kg_max_bwd)
+                      NormContext, tinykg_batchnorm_fwd, tinykg_batchnorm_bwd, tinykg_batchnorm_bwd_static, tinykg_readout_ids, tinykg_kg_max_fwd, tinykg_kg_max_bwd)
 from .stack import KGStack  # noqa: F401,E402

@@ -25,7 +25,7 @@ EXPORTS = [
     "tinykg_kg_uniform_bwd", "tinykg_profile_enable", "tinykg_profile_select",
     "tinykg_profile_report", "tinykg_profile_copy", "tinykg_bpr_loss", "tinykg_bpr_grad",
     "tinykg_gather_rows", "tinykg_scatter_add_rows", "tinykg_fill_zero", "tinykg_readout_ids",
-    "tinykg_batchnorm_workspace_bytes", "tinykg_batchnorm_fwd", "tinykg_batchnorm_bwd",
+    "tinykg_batchnorm_workspace_bytes", "tinykg_batchnorm_fwd", "tinykg_batchnorm_bwd", "tinykg_batchnorm_bwd_static",
     "tinykg_kg_max_arg_bytes", "tinykg_kg_max_workspace_bytes", "tinykg_kg_max_fwd", "tinykg_kg_max_bwd",
 ]
 
@@ -105,6 +105,7 @@ def lib():
                                            vp, sz, vp]
         L.tinykg_batchnorm_bwd.argtypes = [vp, vp, vp, vp, vp, vp, i64, i32, i32, i32, vp, vp, vp, vp, vp, sz,
                                            vp]
+        L.tinykg_batchnorm_bwd_static.argtypes = [vp, vp, vp, vp, vp, vp, i64, i32, i32, i32, vp, vp, vp, vp, vp]
         _lib = L
     return _lib
 
@@ -449,6 +450,21 @@ def tinykg_batchnorm_bwd(ctx, gamma, grad_y, out=None):
                                     _ptr(grad_y), _ptr(gx), _ptr(gg), _ptr(gb), _ptr(ctx.ws), ctx.ws.numel(),
                                     _stream())
     _ok(st, "tinykg_batchnorm_bwd")
+    return gx, gg, gb
+
+
+def tinykg_batchnorm_bwd_static(ctx, gamma, grad_y, out):
+    """tinykg_batchnorm_bwd without a workspace (the library's fixed scratch array; dim <= 128).
+    `out` = (grad_x, grad_gamma, grad_beta), allocated by the caller: nothing is allocated here."""
+    _dev(gamma, torch.float32, "gamma")
+    _dev(grad_y, torch.float32, "grad_y")
+    gx, gg, gb = out
+    for t, nm in ((gx, "grad_x"), (gg, "grad_gamma"), (gb, "grad_beta")):
+        _dev(t, torch.float32, nm)
+    st = lib().tinykg_batchnorm_bwd_static(_ptr(ctx.packed), _ptr(ctx.gmin), _ptr(ctx.gscale), _ptr(ctx.mean),
+                                           _ptr(ctx.rstd), _ptr(gamma), ctx.rows, ctx.dim, ctx.bits, ctx.group,
+                                           _ptr(grad_y), _ptr(gx), _ptr(gg), _ptr(gb), _stream())
+    _ok(st, "tinykg_batchnorm_bwd_static")
     return gx, gg, gb
 
 

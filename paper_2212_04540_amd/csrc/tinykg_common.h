@@ -56,5 +56,16 @@ class ProfileScope {
   hipStream_t st_;
 };
 
+// While one is alive (on this thread's call path: the recorder is not thread-safe) no
+// ProfileScope records anything, so the entry points that must not allocate never create an
+// event even with tinykg_profile_enable(1) in effect.
+class ProfileMute {
+ public:
+  ProfileMute();
+  ~ProfileMute();
+  ProfileMute(const ProfileMute&) = delete;
+  ProfileMute& operator=(const ProfileMute&) = delete;
+};
+
 }  // namespace tinykg
 #endif

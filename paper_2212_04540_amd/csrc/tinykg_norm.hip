@@ -17,6 +17,7 @@
 #include "tinykg_fetch.h"
 
 #include <algorithm>
+#include <atomic>
 
 namespace tinykg {
 
@@ -330,6 +331,65 @@ tinykg_status bwd_impl(Source src, const float* mean, const float* rstd, const f
   return launch_status();
 }
 
+// Argument checks and dispatch shared by tinykg_batchnorm_bwd and its static-scratch variant
+// (shape and bits / group already checked; ws holds norm_layout(dim).total bytes).
+tinykg_status batchnorm_bwd_body(const uint8_t* packed, const float* gmin, const float* gscale,
+                                 const float* mean, const float* rstd, const float* gamma, int64_t rows,
+                                 int dim, int bits, int group, const float* grad_y, float* grad_x,
+                                 float* grad_gamma, float* grad_beta, uint8_t* ws, hipStream_t st) {
+  tinykg_status rc;
+  if (!mean || !rstd || !gamma || !grad_gamma || !grad_beta) return TINYKG_ERR_INVALID_ARG;
+  if (!aligned16(mean) || !aligned16(rstd) || !aligned16(gamma) || !aligned16(grad_gamma) ||
+      !aligned16(grad_beta))
+    return TINYKG_ERR_INVALID_ARG;
+  if (rows == 0) {   // empty sums
+    if ((rc = tinykg_fill_zero(grad_gamma, dim, st)) != TINYKG_OK) return rc;
+    return tinykg_fill_zero(grad_beta, dim, st);
+  }
+  if (!packed || !grad_y || !grad_x || !aligned16(packed) || !aligned16(grad_y) || !aligned16(grad_x))
+    return TINYKG_ERR_INVALID_ARG;
+  if (bits != 32 && (!gmin || !gscale || !aligned16(gmin) || !aligned16(gscale))) return TINYKG_ERR_INVALID_ARG;
+  const Source src{packed, gmin, gscale, bits == 32 ? 0 : ilog2i(group / 4)};
+  switch (bits) {
+    case 1: return bwd_impl<1>(src, mean, rstd, gamma, rows, dim, grad_y, grad_x, grad_gamma, grad_beta, ws, st);
+    case 2: return bwd_impl<2>(src, mean, rstd, gamma, rows, dim, grad_y, grad_x, grad_gamma, grad_beta, ws, st);
+    case 4: return bwd_impl<4>(src, mean, rstd, gamma, rows, dim, grad_y, grad_x, grad_gamma, grad_beta, ws, st);
+    case 8: return bwd_impl<8>(src, mean, rstd, gamma, rows, dim, grad_y, grad_x, grad_gamma, grad_beta, ws, st);
+    case 32: return bwd_impl<32>(src, mean, rstd, gamma, rows, dim, grad_y, grad_x, grad_gamma, grad_beta, ws, st);
+  }
+  return TINYKG_ERR_INVALID_ARG;
+}
+
+// Scratch of tinykg_batchnorm_bwd_static: the partial sums and the coefficient table of a
+// layer of at most kStaticMaxDim columns, in device memory that belongs to the library's code
+// object (every GPU that loads the library holds its own copy until the process ends).
+constexpr int kStaticMaxDim = 128;
+constexpr size_t kStaticScratchBytes =
+    (size_t)kMaxStatBlocks * 2 * kStaticMaxDim * sizeof(double) + (size_t)4 * kStaticMaxDim * sizeof(float);
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+// The array's address on the current device.  In host code the array's name only stands for
+// the symbol; its device address is asked for once per device (with that device current) and
+// kept.  Two threads racing here store the same value.
+constexpr int kMaxDevices = 64;
+std::atomic<void*> g_scratch_ptr[kMaxDevices];
+
+tinykg_status static_scratch(uint8_t** out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess) { (void)hipGetLastError(); return TINYKG_ERR_DEVICE; }
+  if (dev < 0 || dev >= kMaxDevices) return TINYKG_ERR_UNSUPPORTED;
+  void* p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+  if (!p) {
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) {
+      (void)hipGetLastError();
+      return TINYKG_ERR_DEVICE;
+    }
+    g_scratch_ptr[dev].store(p, std::memory_order_release);
+  }
+  *out = static_cast<uint8_t*>(p);
+  return TINYKG_OK;
+}
+
 }  // namespace
 
 }  // namespace tinykg
@@ -393,30 +453,24 @@ tinykg_status tinykg_batchnorm_bwd(const uint8_t* packed, const float* gmin, con
                                    size_t workspace_bytes, void* stream) {
   tinykg_status rc;
   if ((rc = check_norm(rows, dim, bits, group)) != TINYKG_OK) return rc;
-  if (!mean || !rstd || !gamma || !grad_gamma || !grad_beta) return TINYKG_ERR_INVALID_ARG;
-  if (!aligned16(mean) || !aligned16(rstd) || !aligned16(gamma) || !aligned16(grad_gamma) ||
-      !aligned16(grad_beta))
-    return TINYKG_ERR_INVALID_ARG;
   const NormWs L = norm_layout(dim);
   if (!workspace || !aligned16(workspace) || workspace_bytes < L.total) return TINYKG_ERR_WORKSPACE;
-  hipStream_t st = (hipStream_t)stream;
-  if (rows == 0) {   // empty sums
-    if ((rc = tinykg_fill_zero(grad_gamma, dim, stream)) != TINYKG_OK) return rc;
-    return tinykg_fill_zero(grad_beta, dim, stream);
-  }
-  if (!packed || !grad_y || !grad_x || !aligned16(packed) || !aligned16(grad_y) || !aligned16(grad_x))
-    return TINYKG_ERR_INVALID_ARG;
-  if (bits != 32 && (!gmin || !gscale || !aligned16(gmin) || !aligned16(gscale))) return TINYKG_ERR_INVALID_ARG;
-  uint8_t* ws = static_cast<uint8_t*>(workspace);
-  const Source src{packed, gmin, gscale, bits == 32 ? 0 : ilog2i(group / 4)};
-  switch (bits) {
-    case 1: return bwd_impl<1>(src, mean, rstd, gamma, rows, dim, grad_y, grad_x, grad_gamma, grad_beta, ws, st);
-    case 2: return bwd_impl<2>(src, mean, rstd, gamma, rows, dim, grad_y, grad_x, grad_gamma, grad_beta, ws, st);
-    case 4: return bwd_impl<4>(src, mean, rstd, gamma, rows, dim, grad_y, grad_x, grad_gamma, grad_beta, ws, st);
-    case 8: return bwd_impl<8>(src, mean, rstd, gamma, rows, dim, grad_y, grad_x, grad_gamma, grad_beta, ws, st);
-    case 32: return bwd_impl<32>(src, mean, rstd, gamma, rows, dim, grad_y, grad_x, grad_gamma, grad_beta, ws, st);
-  }
-  return TINYKG_ERR_INVALID_ARG;
+  return batchnorm_bwd_body(packed, gmin, gscale, mean, rstd, gamma, rows, dim, bits, group, grad_y, grad_x,
+                            grad_gamma, grad_beta, static_cast<uint8_t*>(workspace), (hipStream_t)stream);
+}
+
+tinykg_status tinykg_batchnorm_bwd_static(const uint8_t* packed, const float* gmin, const float* gscale,
+                                          const float* mean, const float* rstd, const float* gamma,
+                                          int64_t rows, int dim, int bits, int group, const float* grad_y,
+                                          float* grad_x, float* grad_gamma, float* grad_beta, void* stream) {
+  tinykg_status rc;
+  if ((rc = check_norm(rows, dim, bits, group)) != TINYKG_OK) return rc;
+  if (dim > kStaticMaxDim || norm_layout(dim).total > kStaticScratchBytes) return TINYKG_ERR_UNSUPPORTED;
+  uint8_t* ws = nullptr;
+  if ((rc = static_scratch(&ws)) != TINYKG_OK) return rc;
+  ProfileMute mute;   // no event is created or recorded on this path
+  return batchnorm_bwd_body(packed, gmin, gscale, mean, rstd, gamma, rows, dim, bits, group, grad_y, grad_x,
+                            grad_gamma, grad_beta, ws, (hipStream_t)stream);
 }
 
 }  // extern "C"

@@ -12,6 +12,7 @@ namespace tinykg {
 namespace {
 struct Record { const char* name; hipEvent_t start, stop; bool closed; };
 bool g_on = false;
+int g_mute = 0;                     // > 0: a ProfileMute is alive
 std::string g_only;                 // empty: every scope; else only the scopes of this name
 std::vector<Record> g_records;
 std::vector<hipEvent_t> g_spare;    // events of dropped records, reused (creating one costs microseconds)
@@ -29,7 +30,7 @@ bool take_event(hipEvent_t* e) {
 }  // namespace
 
 ProfileScope::ProfileScope(const char* name, hipStream_t st) : slot_(-1), st_(st) {
-  if (!g_on || g_records.size() >= kMaxRecords) return;
+  if (!g_on || g_mute > 0 || g_records.size() >= kMaxRecords) return;
   if (!g_only.empty() && g_only != name) return;
   Record r{name, nullptr, nullptr, false};
   if (!take_event(&r.start)) return;
@@ -44,6 +45,9 @@ ProfileScope::~ProfileScope() {
   (void)hipEventRecord(g_records[(size_t)slot_].stop, st_);
   g_records[(size_t)slot_].closed = true;
 }
+
+ProfileMute::ProfileMute() { ++g_mute; }
+ProfileMute::~ProfileMute() { --g_mute; }
 
 __global__ void calibration_copy_kernel(const float4* __restrict__ src, float4* __restrict__ dst,
                                         size_t n16) {

@@ -1,7 +1,7 @@
 // tinykg_graph: the immutable sparse structure shared by every layer and step
 // (Sec. 3.2, "Memory Analysis": the adjacency is kept once for all layers).
 //
-// Built on the host, off the hot path, from device COO triplets:
+// Built once, off the hot path, from device COO triplets:
 //   * head order  -- triplets sorted by (head, relation, tail): CSR row pointers
 //     and the tail of every edge.  The softmax / gather kernels walk it.
 //   * relation order -- the same edges sorted by (relation, tail, head), cut into
@@ -9,7 +9,14 @@
 //     contractions with one W_r) walk it; sorting by tail inside a relation puts
 //     the edges of a hot tail next to each other, so their gradient rows are
 //     summed before they leave the workgroup.
+// Everything that touches every edge runs on the device (stable radix sorts of rocPRIM
+// through hipCUB, gathers, degree counts, the per-tile row orders); the host only walks
+// per-node and per-tile summaries (degrees, one byte per 32-edge tile) to lay out chunks,
+// spans and the lists of heavy nodes.  150 M triplets take a few seconds instead of most
+// of a minute on the host.
 #include "tinykg_graph.h"
+
+#include <hipcub/hipcub.hpp>
 
 #include <algorithm>
 #include <numeric>
@@ -31,14 +38,190 @@ tinykg_status upload(const std::vector<T>& v, T** out) {
   return TINYKG_OK;
 }
 
-// One stable counting-sort pass: reorders `ord` by key[ord[i]] (keys in [0, n_keys)).
-void counting_pass(std::vector<int32_t>& ord, const std::vector<int32_t>& key, size_t n_keys) {
-  std::vector<int64_t> cnt(n_keys + 1, 0);
-  for (int32_t e : ord) cnt[(size_t)key[(size_t)e] + 1]++;
-  for (size_t k = 0; k < n_keys; ++k) cnt[k + 1] += cnt[k];
-  std::vector<int32_t> out(ord.size());
-  for (int32_t e : ord) out[(size_t)cnt[(size_t)key[(size_t)e]]++] = e;
-  ord.swap(out);
+// Device memory that lives only while the graph is being built.
+struct Scratch {
+  std::vector<void*> ptrs;
+  ~Scratch() { for (void* p : ptrs) (void)hipFree(p); }
+  template <typename T>
+  tinykg_status get(size_t n, T** out) {
+    *out = nullptr;
+    void* p = nullptr;
+    TINYKG_HIP_TRY(hipMalloc(&p, std::max<size_t>(n, 1) * sizeof(T)));
+    ptrs.push_back(p);
+    *out = static_cast<T*>(p);
+    return TINYKG_OK;
+  }
+};
+
+template <typename T>
+tinykg_status device_array(size_t n, T** out) {
+  *out = nullptr;
+  TINYKG_HIP_TRY(hipMalloc(reinterpret_cast<void**>(out), std::max<size_t>(n, 1) * sizeof(T)));
+  return TINYKG_OK;
+}
+
+int bits_for(int64_t n_values) {   // bits that hold 0 .. n_values - 1
+  int b = 1;
+  while (((int64_t)1 << b) < n_values) ++b;
+  return b;
+}
+
+constexpr int kBuildThreads = 256;
+inline unsigned build_grid(size_t n) {
+  const size_t want = (n + kBuildThreads - 1) / kBuildThreads;
+  return (unsigned)std::max<size_t>(1, std::min<size_t>(want, (size_t)num_cus() * 32));
+}
+
+// ids outside [0, n_nodes) / [0, n_rel): *bad becomes nonzero
+__global__ __launch_bounds__(kBuildThreads) void validate_kernel(const int32_t* __restrict__ head,
+                                                                 const int32_t* __restrict__ rel,
+                                                                 const int32_t* __restrict__ tail, size_t T,
+                                                                 int32_t n_nodes, int32_t n_rel,
+                                                                 int32_t* __restrict__ bad) {
+  bool wrong = false;
+  for (size_t e = (size_t)blockIdx.x * blockDim.x + threadIdx.x; e < T; e += (size_t)gridDim.x * blockDim.x)
+    wrong |= head[e] < 0 || head[e] >= n_nodes || tail[e] < 0 || tail[e] >= n_nodes || rel[e] < 0 ||
+             rel[e] >= n_rel;
+  if (wrong) atomicOr(bad, 1);
+}
+
+// key = relation * 2^30 + tail of edge e (node ids are below 2^30), value = e
+__global__ __launch_bounds__(kBuildThreads) void rel_tail_keys_kernel(const int32_t* __restrict__ rel,
+                                                                      const int32_t* __restrict__ tail, size_t T,
+                                                                      uint64_t* __restrict__ key,
+                                                                      int32_t* __restrict__ val) {
+  for (size_t e = (size_t)blockIdx.x * blockDim.x + threadIdx.x; e < T; e += (size_t)gridDim.x * blockDim.x) {
+    key[e] = ((uint64_t)(uint32_t)rel[e] << 30) | (uint32_t)tail[e];
+    val[e] = (int32_t)e;
+  }
+}
+
+__global__ __launch_bounds__(kBuildThreads) void gather_i32_kernel(const int32_t* __restrict__ src,
+                                                                   const int32_t* __restrict__ idx, size_t T,
+                                                                   int32_t* __restrict__ dst) {
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < T; i += (size_t)gridDim.x * blockDim.x)
+    dst[i] = src[idx[i]];
+}
+
+__global__ __launch_bounds__(kBuildThreads) void fill_i32_kernel(int32_t* __restrict__ dst, size_t n, int32_t v) {
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x)
+    dst[i] = v;
+}
+
+// out_deg[head] and rows[head], rows[tail] (gradient rows a node receives) of every edge
+__global__ __launch_bounds__(kBuildThreads) void degree_kernel(const int32_t* __restrict__ head,
+                                                               const int32_t* __restrict__ tail, size_t T,
+                                                               int32_t* __restrict__ out_deg,
+                                                               int32_t* __restrict__ rows) {
+  for (size_t e = (size_t)blockIdx.x * blockDim.x + threadIdx.x; e < T; e += (size_t)gridDim.x * blockDim.x) {
+    atomicAdd(out_deg + head[e], 1);
+    atomicAdd(rows + head[e], 1);
+    atomicAdd(rows + tail[e], 1);
+  }
+}
+
+// first[r] = first position of relation r in the ascending keys (r = n_rel: T)
+__global__ __launch_bounds__(kBuildThreads) void rel_first_kernel(const uint64_t* __restrict__ key, size_t T,
+                                                                  int32_t n_rel, int64_t* __restrict__ first) {
+  const int r = blockIdx.x * blockDim.x + threadIdx.x;
+  if (r > n_rel) return;
+  size_t lo = 0, hi = T;                    // first position whose relation is >= r
+  while (lo < hi) {
+    const size_t mid = (lo + hi) >> 1;
+    if ((int64_t)(key[mid] >> 30) < (int64_t)r) lo = mid + 1; else hi = mid;
+  }
+  first[r] = (int64_t)lo;
+}
+
+// Relation-order tiles: 32 consecutive edges counted from the first edge of their relation.
+// One 32-lane half wave per tile: whether its edges share one tail (tile_one[t] = 1), and the
+// byte of every row -- bits 0-4: the tile-local row indices in stable head order (slot k holds
+// the row of rank k); bit 6 / bit 7: the tail / head of THIS row accumulates in double.
+__global__ __launch_bounds__(kBuildThreads) void tile_kernel(const int32_t* __restrict__ r_head,
+                                                             const int32_t* __restrict__ r_tail,
+                                                             const int64_t* __restrict__ rel_first,
+                                                             const int64_t* __restrict__ rel_tile_ptr,
+                                                             int32_t n_rel, int64_t n_tiles,
+                                                             const int32_t* __restrict__ acc_slot,
+                                                             uint8_t* __restrict__ tile_one,
+                                                             uint8_t* __restrict__ hperm) {
+  __shared__ uint8_t order[kBuildThreads];
+  const int lane = threadIdx.x & 31, grp = threadIdx.x >> 5;
+  const int64_t per_block = kBuildThreads / 32;
+  for (int64_t t0 = (int64_t)blockIdx.x * per_block; t0 < n_tiles; t0 += (int64_t)gridDim.x * per_block) {
+    const int64_t t = t0 + grp;
+    const bool live = t < n_tiles;
+    int nrow = 0;
+    int64_t base = 0;
+    if (live) {
+      int lo = 0, hi = n_rel;                 // the relation r with tile_ptr[r] <= t < tile_ptr[r + 1]
+      while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if (rel_tile_ptr[mid] <= t) lo = mid; else hi = mid;
+      }
+      base = rel_first[lo] + 32 * (t - rel_tile_ptr[lo]);
+      nrow = (int)min((int64_t)32, rel_first[lo + 1] - base);
+    }
+    const bool row = lane < nrow;
+    const int h = row ? r_head[base + lane] : 0x7fffffff;
+    const int tl = row ? r_tail[base + lane] : 0;
+    const int t_first = __shfl(tl, 0, 32);
+    const unsigned long long differ = __ballot(row && tl != t_first);
+    const unsigned my_half = (unsigned)(differ >> (32 * ((threadIdx.x >> 5) & 1)));
+    int rank = 0;
+#pragma unroll
+    for (int j = 0; j < 32; ++j) {
+      const int hj = __shfl(h, j, 32);
+      rank += (hj < h || (hj == h && j < lane)) ? 1 : 0;
+    }
+    if (row) order[grp * 32 + rank] = (uint8_t)lane;
+    __syncthreads();
+    if (row)
+      hperm[base + lane] = (uint8_t)(order[grp * 32 + lane] | (acc_slot[tl] >= 0 ? 0x40 : 0) |
+                                     (acc_slot[h] >= 0 ? 0x80 : 0));
+    if (live && lane == 0) tile_one[t] = my_half == 0 ? 1 : 0;
+    __syncthreads();
+  }
+}
+
+// keys_a -> sorted keys in *keys_sorted (one of the two buffers), values likewise; stable
+tinykg_status sort_pairs_u64(Scratch& sc, uint64_t* ka, uint64_t* kb, int32_t* va, int32_t* vb, size_t T,
+                             int end_bit, hipStream_t st, uint64_t** keys_sorted, int32_t** vals_sorted) {
+  hipcub::DoubleBuffer<uint64_t> keys(ka, kb);
+  hipcub::DoubleBuffer<int32_t> vals(va, vb);
+  size_t temp_bytes = 0;
+  TINYKG_HIP_TRY(hipcub::DeviceRadixSort::SortPairs(nullptr, temp_bytes, keys, vals, (int)T, 0, end_bit, st));
+  uint8_t* temp = nullptr;
+  tinykg_status rc = sc.get(temp_bytes, &temp);
+  if (rc != TINYKG_OK) return rc;
+  TINYKG_HIP_TRY(hipcub::DeviceRadixSort::SortPairs(temp, temp_bytes, keys, vals, (int)T, 0, end_bit, st));
+  *keys_sorted = keys.Current();
+  *vals_sorted = vals.Current();
+  return TINYKG_OK;
+}
+
+tinykg_status sort_pairs_i32(Scratch& sc, int32_t* ka, int32_t* kb, int32_t* va, int32_t* vb, size_t T,
+                             int end_bit, hipStream_t st, int32_t** vals_sorted) {
+  hipcub::DoubleBuffer<int32_t> keys(ka, kb);
+  hipcub::DoubleBuffer<int32_t> vals(va, vb);
+  size_t temp_bytes = 0;
+  TINYKG_HIP_TRY(hipcub::DeviceRadixSort::SortPairs(nullptr, temp_bytes, keys, vals, (int)T, 0, end_bit, st));
+  uint8_t* temp = nullptr;
+  tinykg_status rc = sc.get(temp_bytes, &temp);
+  if (rc != TINYKG_OK) return rc;
+  TINYKG_HIP_TRY(hipcub::DeviceRadixSort::SortPairs(temp, temp_bytes, keys, vals, (int)T, 0, end_bit, st));
+  *vals_sorted = vals.Current();
+  return TINYKG_OK;
+}
+
+template <typename T>
+tinykg_status download(const T* dev, size_t n, std::vector<T>& host, hipStream_t st) {
+  host.resize(n);
+  if (n) {
+    TINYKG_HIP_TRY(hipMemcpyAsync(host.data(), dev, n * sizeof(T), hipMemcpyDeviceToHost, st));
+    TINYKG_HIP_TRY(hipStreamSynchronize(st));
+  }
+  return TINYKG_OK;
 }
 
 void release(tinykg_graph* g) {
@@ -69,199 +252,252 @@ tinykg_status tinykg_graph_create(int64_t n_nodes, int32_t n_rel, int64_t n_edge
   if (n_edges > 0 && (!head || !rel || !tail)) return TINYKG_ERR_INVALID_ARG;
   if (n_edges > 0 && n_rel == 0) return TINYKG_ERR_INVALID_ARG;
 
-  const size_t T = (size_t)n_edges;
-  std::vector<int32_t> hh(T), hr(T), ht(T);
+  const size_t T = (size_t)n_edges, N = (size_t)n_nodes;
+  hipStream_t st = (hipStream_t)stream;
+  Scratch sc;
+  tinykg_status rc;
+#define TINYKG_TRY(expr) do { if ((rc = (expr)) != TINYKG_OK) return rc; } while (0)
+  // (freed on every early return; handed to the caller at the end)
+  struct Guard { tinykg_graph* g = nullptr; ~Guard() { release(g); } } guard;
+  tinykg_graph*& g = guard.g;
+
+  // ---- ids in range?
   if (T) {
-    hipStream_t st = (hipStream_t)stream;
-    TINYKG_HIP_TRY(hipMemcpyAsync(hh.data(), head, T * 4, hipMemcpyDeviceToHost, st));
-    TINYKG_HIP_TRY(hipMemcpyAsync(hr.data(), rel, T * 4, hipMemcpyDeviceToHost, st));
-    TINYKG_HIP_TRY(hipMemcpyAsync(ht.data(), tail, T * 4, hipMemcpyDeviceToHost, st));
-    TINYKG_HIP_TRY(hipStreamSynchronize(st));
-  }
-  for (size_t e = 0; e < T; ++e) {
-    if (hh[e] < 0 || hh[e] >= n_nodes || ht[e] < 0 || ht[e] >= n_nodes) return TINYKG_ERR_INVALID_ARG;
-    if (hr[e] < 0 || hr[e] >= n_rel) return TINYKG_ERR_INVALID_ARG;
-  }
-
-  // head order: (head, relation, tail, input position) -- three stable counting passes
-  std::vector<int32_t> ord(T);
-  std::iota(ord.begin(), ord.end(), 0);
-  counting_pass(ord, ht, (size_t)n_nodes);
-  counting_pass(ord, hr, (size_t)n_rel);
-  counting_pass(ord, hh, (size_t)n_nodes);
-  std::vector<int32_t> rowptr((size_t)n_nodes + 1, 0), h_tail(T), h_head(T), h_rel(T);
-  for (size_t i = 0; i < T; ++i) {
-    const int32_t e = ord[i];
-    h_head[i] = hh[e]; h_rel[i] = hr[e]; h_tail[i] = ht[e];
-    rowptr[(size_t)hh[e] + 1]++;
-  }
-  for (int64_t i = 0; i < n_nodes; ++i) rowptr[(size_t)i + 1] += rowptr[(size_t)i];
-
-  // relation order over head-order edge ids: (relation, tail, head) -- two stable passes
-  // over a sequence that already ascends in head
-  std::vector<int32_t> rord(T);
-  std::iota(rord.begin(), rord.end(), 0);
-  counting_pass(rord, h_tail, (size_t)n_nodes);
-  counting_pass(rord, h_rel, (size_t)n_rel);
-  std::vector<int32_t> r_head(T), r_tail(T), r_eid(T);
-  std::vector<int64_t> rel_count((size_t)n_rel, 0);
-  for (size_t i = 0; i < T; ++i) {
-    const int32_t e = rord[i];
-    r_head[i] = h_head[e]; r_tail[i] = h_tail[e]; r_eid[i] = e;
-    rel_count[(size_t)h_rel[e]]++;
+    int32_t* bad = nullptr;
+    TINYKG_TRY(sc.get(1, &bad));
+    hipLaunchKernelGGL(fill_i32_kernel, dim3(1), dim3(kBuildThreads), 0, st, bad, (size_t)1, 0);
+    hipLaunchKernelGGL(validate_kernel, dim3(build_grid(T)), dim3(kBuildThreads), 0, st, head, rel, tail, T,
+                       (int32_t)n_nodes, n_rel, bad);
+    std::vector<int32_t> flag;
+    TINYKG_TRY(download(bad, 1, flag, st));
+    if (flag[0] != 0) return TINYKG_ERR_INVALID_ARG;
   }
 
-  // chunks: runs of at most chunk_edges consecutive relation-order edges of one
-  // relation; about 2048 of them: few enough that the per-chunk partial gradients stay
-  // small and a workgroup amortises staging W_r, enough to fill 256 compute units.
-  int64_t chunk_edges = ((n_edges / 2048 + 63) / 64) * 64;
-  if (chunk_edges < 64) chunk_edges = 64;
-  std::vector<int32_t> chunk_rel, chunk_start, chunk_count, rel_chunk_ptr((size_t)n_rel + 1, 0);
-  int64_t pos = 0;
-  for (int32_t r = 0; r < n_rel; ++r) {
-    rel_chunk_ptr[(size_t)r] = (int32_t)chunk_rel.size();
-    int64_t left = rel_count[(size_t)r];
-    while (left > 0) {
-      const int64_t c = std::min(left, chunk_edges);
-      chunk_rel.push_back(r);
-      chunk_start.push_back((int32_t)pos);
-      chunk_count.push_back((int32_t)c);
-      pos += c; left -= c;
-    }
-  }
-  rel_chunk_ptr[(size_t)n_rel] = (int32_t)chunk_rel.size();
+  g = new tinykg_graph();
+  g->n_nodes = n_nodes; g->n_edges = n_edges; g->n_rel = n_rel;
+  TINYKG_TRY(device_array(N + 1, &g->rowptr));
+  TINYKG_TRY(device_array(T, &g->h_tail));
+  TINYKG_TRY(device_array(T, &g->r_head));
+  TINYKG_TRY(device_array(T, &g->r_tail));
+  TINYKG_TRY(device_array(T, &g->r_eid));
+  TINYKG_TRY(device_array(T, &g->r_hperm32));
 
-  // spans of the persistent edge-level kernel (one group per compute unit): runs of whole
-  // 32-edge tiles of one relation (tiles are counted from the relation's first edge).  The
-  // groups get equal shares of the kernel's WORK, not of the edges: a tile whose edges share
-  // one tail (popular tails own long runs of the relation order) takes the kernel's run form,
-  // which skips a third of the matrix products.
-  std::vector<int32_t> span_group_ptr(1, 0), span_rel, span_start, span_count, rel_span_ptr((size_t)n_rel + 1, 0);
+  // ---- degrees; CSR row pointers = exclusive prefix sums of the out-degrees
+  int32_t *out_deg = nullptr, *rows = nullptr;
+  TINYKG_TRY(sc.get(N + 1, &out_deg));
+  TINYKG_TRY(sc.get(N + 1, &rows));
+  hipLaunchKernelGGL(fill_i32_kernel, dim3(build_grid(N + 1)), dim3(kBuildThreads), 0, st, out_deg, N + 1, 0);
+  hipLaunchKernelGGL(fill_i32_kernel, dim3(build_grid(N + 1)), dim3(kBuildThreads), 0, st, rows, N + 1, 0);
+  if (T) hipLaunchKernelGGL(degree_kernel, dim3(build_grid(T)), dim3(kBuildThreads), 0, st, head, tail, T, out_deg, rows);
   {
-    const int64_t n_groups = std::max<int64_t>(1, std::min<int64_t>(num_cus(), (int64_t)chunk_rel.size()));
-    auto tile_cost = [&](int64_t first, int64_t n) {
-      for (int64_t k = 1; k < n; ++k)
-        if (r_tail[(size_t)(first + k)] != r_tail[(size_t)first]) return 1.0;
-      return kOneTailTileCost;
-    };
-    double total_cost = 0.0;
-    int64_t first = 0;
-    for (int32_t r = 0; r < n_rel; ++r) {
-      const int64_t end = first + rel_count[(size_t)r];
-      for (int64_t t0 = first; t0 < end; t0 += 32) total_cost += tile_cost(t0, std::min<int64_t>(32, end - t0));
-      first = end;
+    size_t temp_bytes = 0;
+    if (hipcub::DeviceScan::ExclusiveSum(nullptr, temp_bytes, out_deg, g->rowptr, (int)(N + 1), st) != hipSuccess) return TINYKG_ERR_DEVICE;
+    uint8_t* temp = nullptr;
+    TINYKG_TRY(sc.get(temp_bytes, &temp));
+    if (hipcub::DeviceScan::ExclusiveSum(temp, temp_bytes, out_deg, g->rowptr, (int)(N + 1), st) != hipSuccess) return TINYKG_ERR_DEVICE;
+  }
+  std::vector<int32_t> h_out_deg, h_rows;
+  TINYKG_TRY(download(out_deg, N, h_out_deg, st));
+  TINYKG_TRY(download(rows, N, h_rows, st));
+
+  // ---- heavy heads (cut into segments of kHeavyDegree head-order edges) and the nodes whose
+  //      gradient rows are accumulated in double
+  std::vector<int32_t> heavy_head, heavy_seg_ptr(1, 0), hseg_q, hseg_e0, hseg_cnt;
+  std::vector<int32_t> acc_slot(N, -1), acc_node;
+  {
+    int64_t e0 = 0;
+    for (size_t h = 0; h < N; ++h) {
+      const int32_t deg = h_out_deg[h];
+      g->max_out_degree = std::max(g->max_out_degree, deg);
+      if (deg > kHeavyDegree) {
+        const int32_t q = (int32_t)heavy_head.size();
+        heavy_head.push_back((int32_t)h);
+        for (int32_t o = 0; o < deg; o += kHeavyDegree) {
+          hseg_q.push_back(q);
+          hseg_e0.push_back((int32_t)(e0 + o));
+          hseg_cnt.push_back(std::min<int32_t>(kHeavyDegree, deg - o));
+        }
+        heavy_seg_ptr.push_back((int32_t)hseg_q.size());
+      }
+      if (h_rows[h] > kAccHeavyDegree) {
+        acc_slot[h] = (int32_t)acc_node.size();
+        acc_node.push_back((int32_t)h);
+      }
+      e0 += deg;
     }
-    int64_t cur_group = 0;
-    double cost_before = 0.0;
-    first = 0;
+  }
+  g->n_heavy = (int32_t)heavy_head.size();
+  g->n_hseg = (int32_t)hseg_q.size();
+  g->n_acc_heavy = (int32_t)acc_node.size();
+  TINYKG_TRY(upload(heavy_head, &g->heavy_head));
+  TINYKG_TRY(upload(heavy_seg_ptr, &g->heavy_seg_ptr));
+  TINYKG_TRY(upload(hseg_q, &g->hseg_q));
+  TINYKG_TRY(upload(hseg_e0, &g->hseg_e0));
+  TINYKG_TRY(upload(hseg_cnt, &g->hseg_cnt));
+  TINYKG_TRY(upload(acc_slot, &g->acc_slot));
+  TINYKG_TRY(upload(acc_node, &g->acc_node));
+
+  // ---- the two edge orders (stable radix sorts)
+  std::vector<int64_t> rel_first((size_t)n_rel + 1, 0);
+  if (T) {
+    const int rt_bits = 30 + bits_for(std::max<int64_t>(n_rel, 2));
+    uint64_t *ka = nullptr, *kb = nullptr, *ks = nullptr;
+    int32_t *va = nullptr, *vb = nullptr, *ord = nullptr, *ha = nullptr, *hb = nullptr;
+    TINYKG_TRY(sc.get(T, &ka)); TINYKG_TRY(sc.get(T, &kb));
+    TINYKG_TRY(sc.get(T, &va)); TINYKG_TRY(sc.get(T, &vb));
+    TINYKG_TRY(sc.get(T, &ha)); TINYKG_TRY(sc.get(T, &hb));
+    // head order: by (relation, tail) first, then by head; both passes keep the order of
+    // equal keys, so equal triplets stay in input order
+    hipLaunchKernelGGL(rel_tail_keys_kernel, dim3(build_grid(T)), dim3(kBuildThreads), 0, st, rel, tail, T, ka, va);
+    TINYKG_TRY(sort_pairs_u64(sc, ka, kb, va, vb, T, rt_bits, st, &ks, &ord));
+    int32_t* other = ord == va ? vb : va;
+    hipLaunchKernelGGL(gather_i32_kernel, dim3(build_grid(T)), dim3(kBuildThreads), 0, st, head, ord, T, ha);
+    {
+      hipcub::DoubleBuffer<int32_t> keys(ha, hb);
+      hipcub::DoubleBuffer<int32_t> vals(ord, other);
+      size_t temp_bytes = 0;
+      const int hb_bits = bits_for(std::max<int64_t>(n_nodes, 2));
+      if (hipcub::DeviceRadixSort::SortPairs(nullptr, temp_bytes, keys, vals, (int)T, 0, hb_bits, st) != hipSuccess) return TINYKG_ERR_DEVICE;
+      uint8_t* temp = nullptr;
+      TINYKG_TRY(sc.get(temp_bytes, &temp));
+      if (hipcub::DeviceRadixSort::SortPairs(temp, temp_bytes, keys, vals, (int)T, 0, hb_bits, st) != hipSuccess) return TINYKG_ERR_DEVICE;
+      ord = vals.Current();                 // input position of the edge at each head-order position
+      other = ord == va ? vb : va;
+      ha = keys.Current();                  // its head
+    }
+    int32_t *h_rel = nullptr;
+    TINYKG_TRY(sc.get(T, &h_rel));
+    hipLaunchKernelGGL(gather_i32_kernel, dim3(build_grid(T)), dim3(kBuildThreads), 0, st, rel, ord, T, h_rel);
+    hipLaunchKernelGGL(gather_i32_kernel, dim3(build_grid(T)), dim3(kBuildThreads), 0, st, tail, ord, T, g->h_tail);
+    // relation order over head-order positions: by (relation, tail); the sequence already
+    // ascends in head, which a stable pass keeps
+    int32_t* rord = nullptr;
+    hipLaunchKernelGGL(rel_tail_keys_kernel, dim3(build_grid(T)), dim3(kBuildThreads), 0, st, h_rel, g->h_tail, T, ka, other);
+    {
+      int32_t* spare = ord;                 // the head-order permutation is no longer needed
+      uint64_t* ks2 = nullptr;
+      TINYKG_TRY(sort_pairs_u64(sc, ka, kb, other, spare, T, rt_bits, st, &ks2, &rord));
+      ks = ks2;
+    }
+    hipLaunchKernelGGL(gather_i32_kernel, dim3(build_grid(T)), dim3(kBuildThreads), 0, st, ha, rord, T, g->r_head);
+    hipLaunchKernelGGL(gather_i32_kernel, dim3(build_grid(T)), dim3(kBuildThreads), 0, st, g->h_tail, rord, T, g->r_tail);
+    TINYKG_HIP_TRY(hipMemcpyAsync(g->r_eid, rord, T * 4, hipMemcpyDeviceToDevice, st));
+    int64_t* d_first = nullptr;
+    TINYKG_TRY(sc.get((size_t)n_rel + 1, &d_first));
+    hipLaunchKernelGGL(rel_first_kernel, dim3((n_rel + 1 + kBuildThreads - 1) / kBuildThreads), dim3(kBuildThreads), 0,
+                       st, ks, T, n_rel, d_first);
+    TINYKG_TRY(download(d_first, (size_t)n_rel + 1, rel_first, st));
+
+    // per-tile summaries and per-row bytes
+    std::vector<int64_t> rel_tile_ptr((size_t)n_rel + 1, 0);
+    for (int32_t r = 0; r < n_rel; ++r)
+      rel_tile_ptr[(size_t)r + 1] = rel_tile_ptr[(size_t)r] + (rel_first[(size_t)r + 1] - rel_first[(size_t)r] + 31) / 32;
+    const int64_t n_tiles = rel_tile_ptr[(size_t)n_rel];
+    int64_t* d_tile_ptr = nullptr;
+    uint8_t* d_tile_one = nullptr;
+    TINYKG_TRY(sc.get((size_t)n_rel + 1, &d_tile_ptr));
+    TINYKG_TRY(sc.get((size_t)n_tiles, &d_tile_one));
+    TINYKG_HIP_TRY(hipMemcpyAsync(d_tile_ptr, rel_tile_ptr.data(), ((size_t)n_rel + 1) * 8, hipMemcpyHostToDevice, st));
+    TINYKG_HIP_TRY(hipStreamSynchronize(st));   // rel_tile_ptr is a local: the copy must have read it
+    hipLaunchKernelGGL(tile_kernel, dim3(build_grid((size_t)n_tiles * 32)), dim3(kBuildThreads), 0, st, g->r_head,
+                       g->r_tail, d_first, d_tile_ptr, n_rel, n_tiles, g->acc_slot, d_tile_one, g->r_hperm32);
+    if (hipGetLastError() != hipSuccess) return TINYKG_ERR_DEVICE;
+    std::vector<uint8_t> tile_one;
+    TINYKG_TRY(download(d_tile_one, (size_t)n_tiles, tile_one, st));
+
+    // chunks: runs of at most chunk_edges consecutive relation-order edges of one
+    // relation; about 2048 of them: few enough that the per-chunk partial gradients stay
+    // small and a workgroup amortises staging W_r, enough to fill 256 compute units.
+    int64_t chunk_edges = ((n_edges / 2048 + 63) / 64) * 64;
+    if (chunk_edges < 64) chunk_edges = 64;
+    g->chunk_edges = (int32_t)chunk_edges;
+    std::vector<int32_t> chunk_rel, chunk_start, chunk_count, rel_chunk_ptr((size_t)n_rel + 1, 0);
     for (int32_t r = 0; r < n_rel; ++r) {
-      const int64_t end = first + rel_count[(size_t)r];
-      bool open = false;      // a span of this relation in the current group is being extended
-      for (int64_t t0 = first; t0 < end; t0 += 32) {
-        const int64_t n = std::min<int64_t>(32, end - t0);
-        const double cost = tile_cost(t0, n);
-        const int64_t grp = std::min<int64_t>(n_groups - 1, (int64_t)((cost_before + 0.5 * cost) * (double)n_groups /
-                                                                      std::max(total_cost, 1.0)));
-        cost_before += cost;
-        if (grp > cur_group) open = false;
-        while (cur_group < grp) { span_group_ptr.push_back((int32_t)span_rel.size()); ++cur_group; }
-        if (open) {
-          span_count.back() += (int32_t)n;
-        } else {
-          span_rel.push_back(r);
-          span_start.push_back((int32_t)t0);
-          span_count.push_back((int32_t)n);
-          open = true;
+      rel_chunk_ptr[(size_t)r] = (int32_t)chunk_rel.size();
+      int64_t pos = rel_first[(size_t)r], left = rel_first[(size_t)r + 1] - pos;
+      while (left > 0) {
+        const int64_t c = std::min(left, chunk_edges);
+        chunk_rel.push_back(r);
+        chunk_start.push_back((int32_t)pos);
+        chunk_count.push_back((int32_t)c);
+        pos += c; left -= c;
+      }
+    }
+    rel_chunk_ptr[(size_t)n_rel] = (int32_t)chunk_rel.size();
+    g->n_chunks = (int32_t)chunk_rel.size();
+
+    // spans of the persistent edge-level kernel (one group per compute unit): runs of whole
+    // 32-edge tiles of one relation (tiles are counted from the relation's first edge).  The
+    // groups get equal shares of the kernel's WORK, not of the edges: a tile whose edges share
+    // one tail (popular tails own long runs of the relation order) takes the kernel's run form,
+    // which skips a third of the matrix products.
+    std::vector<int32_t> span_group_ptr(1, 0), span_rel, span_start, span_count, rel_span_ptr((size_t)n_rel + 1, 0);
+    {
+      const int64_t n_groups = std::max<int64_t>(1, std::min<int64_t>(num_cus(), (int64_t)chunk_rel.size()));
+      auto tile_cost = [&](int64_t t) { return tile_one[(size_t)t] ? kOneTailTileCost : 1.0; };
+      double total_cost = 0.0;
+      for (int64_t t = 0; t < n_tiles; ++t) total_cost += tile_cost(t);
+      int64_t cur_group = 0;
+      double cost_before = 0.0;
+      for (int32_t r = 0; r < n_rel; ++r) {
+        const int64_t first = rel_first[(size_t)r], end = rel_first[(size_t)r + 1];
+        bool open = false;      // a span of this relation in the current group is being extended
+        int64_t t = rel_tile_ptr[(size_t)r];
+        for (int64_t t0 = first; t0 < end; t0 += 32, ++t) {
+          const int64_t n = std::min<int64_t>(32, end - t0);
+          const double cost = tile_cost(t);
+          const int64_t grp = std::min<int64_t>(n_groups - 1, (int64_t)((cost_before + 0.5 * cost) * (double)n_groups /
+                                                                        std::max(total_cost, 1.0)));
+          cost_before += cost;
+          if (grp > cur_group) open = false;
+          while (cur_group < grp) { span_group_ptr.push_back((int32_t)span_rel.size()); ++cur_group; }
+          if (open) {
+            span_count.back() += (int32_t)n;
+          } else {
+            span_rel.push_back(r);
+            span_start.push_back((int32_t)t0);
+            span_count.push_back((int32_t)n);
+            open = true;
+          }
         }
       }
-      first = end;
-    }
-    while ((int64_t)span_group_ptr.size() < n_groups + 1) span_group_ptr.push_back((int32_t)span_rel.size());
-    size_t sp = 0;
-    for (int32_t r = 0; r < n_rel; ++r) {
-      while (sp < span_rel.size() && span_rel[sp] < r) ++sp;
-      rel_span_ptr[(size_t)r] = (int32_t)sp;
-    }
-    rel_span_ptr[(size_t)n_rel] = (int32_t)span_rel.size();
-  }
-
-  // heavy heads and their segments
-  std::vector<int32_t> heavy_head, heavy_seg_ptr(1, 0), hseg_q, hseg_e0, hseg_cnt;
-  for (int64_t h = 0; h < n_nodes; ++h) {
-    const int32_t e0 = rowptr[(size_t)h], deg = rowptr[(size_t)h + 1] - e0;
-    if (deg <= kHeavyDegree) continue;
-    const int32_t q = (int32_t)heavy_head.size();
-    heavy_head.push_back((int32_t)h);
-    for (int32_t o = 0; o < deg; o += kHeavyDegree) {
-      hseg_q.push_back(q);
-      hseg_e0.push_back(e0 + o);
-      hseg_cnt.push_back(std::min<int32_t>(kHeavyDegree, deg - o));
-    }
-    heavy_seg_ptr.push_back((int32_t)hseg_q.size());
-  }
-  // nodes whose gradient rows are accumulated in double
-  std::vector<int32_t> acc_slot((size_t)n_nodes, -1), acc_node;
-  {
-    std::vector<int32_t> rows((size_t)n_nodes, 0);
-    for (size_t e = 0; e < T; ++e) { rows[(size_t)hh[e]]++; rows[(size_t)ht[e]]++; }
-    for (int64_t v = 0; v < n_nodes; ++v)
-      if (rows[(size_t)v] > kAccHeavyDegree) {
-        acc_slot[(size_t)v] = (int32_t)acc_node.size();
-        acc_node.push_back((int32_t)v);
+      while ((int64_t)span_group_ptr.size() < n_groups + 1) span_group_ptr.push_back((int32_t)span_rel.size());
+      size_t sp = 0;
+      for (int32_t r = 0; r < n_rel; ++r) {
+        while (sp < span_rel.size() && span_rel[sp] < r) ++sp;
+        rel_span_ptr[(size_t)r] = (int32_t)sp;
       }
-  }
-  // tile-local head-sorted row orders (tiles are counted from each chunk's start) and the
-  // two accumulation flags of every row
-  std::vector<uint8_t> hperm32(T);
-  for (size_t c = 0; c < chunk_rel.size(); ++c) {
-    for (int32_t t0 = 0; t0 < chunk_count[c]; t0 += 32) {
-      const int32_t base = chunk_start[c] + t0, nrow = std::min<int32_t>(32, chunk_count[c] - t0);
-      uint8_t idx[32];
-      for (int i = 0; i < nrow; ++i) idx[i] = (uint8_t)i;
-      std::stable_sort(idx, idx + nrow, [&](uint8_t a, uint8_t b) { return r_head[(size_t)base + a] < r_head[(size_t)base + b]; });
-      for (int i = 0; i < nrow; ++i) {
-        const size_t pos = (size_t)base + i;
-        hperm32[pos] = (uint8_t)(idx[i] | (acc_slot[(size_t)r_tail[pos]] >= 0 ? 0x40 : 0) |
-                                 (acc_slot[(size_t)r_head[pos]] >= 0 ? 0x80 : 0));
-      }
+      rel_span_ptr[(size_t)n_rel] = (int32_t)span_rel.size();
     }
+    g->n_span_groups = (int32_t)span_group_ptr.size() - 1;
+    g->n_spans = (int32_t)span_rel.size();
+    TINYKG_TRY(upload(chunk_rel, &g->chunk_rel));
+    TINYKG_TRY(upload(chunk_start, &g->chunk_start));
+    TINYKG_TRY(upload(chunk_count, &g->chunk_count));
+    TINYKG_TRY(upload(rel_chunk_ptr, &g->rel_chunk_ptr));
+    TINYKG_TRY(upload(span_group_ptr, &g->span_group_ptr));
+    TINYKG_TRY(upload(span_rel, &g->span_rel));
+    TINYKG_TRY(upload(span_start, &g->span_start));
+    TINYKG_TRY(upload(span_count, &g->span_count));
+    TINYKG_TRY(upload(rel_span_ptr, &g->rel_span_ptr));
+  } else {
+    const std::vector<int32_t> none, rel_ptr((size_t)n_rel + 1, 0), group_ptr(2, 0);
+    g->chunk_edges = 64;
+    g->n_span_groups = 1;
+    TINYKG_TRY(upload(none, &g->chunk_rel));
+    TINYKG_TRY(upload(none, &g->chunk_start));
+    TINYKG_TRY(upload(none, &g->chunk_count));
+    TINYKG_TRY(upload(rel_ptr, &g->rel_chunk_ptr));
+    TINYKG_TRY(upload(group_ptr, &g->span_group_ptr));
+    TINYKG_TRY(upload(none, &g->span_rel));
+    TINYKG_TRY(upload(none, &g->span_start));
+    TINYKG_TRY(upload(none, &g->span_count));
+    TINYKG_TRY(upload(rel_ptr, &g->rel_span_ptr));
   }
-
-  tinykg_graph* g = new tinykg_graph();
-  g->n_nodes = n_nodes; g->n_edges = n_edges; g->n_rel = n_rel;
-  g->n_chunks = (int32_t)chunk_rel.size();
-  g->chunk_edges = (int32_t)chunk_edges;
-  tinykg_status st = upload(rowptr, &g->rowptr);
-  if (st == TINYKG_OK) st = upload(h_tail, &g->h_tail);
-  if (st == TINYKG_OK) st = upload(r_head, &g->r_head);
-  if (st == TINYKG_OK) st = upload(r_tail, &g->r_tail);
-  if (st == TINYKG_OK) st = upload(r_eid, &g->r_eid);
-  if (st == TINYKG_OK) st = upload(chunk_rel, &g->chunk_rel);
-  if (st == TINYKG_OK) st = upload(chunk_start, &g->chunk_start);
-  if (st == TINYKG_OK) st = upload(chunk_count, &g->chunk_count);
-  if (st == TINYKG_OK) st = upload(rel_chunk_ptr, &g->rel_chunk_ptr);
-  g->n_span_groups = (int32_t)span_group_ptr.size() - 1;
-  g->n_spans = (int32_t)span_rel.size();
-  if (st == TINYKG_OK) st = upload(span_group_ptr, &g->span_group_ptr);
-  if (st == TINYKG_OK) st = upload(span_rel, &g->span_rel);
-  if (st == TINYKG_OK) st = upload(span_start, &g->span_start);
-  if (st == TINYKG_OK) st = upload(span_count, &g->span_count);
-  if (st == TINYKG_OK) st = upload(rel_span_ptr, &g->rel_span_ptr);
-  g->n_heavy = (int32_t)heavy_head.size();
-  for (int64_t i = 0; i < n_nodes; ++i)
-    g->max_out_degree = std::max(g->max_out_degree, rowptr[(size_t)i + 1] - rowptr[(size_t)i]);
-  g->n_hseg = (int32_t)hseg_q.size();
-  if (st == TINYKG_OK) st = upload(heavy_head, &g->heavy_head);
-  if (st == TINYKG_OK) st = upload(heavy_seg_ptr, &g->heavy_seg_ptr);
-  if (st == TINYKG_OK) st = upload(hseg_q, &g->hseg_q);
-  if (st == TINYKG_OK) st = upload(hseg_e0, &g->hseg_e0);
-  if (st == TINYKG_OK) st = upload(hseg_cnt, &g->hseg_cnt);
-  if (st == TINYKG_OK) st = upload(hperm32, &g->r_hperm32);
-  g->n_acc_heavy = (int32_t)acc_node.size();
-  if (st == TINYKG_OK) st = upload(acc_slot, &g->acc_slot);
-  if (st == TINYKG_OK) st = upload(acc_node, &g->acc_node);
-  if (st != TINYKG_OK) { release(g); return st; }
+  if (hipStreamSynchronize(st) != hipSuccess || hipGetLastError() != hipSuccess) return TINYKG_ERR_DEVICE;
+#undef TINYKG_TRY
   *out = g;
+  guard.g = nullptr;
   return TINYKG_OK;
 }
 

@@ -121,10 +121,11 @@ def test_small_stack_end_to_end_against_the_oracle_chain(tk):
     layer_grads, pgrads = stack.backward(tp)
     torch.cuda.synchronize()
     assert abs(float(loss.cpu()[0]) - want["loss"]) <= 1e-5 * want["loss"]
-    close(layer_grads[0], want["layer_grads"][0], "grad_E0", tol=1e-4, case="end to end (bound 1e-4)")
+    # (measured: the compounded error through two layers stays below 0.3 of the one-layer bound)
+    close(layer_grads[0], want["layer_grads"][0], "grad_E0", case="end to end")
     for l in range(2):
         for a, w, nm in zip(pgrads[l], want["param_grads"][l], ("grad_Wr", "grad_er", "grad_W")):
-            close(a, w, f"{nm} layer {l}", tol=1e-4, row_term=False, case="end to end (bound 1e-4)")
+            close(a, w, f"{nm} layer {l}", row_term=False, case="end to end")
     graph.close()
 
 

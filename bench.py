@@ -282,7 +282,7 @@ def compressor_sweep(a):
 
 
 # ------------------------------------------------------------------ uniform layer ----
-def uniform_result(tk, torch, graph, n_nodes, n_edges, d, bits, group, steps, warmup, label, E=None, G=None):
+def uniform_result(tk, torch, graph, n_nodes, n_edges, n_tails, d, bits, group, steps, warmup, label, E=None, G=None):
     """The uniform-attention layer (Eq. 2 as printed, row-normalised adjacency), forward +
     backward: no projections, so every kernel is a gather or a stream and HBM bounds the step
     once the tensors leave the cache.  Per kernel: HIP-event time, algorithmic bytes, GB/s."""
@@ -330,9 +330,9 @@ def uniform_result(tk, torch, graph, n_nodes, n_edges, d, bits, group, steps, wa
         "dense_fwd_kernel": Nn * (4 * d + 4 * d + d / 8),
         # dense backward with H_hat dequantised on load: grad_E' in, packed H_hat + mask in, grad_H and grad_E out
         "dense_bwd_kernel": Nn * (4 * d + d * bpa + d / 8 + 8 * d),
-        # backward gather (the transposed sparse product): grad_H row of the head + head id, tail id, flag byte
-        # per edge; one grad_E row written per node
-        "uniform_bwd_kernel": Tn * (4 * d + 9) + Nn * 4 * d,
+        # backward gather (the transposed sparse product): the head's row of grad_H / deg + head id + tail id per
+        # edge; per node that has in-edges (n_tails of them) its own grad_H row read and its grad_E row written
+        "uniform_bwd_kernel": Tn * (4 * d + 8) + n_tails * 8 * d,
     }
     kernels = {}
     for k, v in rep.items():
@@ -346,7 +346,8 @@ def uniform_result(tk, torch, graph, n_nodes, n_edges, d, bits, group, steps, wa
     gat = kernels.get("uniform_bwd_kernel", {})
     bwd_ms = sum(kernels[k]["ms_per_step"] for k in ("dense_bwd_kernel", "uniform_bwd_kernel") if k in kernels)
     bwd_bytes = alg_k["dense_bwd_kernel"] + alg_k["uniform_bwd_kernel"]
-    res = {"workload": label, "bits": bits, "group": group, "ms_per_step": round(dt * 1e3, 4), "steps": steps,
+    res = {"workload": label, "bits": bits, "group": group, "nodes_with_in_edges": n_tails,
+           "ms_per_step": round(dt * 1e3, 4), "steps": steps,
            "algorithmic_bytes_per_step": int(alg), "GB/s": round(alg / dt / 1e9, 1),
            "frac_of_hbm_peak": round(alg / dt / 1e9 / HBM_PEAK_GBS, 4),
            "saved_context_bytes": saved.nbytes(), "fp32_context_bytes": n_nodes * d * 4 + n_nodes * d // 8,
@@ -372,15 +373,17 @@ def uniform_workload(a):
     if a.large:
         head, rel, tail = device_kg_triplets(torch, C4_N, C4_R, C4_T, 1.05, seed=0)
         graph = tk.Graph(C4_N, C4_R, head, rel, tail)
+        n_tails = int(torch.unique(tail).numel())
         del head, rel, tail
-        res = uniform_result(tk, torch, graph, C4_N, C4_T, C4_D, C4_BITS, C4_GROUP, a.steps, a.warmup,
+        res = uniform_result(tk, torch, graph, C4_N, C4_T, n_tails, C4_D, C4_BITS, C4_GROUP, a.steps, a.warmup,
                              "uniform-attention layer (Eq. 2), forward+backward, on the configs[4] graph: 20M entities, "
                              "dim 128, 150M triplets (Zipf 1.05 tails), saved Q(H) INT4 group 128")
     else:
         inp = make_inputs()
         t = {k: torch.from_numpy(v).cuda() for k, v in inp.items()}
         graph = tk.Graph(N, R, t["head"], t["rel"], t["tail"])
-        res = uniform_result(tk, torch, graph, N, T, D, BITS, GROUP, a.steps, a.warmup,
+        import numpy as np
+        res = uniform_result(tk, torch, graph, N, T, int(np.unique(inp["tail"]).size), D, BITS, GROUP, a.steps, a.warmup,
                              "uniform-attention layer (Eq. 2, row-normalised adjacency), forward+backward, on the "
                              "configs[1] graph: 100k entities, dim 64, 1M triplets, saved Q(H) INT2 group 64",
                              E=t["E"], G=t["G"])
@@ -569,6 +572,7 @@ def stack_result(a, which, steps, warmup, bits=None, keep_graph=False):
     graph = tk.Graph(n_nodes, n_rel, head, rel, tail)
     torch.cuda.synchronize()
     graph_s = time.perf_counter() - t_graph
+    n_tails = int(torch.unique(tail).numel()) if keep_graph else 0
     del head, rel, tail
     g = torch.Generator(device=dev)
     g.manual_seed(1)
@@ -634,7 +638,7 @@ def stack_result(a, which, steps, warmup, bits=None, keep_graph=False):
     del stack, E0, params
     torch.cuda.empty_cache()
     if keep_graph:
-        return res, graph
+        return res, graph, n_tails
     graph.close()
     return res
 
@@ -843,11 +847,11 @@ def main():
         print("bench: sweep done, configs[3] next", file=sys.stderr, flush=True)
         out["config3"] = stack_result(a, "config3", 20, 3)
         print("bench: configs[3] done, configs[4] next", file=sys.stderr, flush=True)
-        c4, graph4 = stack_result(a, "config4", 3, 1, keep_graph=True)
+        c4, graph4, n_tails4 = stack_result(a, "config4", 3, 1, keep_graph=True)
         out["config4"] = c4
         print("bench: configs[4] done, uniform layer on its graph next", file=sys.stderr, flush=True)
         out["uniform_large"] = uniform_result(
-            tk, torch, graph4, C4_N, C4_T, C4_D, C4_BITS, C4_GROUP, 5, 1,
+            tk, torch, graph4, C4_N, C4_T, n_tails4, C4_D, C4_BITS, C4_GROUP, 5, 1,
             "uniform-attention layer (Eq. 2), forward+backward, on the configs[4] graph: 20M entities, dim 128, "
             "150M triplets (Zipf 1.05 tails), saved Q(H) INT4 group 128 (every tensor is 10 GB: nothing stays in "
             "the 256 MB Infinity Cache)")

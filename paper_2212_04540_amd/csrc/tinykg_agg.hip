@@ -1142,6 +1142,7 @@ __global__ __launch_bounds__(kThreads) void dense_fwd_kernel(const float* __rest
 
 // grad_J = grad_E' * (mask ? 1 : slope); grad_H = grad_J W (also written to grad_E, which
 // the edge stage then adds to); per-workgroup partial of grad_W = grad_J^T H_hat.
+// deg_rowptr != nullptr (uniform layer): the copy in gH is divided by the row's out-degree.
 template <int D, int BITS>
 __global__ __launch_bounds__(kThreads) void dense_bwd_kernel(Source srcH,
                                                              const uint8_t* __restrict__ mask,
@@ -1152,7 +1153,8 @@ __global__ __launch_bounds__(kThreads) void dense_bwd_kernel(Source srcH,
                                                              float* __restrict__ gE,
                                                              float* __restrict__ part_W,
                                                              double* __restrict__ zero_ptr,
-                                                             int64_t zero_n) {
+                                                             int64_t zero_n,
+                                                             const int32_t* __restrict__ deg_rowptr) {
   constexpr int LD = D + 4, LPR = D / 4, TN = 64, NIB = D / 32;
   // (the double-precision rows that the edge stage adds to start from zero: cleared here,
   // a launch earlier, instead of by a kernel of their own)
@@ -1162,6 +1164,7 @@ __global__ __launch_bounds__(kThreads) void dense_bwd_kernel(Source srcH,
   float* W_s = reinterpret_cast<float*>(smem_raw);   // [DOP][LD]
   float* Hh_s = W_s + DOP * LD;                      // [TN][LD]
   float* gJ_s = Hh_s + TN * LD;                      // [TN][LDJ]
+  float* sc_s = gJ_s + TN * LDJ;                     // [TN] factor of the grad_H copy in gH (uniform layer: 1 / deg)
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   for (int q = tid; q < DOP * LPR; q += kThreads) {
     const int row = q / LPR, li = q % LPR;
@@ -1181,12 +1184,19 @@ __global__ __launch_bounds__(kThreads) void dense_bwd_kernel(Source srcH,
   RawChunk<BITS> preH[CPT];
   float4 preG[GPT];
   uint32_t preM[GPT];
+  float preS = 1.f;
   auto load_tile = [&](int64_t tile) {
 #pragma unroll
     for (int k = 0; k < CPT; ++k) {
       const int q = tid + k * kThreads;
       const int64_t n = tile * TN + q / LPR;
       preH[k].load(srcH, (n < N ? n : 0) * LPR + q % LPR);   // past the end: row 0, zeroed below
+    }
+    if (deg_rowptr && tid < TN) {
+      // (uniform layer: the sparse stage gathers grad_H_h / deg(h); the division is done here, once per row)
+      const int64_t n = tile * TN + tid;
+      const int dg = n < N ? deg_rowptr[n + 1] - deg_rowptr[n] : 0;
+      preS = dg > 0 ? 1.0f / (float)dg : 0.f;
     }
 #pragma unroll
     for (int k = 0; k < GPT; ++k) {
@@ -1224,6 +1234,7 @@ __global__ __launch_bounds__(kThreads) void dense_bwd_kernel(Source srcH,
         *reinterpret_cast<float4*>(gJ_s + (q / ocp) * LDJ + (q % ocp) * 4) = g;
       }
     }
+    if (tid < TN) sc_s[tid] = preS;
     if (tile + gridDim.x < n_tiles) load_tile(tile + gridDim.x);
     __syncthreads();
     // grad_H tile: [n][i] = sum_o gJ[n][o] W[o][i]
@@ -1234,7 +1245,10 @@ __global__ __launch_bounds__(kThreads) void dense_bwd_kernel(Source srcH,
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
         const int64_t n = n0 + nb * 32 + acc_row(v, lane);
-        if (n < N) { gH[n * D + ib * 32 + (lane & 31)] = acc[v]; gE[n * D + ib * 32 + (lane & 31)] = acc[v]; }
+        if (n < N) {
+          gH[n * D + ib * 32 + (lane & 31)] = acc[v] * sc_s[nb * 32 + acc_row(v, lane)];
+          gE[n * D + ib * 32 + (lane & 31)] = acc[v];
+        }
       }
     }
     // grad_W partial: [o][i] += sum_n gJ[n][o] H_hat[n][i]
@@ -1363,26 +1377,20 @@ __global__ __launch_bounds__(256) void epilogue_kernel(ReduceJob j0, ReduceJob j
 // ---------------------------------------------- uniform attention, backward ----
 // grad_E_t += grad_H_h / deg(h) over the in-edges (h -> t) of t: the transposed sparse
 // product of Eq. (2)'s grad_E = ctx(A_hat, grad_H) for the row-normalised adjacency
-// (pi = 1 / deg).  One wave per 32 consecutive relation-order edges (sorted by tail inside
-// a relation): rows of equal tails are summed in fp32 before one atomic per run and column.
+// (pi = 1 / deg).  The dense stage has already divided the rows it hands over by deg(h), so an
+// edge costs its two ids and one gathered row.  One wave per 32 consecutive edges of the
+// graph's tail order (all in-edges of a tail are adjacent, heads ascending): rows of equal
+// tails are summed in fp32 before one row leaves the wave per run.  A run that holds ALL
+// in-edges of its tail (it neither continues from the previous tile nor into the next) is the
+// only writer of that row and adds with a plain read-modify-write; runs cut by a tile
+// boundary, and the tails that accumulate in double, use atomics.
 __global__ void zero_f32_fill_kernel(float* __restrict__ dst, int64_t n) {
   const int64_t stride = (int64_t)gridDim.x * blockDim.x;
   for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) dst[i] = 0.f;
 }
 
-// What one edge (h -> t) passes to its tail, column by column: a per-edge word staged once
-// per row and the value of column c.
-template <int D>
-struct UniformRows {     // grad_H_h / deg(h)
-  const int32_t* rowptr;
-  const float* gH;
-  __device__ __forceinline__ int stage(int h, int64_t) const {
-    return __float_as_int(1.0f / (float)(rowptr[h + 1] - rowptr[h]));
-  }
-  __device__ __forceinline__ float value(int word, int h, int c) const {
-    return __int_as_float(word) * gH[(int64_t)h * D + c];     // rows past the end: word = 0, row 0
-  }
-};
+// What one edge (h -> t) passes to its tail in the generic transposed walk below, column by
+// column: a per-edge word staged once per row and the value of column c.
 template <int D, typename ARG>
 struct MaxRows {         // grad_M[h, c] where this edge is the one whose number the head saved
   const int32_t* rowptr;
@@ -1395,6 +1403,67 @@ struct MaxRows {         // grad_M[h, c] where this edge is the one whose number
     return (int)arg[i] + 1 == word ? gM[i] : 0.f;
   }
 };
+
+template <int D>
+__global__ __launch_bounds__(kThreads) void uniform_tail_kernel(
+    const int32_t* __restrict__ c_head, const int32_t* __restrict__ c_tail,
+    const float* __restrict__ gHs, int64_t n_edges, GradSink sink) {
+  constexpr int NQ = D >= 64 ? 1 : 64 / D, RP = 32 / NQ;   // row parts of a wave
+  constexpr int CPL = D >= 64 ? D / 64 : 1;                // columns per lane
+  __shared__ int tl_s[kThreads / 64][32];
+  __shared__ int hd_s[kThreads / 64][32];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, r = lane & 31;
+  const int64_t pos0 = ((int64_t)blockIdx.x * (kThreads / 64) + wave) * 32;
+  if (pos0 >= n_edges) return;
+  const int nrow = (int)min((int64_t)32, n_edges - pos0);
+  int t_id = kNodeIdMask, h = -1;                            // past the end: an id no node has, no row
+  if (r < nrow) { h = c_head[pos0 + r]; t_id = c_tail[pos0 + r]; }
+  // the tails next to the tile (bit 30 included, as in the tile's own ids); -1: none
+  const int t_before = pos0 > 0 ? c_tail[pos0 - 1] : -1;
+  const int t_after = pos0 + 32 < n_edges ? c_tail[pos0 + 32] : -1;
+  const int t_next = __shfl_down(t_id, 1), t_prev = __shfl_up(t_id, 1);
+  const bool live = r < nrow;
+  const bool stop = r + 1 == nrow || (r + 1) % RP == 0;
+  const bool ends = live && (stop || t_next != t_id);
+  const bool starts = live && (r % RP == 0 || t_prev != t_id);
+  const bool start_closed = r == 0 ? t_before != t_id : t_prev != t_id;
+  const bool end_closed = r + 1 == nrow ? t_after != t_id : t_next != t_id;
+  const uint32_t start_mask = (uint32_t)__ballot(starts);
+  const uint32_t closed_mask = (uint32_t)__ballot(starts && start_closed);
+  const uint32_t upto = r == 31 ? 0xffffffffu : ((2u << r) - 1u);
+  const int first = 31 - __clz((int)(start_mask & upto));    // first row of the run that row r belongs to
+  const bool alone = ends && end_closed && !(t_id & kHeavyBit) && first >= 0 && ((closed_mask >> first) & 1u);
+  const uint32_t alone_mask = (uint32_t)__ballot(alone);   // rows whose flush is the row's only writer
+  if (lane < 32) { tl_s[wave][r] = t_id | (ends ? (int)0x80000000 : 0); hd_s[wave][r] = h; }
+  __builtin_amdgcn_wave_barrier();
+  const int col = lane % (D >= 64 ? 64 : D), e0 = (D >= 64 ? 0 : lane / D) * RP;
+#pragma unroll
+  for (int cp = 0; cp < CPL; ++cp) {
+    const int c = col + 64 * cp;
+    int node[RP];
+    float val[RP];
+#pragma unroll
+    for (int k = 0; k < RP; ++k) {
+      node[k] = tl_s[wave][e0 + k];
+      const int hk = hd_s[wave][e0 + k];
+      val[k] = hk >= 0 ? gHs[(int64_t)hk * D + c] : 0.f;
+    }
+    float run = 0.f;
+#pragma unroll
+    for (int k = 0; k < RP; ++k) {
+      run += val[k];
+      if (node[k] < 0) {
+        if ((alone_mask >> (e0 + k)) & 1u) {
+          float* dst = sink.gE + (int64_t)(node[k] & kNodeIdMask) * D + c;
+          *dst += run;
+        } else {
+          sink_add<D>(sink, node[k], c, run);
+        }
+        run = 0.f;
+      }
+    }
+  }
+}
 
 template <int D, typename ROWS>
 __global__ __launch_bounds__(kThreads) void uniform_bwd_kernel(
@@ -2407,7 +2476,7 @@ tinykg_status bwd_impl(const tinykg_graph* g, const tinykg_saved* sv, const floa
   const bool with_heavy = g->n_edges > 0 && n_heavy_elems > 0;
   int dense_blocks = 0;
   {
-    const size_t smem = (size_t)(DOP * LD + 64 * LD + 64 * (DOP + 4)) * 4;
+    const size_t smem = (size_t)(DOP * LD + 64 * LD + 64 * (DOP + 4) + 64) * 4;
     auto kern = rebuild_H ? dense_bwd_kernel<D, 32> : dense_bwd_kernel<D, BITS>;
     if ((rc = set_smem(kern, smem)) != TINYKG_OK) return rc;
     const int grid = dense_grid(N);
@@ -2415,7 +2484,8 @@ tinykg_status bwd_impl(const tinykg_graph* g, const tinykg_saved* sv, const floa
     {
       ProfileScope prof("dense_bwd_kernel", st);
       hipLaunchKernelGGL(kern, dim3(grid), dim3(kThreads), smem, st, srcH, sv->mask_J, gEout, W,
-                         d_out, slope, N, gH, gE, pW, acc, with_heavy ? n_heavy_elems * kHeavyReplicas : 0);
+                         d_out, slope, N, gH, gE, pW, acc, with_heavy ? n_heavy_elems * kHeavyReplicas : 0,
+                         uniform ? g->rowptr : (const int32_t*)nullptr);
     }
     if ((rc = launch_status()) != TINYKG_OK) return rc;
   }
@@ -2423,8 +2493,8 @@ tinykg_status bwd_impl(const tinykg_graph* g, const tinykg_saved* sv, const floa
     const GradSink sink{gE, acc, g->acc_slot};
     const int64_t waves = (g->n_edges + 31) / 32;
     ProfileScope prof("uniform_bwd_kernel", st);
-    hipLaunchKernelGGL((uniform_bwd_kernel<D, UniformRows<D>>), dim3((unsigned)((waves + 3) / 4)), dim3(kThreads),
-                       0, st, g->r_head, g->r_tail, g->r_hperm32, UniformRows<D>{g->rowptr, gH}, g->n_edges, sink);
+    hipLaunchKernelGGL((uniform_tail_kernel<D>), dim3((unsigned)((waves + 3) / 4)), dim3(kThreads), 0, st,
+                       g->c_head, g->c_tail, gH, g->n_edges, sink);
     if ((rc = launch_status()) != TINYKG_OK) return rc;
   }
   if (!uniform && g->n_chunks > 0) {

@@ -44,6 +44,11 @@ struct tinykg_graph {
   // before they are scattered), bit 6 / bit 7: the tail / head of THIS row is a node that
   // accumulates its gradient in double
   uint8_t* r_hperm32 = nullptr;      // [n_edges]
+  // tail order (edges sorted by tail, then head): what the transposed sparse product of the
+  // uniform-attention layer walks -- all in-edges of a tail are adjacent, so their rows are
+  // summed before they leave the wave and most tails are written by exactly one wave
+  int32_t* c_head = nullptr;   // [n_edges]
+  int32_t* c_tail = nullptr;   // [n_edges] bit 30: the tail accumulates its gradient in double
   // nodes that receive more than kAccHeavyDegree gradient rows (in-edges + out-edges)
   // accumulate them in double, in a compact buffer; all others in fp32
   int32_t n_acc_heavy = 0;

@@ -96,6 +96,25 @@ __global__ __launch_bounds__(kBuildThreads) void rel_tail_keys_kernel(const int3
   }
 }
 
+__global__ __launch_bounds__(kBuildThreads) void iota_i32_kernel(int32_t* __restrict__ dst, size_t n) {
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x)
+    dst[i] = (int32_t)i;
+}
+
+// the tail order's arrays from the sorted head-order positions; bit 30 of a tail: accumulates in double
+__global__ __launch_bounds__(kBuildThreads) void tail_order_kernel(const int32_t* __restrict__ h_head,
+                                                                   const int32_t* __restrict__ h_tail,
+                                                                   const int32_t* __restrict__ pos, size_t T,
+                                                                   const int32_t* __restrict__ acc_slot,
+                                                                   int32_t* __restrict__ c_head,
+                                                                   int32_t* __restrict__ c_tail) {
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < T; i += (size_t)gridDim.x * blockDim.x) {
+    const int32_t p = pos[i], t = h_tail[p];
+    c_head[i] = h_head[p];
+    c_tail[i] = t | (acc_slot[t] >= 0 ? 0x40000000 : 0);
+  }
+}
+
 __global__ __launch_bounds__(kBuildThreads) void gather_i32_kernel(const int32_t* __restrict__ src,
                                                                    const int32_t* __restrict__ idx, size_t T,
                                                                    int32_t* __restrict__ dst) {
@@ -228,7 +247,7 @@ void release(tinykg_graph* g) {
   if (!g) return;
   void* ptrs[] = {g->rowptr, g->h_tail, g->r_head, g->r_tail, g->r_eid, g->chunk_rel,
                   g->chunk_start, g->chunk_count, g->rel_chunk_ptr, g->heavy_head, g->heavy_seg_ptr,
-                  g->hseg_q, g->hseg_e0, g->hseg_cnt, g->r_hperm32, g->acc_slot, g->acc_node,
+                  g->hseg_q, g->hseg_e0, g->hseg_cnt, g->r_hperm32, g->acc_slot, g->acc_node, g->c_head, g->c_tail,
                   g->span_group_ptr, g->span_rel, g->span_start, g->span_count, g->rel_span_ptr};
   for (void* p : ptrs)
     if (p) (void)hipFree(p);
@@ -281,6 +300,8 @@ tinykg_status tinykg_graph_create(int64_t n_nodes, int32_t n_rel, int64_t n_edge
   TINYKG_TRY(device_array(T, &g->r_tail));
   TINYKG_TRY(device_array(T, &g->r_eid));
   TINYKG_TRY(device_array(T, &g->r_hperm32));
+  TINYKG_TRY(device_array(T, &g->c_head));
+  TINYKG_TRY(device_array(T, &g->c_tail));
 
   // ---- degrees; CSR row pointers = exclusive prefix sums of the out-degrees
   int32_t *out_deg = nullptr, *rows = nullptr;
@@ -387,6 +408,17 @@ tinykg_status tinykg_graph_create(int64_t n_nodes, int32_t n_rel, int64_t n_edge
     hipLaunchKernelGGL(rel_first_kernel, dim3((n_rel + 1 + kBuildThreads - 1) / kBuildThreads), dim3(kBuildThreads), 0,
                        st, ks, T, n_rel, d_first);
     TINYKG_TRY(download(d_first, (size_t)n_rel + 1, rel_first, st));
+
+    // tail order over head-order positions: one stable pass by tail; heads ascend inside a tail
+    {
+      int32_t *ta = nullptr, *tb = nullptr, *cord = nullptr;
+      TINYKG_TRY(sc.get(T, &ta)); TINYKG_TRY(sc.get(T, &tb));
+      TINYKG_HIP_TRY(hipMemcpyAsync(ta, g->h_tail, T * 4, hipMemcpyDeviceToDevice, st));
+      hipLaunchKernelGGL(iota_i32_kernel, dim3(build_grid(T)), dim3(kBuildThreads), 0, st, va, T);
+      TINYKG_TRY(sort_pairs_i32(sc, ta, tb, va, vb, T, bits_for(std::max<int64_t>(n_nodes, 2)), st, &cord));
+      hipLaunchKernelGGL(tail_order_kernel, dim3(build_grid(T)), dim3(kBuildThreads), 0, st, ha, g->h_tail, cord, T,
+                         g->acc_slot, g->c_head, g->c_tail);
+    }
 
     // per-tile summaries and per-row bytes
     std::vector<int64_t> rel_tile_ptr((size_t)n_rel + 1, 0);

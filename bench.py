@@ -236,6 +236,19 @@ def sweep_cells(tk, torch, steps, with_variance):
                 gbs = n * bpe / (ms / cnt) / 1e6
                 cell[key] = {"ms": round(ms / cnt, 4), "GB/s": round(gbs, 1),
                              "frac_of_hbm_peak": round(gbs / HBM_PEAK_GBS, 4)}
+            pair_ms = cell["quantize_pack"]["ms"] + cell["unpack_dequantize"]["ms"]
+            cell["pair_frac_of_hbm_peak"] = round(2 * n * bpe / pair_ms / 1e6 / HBM_PEAK_GBS, 4)
+            # the dequantizer launched back to back: it then does not inherit the write-back of the dirty
+            # lines that the quantizer's launch left in the 256 MB last-level cache (about 40 us when full)
+            tk.tinykg_profile_enable(True)
+            for i in range(steps):
+                tk.tinykg_dequantize(*buf, C2_ROWS, C2_DIM, bits, group, out=out)
+            torch.cuda.synchronize()
+            cnt, ms = tk.tinykg_profile_report()["dequantize_kernel"]
+            tk.tinykg_profile_enable(False)
+            gbs = n * bpe / (ms / cnt) / 1e6
+            cell["unpack_dequantize_back_to_back"] = {"ms": round(ms / cnt, 4), "GB/s": round(gbs, 1),
+                                                      "frac_of_hbm_peak": round(gbs / HBM_PEAK_GBS, 4)}
             if with_variance:
                 cell["variance"] = variance_stats(tk, torch, sub, bits, group)
             cells.append(cell)
@@ -256,9 +269,15 @@ def sweep_cells(tk, torch, steps, with_variance):
 def sweep_object(cells, copy, steps):
     fq = [c["quantize_pack"]["frac_of_hbm_peak"] for c in cells]
     fd = [c["unpack_dequantize"]["frac_of_hbm_peak"] for c in cells]
+    fp = [c["pair_frac_of_hbm_peak"] for c in cells]
+    fb = [c["unpack_dequantize_back_to_back"]["frac_of_hbm_peak"] for c in cells]
     return {"workload": f"configs[2]: {C2_ROWS}x{C2_DIM} fp32 Student-t(3) (2 GiB), bits in {{2,4,8}} x group in "
                         "{32,64,256}; HIP-event averages per launch, GB/s = (4 + b/8 + 8/G) B x 2^29 / time",
+            "schedule": "quantize and dequantize launches alternate (each dequantize launch inherits the write-back of "
+                        "the dirty lines its quantize launch left in the last-level cache); unpack_dequantize_back_to_back "
+                        "times the dequantizer's launches in a row; pair = both kernels' bytes over both kernels' time",
             "launches_per_cell": steps, "min_frac_quantize_pack": min(fq), "min_frac_unpack_dequantize": min(fd),
+            "min_frac_pair": min(fp), "min_frac_unpack_dequantize_back_to_back": min(fb),
             "plain_copy": copy, "cells": cells}
 
 

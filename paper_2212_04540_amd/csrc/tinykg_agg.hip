@@ -1143,8 +1143,13 @@ __global__ __launch_bounds__(kThreads) void dense_fwd_kernel(const float* __rest
 // grad_J = grad_E' * (mask ? 1 : slope); grad_H = grad_J W (also written to grad_E, which
 // the edge stage then adds to); per-workgroup partial of grad_W = grad_J^T H_hat.
 // deg_rowptr != nullptr (uniform layer): the copy in gH is divided by the row's out-degree.
+// Eight waves at d = 128 (two per SIMD: one wave's LDS reads and stores overlap the other's
+// products; a single resident workgroup has nothing else to overlap them with), four below.
+template <int D>
+constexpr int dense_bwd_waves() { return D == 128 ? 8 : 4; }
+
 template <int D, int BITS>
-__global__ __launch_bounds__(kThreads) void dense_bwd_kernel(Source srcH,
+__global__ __launch_bounds__(dense_bwd_waves<D>() * 64) void dense_bwd_kernel(Source srcH,
                                                              const uint8_t* __restrict__ mask,
                                                              const float* __restrict__ gEout,
                                                              const float* __restrict__ W, int d_out,
@@ -1156,9 +1161,11 @@ __global__ __launch_bounds__(kThreads) void dense_bwd_kernel(Source srcH,
                                                              int64_t zero_n,
                                                              const int32_t* __restrict__ deg_rowptr) {
   constexpr int LD = D + 4, LPR = D / 4, TN = 64, NIB = D / 32;
+  constexpr int NWV = dense_bwd_waves<D>(), NT = NWV * 64;   // waves, threads
+  constexpr int NWB = (4 * NIB + NWV - 1) / NWV;             // grad_W blocks per wave (at most 4 NIB blocks)
   // (the double-precision rows that the edge stage adds to start from zero: cleared here,
   // a launch earlier, instead of by a kernel of their own)
-  for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < zero_n; i += (int64_t)gridDim.x * kThreads)
+  for (int64_t i = (int64_t)blockIdx.x * NT + threadIdx.x; i < zero_n; i += (int64_t)gridDim.x * NT)
     zero_ptr[i] = 0.0;
   const int DOP = (d_out + 31) & ~31, LDJ = DOP + 4, NOB = DOP / 32;
   float* W_s = reinterpret_cast<float*>(smem_raw);   // [DOP][LD]
@@ -1166,21 +1173,21 @@ __global__ __launch_bounds__(kThreads) void dense_bwd_kernel(Source srcH,
   float* gJ_s = Hh_s + TN * LD;                      // [TN][LDJ]
   float* sc_s = gJ_s + TN * LDJ;                     // [TN] factor of the grad_H copy in gH (uniform layer: 1 / deg)
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  for (int q = tid; q < DOP * LPR; q += kThreads) {
+  for (int q = tid; q < DOP * LPR; q += NT) {
     const int row = q / LPR, li = q % LPR;
     float4 w = make_float4(0.f, 0.f, 0.f, 0.f);
     if (row < d_out) w = reinterpret_cast<const float4*>(W)[row * LPR + li];
     *reinterpret_cast<float4*>(W_s + row * LD + li * 4) = w;
   }
-  floatx16 accW[NIB];
+  floatx16 accW[NWB];
 #pragma unroll
-  for (int j = 0; j < NIB; ++j) accW[j] = floatx16{0};
+  for (int j = 0; j < NWB; ++j) accW[j] = floatx16{0};
 
   const int64_t n_tiles = (N + TN - 1) / TN;
   const int ocp = DOP / 4, oc = d_out / 4;
   // the saved rows, upstream gradient and mask bits of the workgroup's next tile are
   // requested while the current one is multiplied (d_out <= 128: at most 8 chunks a thread)
-  constexpr int CPT = TN * LPR / kThreads, GPT = TN * 32 / kThreads;
+  constexpr int CPT = TN * LPR / NT, GPT = TN * 32 / NT;
   RawChunk<BITS> preH[CPT];
   float4 preG[GPT];
   uint32_t preM[GPT];
@@ -1188,7 +1195,7 @@ __global__ __launch_bounds__(kThreads) void dense_bwd_kernel(Source srcH,
   auto load_tile = [&](int64_t tile) {
 #pragma unroll
     for (int k = 0; k < CPT; ++k) {
-      const int q = tid + k * kThreads;
+      const int q = tid + k * NT;
       const int64_t n = tile * TN + q / LPR;
       preH[k].load(srcH, (n < N ? n : 0) * LPR + q % LPR);   // past the end: row 0, zeroed below
     }
@@ -1200,7 +1207,7 @@ __global__ __launch_bounds__(kThreads) void dense_bwd_kernel(Source srcH,
     }
 #pragma unroll
     for (int k = 0; k < GPT; ++k) {
-      const int q = tid + k * kThreads;
+      const int q = tid + k * NT;
       const int64_t n = tile * TN + q / ocp;
       const int c4 = q % ocp;
       preG[k] = make_float4(0.f, 0.f, 0.f, 0.f);
@@ -1218,14 +1225,14 @@ __global__ __launch_bounds__(kThreads) void dense_bwd_kernel(Source srcH,
     __syncthreads();
 #pragma unroll
     for (int k = 0; k < CPT; ++k) {
-      const int q = tid + k * kThreads;
+      const int q = tid + k * NT;
       const int row = q / LPR;
       const float4 x = n0 + row < N ? preH[k].get() : make_float4(0.f, 0.f, 0.f, 0.f);
       *reinterpret_cast<float4*>(Hh_s + row * LD + (q % LPR) * 4) = x;
     }
 #pragma unroll
     for (int k = 0; k < GPT; ++k) {
-      const int q = tid + k * kThreads;
+      const int q = tid + k * NT;
       if (q < TN * ocp) {
         float4 g = preG[k];
         const uint32_t mb = preM[k];
@@ -1238,7 +1245,7 @@ __global__ __launch_bounds__(kThreads) void dense_bwd_kernel(Source srcH,
     if (tile + gridDim.x < n_tiles) load_tile(tile + gridDim.x);
     __syncthreads();
     // grad_H tile: [n][i] = sum_o gJ[n][o] W[o][i]
-    for (int blk = wave; blk < 2 * NIB; blk += 4) {
+    for (int blk = wave; blk < 2 * NIB; blk += NWV) {
       const int nb = blk & 1, ib = blk >> 1;
       floatx16 acc = {0};
       mfma_block<KCONT, KMAJOR>(gJ_s + nb * 32 * LDJ, LDJ, W_s + ib * 32, LD, DOP, acc);
@@ -1253,8 +1260,8 @@ __global__ __launch_bounds__(kThreads) void dense_bwd_kernel(Source srcH,
     }
     // grad_W partial: [o][i] += sum_n gJ[n][o] H_hat[n][i]
 #pragma unroll
-    for (int j = 0; j < NIB; ++j) {
-      const int blk = wave + 4 * j;
+    for (int j = 0; j < NWB; ++j) {
+      const int blk = wave + NWV * j;
       if (blk < NOB * NIB) {
         const int ob = blk / NIB, ib = blk % NIB;
         mfma_block<KMAJOR, KMAJOR>(gJ_s + ob * 32, LDJ, Hh_s + ib * 32, LD, TN, accW[j]);
@@ -1263,8 +1270,8 @@ __global__ __launch_bounds__(kThreads) void dense_bwd_kernel(Source srcH,
   }
   float* out = part_W + (size_t)blockIdx.x * d_out * D;
 #pragma unroll
-  for (int j = 0; j < NIB; ++j) {
-    const int blk = wave + 4 * j;
+  for (int j = 0; j < NWB; ++j) {
+    const int blk = wave + NWV * j;
     if (blk < NOB * NIB) {
       const int ob = blk / NIB, ib = blk % NIB;
 #pragma unroll
@@ -2483,7 +2490,7 @@ tinykg_status bwd_impl(const tinykg_graph* g, const tinykg_saved* sv, const floa
     dense_blocks = grid;
     {
       ProfileScope prof("dense_bwd_kernel", st);
-      hipLaunchKernelGGL(kern, dim3(grid), dim3(kThreads), smem, st, srcH, sv->mask_J, gEout, W,
+      hipLaunchKernelGGL(kern, dim3(grid), dim3(dense_bwd_waves<D>() * 64), smem, st, srcH, sv->mask_J, gEout, W,
                          d_out, slope, N, gH, gE, pW, acc, with_heavy ? n_heavy_elems * kHeavyReplicas : 0,
                          uniform ? g->rowptr : (const int32_t*)nullptr);
     }

@@ -50,20 +50,23 @@ __device__ __forceinline__ int acc_row(int v, int lane) {
   return (v & 3) + 4 * (lane >> 5) + 8 * (v >> 2);
 }
 
-// tanh without branches.  |x| >= 1/8: 1 - 2 / (exp(2x) + 1) on the hardware exp2 / rcp units;
-// the subtraction from 1 bounds the ABSOLUTE error by that of the quotient (below 2e-7), i.e.
-// a relative error below 2e-6 there; exp overflow gives exactly 1, underflow exactly -1.
-// |x| < 1/8: the odd series x - x^3/3 + 2x^5/15 - 17x^7/315 (truncation below 2e-9 of the
-// value), because near 0 the first form loses the value's leading digits in the subtraction
-// and grad_a = grad_s tanh(b) inherits the RELATIVE error of tanh.
+// tanh without branches: 1 - 2 / (exp(2x) + 1) on the hardware exp2 / rcp units.  The
+// subtraction from 1 bounds the ABSOLUTE error by that of the quotient (below 2e-7 for every
+// x); exp overflow gives exactly 1, underflow exactly -1.  Enough for the scores
+// s = a . tanh(b), whose error enters the softmax weights as an absolute error of s.
 __device__ __forceinline__ float fast_tanh(float x) {
   const float e = __builtin_amdgcn_exp2f(x * 2.885390081777927f);   // exp(2x)
-  const float big = fmaf(-2.0f, __builtin_amdgcn_rcpf(e + 1.0f), 1.0f);
+  return fmaf(-2.0f, __builtin_amdgcn_rcpf(e + 1.0f), 1.0f);
+}
+
+// tanh accurate in RELATIVE terms, for grad_a = grad_s tanh(b), which inherits the relative
+// error of tanh: near 0 the form above loses the value's leading digits in the subtraction.
+// |x| < 1/8: the odd series x - x^3/3 + 2x^5/15 (truncation below 3e-7 of the value);
+// elsewhere the form above, whose absolute error is then below 2e-6 of the value.
+__device__ __forceinline__ float tanh_rel(float x) {
   const float x2 = x * x;
-  float p = fmaf(x2, -17.0f / 315.0f, 2.0f / 15.0f);
-  p = fmaf(x2, p, -1.0f / 3.0f);
-  const float small = fmaf(x * x2, p, x);
-  return fabsf(x) < 0.125f ? small : big;
+  const float small = fmaf(x * x2, fmaf(x2, 2.0f / 15.0f, -1.0f / 3.0f), x);
+  return fabsf(x) < 0.125f ? small : fast_tanh(x);
 }
 
 template <int AM, int BM>
@@ -1687,7 +1690,7 @@ __global__ __launch_bounds__(kCoopWaves * 64) void edge_bwd_kernel(
         float da[4], f[4];
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
-          const float vv = fast_tanh(acc1[4 * vg + u] + er_s[c0 + u]);
+          const float vv = tanh_rel(acc1[4 * vg + u] + er_s[c0 + u]);
           da[u] = g * vv;
           f[u] = g * (1.f - vv * vv);
         }
@@ -2003,7 +2006,7 @@ __device__ __forceinline__ void edge_wave_span(
         for (int u = 0; u < 4; ++u) {
 #pragma unroll
           for (int cb = 0; cb < NB; ++cb) {
-            const float vv = fast_tanh(accB[cb][4 * q + u] + er_c[cb]);
+            const float vv = tanh_rel(accB[cb][4 * q + u] + er_c[cb]);
             const float db = gq[u] * accA[cb][4 * q + u] * (1.f - vv * vv);
             accA[cb][4 * q + u] = gq[u] * vv;
             accB[cb][4 * q + u] = db;

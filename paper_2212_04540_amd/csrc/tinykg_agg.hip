@@ -2256,6 +2256,448 @@ __global__ __launch_bounds__(kEdgeWaves * 64) void edge_wave_kernel(
   }
 }
 
+// ---------------------------------------------- edge-level backward, code form ----
+// The d <= 64 edge kernel for a compressed context whose quantisation group covers at least a
+// row (every row then has ONE (Z, scale) pair), with ALL six products on the bf16 matrix cores:
+//   1a  a, b: Eq. (4) is linear, W_r e_hat = scale (W_r code) + Z (W_r 1); the integer codes are
+//       exact bfloat16 values, so each product is three piece products with the pieces of W_r
+//       (split once per span into LDS), and the rows are neither dequantised nor split.  The
+//       row fragments come straight from the registers the rows were fetched into.
+//   1c  grad_W_r = sum_e grad[e] e_hat[e]^T = sum_e (scale_e grad[e]) code[e]^T + (sum_e mid_e grad[e]) 1^T:
+//       the left operand is the accumulator of step 1 itself (lane = channel, registers =
+//       edges: exactly the operand layout with the edges as contraction index), scaled and
+//       split in registers; the codes are read column-wise from the tile's code matrix in LDS;
+//       the rank-one part is a per-lane sum that joins the tile's own partial sum.  (The codes
+//       are centred, code - B/2, and Z becomes the row's midpoint: see where they are packed.)
+//   2   Pt = grad_a W_r, Ph = grad_b W_r: grad rows go through LDS once (they must change from
+//       lane = channel to lane = edge), are split on the fly and meet the pieces of W_r^T (split
+//       once per span into LDS as well): six piece products.  The two sides run one after the
+//       other through ONE fp32 buffer that overlays the (by then dead) code matrices.
+// LDS: pieces of W_r and of W_r^T (2 x 27 KiB at d = 64) and 10.3 KiB per wave.
+// Everything else (flags, scatter, partial sums) as in the fp32 form below.
+template <int D>
+constexpr int edge_code_region_bytes() { return 2 * 32 * (D + 8) * 2 + 10 * 32 * 4; }
+template <int D>
+constexpr int edge_code_smem_bytes() {
+  // pieces of W_r and W_r^T, row sums, e_r, the waves' regions -- or, at the end of a span, the
+  // waves' partial grad_W_r (which overlay everything)
+  constexpr int work = 2 * 3 * D * (D + 8) * 2 + 2 * D * 4 + kEdgeWaves * edge_code_region_bytes<D>();
+  constexpr int comb = kEdgeWaves * ((D / 32) * (D / 32) * 1024 + D) * 4;
+  return work > comb ? work : comb;
+}
+
+// W_r^T as three bf16 matrices: Wt[i][c] = W[c][i], rows padded like stage_split_matrix's.
+template <int D>
+__device__ __forceinline__ void stage_split_matrix_transposed(const float* __restrict__ W, uint16_t* __restrict__ Wt,
+                                                              int tid, int n_threads) {
+  constexpr int LDW = D + 8;
+  for (int q = tid; q < D * D; q += n_threads) {
+    const int c = q / D, i = q % D;              // coalesced reads of W, strided 2-byte writes
+    const float x = W[q];
+    const uint32_t hb = __float_as_uint(x) & 0xFFFF0000u;
+    const float r1 = x - __uint_as_float(hb);
+    const uint32_t mb = __float_as_uint(r1) & 0xFFFF0000u;
+    const uint32_t lb = __float_as_uint(r1 - __uint_as_float(mb));
+    Wt[i * LDW + c] = (uint16_t)(hb >> 16);
+    Wt[D * LDW + i * LDW + c] = (uint16_t)(mb >> 16);
+    Wt[2 * D * LDW + i * LDW + c] = (uint16_t)(lb >> 16);
+  }
+}
+
+// Sum of the integer codes of a whole row, from the two lane halves that hold it.
+template <int D, int BITS>
+__device__ __forceinline__ float code_sum(const HalfRow<D, BITS>& h) {
+  uint32_t sum = 0;
+#pragma unroll
+  for (int k = 0; k < HalfRow<D, BITS>::NW; ++k) {
+    uint32_t w = h.w[k];
+    if (BITS == 1) { sum += (uint32_t)__builtin_popcount(w); continue; }
+    if (BITS == 2) w = (w & 0x33333333u) + ((w >> 2) & 0x33333333u);              // 4-bit sums of two codes
+    if (BITS <= 4) w = (w & 0x0F0F0F0Fu) + ((w >> 4) & 0x0F0F0F0Fu);              // byte sums
+    sum = __builtin_amdgcn_sad_u8(w, 0u, sum);
+  }
+  const float f = (float)sum;
+  return f + __shfl_xor(f, 32);
+}
+
+template <int D, int BITS>
+__device__ __forceinline__ void edge_code_span(
+    const int ch, const Source& src, const float* __restrict__ Wr, const float* __restrict__ er,
+    const int32_t* __restrict__ r_head, const int32_t* __restrict__ r_tail,
+    const int32_t* __restrict__ r_eid, const uint8_t* __restrict__ r_hperm, const ChunkList& chunks,
+    const float* __restrict__ pi, const float* __restrict__ gs, const float* __restrict__ gH,
+    const GradSink& sink, float* __restrict__ part_Wr, float* __restrict__ part_er) {
+  constexpr int LD = D + 4, LDW = D + 8, KH = D / 2, NB = D / 32, NM = KH / 8, NW = kEdgeWaves;
+  constexpr int NT = NW * 64, REGION = edge_code_region_bytes<D>();
+  constexpr int NQ = 64 / D, RP = 32 / NQ;        // scatter: row parts of a wave
+  uint16_t* Wp = reinterpret_cast<uint16_t*>(smem_raw);                 // [3][D][LDW]: W_r, k = i contiguous
+  uint16_t* Wtp = Wp + 3 * D * LDW;                                     // [3][D][LDW]: W_r^T, k = c contiguous
+  float* wsum_s = reinterpret_cast<float*>(Wtp + 3 * D * LDW);          // row sums of W_r
+  float* er_s = wsum_s + D;
+  unsigned char* regions = reinterpret_cast<unsigned char*>(er_s + D);
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  unsigned char* mine = regions + wave * REGION;
+  uint16_t* Ct_s = reinterpret_cast<uint16_t*>(mine);                   // [32][LDW] codes of the tail rows
+  uint16_t* Ch_s = Ct_s + 32 * LDW;                                     // [32][LDW] codes of the head rows
+  float* G_s = reinterpret_cast<float*>(mine);                          // [32][LD] fp32, overlays both (step 2)
+  float* gs_s = reinterpret_cast<float*>(mine + 2 * 32 * LDW * 2);
+  float* pi_s = gs_s + 32;
+  float* zt_s = pi_s + 32;                         // (mid, scale) of the tail / head row of edge e
+  float* st_s = zt_s + 32;
+  float* zh_s = st_s + 32;
+  float* sh_s = zh_s + 32;
+  int* tl_s = reinterpret_cast<int*>(sh_s + 32);   // tail of row e; sign bit: a tail run ends here
+  int* hd_s = tl_s + 32;                           // head of row e
+  int* hp_s = hd_s + 32;                           // row of head-order rank k
+  int* hr_s = hp_s + 32;                           // head of rank k; sign bit: a head run ends here
+  static_assert(2 * 32 * LDW * 2 >= 32 * LD * 4, "the fp32 buffer must fit over the two code matrices");
+
+  const int rel = chunks.rel[ch], start = chunks.start[ch], count = chunks.count[ch];
+  const int r = lane & 31, hh = lane >> 5;
+  const int n_wt = (count + 31) >> 5;
+
+  stage_split_matrix<D>(Wr + (size_t)rel * D * D, Wp, tid, NT);
+  stage_split_matrix_transposed<D>(Wr + (size_t)rel * D * D, Wtp, tid, NT);
+  for (int c = tid; c < D; c += NT) {
+    er_s[c] = er[(size_t)rel * D + c];
+    const float4* row = reinterpret_cast<const float4*>(Wr + ((size_t)rel * D + c) * D);
+    double sum = 0.0;
+    for (int q = 0; q < D / 4; ++q) { const float4 w = row[q]; sum += (double)w.x + (double)w.y + (double)w.z + (double)w.w; }
+    wsum_s[c] = (float)sum;
+  }
+  __syncthreads();
+
+  float er_c[NB], ws_c[NB], er_acc[NB];
+#pragma unroll
+  for (int cb = 0; cb < NB; ++cb) { er_c[cb] = er_s[cb * 32 + r]; ws_c[cb] = wsum_s[cb * 32 + r]; er_acc[cb] = 0.f; }
+  floatx16 accW[NB * NB];
+#pragma unroll
+  for (int j = 0; j < NB * NB; ++j) accW[j] = floatx16{0};
+
+  for (int wt = wave; wt < n_wt; wt += NW) {
+    // ---- stage: ids, flags, per-edge scalars; rows fetched as raw codes
+    int t_ld = 0, h_ld = 0, e_ld = -1, hp_ld = 0;   // past the end: node 0 (a valid row), weight 0
+    {
+      const int row = wt * 32 + r;
+      if (row < count) {
+        const int pos = start + row;
+        t_ld = r_tail[pos]; h_ld = r_head[pos]; e_ld = r_eid[pos]; hp_ld = r_hperm[pos];
+      }
+    }
+    HalfRow<D, BITS> nt, nh;
+    nt.load(src, t_ld, hh);
+    nh.load(src, h_ld, hh);
+    float g_ld = 0.f, p_ld = 0.f;
+    if (e_ld >= 0) { g_ld = gs[e_ld]; p_ld = pi[e_ld]; }
+    const int nrow = min(32, count - wt * 32);
+    {
+      const int perm = hp_ld & 31;
+      const int t_id = t_ld | ((hp_ld & 0x40) ? kHeavyBit : 0), h_id = h_ld | ((hp_ld & 0x80) ? kHeavyBit : 0);
+      const int h_rank = __shfl(h_id, perm);                    // head of rank r
+      const int t_next = __shfl_down(t_id, 1), h_next = __shfl_down(h_rank, 1);
+      const bool stop = r + 1 == nrow || (r + 1) % RP == 0;
+      const int t_flag = (r < nrow && (stop || t_next != t_id)) ? (int)0x80000000 : 0;
+      const int h_flag = (r < nrow && (stop || h_next != h_rank)) ? (int)0x80000000 : 0;
+      if (hh == 0) {
+        gs_s[r] = g_ld; pi_s[r] = p_ld; hd_s[r] = h_ld; hp_s[r] = perm;
+        tl_s[r] = t_id | t_flag; hr_s[r] = h_rank | h_flag;
+        st_s[r] = nt.s; sh_s[r] = nh.s;
+      }
+    }
+    // the codes as bfloat16 values (exact): operand fragments of step 1a, and the code matrices
+    Bf16Frag tc[NM], hc[NM];
+    float mid_t, mid_h;
+    {
+      // (centred on the row's own mean code, rounded to an integer m: code - m is a small integer,
+      // an exact bfloat16 value like the code, and e_hat = mid + scale (code - m) with
+      // mid = Z + scale m splits every sum into a part of the size of the row's spread and a part
+      // of the size of its mean, instead of two parts of the size of |Z| that cancel)
+      const float mt = rintf(code_sum(nt) * (1.0f / (float)D)), mh = rintf(code_sum(nh) * (1.0f / (float)D));
+      auto pack = [](uint32_t c0, uint32_t c1, float m) {
+        return __builtin_amdgcn_perm(__float_as_uint((float)c1 - m), __float_as_uint((float)c0 - m), 0x07060302u);
+      };
+      mid_t = fmaf(nt.s, mt, nt.z);
+      mid_h = fmaf(nh.s, mh, nh.z);
+#pragma unroll
+      for (int m = 0; m < NM; ++m) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          tc[m].u[i] = pack(nt.code(8 * m + 2 * i), nt.code(8 * m + 2 * i + 1), mt);
+          hc[m].u[i] = pack(nh.code(8 * m + 2 * i), nh.code(8 * m + 2 * i + 1), mh);
+        }
+        *reinterpret_cast<uint4*>(Ct_s + r * LDW + hh * KH + 8 * m) = *reinterpret_cast<const uint4*>(tc[m].u);
+        *reinterpret_cast<uint4*>(Ch_s + r * LDW + hh * KH + 8 * m) = *reinterpret_cast<const uint4*>(hc[m].u);
+      }
+    }
+    if (hh == 0) { zt_s[r] = mid_t; zh_s[r] = mid_h; }
+    phase_fence();
+
+    // ---- 1a. code products: accumulator row = edge, lane column = channel
+    floatx16 accA[NB], accB[NB];
+#pragma unroll
+    for (int cb = 0; cb < NB; ++cb) { accA[cb] = floatx16{0}; accB[cb] = floatx16{0}; }
+    {
+      int wofs = 0;
+      asm volatile("" : "+v"(wofs));    // the pieces are re-read from LDS, never parked in registers
+      const uint16_t* wrow = Wp + r * LDW + hh * KH + wofs;
+#pragma unroll
+      for (int m = 0; m < NM; ++m) {
+        Bf16Frag wh[NB], wm[NB], wl[NB];
+#pragma unroll
+        for (int cb = 0; cb < NB; ++cb) {
+          const uint16_t* wp = wrow + cb * 32 * LDW + 8 * m;
+          *reinterpret_cast<uint4*>(wh[cb].u) = *reinterpret_cast<const uint4*>(wp);
+          *reinterpret_cast<uint4*>(wm[cb].u) = *reinterpret_cast<const uint4*>(wp + D * LDW);
+          *reinterpret_cast<uint4*>(wl[cb].u) = *reinterpret_cast<const uint4*>(wp + 2 * D * LDW);
+        }
+#define TINYKG_CODE_STEP(WP)                                                                               \
+        _Pragma("unroll") for (int cb = 0; cb < NB; ++cb) {                                                \
+          accA[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tc[m].v, WP[cb].v, accA[cb], 0, 0, 0);        \
+          accB[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(hc[m].v, WP[cb].v, accB[cb], 0, 0, 0);        \
+        }
+        TINYKG_CODE_STEP(wl)
+        TINYKG_CODE_STEP(wm)
+        TINYKG_CODE_STEP(wh)
+#undef TINYKG_CODE_STEP
+        __builtin_amdgcn_sched_barrier(0);   // one k-step's fragments at a time
+      }
+    }
+    // ---- 1b. a = s_t acc + Z_t (W_r 1), b = s_h acc + Z_h (W_r 1) + e_r;
+    //          grad_a = gs tanh(b), grad_b = gs a (1 - tanh(b)^2), in place
+    float zw_t[NB];          // sum over this lane's edges of mid_t grad_a + mid_h grad_b, channel cb * 32 + r
+    {
+      float er_t[NB];
+#pragma unroll
+      for (int cb = 0; cb < NB; ++cb) { er_t[cb] = 0.f; zw_t[cb] = 0.f; }
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {                    // registers 4q .. 4q + 3: edges 8q + 4hh + u
+        const float4 g4 = *reinterpret_cast<const float4*>(gs_s + 8 * q + 4 * hh);
+        const float4 a4 = *reinterpret_cast<const float4*>(st_s + 8 * q + 4 * hh);
+        const float4 b4 = *reinterpret_cast<const float4*>(sh_s + 8 * q + 4 * hh);
+        const float4 c4 = *reinterpret_cast<const float4*>(zt_s + 8 * q + 4 * hh);
+        const float4 d4 = *reinterpret_cast<const float4*>(zh_s + 8 * q + 4 * hh);
+        const float gq[4] = {g4.x, g4.y, g4.z, g4.w}, stq[4] = {a4.x, a4.y, a4.z, a4.w};
+        const float shq[4] = {b4.x, b4.y, b4.z, b4.w}, ztq[4] = {c4.x, c4.y, c4.z, c4.w};
+        const float zhq[4] = {d4.x, d4.y, d4.z, d4.w};
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+#pragma unroll
+          for (int cb = 0; cb < NB; ++cb) {
+            const int v = 4 * q + u;
+            const float a = fmaf(stq[u], accA[cb][v], ztq[u] * ws_c[cb]);
+            const float b = fmaf(shq[u], accB[cb][v], fmaf(zhq[u], ws_c[cb], er_c[cb]));
+            const float vv = tanh_rel(b);
+            const float db = gq[u] * a * (1.f - vv * vv);
+            const float da = gq[u] * vv;
+            accA[cb][v] = da;
+            accB[cb][v] = db;
+            er_t[cb] += db;
+            zw_t[cb] = fmaf(ztq[u], da, fmaf(zhq[u], db, zw_t[cb]));
+          }
+        }
+      }
+#pragma unroll
+      for (int cb = 0; cb < NB; ++cb) er_acc[cb] += er_t[cb];
+    }
+    // ---- 1c. grad_W_r[c][i] += sum_e (s_t grad_a)[e][c] code_t[e][i] + (s_h grad_b)[e][c] code_h[e][i]
+    //      (a fresh accumulator per tile keeps the fp32 running sum short)
+#pragma unroll
+    for (int cb = 0; cb < NB; ++cb) {
+      floatx16 accT[NB];
+#pragma unroll
+      for (int ib = 0; ib < NB; ++ib) accT[ib] = floatx16{0};
+#pragma unroll
+      for (int ks = 0; ks < 2; ++ks) {
+#pragma unroll
+        for (int side = 0; side < 2; ++side) {
+          // pieces of the scaled gradients of registers 8 ks .. 8 ks + 7 (edges 16 ks + 4 hh + {0..3, 8..11})
+          const float* sc_s = side == 0 ? st_s : sh_s;
+          const uint16_t* C_s = side == 0 ? Ct_s : Ch_s;
+          Bf16Frag xh, xm, xl;
+          {
+            const float4 s0 = *reinterpret_cast<const float4*>(sc_s + 16 * ks + 4 * hh), s1 = *reinterpret_cast<const float4*>(sc_s + 16 * ks + 8 + 4 * hh);
+            const float sv[8] = {s0.x, s0.y, s0.z, s0.w, s1.x, s1.y, s1.z, s1.w};
+            float x[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) x[j] = sv[j] * (side == 0 ? accA[cb][8 * ks + j] : accB[cb][8 * ks + j]);
+            split3x8(x, xh, xm, xl);
+          }
+          // codes of column ib * 32 + r at the eight edges of this lane half and k-step
+          Bf16Frag cf[NB];
+#pragma unroll
+          for (int ib = 0; ib < NB; ++ib) {
+#pragma unroll
+            for (int w2 = 0; w2 < 4; ++w2) {
+              const int e0 = acc_row(8 * ks + 2 * w2, lane), e1 = acc_row(8 * ks + 2 * w2 + 1, lane);
+              cf[ib].u[w2] = (uint32_t)C_s[e0 * LDW + ib * 32 + r] | ((uint32_t)C_s[e1 * LDW + ib * 32 + r] << 16);
+            }
+          }
+#pragma unroll
+          for (int ib = 0; ib < NB; ++ib) accT[ib] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xl.v, cf[ib].v, accT[ib], 0, 0, 0);
+#pragma unroll
+          for (int ib = 0; ib < NB; ++ib) accT[ib] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xm.v, cf[ib].v, accT[ib], 0, 0, 0);
+#pragma unroll
+          for (int ib = 0; ib < NB; ++ib) accT[ib] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xh.v, cf[ib].v, accT[ib], 0, 0, 0);
+          __builtin_amdgcn_sched_barrier(0);
+        }
+      }
+      // the tile's rank-one part (sum_e mid_e grad[e][c]) 1^T joins the tile's sum here, so that the
+      // long running sum carries the net value: row c of the block needs the sum of channel c,
+      // which lane c % 32 holds (both halves of the wave together)
+      {
+        const float zc = zw_t[cb] + __shfl_xor(zw_t[cb], 32);
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const float zr = __shfl(zc, acc_row(v, lane));
+#pragma unroll
+          for (int ib = 0; ib < NB; ++ib) accT[ib][v] += zr;
+        }
+      }
+#pragma unroll
+      for (int ib = 0; ib < NB; ++ib) {
+        accW[cb * NB + ib] += accT[ib];
+        asm volatile("" : "+v"(accW[cb * NB + ib]));   // pins the addition here
+      }
+    }
+    phase_fence();   // the code matrices are dead from here on: G_s overlays them
+
+    const int si = lane % D, se0 = (lane / D) * RP;   // scatter: this lane's column and rows
+    // ---- 2. per side: G_s <- grad (as [e][c]); P = G W_r on the bf16 matrix cores (rows split on
+    //      the fly, pieces of W_r^T from LDS); G_s <- P (as [e][i]); rows walked in tail order
+    //      resp. head order with running sums, one atomic per run and column
+#pragma unroll
+    for (int side = 0; side < 2; ++side) {
+#pragma unroll
+      for (int cb = 0; cb < NB; ++cb) {
+#pragma unroll
+        for (int v = 0; v < 16; ++v)
+          G_s[acc_row(v, lane) * LD + cb * 32 + r] = side == 0 ? accA[cb][v] : accB[cb][v];
+      }
+      phase_fence();
+      floatx16 accP[NB];
+#pragma unroll
+      for (int ib = 0; ib < NB; ++ib) accP[ib] = floatx16{0};
+      {
+        int wofs = 0;
+        asm volatile("" : "+v"(wofs));
+        const uint16_t* wtrow = Wtp + r * LDW + hh * KH + wofs;
+        const float* grow = G_s + r * LD + hh * KH;
+#pragma unroll
+        for (int m = 0; m < NM; ++m) {
+          const float4 lo4 = *reinterpret_cast<const float4*>(grow + 8 * m), hi4 = *reinterpret_cast<const float4*>(grow + 8 * m + 4);
+          const float x[8] = {lo4.x, lo4.y, lo4.z, lo4.w, hi4.x, hi4.y, hi4.z, hi4.w};
+          Bf16Frag gh, gm, gl;
+          split3x8(x, gh, gm, gl);
+          Bf16Frag wh[NB], wm[NB], wl[NB];
+#pragma unroll
+          for (int ib = 0; ib < NB; ++ib) {
+            const uint16_t* wp = wtrow + ib * 32 * LDW + 8 * m;
+            *reinterpret_cast<uint4*>(wh[ib].u) = *reinterpret_cast<const uint4*>(wp);
+            *reinterpret_cast<uint4*>(wm[ib].u) = *reinterpret_cast<const uint4*>(wp + D * LDW);
+            *reinterpret_cast<uint4*>(wl[ib].u) = *reinterpret_cast<const uint4*>(wp + 2 * D * LDW);
+          }
+#pragma unroll
+          for (int ib = 0; ib < NB; ++ib) {
+            accP[ib] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(gh.v, wl[ib].v, accP[ib], 0, 0, 0);
+            accP[ib] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(gl.v, wh[ib].v, accP[ib], 0, 0, 0);
+            accP[ib] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(gm.v, wm[ib].v, accP[ib], 0, 0, 0);
+            accP[ib] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(gh.v, wm[ib].v, accP[ib], 0, 0, 0);
+            accP[ib] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(gm.v, wh[ib].v, accP[ib], 0, 0, 0);
+            accP[ib] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(gh.v, wh[ib].v, accP[ib], 0, 0, 0);
+          }
+          __builtin_amdgcn_sched_barrier(0);
+        }
+      }
+      phase_fence();
+#pragma unroll
+      for (int ib = 0; ib < NB; ++ib) {
+#pragma unroll
+        for (int v = 0; v < 16; ++v) G_s[acc_row(v, lane) * LD + ib * 32 + r] = accP[ib][v];
+      }
+      phase_fence();
+      constexpr int RB = RP < 16 ? RP : 16;        // rows whose LDS reads are issued together
+      float run = 0.f;
+#pragma unroll
+      for (int k0 = 0; k0 < RP; k0 += RB) {
+        int node[RB];
+        float val[RB];
+#pragma unroll
+        for (int k = 0; k < RB; ++k) {
+          if (side == 0) {
+            // (the e_t term of H_h: pi_e grad_H_h, the head's row fetched here)
+            node[k] = tl_s[se0 + k0 + k];
+            const int hk = D == 64 ? __builtin_amdgcn_readfirstlane(hd_s[se0 + k0 + k]) : hd_s[se0 + k0 + k];
+            val[k] = fmaf(pi_s[se0 + k0 + k], gH[(int64_t)hk * D + si], G_s[(se0 + k0 + k) * LD + si]);
+          } else {
+            node[k] = hr_s[se0 + k0 + k];
+            const int pk = D == 64 ? __builtin_amdgcn_readfirstlane(hp_s[se0 + k0 + k]) : hp_s[se0 + k0 + k];
+            val[k] = G_s[pk * LD + si];
+          }
+        }
+#pragma unroll
+        for (int k = 0; k < RB; ++k) {
+          run += val[k];
+          const int nk = D == 64 ? __builtin_amdgcn_readfirstlane(node[k]) : node[k];
+          if (nk < 0) {
+            sink_add<D>(sink, nk, si, run);
+            run = 0.f;
+          }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+      }
+      phase_fence();   // the other side (or the next tile) overwrites G_s
+    }
+  }
+
+  // fixed-order combination of the eight waves' partial sums (the buffers overlay everything
+  // the span used: every wave must have finished its tiles)
+  __syncthreads();
+  {
+    constexpr int CW = NB * NB * 1024 + D;        // floats per wave
+    float* comb = reinterpret_cast<float*>(smem_raw);
+    float* mine_c = comb + wave * CW;
+#pragma unroll
+    for (int j = 0; j < NB * NB; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) mine_c[(j * 16 + v) * 64 + lane] = accW[j][v];
+#pragma unroll
+    for (int cb = 0; cb < NB; ++cb) {
+      const float both = er_acc[cb] + __shfl_xor(er_acc[cb], 32);
+      if (hh == 0) mine_c[NB * NB * 1024 + cb * 32 + r] = both;
+    }
+    __syncthreads();
+    float* outW = part_Wr + (size_t)ch * D * D;
+    for (int f = tid; f < D * D; f += NT) {
+      const int l = f & 63, v = (f >> 6) & 15, j = f >> 10;
+      const int cb = j / NB, ib = j % NB;
+      float sum = 0.f;
+#pragma unroll
+      for (int w = 0; w < NW; ++w) sum += comb[w * CW + f];
+      outW[(cb * 32 + acc_row(v, l)) * D + ib * 32 + (l & 31)] = sum;
+    }
+    if (tid < D) {
+      float sum = 0.f;
+#pragma unroll
+      for (int w = 0; w < NW; ++w) sum += comb[w * CW + NB * NB * 1024 + tid];
+      part_er[(size_t)ch * D + tid] = sum;
+    }
+  }
+}
+
+template <int D, int BITS>
+__global__ __launch_bounds__(kEdgeWaves * 64) void edge_code_kernel(
+    Source src, const float* __restrict__ Wr, const float* __restrict__ er,
+    const int32_t* __restrict__ r_head, const int32_t* __restrict__ r_tail,
+    const int32_t* __restrict__ r_eid, const uint8_t* __restrict__ r_hperm, ChunkList spans,
+    const int32_t* __restrict__ group_ptr, const float* __restrict__ pi, const float* __restrict__ gs,
+    const float* __restrict__ gH, GradSink sink, float* __restrict__ part_Wr, float* __restrict__ part_er) {
+  const int first = group_ptr[blockIdx.x], last = group_ptr[blockIdx.x + 1];
+  for (int sp = first; sp < last; ++sp) {
+    if (sp != first) __syncthreads();   // the previous span's combination has read the waves' partial sums
+    edge_code_span<D, BITS>(sp, src, Wr, er, r_head, r_tail, r_eid, r_hperm, spans, pi, gs, gH, sink, part_Wr, part_er);
+  }
+}
+
 // ------------------------------------------------------------- host helpers ----
 size_t align256(size_t b) { return (b + 255) & ~(size_t)255; }
 
@@ -2309,7 +2751,7 @@ BwdWs bwd_layout(const tinykg_graph* g, int d, int d_out) {
   w.pW = w.acc + align256((size_t)g->n_acc_heavy * kHeavyReplicas * d * 8);
   w.pWr = w.pW + align256((size_t)dense_grid(g->n_nodes) * d_out * d * 4);
   // (one partial per chunk, or per span of the persistent kernel, whichever are more)
-  const size_t n_part = (size_t)std::max(g->n_chunks, g->n_spans);
+  const size_t n_part = (size_t)std::max(g->n_chunks, std::max(g->n_spans, g->n_espans));
   w.per = w.pWr + align256(n_part * d * d * 4);
   w.hv = heavy_layout(g, d, w.per + align256(n_part * d * 4));
   w.total = w.hv.end;
@@ -2466,6 +2908,9 @@ tinykg_status bwd_impl(const tinykg_graph* g, const tinykg_saved* sv, const floa
   Source srcE{sv->packed_E, sv->gmin_E, sv->gscale_E, gl2};
   Source srcH{sv->packed_H, sv->gmin_H, sv->gscale_H, gl2};
   tinykg_status rc = TINYKG_OK;
+  // which partial sums of grad_W_r / grad_e_r belong to relation r (per span of the persistent
+  // kernel that ran, per chunk from the d = 128 one)
+  const int32_t* part_ptr = D <= 64 ? g->rel_span_ptr : g->rel_chunk_ptr;
 
   // (uniform: pi = 1 / deg, only the transposed sparse product is left)
   // H was not saved: rebuild it from E_hat (scores first), in the buffer that grad_H then
@@ -2539,14 +2984,31 @@ tinykg_status bwd_impl(const tinykg_graph* g, const tinykg_saved* sv, const floa
     ChunkList cl{g->chunk_rel, g->chunk_start, g->chunk_count};
     const GradSink sink{gE, acc, g->acc_slot};
     if constexpr (D <= 64) {
-      const size_t smem = (size_t)(D * LD + D + kEdgeWaves * edge_wave_region<D>()) * 4;
-      auto kern = edge_wave_kernel<D, BITS>;
-      if ((rc = set_smem(kern, smem)) != TINYKG_OK) return rc;
-      ProfileScope prof("edge_bwd_kernel", st);
-      const ChunkList spans{g->span_rel, g->span_start, g->span_count};
-      hipLaunchKernelGGL(kern, dim3(g->n_span_groups), dim3(kEdgeWaves * 64), smem, st, srcE, Wr, er,
-                         g->r_head, g->r_tail, g->r_eid, g->r_hperm32, spans, g->span_group_ptr, pi, gs, gH,
-                         sink, pWr, per);
+      bool code_form = false;
+      if constexpr (BITS != 32) code_form = group >= D;   // one (Z, scale) pair per row
+      part_ptr = code_form ? g->rel_espan_ptr : g->rel_span_ptr;
+      if constexpr (BITS != 32) {
+        if (code_form) {
+          const size_t smem = (size_t)edge_code_smem_bytes<D>();
+          auto kern = edge_code_kernel<D, BITS>;
+          if ((rc = set_smem(kern, smem)) != TINYKG_OK) return rc;
+          ProfileScope prof("edge_bwd_kernel", st);
+          const ChunkList spans{g->espan_rel, g->espan_start, g->espan_count};
+          hipLaunchKernelGGL(kern, dim3(g->n_span_groups), dim3(kEdgeWaves * 64), smem, st, srcE, Wr, er,
+                             g->r_head, g->r_tail, g->r_eid, g->r_hperm32, spans, g->espan_group_ptr, pi, gs, gH,
+                             sink, pWr, per);
+        }
+      }
+      if (!code_form) {
+        const size_t smem = (size_t)(D * LD + D + kEdgeWaves * edge_wave_region<D>()) * 4;
+        auto kern = edge_wave_kernel<D, BITS>;
+        if ((rc = set_smem(kern, smem)) != TINYKG_OK) return rc;
+        ProfileScope prof("edge_bwd_kernel", st);
+        const ChunkList spans{g->span_rel, g->span_start, g->span_count};
+        hipLaunchKernelGGL(kern, dim3(g->n_span_groups), dim3(kEdgeWaves * 64), smem, st, srcE, Wr, er,
+                           g->r_head, g->r_tail, g->r_eid, g->r_hperm32, spans, g->span_group_ptr, pi, gs, gH,
+                           sink, pWr, per);
+      }
     } else {
       const size_t smem = (size_t)(D * LD + 4 * TE * LD + D + 6 * TE + 2 * D + 4) * 4;
       auto kern = edge_bwd_kernel<D, TE, BITS>;
@@ -2562,7 +3024,7 @@ tinykg_status bwd_impl(const tinykg_graph* g, const tinykg_saved* sv, const floa
     const bool edge_grads = !uniform && g->n_rel > 0;
     const ReduceJob jW{pW, nullptr, dense_blocks, d_out * D, (d_out * D + 63) / 64, 1, gW};
     // (partial sums per span from the persistent kernel, per chunk from the d = 128 one)
-    const int32_t* part_ptr = D <= 64 ? g->rel_span_ptr : g->rel_chunk_ptr;
+    // (part_ptr: set where the edge kernel was chosen)
     const ReduceJob jWr{pWr, part_ptr, 0, D * D, edge_grads ? (D * D + 63) / 64 : 0, g->n_rel, gWr};
     const ReduceJob jer{per, part_ptr, 0, D, edge_grads ? (D + 63) / 64 : 0, g->n_rel, ger};
     const HeavyFinish hf{acc, g->acc_node, with_heavy ? n_heavy_elems : 0, D, gE};

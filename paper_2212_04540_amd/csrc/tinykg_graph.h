@@ -31,6 +31,14 @@ struct tinykg_graph {
   int32_t* span_start = nullptr;     // [n_spans] first relation-order position
   int32_t* span_count = nullptr;     // [n_spans]
   int32_t* rel_span_ptr = nullptr;   // [n_rel + 1] spans of relation r: [ptr[r], ptr[r+1])
+  // the same cut with every tile counted alike (for the edge-level kernel whose products all
+  // run on the bf16 matrix cores: a one-tail tile is no cheaper there)
+  int32_t n_espans = 0;
+  int32_t* espan_group_ptr = nullptr;
+  int32_t* espan_rel = nullptr;
+  int32_t* espan_start = nullptr;
+  int32_t* espan_count = nullptr;
+  int32_t* rel_espan_ptr = nullptr;
   // heads with more than kHeavyDegree out-edges are cut into segments of that many
   // head-order edges, so that one wave never walks a 10^5-edge neighbourhood alone
   int32_t n_heavy = 0, n_hseg = 0;

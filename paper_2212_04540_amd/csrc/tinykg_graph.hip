@@ -248,7 +248,8 @@ void release(tinykg_graph* g) {
   void* ptrs[] = {g->rowptr, g->h_tail, g->r_head, g->r_tail, g->r_eid, g->chunk_rel,
                   g->chunk_start, g->chunk_count, g->rel_chunk_ptr, g->heavy_head, g->heavy_seg_ptr,
                   g->hseg_q, g->hseg_e0, g->hseg_cnt, g->r_hperm32, g->acc_slot, g->acc_node, g->c_head, g->c_tail,
-                  g->span_group_ptr, g->span_rel, g->span_start, g->span_count, g->rel_span_ptr};
+                  g->span_group_ptr, g->span_rel, g->span_start, g->span_count, g->rel_span_ptr,
+                  g->espan_group_ptr, g->espan_rel, g->espan_start, g->espan_count, g->rel_espan_ptr};
   for (void* p : ptrs)
     if (p) (void)hipFree(p);
   delete g;
@@ -463,10 +464,15 @@ tinykg_status tinykg_graph_create(int64_t n_nodes, int32_t n_rel, int64_t n_edge
     // groups get equal shares of the kernel's WORK, not of the edges: a tile whose edges share
     // one tail (popular tails own long runs of the relation order) takes the kernel's run form,
     // which skips a third of the matrix products.
-    std::vector<int32_t> span_group_ptr(1, 0), span_rel, span_start, span_count, rel_span_ptr((size_t)n_rel + 1, 0);
-    {
+    struct Spans { std::vector<int32_t> group_ptr, rel, start, count, rel_ptr; };
+    auto cut_spans = [&](double one_tail_cost) {
+      Spans S;
+      S.group_ptr.assign(1, 0);
+      S.rel_ptr.assign((size_t)n_rel + 1, 0);
+      std::vector<int32_t>&span_group_ptr = S.group_ptr, &span_rel = S.rel, &span_start = S.start, &span_count = S.count,
+                          &rel_span_ptr = S.rel_ptr;
       const int64_t n_groups = std::max<int64_t>(1, std::min<int64_t>(num_cus(), (int64_t)chunk_rel.size()));
-      auto tile_cost = [&](int64_t t) { return tile_one[(size_t)t] ? kOneTailTileCost : 1.0; };
+      auto tile_cost = [&](int64_t t) { return tile_one[(size_t)t] ? one_tail_cost : 1.0; };
       double total_cost = 0.0;
       for (int64_t t = 0; t < n_tiles; ++t) total_cost += tile_cost(t);
       int64_t cur_group = 0;
@@ -500,18 +506,26 @@ tinykg_status tinykg_graph_create(int64_t n_nodes, int32_t n_rel, int64_t n_edge
         rel_span_ptr[(size_t)r] = (int32_t)sp;
       }
       rel_span_ptr[(size_t)n_rel] = (int32_t)span_rel.size();
-    }
-    g->n_span_groups = (int32_t)span_group_ptr.size() - 1;
-    g->n_spans = (int32_t)span_rel.size();
+      return S;
+    };
+    const Spans SA = cut_spans(kOneTailTileCost), SE = cut_spans(1.0);
+    g->n_span_groups = (int32_t)SA.group_ptr.size() - 1;
+    g->n_spans = (int32_t)SA.rel.size();
+    g->n_espans = (int32_t)SE.rel.size();
     TINYKG_TRY(upload(chunk_rel, &g->chunk_rel));
     TINYKG_TRY(upload(chunk_start, &g->chunk_start));
     TINYKG_TRY(upload(chunk_count, &g->chunk_count));
     TINYKG_TRY(upload(rel_chunk_ptr, &g->rel_chunk_ptr));
-    TINYKG_TRY(upload(span_group_ptr, &g->span_group_ptr));
-    TINYKG_TRY(upload(span_rel, &g->span_rel));
-    TINYKG_TRY(upload(span_start, &g->span_start));
-    TINYKG_TRY(upload(span_count, &g->span_count));
-    TINYKG_TRY(upload(rel_span_ptr, &g->rel_span_ptr));
+    TINYKG_TRY(upload(SA.group_ptr, &g->span_group_ptr));
+    TINYKG_TRY(upload(SA.rel, &g->span_rel));
+    TINYKG_TRY(upload(SA.start, &g->span_start));
+    TINYKG_TRY(upload(SA.count, &g->span_count));
+    TINYKG_TRY(upload(SA.rel_ptr, &g->rel_span_ptr));
+    TINYKG_TRY(upload(SE.group_ptr, &g->espan_group_ptr));
+    TINYKG_TRY(upload(SE.rel, &g->espan_rel));
+    TINYKG_TRY(upload(SE.start, &g->espan_start));
+    TINYKG_TRY(upload(SE.count, &g->espan_count));
+    TINYKG_TRY(upload(SE.rel_ptr, &g->rel_espan_ptr));
   } else {
     const std::vector<int32_t> none, rel_ptr((size_t)n_rel + 1, 0), group_ptr(2, 0);
     g->chunk_edges = 64;
@@ -525,6 +539,11 @@ tinykg_status tinykg_graph_create(int64_t n_nodes, int32_t n_rel, int64_t n_edge
     TINYKG_TRY(upload(none, &g->span_start));
     TINYKG_TRY(upload(none, &g->span_count));
     TINYKG_TRY(upload(rel_ptr, &g->rel_span_ptr));
+    TINYKG_TRY(upload(group_ptr, &g->espan_group_ptr));
+    TINYKG_TRY(upload(none, &g->espan_rel));
+    TINYKG_TRY(upload(none, &g->espan_start));
+    TINYKG_TRY(upload(none, &g->espan_count));
+    TINYKG_TRY(upload(rel_ptr, &g->rel_espan_ptr));
   }
   if (hipStreamSynchronize(st) != hipSuccess || hipGetLastError() != hipSuccess) return TINYKG_ERR_DEVICE;
 #undef TINYKG_TRY

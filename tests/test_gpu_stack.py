@@ -85,7 +85,8 @@ def run_stack(tk, N, R, head, rel, tail, dims, bits, group, batch, seed=3, threa
                                                      float(np.float32(SLOPE)), g[l + 1], threads=threads)
         close(g[l], wgE + rgrads[l], f"grad_E^({l})", case=case)
         for a, w, nm in zip(pgrads[l], (wgWr, wger, wgW), ("grad_Wr", "grad_er", "grad_W")):
-            close(a, w, f"{nm} layer {l}", row_term=False, case=case)
+            # (grad_W_r, like grad_E, is a sum over up to 10^6 edges whose terms nearly cancel: row term)
+            close(a, w, f"{nm} layer {l}", row_term=nm == "grad_Wr", case=case)
     graph.close()
     return stack
 

@@ -31,8 +31,8 @@ struct tinykg_graph {
   int32_t* span_start = nullptr;     // [n_spans] first relation-order position
   int32_t* span_count = nullptr;     // [n_spans]
   int32_t* rel_span_ptr = nullptr;   // [n_rel + 1] spans of relation r: [ptr[r], ptr[r+1])
-  // the same cut with every tile counted alike (for the edge-level kernel whose products all
-  // run on the bf16 matrix cores: a one-tail tile is no cheaper there)
+  // the same cut with a one-tail tile counted almost like any other (for the code form of the
+  // edge-level kernel, whose products all run on the bf16 matrix cores)
   int32_t n_espans = 0;
   int32_t* espan_group_ptr = nullptr;
   int32_t* espan_rel = nullptr;

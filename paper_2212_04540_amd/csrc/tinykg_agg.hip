@@ -2374,21 +2374,27 @@ __device__ __forceinline__ void edge_code_span(
 #pragma unroll
   for (int j = 0; j < NB * NB; ++j) accW[j] = floatx16{0};
 
+  // the ids of a wave's next tile are requested a tile ahead (four registers): one hop less in
+  // the chain ids -> rows that every tile starts with
+  int t_nx = 0, h_nx = 0, e_nx = -1, hp_nx = 0;
+  auto load_idx = [&](int tile) {
+    const int row = tile * 32 + r;
+    t_nx = 0; h_nx = 0; e_nx = -1; hp_nx = 0;       // past the end: node 0 (a valid row), weight 0
+    if (tile < n_wt && row < count) {
+      const int pos = start + row;
+      t_nx = r_tail[pos]; h_nx = r_head[pos]; e_nx = r_eid[pos]; hp_nx = r_hperm[pos];
+    }
+  };
+  load_idx(wave);
   for (int wt = wave; wt < n_wt; wt += NW) {
     // ---- stage: ids, flags, per-edge scalars; rows fetched as raw codes
-    int t_ld = 0, h_ld = 0, e_ld = -1, hp_ld = 0;   // past the end: node 0 (a valid row), weight 0
-    {
-      const int row = wt * 32 + r;
-      if (row < count) {
-        const int pos = start + row;
-        t_ld = r_tail[pos]; h_ld = r_head[pos]; e_ld = r_eid[pos]; hp_ld = r_hperm[pos];
-      }
-    }
+    const int t_ld = t_nx, h_ld = h_nx, e_ld = e_nx, hp_ld = hp_nx;
     HalfRow<D, BITS> nt, nh;
     nt.load(src, t_ld, hh);
     nh.load(src, h_ld, hh);
     float g_ld = 0.f, p_ld = 0.f;
     if (e_ld >= 0) { g_ld = gs[e_ld]; p_ld = pi[e_ld]; }
+    load_idx(wt + NW);
     const int nrow = min(32, count - wt * 32);
     {
       const int perm = hp_ld & 31;
@@ -2608,6 +2614,19 @@ __device__ __forceinline__ void edge_code_span(
           __builtin_amdgcn_sched_barrier(0);
         }
       }
+      // (tails: the e_t term of H_h adds pi_e grad_H_h to the row; the heads' rows of grad_H are fetched
+      // in batches of RB rows, each batch requested while the one before it is summed, the first one
+      // here, while the products drain)
+      constexpr int RB = RP < 8 ? RP : 8;
+      float gnext[RB];
+      auto fetch_gh = [&](int k0) {
+#pragma unroll
+        for (int k = 0; k < RB; ++k) {
+          const int hk = D == 64 ? __builtin_amdgcn_readfirstlane(hd_s[se0 + k0 + k]) : hd_s[se0 + k0 + k];
+          gnext[k] = gH[(int64_t)hk * D + si];
+        }
+      };
+      if (side == 0) fetch_gh(0);
       phase_fence();
 #pragma unroll
       for (int ib = 0; ib < NB; ++ib) {
@@ -2615,19 +2634,20 @@ __device__ __forceinline__ void edge_code_span(
         for (int v = 0; v < 16; ++v) G_s[acc_row(v, lane) * LD + ib * 32 + r] = accP[ib][v];
       }
       phase_fence();
-      constexpr int RB = RP < 16 ? RP : 16;        // rows whose LDS reads are issued together
       float run = 0.f;
 #pragma unroll
       for (int k0 = 0; k0 < RP; k0 += RB) {
         int node[RB];
         float val[RB];
+        float gcur[RB];
+#pragma unroll
+        for (int k = 0; k < RB; ++k) gcur[k] = side == 0 ? gnext[k] : 0.f;
+        if (side == 0 && k0 + RB < RP) fetch_gh(k0 + RB);
 #pragma unroll
         for (int k = 0; k < RB; ++k) {
           if (side == 0) {
-            // (the e_t term of H_h: pi_e grad_H_h, the head's row fetched here)
             node[k] = tl_s[se0 + k0 + k];
-            const int hk = D == 64 ? __builtin_amdgcn_readfirstlane(hd_s[se0 + k0 + k]) : hd_s[se0 + k0 + k];
-            val[k] = fmaf(pi_s[se0 + k0 + k], gH[(int64_t)hk * D + si], G_s[(se0 + k0 + k) * LD + si]);
+            val[k] = fmaf(pi_s[se0 + k0 + k], gcur[k], G_s[(se0 + k0 + k) * LD + si]);
           } else {
             node[k] = hr_s[se0 + k0 + k];
             const int pk = D == 64 ? __builtin_amdgcn_readfirstlane(hp_s[se0 + k0 + k]) : hp_s[se0 + k0 + k];

@@ -88,27 +88,27 @@ def tile_stats(rel, tail):
     return tiles, one
 
 
-def edge_executed(tiles, one_tail, d=D):
-    """What the d <= 64 edge kernel executes on the matrix cores (whole 32-row tiles): every
-    tile forms a and b as 2 x 6 bfloat16 piece products; an ordinary tile runs four fp32
-    products (W_r^T grad_a, W_r^T grad_b, two outer products), a one-tail tile two (its
-    tail-side pair collapses to vector work on the sum of grad_a)."""
+def edge_executed(tiles, d=D):
+    """What the d <= 64 edge kernel executes on the matrix cores for a compressed context (its code
+    form, whole 32-row tiles), all of it bfloat16 piece products: a and b as three products each
+    (codes are exact bfloat16 values), the two outer products for grad_W_r likewise three each,
+    W_r^T grad_a and W_r^T grad_b six each."""
     prod = 2 * 32 * d * d
-    fp32 = (4 * (tiles - one_tail) + 2 * one_tail) * prod
-    bf16 = tiles * 2 * 6 * prod
-    return fp32, bf16
+    return 0, tiles * (2 * 3 + 2 * 3 + 2 * 6) * prod
 
 
 def parse_profile_rows(path, kernel_prefix):
-    """Rows of a committed rocprofv3 summary that start with `kernel_prefix<`: list of token lists."""
+    """Rows of a committed rocprofv3 summary whose kernel name starts with `kernel_prefix`: token lists."""
     try:
-        return [l.split() for l in open(path) if l.startswith(kernel_prefix + "<") or l.startswith(kernel_prefix + " ")]
+        n = len(kernel_prefix)
+        return [l.split() for l in open(path) if l.startswith(kernel_prefix) and l[n:n + 1] in ("<", " ", ",", ">")]
     except OSError:
         return []
 
 
-PROFILE_STEP = os.path.join(ROOT, "profiles", "aggregation_step_configs1_and_compressor_configs2.txt")
-PROFILE_SQ = os.path.join(ROOT, "profiles", "sq_counters_aggregation_step_configs1_and_compressor_configs2.txt")
+PROFILE_STEP = os.path.join(ROOT, "profiles", "aggregation_step_configs1.txt")
+PROFILE_ALL = os.path.join(ROOT, "profiles", "default_bench_all_configs.txt")
+PROFILE_SQ = os.path.join(ROOT, "profiles", "sq_counters_configs1_step.txt")
 
 
 def profiled_traffic(kernel, summary=None):
@@ -295,8 +295,8 @@ def compressor_sweep(a):
                                "bits in {2,4,8} x group in {32,64,256}; value = quantize+pack of INT2/G64"},
         "roofline": {"kernel": "quantize_kernel", "bound": "hbm", "achieved": ref["quantize_pack"]["GB/s"],
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": ref["quantize_pack"]["frac_of_hbm_peak"],
-                     "traffic": profiled_traffic("quantize_kernel"),
-                     "traffic_source": "offline rocprofv3 counters, profiles/" + os.path.basename(PROFILE_STEP)},
+                     "traffic": profiled_traffic("quantize_kernel<float, 2, 64", PROFILE_ALL),
+                     "traffic_source": "offline rocprofv3 counters, profiles/" + os.path.basename(PROFILE_ALL)},
         "plain_copy": copy, "cells": cells}))
 
 
@@ -376,8 +376,9 @@ def uniform_result(tk, torch, graph, n_nodes, n_edges, n_tails, d, bits, group, 
                                       "frac_of_hbm_peak": round(bwd_bytes / (bwd_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4) if bwd_ms else None},
            "roofline": {"kernel": "uniform_bwd_kernel", "bound": "hbm", "achieved": gat.get("algorithmic_GBps"),
                         "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gat.get("frac_of_hbm_peak"),
-                        "traffic": profiled_traffic("uniform_bwd_kernel", os.path.join(ROOT, "profiles", "uniform_layer_configs4_graph.txt")),
-                        "traffic_source": "offline rocprofv3 counters, profiles/uniform_layer_configs4_graph.txt",
+                        "rocprof_name": f"uniform_tail_kernel<{d}>",
+                        "traffic": profiled_traffic(f"uniform_tail_kernel<{d}>", PROFILE_ALL) if n_nodes == C4_N else None,
+                        "traffic_source": "offline rocprofv3 counters (not this run), profiles/" + os.path.basename(PROFILE_ALL),
                         "avg_launch_ms": gat.get("ms_per_step")},
            "kernels": kernels}
     del saved, ws, E_out, grads
@@ -748,10 +749,10 @@ def config1_result(a, tk, torch, inp):
     dom_ms = dom[1] / dom[0]
     achieved = edge_bwd_flops() / (dom_ms * 1e-3) / 1e12
     tiles, one_tail = tile_stats(inp["rel"], inp["tail"])
-    ex32, ex16 = edge_executed(tiles, one_tail)
+    ex32, ex16 = edge_executed(tiles)
     pipe_floor_ms = (ex32 / (MFMA_FP32_PEAK_TFLOPS * 1e12) + ex16 / (MFMA_BF16_PEAK_TFLOPS * 1e12)) * 1e3
-    traffic = profiled_traffic("edge_wave_kernel")
-    mfma_busy, wait = profiled_sq("edge_wave_kernel")
+    traffic = profiled_traffic("edge_code_kernel")
+    mfma_busy, wait = profiled_sq("edge_code_kernel")
     bpa = bytes_per_activation(BITS, GROUP)
     # the kernel's own compulsory bytes: two packed rows + ids, weights, flag byte and the head's grad_H row per
     # edge; one grad_E row per node; W_r once per relation
@@ -775,14 +776,13 @@ def config1_result(a, tk, torch, inp):
         "frac_of_hbm_peak": round(alg / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 5),
         "ms_per_step_as_hip_graph": round(graph_ms, 4) if isinstance(graph_ms, float) else graph_ms,
         "launches_per_step": sum(k["launches_per_step"] for k in kernels.values()),
-        "roofline": {"kernel": "edge_bwd_kernel", "rocprof_name": "edge_wave_kernel<64, 2>", "bound": "mfma",
+        "roofline": {"kernel": "edge_bwd_kernel", "rocprof_name": "edge_code_kernel<64, 2>", "bound": "mfma",
                      "achieved": round(achieved, 3), "peak": MFMA_FP32_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": round(achieved / MFMA_FP32_PEAK_TFLOPS, 4),
                      "avg_launch_ms": round(dom_ms, 4),
                      "algorithmic_flops": edge_bwd_flops(),
                      "executed": {"tiles": tiles, "one_tail_tiles": one_tail,
                                   "fp32_pipe_flops": ex32, "bf16_pipe_flops": ex16,
-                                  "fp32_pipe_TFLOPs": round(ex32 / (dom_ms * 1e-3) / 1e12, 2),
                                   "bf16_pipe_TFLOPs": round(ex16 / (dom_ms * 1e-3) / 1e12, 2),
                                   "matrix_pipe_floor_ms": round(pipe_floor_ms, 4),
                                   "frac_of_matrix_pipe_floor": round(pipe_floor_ms / dom_ms, 4)},
@@ -795,11 +795,12 @@ def config1_result(a, tk, torch, inp):
                      "kernel_algorithmic_bytes": int(kernel_alg),
                      "traffic_over_algorithmic": round(traffic / kernel_alg, 2) if traffic else None,
                      "note": "frac prices the ALGORITHMIC fp32 flops (six k x d products for every triplet) over the "
-                             "launch time against the fp32 matrix peak.  `executed` is what the kernel runs: a and b "
-                             "as six bfloat16 piece products each on the bf16 matrix cores (dense peak 2500 TFLOP/s), "
-                             "the other products on the fp32 matrix cores, two of them skipped for a tile whose edges "
-                             "share one tail; frac_of_matrix_pipe_floor is the time both pipes need at their peaks "
-                             "over the launch time"},
+                             "launch time against the fp32 matrix peak (157.3 TFLOP/s).  `executed` is what the kernel "
+                             "runs: every product on the bf16 matrix cores (dense peak 2500 TFLOP/s) as exact bfloat16 "
+                             "piece products -- three per product where one operand is a matrix of integer codes, six "
+                             "otherwise -- at fp32 accuracy; frac_of_matrix_pipe_floor is the time that pipe needs at "
+                             "its peak over the launch time (the kernel is bound by its vector work and LDS round "
+                             "trips, not by the matrix pipe: see mfma_busy)"},
         "kernels": kernels,
         "kernels_note": f"per-kernel device times from a separate pass of {breakdown_steps} steps after the timed "
                         "region (every launch bracketed by HIP events); roofline.avg_launch_ms is measured "

@@ -2718,6 +2718,382 @@ __global__ __launch_bounds__(kEdgeWaves * 64) void edge_code_kernel(
   }
 }
 
+// ----------------------------- edge-level backward, code form, cooperative (d = 128) ----
+// The d = 128 edge kernel for a compressed context with one (Z, scale) pair per row, all six
+// products on the bf16 matrix cores.  At d = 128 the three bfloat16 pieces of W_r take 102 KiB
+// of LDS in ONE layout, so there is no room for W_r^T beside them and none for a region per
+// wave: one eight-wave workgroup shares a 32-edge tile (as in the fp32 cooperative kernel
+// above, same phases and barriers) and the products that contract over W_r's ROW index read
+// W_r column-wise, two bytes at a time.
+//   stage  rows arrive as raw codes (prefetched a tile ahead); each row's codes are centred on
+//          its rounded mean m and stored as bfloat16 (exact): C[e][k] = code - m, with
+//          e_hat = mid + scale C, mid = Z + scale m  (Eq. 4)
+//   1a     waves 0-3: a, waves 4-7: b for one channel block: three piece products
+//          (pieces of W_r) x (codes), then a = s_t acc + mid_t (W_r 1), b likewise + e_r
+//   1b     b-waves: grad_a = gs tanh(b) and f = gs (1 - tanh(b)^2) to LDS; a-waves: grad_b = a f
+//   1c     every wave two 32 x 32 blocks of grad_W_r += (scale grad)^T C: gradient columns read
+//          from LDS, scaled, split three ways in registers; codes read column-wise
+//   2      Pt = grad_a W_r (waves 0-3) / Ph = grad_b W_r (waves 4-7), one column block each: rows
+//          split on the fly, six piece products against column-wise reads of the pieces of W_r
+//   3      Pt, Ph to LDS (over grad_a, grad_b); flag-driven scatter
+// The rank-one parts of grad_W_r, (sum_e mid_e grad[e][c]) 1^T, and grad_e_r are column sums
+// that every thread keeps for one column and eight of the tile's rows; they join the blocks
+// when the chunk is finished.
+template <int D>
+constexpr int edge_coop_code_smem_bytes() {
+  return 3 * D * (D + 8) * 2 + 2 * D * 4 + 2 * 32 * (D + 8) * 2 + 2 * 32 * (D + 4) * 4 + 10 * 32 * 4;
+}
+
+template <int D, int TE, int BITS>
+__global__ __launch_bounds__(kCoopWaves * 64) void edge_coop_code_kernel(
+    Source src, const float* __restrict__ Wr, const float* __restrict__ er,
+    const int32_t* __restrict__ r_head, const int32_t* __restrict__ r_tail,
+    const int32_t* __restrict__ r_eid, const uint8_t* __restrict__ r_hperm, ChunkList chunks,
+    const float* __restrict__ pi, const float* __restrict__ gs, const float* __restrict__ gH,
+    GradSink sink, float* __restrict__ part_Wr, float* __restrict__ part_er) {
+  static_assert(TE == 32 && D == 128 && BITS != 32, "eight waves: four channel blocks x {a, b}; packed rows");
+  constexpr int NT = kCoopWaves * 64;
+  constexpr int LD = D + 4, LDW = D + 8, LPR = D / 4, NIB = D / 32;
+  constexpr int NBW = NIB * NIB / kCoopWaves;     // grad_W_r blocks per wave (2: one row block, two column blocks)
+  constexpr int NQ = NT / D, RP = TE / NQ;        // scatter and column sums: row parts (4 x 8 rows)
+  constexpr int CPT = TE * LPR / NT;              // row chunks per thread and matrix (2)
+  constexpr int RSTEP = NT / LPR;                 // rows between a thread's chunks
+  static_assert(NBW == 2 && NIB % NBW == 0, "a wave's blocks share their row block");
+  uint16_t* Wp = reinterpret_cast<uint16_t*>(smem_raw);                 // [3][D][LDW] pieces of W_r
+  float* wsum_s = reinterpret_cast<float*>(Wp + 3 * D * LDW);           // row sums of W_r
+  float* er_s = wsum_s + D;
+  uint16_t* Ct_s = reinterpret_cast<uint16_t*>(er_s + D);               // [TE][LDW] centred codes, tail rows
+  uint16_t* Ch_s = Ct_s + TE * LDW;                                     // [TE][LDW] head rows
+  float* dA_s = reinterpret_cast<float*>(Ch_s + TE * LDW);              // [TE][LD] grad_a, later Pt
+  float* dB_s = dA_s + TE * LD;                                         // [TE][LD] f, grad_b, later Ph
+  float* gs_s = dB_s + TE * LD;
+  float* pi_s = gs_s + TE;
+  float* zt_s = pi_s + TE;                         // (mid, scale) of the tail / head row of edge e
+  float* st_s = zt_s + TE;
+  float* zh_s = st_s + TE;
+  float* sh_s = zh_s + TE;
+  int* tl_s = reinterpret_cast<int*>(sh_s + TE);   // tail of row e; sign bit: a tail run ends here
+  int* hd_s = tl_s + TE;                           // head of row e
+  int* hp_s = hd_s + TE;                           // row of head-order rank k
+  int* hr_s = hp_s + TE;                           // head of rank k; sign bit: a head run ends here
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int r = lane & 31, hh = lane >> 5;
+  const int ch = blockIdx.x;
+  const int rel = chunks.rel[ch], start = chunks.start[ch], count = chunks.count[ch];
+  const int row0 = tid / LPR, li = tid % LPR;     // this thread stages rows row0 + k * RSTEP
+  const int blk4 = wave & 3;                      // channel / column block of this wave's products
+  const bool b_side = wave >= 4;                  // waves 4-7: b and Ph; waves 0-3: a and Pt
+
+  // prefetch: raw rows of the next tile, node ids of the tile after it
+  int tn[CPT], hn[CPT];
+  auto load_ids = [&](int t0) {
+#pragma unroll
+    for (int k = 0; k < CPT; ++k) {
+      const int row = t0 + row0 + k * RSTEP;
+      tn[k] = 0; hn[k] = 0;
+      if (row < count) { tn[k] = r_tail[start + row]; hn[k] = r_head[start + row]; }
+    }
+  };
+  RawChunk<BITS> rt[CPT], rh[CPT];
+  auto load_rows = [&]() {
+#pragma unroll
+    for (int k = 0; k < CPT; ++k) {
+      rt[k].load(src, (int64_t)tn[k] * LPR + li);
+      rh[k].load(src, (int64_t)hn[k] * LPR + li);
+    }
+  };
+  // per-edge scalars of the tile, held by the first wave (lane l and l + 32: row l % 32)
+  int t_nx = 0, h_nx = 0, e_nx = -1, hp_nx = 0;
+  auto load_edge = [&](int t0) {
+    t_nx = 0; h_nx = 0; e_nx = -1; hp_nx = 0;
+    if (wave == 0 && t0 + r < count) {
+      const int pos = start + t0 + r;
+      t_nx = r_tail[pos]; h_nx = r_head[pos]; e_nx = r_eid[pos]; hp_nx = r_hperm[pos];
+    }
+  };
+  float g_ld = 0.f, p_ld = 0.f;
+  int t_ld = 0, h_ld = 0, hp_ld = 0;
+  auto load_weights = [&]() {
+    g_ld = 0.f; p_ld = 0.f;
+    if (e_nx >= 0) { g_ld = gs[e_nx]; p_ld = pi[e_nx]; }
+    t_ld = t_nx; h_ld = h_nx; hp_ld = hp_nx;
+  };
+  load_ids(0);
+  load_edge(0);
+  load_rows();
+  load_weights();
+  load_ids(TE);
+  load_edge(TE);
+
+  stage_split_matrix<D>(Wr + (size_t)rel * D * D, Wp, tid, NT);
+  for (int c = tid; c < D; c += NT) {
+    er_s[c] = er[(size_t)rel * D + c];
+    const float4* row = reinterpret_cast<const float4*>(Wr + ((size_t)rel * D + c) * D);
+    double sum = 0.0;
+    for (int q = 0; q < D / 4; ++q) { const float4 w = row[q]; sum += (double)w.x + (double)w.y + (double)w.z + (double)w.w; }
+    wsum_s[c] = (float)sum;
+  }
+
+  floatx16 accW[NBW];
+#pragma unroll
+  for (int j = 0; j < NBW; ++j) accW[j] = floatx16{0};
+  const int si = tid % D, se0 = (tid / D) * RP;   // column sums and scatter: this thread's column and rows
+  float er_acc = 0.f, zw_acc = 0.f;               // sum_e grad_b[e][si];  sum_e mid_t grad_a + mid_h grad_b
+
+  // four centred codes of a chunk as bfloat16 (exact small integers)
+  auto centred = [](uint32_t w, float m) {
+    constexpr uint32_t B = (1u << (BITS & 31)) - 1u;
+    constexpr int SH = BITS & 31;
+    const float c0 = (float)(w & B) - m, c1 = (float)((w >> SH) & B) - m;
+    const float c2 = (float)((w >> (2 * SH)) & B) - m, c3 = (float)((w >> (3 * SH)) & B) - m;
+    return make_uint2(__builtin_amdgcn_perm(__float_as_uint(c1), __float_as_uint(c0), 0x07060302u),
+                      __builtin_amdgcn_perm(__float_as_uint(c3), __float_as_uint(c2), 0x07060302u));
+  };
+  auto code_sum4 = [](uint32_t w) {
+    constexpr uint32_t B = (1u << (BITS & 31)) - 1u;
+    constexpr int SH = BITS & 31;
+    return (float)((w & B) + ((w >> SH) & B) + ((w >> (2 * SH)) & B) + ((w >> (3 * SH)) & B));
+  };
+
+  for (int t0 = 0; t0 < count; t0 += TE) {
+    const int nrow = min(TE, count - t0);
+    __syncthreads();   // previous tile's scatter has finished reading LDS (first tile: W_r is staged)
+#pragma unroll
+    for (int k = 0; k < CPT; ++k) {
+      const int row = row0 + k * RSTEP;
+      // (the 32 lanes of a wave half hold one row: its mean code, rounded to an integer)
+      const float mt = rintf(slot_sum<32>(code_sum4(rt[k].w[0])) * (1.0f / (float)D));
+      const float mh = rintf(slot_sum<32>(code_sum4(rh[k].w[0])) * (1.0f / (float)D));
+      *reinterpret_cast<uint2*>(Ct_s + row * LDW + li * 4) = centred(rt[k].w[0], mt);
+      *reinterpret_cast<uint2*>(Ch_s + row * LDW + li * 4) = centred(rh[k].w[0], mh);
+      if (li == 0) {
+        st_s[row] = rt[k].s; zt_s[row] = fmaf(rt[k].s, mt, rt[k].z);
+        sh_s[row] = rh[k].s; zh_s[row] = fmaf(rh[k].s, mh, rh[k].z);
+      }
+    }
+    if (wave == 0) {
+      // where the scatter flushes its running sums (see the wave-independent kernel)
+      const int perm = hp_ld & 31;
+      const int t_id = t_ld | ((hp_ld & 0x40) ? kHeavyBit : 0), h_id = h_ld | ((hp_ld & 0x80) ? kHeavyBit : 0);
+      const int h_rank = __shfl(h_id, perm);
+      const int t_next = __shfl_down(t_id, 1), h_next = __shfl_down(h_rank, 1);
+      const bool stop = r + 1 == nrow || (r + 1) % RP == 0;
+      const int t_flag = (r < nrow && (stop || t_next != t_id)) ? (int)0x80000000 : 0;
+      const int h_flag = (r < nrow && (stop || h_next != h_rank)) ? (int)0x80000000 : 0;
+      if (lane < 32) {
+        gs_s[r] = g_ld; pi_s[r] = p_ld; hd_s[r] = h_ld; hp_s[r] = perm;
+        tl_s[r] = t_id | t_flag; hr_s[r] = h_rank | h_flag;
+      }
+    }
+    if (t0 + TE < count) {
+      load_rows();
+      load_weights();
+      load_ids(t0 + 2 * TE);
+      load_edge(t0 + 2 * TE);
+    }
+    __syncthreads();
+    // ---- 1a. a (waves 0-3) or b (waves 4-7) of channel block blk4 as [c][e], lane = edge:
+    //      (pieces of W_r, rows of the block) x (codes), eight k-values per lane half and step
+    floatx16 acc1 = {0};
+    {
+      const uint16_t* wrow = Wp + (blk4 * 32 + r) * LDW + hh * 8;
+      const uint16_t* crow = (b_side ? Ch_s : Ct_s) + r * LDW + hh * 8;
+#pragma unroll 2
+      for (int m = 0; m < D / 16; ++m) {
+        Bf16Frag wh, wm, wl, cf;
+        *reinterpret_cast<uint4*>(cf.u) = *reinterpret_cast<const uint4*>(crow + 16 * m);
+        *reinterpret_cast<uint4*>(wh.u) = *reinterpret_cast<const uint4*>(wrow + 16 * m);
+        *reinterpret_cast<uint4*>(wm.u) = *reinterpret_cast<const uint4*>(wrow + D * LDW + 16 * m);
+        *reinterpret_cast<uint4*>(wl.u) = *reinterpret_cast<const uint4*>(wrow + 2 * D * LDW + 16 * m);
+        acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wl.v, cf.v, acc1, 0, 0, 0);
+        acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wm.v, cf.v, acc1, 0, 0, 0);
+        acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wh.v, cf.v, acc1, 0, 0, 0);
+      }
+    }
+    // ---- 1b. the affine part of Eq. (4), then grad_a and f (b-waves); a stays in registers
+    {
+      const float sc = b_side ? sh_s[r] : st_s[r], mid = b_side ? zh_s[r] : zt_s[r];
+      const float g = gs_s[r];
+#pragma unroll
+      for (int vg = 0; vg < 4; ++vg) {
+        const int c0 = blk4 * 32 + 8 * vg + 4 * hh;
+        const float4 ws4 = *reinterpret_cast<const float4*>(wsum_s + c0);
+        const float4 er4 = *reinterpret_cast<const float4*>(er_s + c0);
+        const float wsv[4] = {ws4.x, ws4.y, ws4.z, ws4.w}, erv[4] = {er4.x, er4.y, er4.z, er4.w};
+        if (b_side) {
+          float da[4], f[4];
+#pragma unroll
+          for (int u = 0; u < 4; ++u) {
+            const float vv = tanh_rel(fmaf(sc, acc1[4 * vg + u], fmaf(mid, wsv[u], erv[u])));
+            da[u] = g * vv;
+            f[u] = g * (1.f - vv * vv);
+          }
+          *reinterpret_cast<float4*>(dA_s + r * LD + c0) = make_float4(da[0], da[1], da[2], da[3]);
+          *reinterpret_cast<float4*>(dB_s + r * LD + c0) = make_float4(f[0], f[1], f[2], f[3]);
+        } else {
+#pragma unroll
+          for (int u = 0; u < 4; ++u) acc1[4 * vg + u] = fmaf(sc, acc1[4 * vg + u], mid * wsv[u]);
+        }
+      }
+    }
+    __syncthreads();
+    // ---- 1b'. grad_b = a * f (the wave that holds a; each element is its own)
+    if (!b_side) {
+#pragma unroll
+      for (int vg = 0; vg < 4; ++vg) {
+        const int c0 = blk4 * 32 + 8 * vg + 4 * hh;
+        float4 f = *reinterpret_cast<const float4*>(dB_s + r * LD + c0);
+        f.x *= acc1[4 * vg + 0]; f.y *= acc1[4 * vg + 1]; f.z *= acc1[4 * vg + 2]; f.w *= acc1[4 * vg + 3];
+        *reinterpret_cast<float4*>(dB_s + r * LD + c0) = f;
+      }
+    }
+    __syncthreads();
+    // ---- 1c. grad_W_r blocks [c][i] += sum_e (s_t grad_a)[e][c] C_t[e][i] + (s_h grad_b)[e][c] C_h[e][i]
+    //      (a fresh accumulator per tile keeps the fp32 running sum short)
+    {
+      const int cb = wave / (NIB / NBW), ib0 = (wave % (NIB / NBW)) * NBW;
+      floatx16 accT[NBW];
+#pragma unroll
+      for (int j = 0; j < NBW; ++j) accT[j] = floatx16{0};
+#pragma unroll 1
+      for (int ks = 0; ks < TE / 16; ++ks) {
+#pragma unroll
+        for (int side = 0; side < 2; ++side) {
+          const float* G_s = side == 0 ? dA_s : dB_s;
+          const float* sc_s = side == 0 ? st_s : sh_s;
+          const uint16_t* C_s = side == 0 ? Ct_s : Ch_s;
+          const int e0 = 16 * ks + 8 * hh;          // this lane half's eight edges of the step
+          Bf16Frag xh, xm, xl;
+          {
+            const float4 s0 = *reinterpret_cast<const float4*>(sc_s + e0), s1 = *reinterpret_cast<const float4*>(sc_s + e0 + 4);
+            const float sv[8] = {s0.x, s0.y, s0.z, s0.w, s1.x, s1.y, s1.z, s1.w};
+            float x[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) x[i] = sv[i] * G_s[(e0 + i) * LD + cb * 32 + r];
+            split3x8(x, xh, xm, xl);
+          }
+          Bf16Frag cf[NBW];
+#pragma unroll
+          for (int j = 0; j < NBW; ++j) {
+            const uint16_t* cc = C_s + e0 * LDW + (ib0 + j) * 32 + r;
+#pragma unroll
+            for (int w2 = 0; w2 < 4; ++w2)
+              cf[j].u[w2] = (uint32_t)cc[(2 * w2) * LDW] | ((uint32_t)cc[(2 * w2 + 1) * LDW] << 16);
+          }
+#pragma unroll
+          for (int j = 0; j < NBW; ++j) accT[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xl.v, cf[j].v, accT[j], 0, 0, 0);
+#pragma unroll
+          for (int j = 0; j < NBW; ++j) accT[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xm.v, cf[j].v, accT[j], 0, 0, 0);
+#pragma unroll
+          for (int j = 0; j < NBW; ++j) accT[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xh.v, cf[j].v, accT[j], 0, 0, 0);
+          __builtin_amdgcn_sched_barrier(0);
+        }
+      }
+#pragma unroll
+      for (int j = 0; j < NBW; ++j) accW[j] += accT[j];
+    }
+    // grad_H rows of the tile's heads (the e_t term of H_h): requested before the last products
+    float ghv[RP];
+#pragma unroll
+    for (int k = 0; k < RP; ++k) ghv[k] = gH[(int64_t)hd_s[se0 + k] * D + si];
+    // ---- 2. Pt = grad_a W_r (waves 0-3) or Ph = grad_b W_r (waves 4-7), column block blk4, as [e][i]:
+    //      (rows of the gradients, split on the fly) x (pieces of W_r read down its columns)
+    floatx16 accP = {0};
+    {
+      const float* grow = (b_side ? dB_s : dA_s) + r * LD + hh * 8;
+      const uint16_t* wcol = Wp + (hh * 8) * LDW + blk4 * 32 + r;
+#pragma unroll 2
+      for (int m = 0; m < D / 16; ++m) {
+        const float4 lo4 = *reinterpret_cast<const float4*>(grow + 16 * m), hi4 = *reinterpret_cast<const float4*>(grow + 16 * m + 4);
+        const float x[8] = {lo4.x, lo4.y, lo4.z, lo4.w, hi4.x, hi4.y, hi4.z, hi4.w};
+        Bf16Frag gh, gm, gl, wh, wm, wl;
+        split3x8(x, gh, gm, gl);
+#pragma unroll
+        for (int w2 = 0; w2 < 4; ++w2) {
+          const uint16_t* p0 = wcol + (16 * m + 2 * w2) * LDW;
+          wh.u[w2] = (uint32_t)p0[0] | ((uint32_t)p0[LDW] << 16);
+          wm.u[w2] = (uint32_t)p0[D * LDW] | ((uint32_t)p0[D * LDW + LDW] << 16);
+          wl.u[w2] = (uint32_t)p0[2 * D * LDW] | ((uint32_t)p0[2 * D * LDW + LDW] << 16);
+        }
+        mfma_split(gh, gm, gl, wh, wm, wl, accP);
+        __builtin_amdgcn_sched_barrier(0);   // one k-step's fragments at a time
+      }
+    }
+    // column sums over this thread's eight rows: grad_e_r and the rank-one part of grad_W_r
+    {
+      float se = 0.f, sz = 0.f;
+#pragma unroll
+      for (int k = 0; k < RP; ++k) {
+        const float da = dA_s[(se0 + k) * LD + si], db = dB_s[(se0 + k) * LD + si];
+        se += db;
+        sz = fmaf(zt_s[se0 + k], da, fmaf(zh_s[se0 + k], db, sz));
+      }
+      er_acc += se;
+      zw_acc += sz;
+    }
+    __syncthreads();   // every read of grad_a / grad_b is done: they become Pt / Ph
+    {
+      float* P_s = b_side ? dB_s : dA_s;
+#pragma unroll
+      for (int v = 0; v < 16; ++v) P_s[acc_row(v, lane) * LD + blk4 * 32 + r] = accP[v];
+    }
+    __syncthreads();
+    // scatter: every LDS read is independent of the running sums; a run inside a tile is
+    // summed in fp32 and leaves as one atomic per column.  Rows past the end of the chunk
+    // carry exact zeros (their weights gs, pi are 0) and no flag.
+#pragma unroll
+    for (int side = 0; side < 2; ++side) {
+      int node[RP];
+      float val[RP];
+#pragma unroll
+      for (int k = 0; k < RP; ++k) {
+        if (side == 0) {
+          node[k] = tl_s[se0 + k];
+          val[k] = fmaf(pi_s[se0 + k], ghv[k], dA_s[(se0 + k) * LD + si]);
+        } else {
+          node[k] = hr_s[se0 + k];
+          val[k] = dB_s[hp_s[se0 + k] * LD + si];
+        }
+      }
+      float run = 0.f;
+#pragma unroll
+      for (int k = 0; k < RP; ++k) {
+        run += val[k];
+        if (node[k] < 0) {
+          sink_add<D>(sink, node[k], si, run);
+          run = 0.f;
+        }
+      }
+    }
+  }
+  // the four row parts' column sums, in fixed order; the rank-one part joins the blocks
+  __syncthreads();
+  float* colsum_s = dA_s;                          // [2][NQ][D]
+  colsum_s[(tid / D) * D + si] = er_acc;
+  colsum_s[(NQ + tid / D) * D + si] = zw_acc;
+  __syncthreads();
+  float* outW = part_Wr + (size_t)ch * D * D;
+  {
+    const int cb = wave / (NIB / NBW), ib0 = (wave % (NIB / NBW)) * NBW;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      const int c = cb * 32 + acc_row(v, lane);
+      float zw = 0.f;
+#pragma unroll
+      for (int q = 0; q < NQ; ++q) zw += colsum_s[(NQ + q) * D + c];
+#pragma unroll
+      for (int j = 0; j < NBW; ++j) outW[c * D + (ib0 + j) * 32 + r] = accW[j][v] + zw;
+    }
+  }
+  if (tid < D) {
+    float sum = 0.f;
+#pragma unroll
+    for (int q = 0; q < NQ; ++q) sum += colsum_s[q * D + tid];
+    part_er[(size_t)ch * D + tid] = sum;
+  }
+}
+
 // ------------------------------------------------------------- host helpers ----
 size_t align256(size_t b) { return (b + 255) & ~(size_t)255; }
 
@@ -3030,12 +3406,26 @@ tinykg_status bwd_impl(const tinykg_graph* g, const tinykg_saved* sv, const floa
                            sink, pWr, per);
       }
     } else {
-      const size_t smem = (size_t)(D * LD + 4 * TE * LD + D + 6 * TE + 2 * D + 4) * 4;
-      auto kern = edge_bwd_kernel<D, TE, BITS>;
-      if ((rc = set_smem(kern, smem)) != TINYKG_OK) return rc;
-      ProfileScope prof("edge_bwd_kernel", st);
-      hipLaunchKernelGGL(kern, dim3(g->n_chunks), dim3(kCoopWaves * 64), smem, st, srcE, Wr, er, g->r_head,
-                         g->r_tail, g->r_eid, g->r_hperm32, cl, pi, gs, gH, sink, pWr, per);
+      bool code_form = false;
+      if constexpr (BITS != 32) code_form = group >= D;   // one (Z, scale) pair per row
+      if constexpr (BITS != 32) {
+        if (code_form) {
+          const size_t smem = (size_t)edge_coop_code_smem_bytes<D>();
+          auto kern = edge_coop_code_kernel<D, TE, BITS>;
+          if ((rc = set_smem(kern, smem)) != TINYKG_OK) return rc;
+          ProfileScope prof("edge_bwd_kernel", st);
+          hipLaunchKernelGGL(kern, dim3(g->n_chunks), dim3(kCoopWaves * 64), smem, st, srcE, Wr, er, g->r_head,
+                             g->r_tail, g->r_eid, g->r_hperm32, cl, pi, gs, gH, sink, pWr, per);
+        }
+      }
+      if (!code_form) {
+        const size_t smem = (size_t)(D * LD + 4 * TE * LD + D + 6 * TE + 2 * D + 4) * 4;
+        auto kern = edge_bwd_kernel<D, TE, BITS>;
+        if ((rc = set_smem(kern, smem)) != TINYKG_OK) return rc;
+        ProfileScope prof("edge_bwd_kernel", st);
+        hipLaunchKernelGGL(kern, dim3(g->n_chunks), dim3(kCoopWaves * 64), smem, st, srcE, Wr, er, g->r_head,
+                           g->r_tail, g->r_eid, g->r_hperm32, cl, pi, gs, gH, sink, pWr, per);
+      }
     }
     if ((rc = launch_status()) != TINYKG_OK) return rc;
   }

@@ -271,6 +271,43 @@ def test_tiles_whose_edges_share_one_tail(tk, d, bits, group):
     run_protocol(tk, N, R, head[perm], rel[perm], tail[perm], d, d, bits, group, data_seed=21)
 
 
+@pytest.mark.parametrize("d,bits,group", [(64, 2, 64), (32, 2, 64), (64, 4, 32), (128, 4, 128)])
+def test_tail_runs_of_1_31_32_33_edges_across_tile_and_span_borders(tk, d, bits, group):
+    # inside a relation the edges are sorted by tail, so equal tails form runs; every kernel of the
+    # backward pass that sums over a run (scatter run sums, one-tail tiles) must get runs right
+    # that start or end exactly on a 32-edge tile border, one edge before or after it, that span
+    # several tiles, and single edges between them.  Every tile of this graph is its own span (a
+    # small graph gives each persistent workgroup at most one tile) and a graph this small is cut
+    # into chunks of 64 edges, a chunk border on every second tile border: the runs straddle both.
+    N = 600
+    rng = np.random.default_rng(33)
+    lengths = {0: [1, 31, 32, 33, 1, 33, 32, 31, 1, 1, 30, 64, 2, 95, 33],       # borders hit exactly / off by one
+               1: [33, 31, 32, 1, 32, 32, 31, 33, 96, 1],
+               2: [1] * 70 + [32] + [1] * 31 + [33]}
+    head, rel, tail = [], [], []
+    for r, runs in lengths.items():
+        tails = rng.choice(N, size=len(runs), replace=False)
+        tails.sort()                                  # run order inside the relation = tail order
+        for t, n in zip(tails, runs):
+            head.append(rng.integers(0, N, n)); tail.append(np.full(n, t)); rel.append(np.full(n, r))
+    head, rel, tail = (np.concatenate(a).astype(np.int32) for a in (head, rel, tail))
+    perm = rng.permutation(head.size)
+    head, rel, tail = head[perm], rel[perm], tail[perm]
+    E = gen.entity_embeddings(N, d, seed=41)
+    Wr, er, W = gen.layer_params(3, d, d, d, seed=42)
+    G = gen.upstream_grad(N, d, seed=43)
+    L = Layer(tk, N, 3, head, rel, tail, E, Wr, er, W, G)
+    for b in (bits, 32):
+        Eo, sv = L.forward(b, group, 7)
+        ctx = L.saved_to_host(sv)
+        grads = L.backward(sv, b, group)
+        Eh, Hh, mk = ref.restore_context(ctx, N, d, d)
+        want = ref.aggregate_bwd(N, head, rel, tail, Eh, Hh, mk, Wr, er, W, SLOPE, G, threads=4)
+        for a, w, nm in zip(grads, want, ("grad_E", "grad_Wr", "grad_er", "grad_W")):
+            close(a, w, f"{nm} (bits={b})", tol=1e-5, row_term=nm in ("grad_E", "grad_Wr"))
+    L.graph.close()
+
+
 def test_zero_relation_maps_give_the_normalised_adjacency_spmm(tk):
     # W_r = 0 => uniform attention => H = E + D^-1 A E  (Eq. 2's spmm), on the GPU path
     import scipy.sparse as sp

@@ -250,10 +250,10 @@ __device__ __forceinline__ void mfma_split(const Bf16Frag& wh, const Bf16Frag& w
 // W_r (fp32, [D][D] row-major in global memory) as three bf16 matrices in LDS, rows padded
 // to D + 8 halves (row stride = 16 bytes mod 128: the 128-bit row reads of 32 lanes that
 // hold 32 different rows spread over all banks).
-template <int D>
+template <int D, int LDW = D + 8>
 __device__ __forceinline__ void stage_split_matrix(const float* __restrict__ W, uint16_t* __restrict__ Wp,
                                                    int tid, int n_threads) {
-  constexpr int LDW = D + 8, LPR = D / 4;
+  constexpr int LPR = D / 4;
   for (int q = tid; q < D * LPR; q += n_threads) {
     const float4 w = reinterpret_cast<const float4*>(W)[q];
     const float x[4] = {w.x, w.y, w.z, w.w};
@@ -2304,6 +2304,20 @@ __device__ __forceinline__ void stage_split_matrix_transposed(const float* __res
   }
 }
 
+// Four consecutive rows of one column of a row-major matrix of 16-bit values in LDS, for each of
+// 32 columns at once: lane l receives M[row0 + 0..3][col0 + l % 32].  `ld` in elements; row0 may
+// differ between the two lane halves.  (The transposing LDS read: each group of sixteen lanes
+// passes the addresses of the sixteen 8-byte pieces of its 4 x 16 block, lane p of the group that
+// of row p / 4, piece p % 4, and lane i of the group receives column i.)
+__device__ __forceinline__ uint2 lds_column4(const uint16_t* M, int ld, int row0, int col0, int lane) {
+  typedef short short4v __attribute__((ext_vector_type(4)));
+  const uint16_t* p = M + (row0 + ((lane & 15) >> 2)) * ld + col0 + ((lane >> 4) & 1) * 16 + (lane & 3) * 4;
+  const short4v v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) short4v*)(p));
+  union { short4v s; uint2 u; } cv;
+  cv.s = v;
+  return cv.u;
+}
+
 // Sum of the integer codes of a whole row, from the two lane halves that hold it.
 template <int D, int BITS>
 __device__ __forceinline__ float code_sum(const HalfRow<D, BITS>& h) {
@@ -2532,11 +2546,9 @@ __device__ __forceinline__ void edge_code_span(
           Bf16Frag cf[NB];
 #pragma unroll
           for (int ib = 0; ib < NB; ++ib) {
-#pragma unroll
-            for (int w2 = 0; w2 < 4; ++w2) {
-              const int e0 = acc_row(8 * ks + 2 * w2, lane), e1 = acc_row(8 * ks + 2 * w2 + 1, lane);
-              cf[ib].u[w2] = (uint32_t)C_s[e0 * LDW + ib * 32 + r] | ((uint32_t)C_s[e1 * LDW + ib * 32 + r] << 16);
-            }
+            const uint2 lo = lds_column4(C_s, LDW, 16 * ks + 4 * hh, ib * 32, lane);
+            const uint2 hi = lds_column4(C_s, LDW, 16 * ks + 8 + 4 * hh, ib * 32, lane);
+            cf[ib].u[0] = lo.x; cf[ib].u[1] = lo.y; cf[ib].u[2] = hi.x; cf[ib].u[3] = hi.y;
           }
 #pragma unroll
           for (int ib = 0; ib < NB; ++ib) accT[ib] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xl.v, cf[ib].v, accT[ib], 0, 0, 0);
@@ -2741,7 +2753,7 @@ __global__ __launch_bounds__(kEdgeWaves * 64) void edge_code_kernel(
 // when the chunk is finished.
 template <int D>
 constexpr int edge_coop_code_smem_bytes() {
-  return 3 * D * (D + 8) * 2 + 2 * D * 4 + 2 * 32 * (D + 8) * 2 + 2 * 32 * (D + 4) * 4 + 10 * 32 * 4;
+  return 3 * D * (D + 16) * 2 + D * 4 + 2 * 32 * (D + 8) * 2 + 2 * 32 * (D + 4) * 4 + 10 * 32 * 4;
 }
 
 template <int D, int TE, int BITS>
@@ -2753,16 +2765,17 @@ __global__ __launch_bounds__(kCoopWaves * 64) void edge_coop_code_kernel(
     GradSink sink, float* __restrict__ part_Wr, float* __restrict__ part_er) {
   static_assert(TE == 32 && D == 128 && BITS != 32, "eight waves: four channel blocks x {a, b}; packed rows");
   constexpr int NT = kCoopWaves * 64;
-  constexpr int LD = D + 4, LDW = D + 8, LPR = D / 4, NIB = D / 32;
+  constexpr int LD = D + 4, LDW = D + 8, LDWW = D + 16, LPR = D / 4, NIB = D / 32;
   constexpr int NBW = NIB * NIB / kCoopWaves;     // grad_W_r blocks per wave (2: one row block, two column blocks)
   constexpr int NQ = NT / D, RP = TE / NQ;        // scatter and column sums: row parts (4 x 8 rows)
   constexpr int CPT = TE * LPR / NT;              // row chunks per thread and matrix (2)
   constexpr int RSTEP = NT / LPR;                 // rows between a thread's chunks
   static_assert(NBW == 2 && NIB % NBW == 0, "a wave's blocks share their row block");
-  uint16_t* Wp = reinterpret_cast<uint16_t*>(smem_raw);                 // [3][D][LDW] pieces of W_r
-  float* wsum_s = reinterpret_cast<float*>(Wp + 3 * D * LDW);           // row sums of W_r
-  float* er_s = wsum_s + D;
-  uint16_t* Ct_s = reinterpret_cast<uint16_t*>(er_s + D);               // [TE][LDW] centred codes, tail rows
+  // (rows of the pieces 288 bytes apart: the four rows of a transposing read then fall into
+  // different banks, and so do the 128-bit row reads of eight lanes)
+  uint16_t* Wp = reinterpret_cast<uint16_t*>(smem_raw);                 // [3][D][LDWW] pieces of W_r
+  float* wsum_s = reinterpret_cast<float*>(Wp + 3 * D * LDWW);          // row sums of W_r
+  uint16_t* Ct_s = reinterpret_cast<uint16_t*>(wsum_s + D);             // [TE][LDW] centred codes, tail rows
   uint16_t* Ch_s = Ct_s + TE * LDW;                                     // [TE][LDW] head rows
   float* dA_s = reinterpret_cast<float*>(Ch_s + TE * LDW);              // [TE][LD] grad_a, later Pt
   float* dB_s = dA_s + TE * LD;                                         // [TE][LD] f, grad_b, later Ph
@@ -2826,9 +2839,8 @@ __global__ __launch_bounds__(kCoopWaves * 64) void edge_coop_code_kernel(
   load_ids(TE);
   load_edge(TE);
 
-  stage_split_matrix<D>(Wr + (size_t)rel * D * D, Wp, tid, NT);
+  stage_split_matrix<D, LDWW>(Wr + (size_t)rel * D * D, Wp, tid, NT);
   for (int c = tid; c < D; c += NT) {
-    er_s[c] = er[(size_t)rel * D + c];
     const float4* row = reinterpret_cast<const float4*>(Wr + ((size_t)rel * D + c) * D);
     double sum = 0.0;
     for (int q = 0; q < D / 4; ++q) { const float4 w = row[q]; sum += (double)w.x + (double)w.y + (double)w.z + (double)w.w; }
@@ -2897,15 +2909,15 @@ __global__ __launch_bounds__(kCoopWaves * 64) void edge_coop_code_kernel(
     //      (pieces of W_r, rows of the block) x (codes), eight k-values per lane half and step
     floatx16 acc1 = {0};
     {
-      const uint16_t* wrow = Wp + (blk4 * 32 + r) * LDW + hh * 8;
+      const uint16_t* wrow = Wp + (blk4 * 32 + r) * LDWW + hh * 8;
       const uint16_t* crow = (b_side ? Ch_s : Ct_s) + r * LDW + hh * 8;
 #pragma unroll 2
       for (int m = 0; m < D / 16; ++m) {
         Bf16Frag wh, wm, wl, cf;
         *reinterpret_cast<uint4*>(cf.u) = *reinterpret_cast<const uint4*>(crow + 16 * m);
         *reinterpret_cast<uint4*>(wh.u) = *reinterpret_cast<const uint4*>(wrow + 16 * m);
-        *reinterpret_cast<uint4*>(wm.u) = *reinterpret_cast<const uint4*>(wrow + D * LDW + 16 * m);
-        *reinterpret_cast<uint4*>(wl.u) = *reinterpret_cast<const uint4*>(wrow + 2 * D * LDW + 16 * m);
+        *reinterpret_cast<uint4*>(wm.u) = *reinterpret_cast<const uint4*>(wrow + D * LDWW + 16 * m);
+        *reinterpret_cast<uint4*>(wl.u) = *reinterpret_cast<const uint4*>(wrow + 2 * D * LDWW + 16 * m);
         acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wl.v, cf.v, acc1, 0, 0, 0);
         acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wm.v, cf.v, acc1, 0, 0, 0);
         acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wh.v, cf.v, acc1, 0, 0, 0);
@@ -2919,7 +2931,7 @@ __global__ __launch_bounds__(kCoopWaves * 64) void edge_coop_code_kernel(
       for (int vg = 0; vg < 4; ++vg) {
         const int c0 = blk4 * 32 + 8 * vg + 4 * hh;
         const float4 ws4 = *reinterpret_cast<const float4*>(wsum_s + c0);
-        const float4 er4 = *reinterpret_cast<const float4*>(er_s + c0);
+        const float4 er4 = *reinterpret_cast<const float4*>(er + (size_t)rel * D + c0);   // (cached: 512 bytes per relation)
         const float wsv[4] = {ws4.x, ws4.y, ws4.z, ws4.w}, erv[4] = {er4.x, er4.y, er4.z, er4.w};
         if (b_side) {
           float da[4], f[4];
@@ -2976,10 +2988,8 @@ __global__ __launch_bounds__(kCoopWaves * 64) void edge_coop_code_kernel(
           Bf16Frag cf[NBW];
 #pragma unroll
           for (int j = 0; j < NBW; ++j) {
-            const uint16_t* cc = C_s + e0 * LDW + (ib0 + j) * 32 + r;
-#pragma unroll
-            for (int w2 = 0; w2 < 4; ++w2)
-              cf[j].u[w2] = (uint32_t)cc[(2 * w2) * LDW] | ((uint32_t)cc[(2 * w2 + 1) * LDW] << 16);
+            const uint2 lo = lds_column4(C_s, LDW, e0, (ib0 + j) * 32, lane), hi = lds_column4(C_s, LDW, e0 + 4, (ib0 + j) * 32, lane);
+            cf[j].u[0] = lo.x; cf[j].u[1] = lo.y; cf[j].u[2] = hi.x; cf[j].u[3] = hi.y;
           }
 #pragma unroll
           for (int j = 0; j < NBW; ++j) accT[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xl.v, cf[j].v, accT[j], 0, 0, 0);
@@ -3002,19 +3012,20 @@ __global__ __launch_bounds__(kCoopWaves * 64) void edge_coop_code_kernel(
     floatx16 accP = {0};
     {
       const float* grow = (b_side ? dB_s : dA_s) + r * LD + hh * 8;
-      const uint16_t* wcol = Wp + (hh * 8) * LDW + blk4 * 32 + r;
 #pragma unroll 2
       for (int m = 0; m < D / 16; ++m) {
         const float4 lo4 = *reinterpret_cast<const float4*>(grow + 16 * m), hi4 = *reinterpret_cast<const float4*>(grow + 16 * m + 4);
         const float x[8] = {lo4.x, lo4.y, lo4.z, lo4.w, hi4.x, hi4.y, hi4.z, hi4.w};
         Bf16Frag gh, gm, gl, wh, wm, wl;
         split3x8(x, gh, gm, gl);
-#pragma unroll
-        for (int w2 = 0; w2 < 4; ++w2) {
-          const uint16_t* p0 = wcol + (16 * m + 2 * w2) * LDW;
-          wh.u[w2] = (uint32_t)p0[0] | ((uint32_t)p0[LDW] << 16);
-          wm.u[w2] = (uint32_t)p0[D * LDW] | ((uint32_t)p0[D * LDW + LDW] << 16);
-          wl.u[w2] = (uint32_t)p0[2 * D * LDW] | ((uint32_t)p0[2 * D * LDW + LDW] << 16);
+        {
+          const int j0 = 16 * m + 8 * hh;
+          const uint2 h0 = lds_column4(Wp, LDWW, j0, blk4 * 32, lane), h1 = lds_column4(Wp, LDWW, j0 + 4, blk4 * 32, lane);
+          const uint2 m0 = lds_column4(Wp + D * LDWW, LDWW, j0, blk4 * 32, lane), m1 = lds_column4(Wp + D * LDWW, LDWW, j0 + 4, blk4 * 32, lane);
+          const uint2 l0 = lds_column4(Wp + 2 * D * LDWW, LDWW, j0, blk4 * 32, lane), l1 = lds_column4(Wp + 2 * D * LDWW, LDWW, j0 + 4, blk4 * 32, lane);
+          wh.u[0] = h0.x; wh.u[1] = h0.y; wh.u[2] = h1.x; wh.u[3] = h1.y;
+          wm.u[0] = m0.x; wm.u[1] = m0.y; wm.u[2] = m1.x; wm.u[3] = m1.y;
+          wl.u[0] = l0.x; wl.u[1] = l0.y; wl.u[2] = l1.x; wl.u[3] = l1.y;
         }
         mfma_split(gh, gm, gl, wh, wm, wl, accP);
         __builtin_amdgcn_sched_barrier(0);   // one k-step's fragments at a time

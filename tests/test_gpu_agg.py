@@ -162,7 +162,8 @@ def run_protocol(tk, N, R, head, rel, tail, d, dout, bits, group, seed=5, data_s
 
 @pytest.mark.parametrize("d,dout,bits,group", [(64, 64, 2, 64), (32, 16, 2, 64), (128, 128, 4, 128),
                                                (64, 32, 8, 32), (64, 64, 1, 256), (32, 48, 4, 32),
-                                               (128, 16, 2, 64)])
+                                               (128, 16, 2, 64), (128, 64, 8, 256), (128, 128, 1, 128),
+                                               (128, 32, 2, 128), (32, 32, 1, 32), (64, 64, 4, 128)])
 def test_small_graph_all_shapes(tk, d, dout, bits, group):
     # several node tiles and edge tiles with ragged tails: 333 nodes -> pad so N*d % group == 0
     N, R, T = 336, 5, 3000

@@ -2736,7 +2736,9 @@ __global__ __launch_bounds__(kEdgeWaves * 64) void edge_code_kernel(
 // of LDS in ONE layout, so there is no room for W_r^T beside them and none for a region per
 // wave: one eight-wave workgroup shares a 32-edge tile (as in the fp32 cooperative kernel
 // above, same phases and barriers) and the products that contract over W_r's ROW index read
-// W_r column-wise, two bytes at a time.
+// W_r column-wise with the transposing LDS read (lds_column4); so do the code columns of 1c.
+// The k-loops are unrolled by two, not fully: at 256 registers per wave the fully unrolled
+// form makes the register allocator serialise every LDS read with its use (measured 1.7 times slower).
 //   stage  rows arrive as raw codes (prefetched a tile ahead); each row's codes are centred on
 //          its rounded mean m and stored as bfloat16 (exact): C[e][k] = code - m, with
 //          e_hat = mid + scale C, mid = Z + scale m  (Eq. 4)

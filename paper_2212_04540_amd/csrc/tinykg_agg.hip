@@ -3107,6 +3107,213 @@ __global__ __launch_bounds__(kCoopWaves * 64) void edge_coop_code_kernel(
   }
 }
 
+// The dense backward stage for d_in = d_out = 128 and a compressed H_hat with one (Z, scale)
+// pair per row, on the bf16 matrix cores (same outputs as dense_bwd_kernel):
+//   grad_H = grad_J W:        (rows of grad_J, split three ways on the fly) x (pieces of W, split once
+//                             into LDS, read down their columns with the transposing LDS read): six
+//                             piece products
+//   grad_W += grad_J^T H_hat: Eq. (4) row by row, H_hat[n] = mid_n + s_n C[n] with C the codes centred on
+//                             the row's rounded mean (exact bfloat16 values): (s_n grad_J[n])^T C as three
+//                             piece products -- gradient columns read from LDS, scaled, split; code
+//                             columns by transposing reads -- plus the rank-one part (sum_n mid_n grad_J[n]) 1^T,
+//                             a column sum that each thread keeps for one column and 16 rows of the tile.
+// Eight waves: wave w owns block (w & 1, w >> 1) of the 2 x 4 blocks of the grad_H tile and two of
+// the sixteen blocks of grad_W (one row block, two column blocks).
+constexpr int kDenseCodeWaves = 8;
+constexpr int dense_code_smem_bytes() {
+  return 3 * 128 * (128 + 16) * 2 + 64 * (128 + 16) * 2 + 64 * (128 + 4) * 4 + 3 * 64 * 4;
+}
+
+template <int BITS>
+__global__ __launch_bounds__(kDenseCodeWaves * 64) void dense_bwd_code_kernel(
+    Source srcH, const uint8_t* __restrict__ mask, const float* __restrict__ gEout, const float* __restrict__ W,
+    float slope, int64_t N, float* __restrict__ gH, float* __restrict__ gE, float* __restrict__ part_W,
+    double* __restrict__ zero_ptr, int64_t zero_n, const int32_t* __restrict__ deg_rowptr) {
+  static_assert(BITS != 32, "packed rows");
+  constexpr int D = 128, DO = 128, TN = 64, LD = D + 4, LDW = D + 16, LDWW = DO + 16, LPR = D / 4, NIB = D / 32;
+  constexpr int NT = kDenseCodeWaves * 64;
+  constexpr int NQ = NT / DO, RP = TN / NQ;       // column sums: row parts (4 x 16 rows)
+  for (int64_t i = (int64_t)blockIdx.x * NT + threadIdx.x; i < zero_n; i += (int64_t)gridDim.x * NT)
+    zero_ptr[i] = 0.0;
+  uint16_t* Wp = reinterpret_cast<uint16_t*>(smem_raw);                 // [3][DO][LDWW] pieces of W (rows o)
+  uint16_t* C_s = Wp + 3 * DO * LDWW;                                   // [TN][LDW] centred codes of H_hat
+  float* gJ_s = reinterpret_cast<float*>(C_s + TN * LDW);               // [TN][LD] grad_J
+  float* sc_s = gJ_s + TN * LD;                    // [TN] factor of the grad_H copy in gH (uniform layer: 1 / deg)
+  float* s_s = sc_s + TN;                          // [TN] scale of the row
+  float* mid_s = s_s + TN;                         // [TN] Z + scale m
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int r = lane & 31, hh = lane >> 5;
+  stage_split_matrix<D, LDWW>(W, Wp, tid, NT);
+
+  floatx16 accW[2];
+  accW[0] = floatx16{0}; accW[1] = floatx16{0};
+  const int so = tid % DO, sn0 = (tid / DO) * RP;  // column sums: this thread's column and rows
+  float zw_acc = 0.f;
+
+  const int64_t n_tiles = (N + TN - 1) / TN;
+  constexpr int CPT = TN * LPR / NT, GPT = TN * (DO / 4) / NT;   // 4 and 4
+  RawChunk<BITS> preH[CPT];
+  float4 preG[GPT];
+  uint32_t preM[GPT];
+  float preS = 1.f;
+  auto load_tile = [&](int64_t tile) {
+#pragma unroll
+    for (int k = 0; k < CPT; ++k) {
+      const int q = tid + k * NT;
+      const int64_t n = tile * TN + q / LPR;
+      preH[k].load(srcH, (n < N ? n : 0) * LPR + q % LPR);   // past the end: row 0 (its grad_J row is zero)
+    }
+    if (deg_rowptr && tid < TN) {
+      const int64_t n = tile * TN + tid;
+      const int dg = n < N ? deg_rowptr[n + 1] - deg_rowptr[n] : 0;
+      preS = dg > 0 ? 1.0f / (float)dg : 0.f;
+    }
+#pragma unroll
+    for (int k = 0; k < GPT; ++k) {
+      const int q = tid + k * NT;
+      const int64_t n = tile * TN + q / (DO / 4);
+      const int c4 = q % (DO / 4);
+      preG[k] = make_float4(0.f, 0.f, 0.f, 0.f);
+      preM[k] = 0u;
+      if (n < N) {
+        preG[k] = reinterpret_cast<const float4*>(gEout)[n * (DO / 4) + c4];
+        const int64_t bit = (n * (DO / 4) + c4) * 4;
+        preM[k] = (mask[bit >> 3] >> (bit & 7)) & 0xFu;
+      }
+    }
+  };
+  auto centred = [](uint32_t w, float m) {
+    constexpr uint32_t B = (1u << (BITS & 31)) - 1u;
+    constexpr int SH = BITS & 31;
+    const float c0 = (float)(w & B) - m, c1 = (float)((w >> SH) & B) - m;
+    const float c2 = (float)((w >> (2 * SH)) & B) - m, c3 = (float)((w >> (3 * SH)) & B) - m;
+    return make_uint2(__builtin_amdgcn_perm(__float_as_uint(c1), __float_as_uint(c0), 0x07060302u),
+                      __builtin_amdgcn_perm(__float_as_uint(c3), __float_as_uint(c2), 0x07060302u));
+  };
+  auto code_sum4 = [](uint32_t w) {
+    constexpr uint32_t B = (1u << (BITS & 31)) - 1u;
+    constexpr int SH = BITS & 31;
+    return (float)((w & B) + ((w >> SH) & B) + ((w >> (2 * SH)) & B) + ((w >> (3 * SH)) & B));
+  };
+  if (blockIdx.x < n_tiles) load_tile(blockIdx.x);
+  for (int64_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
+    const int64_t n0 = tile * TN;
+    __syncthreads();   // the previous tile's readers are done (first tile: W is staged)
+#pragma unroll
+    for (int k = 0; k < CPT; ++k) {
+      const int q = tid + k * NT;
+      const int row = q / LPR, li = q % LPR;
+      // (the 32 lanes of a wave half hold one row: its mean code, rounded to an integer)
+      const float m = rintf(slot_sum<32>(code_sum4(preH[k].w[0])) * (1.0f / (float)D));
+      *reinterpret_cast<uint2*>(C_s + row * LDW + li * 4) = centred(preH[k].w[0], m);
+      if (li == 0) { s_s[row] = preH[k].s; mid_s[row] = fmaf(preH[k].s, m, preH[k].z); }
+    }
+#pragma unroll
+    for (int k = 0; k < GPT; ++k) {
+      const int q = tid + k * NT;
+      float4 g = preG[k];
+      const uint32_t mb = preM[k];
+      g.x *= (mb & 1u) ? 1.f : slope; g.y *= (mb & 2u) ? 1.f : slope;
+      g.z *= (mb & 4u) ? 1.f : slope; g.w *= (mb & 8u) ? 1.f : slope;
+      *reinterpret_cast<float4*>(gJ_s + (q / (DO / 4)) * LD + (q % (DO / 4)) * 4) = g;
+    }
+    if (tid < TN) sc_s[tid] = preS;
+    if (tile + gridDim.x < n_tiles) load_tile(tile + gridDim.x);
+    __syncthreads();
+    // ---- grad_W blocks [o][i] += sum_n (s_n gJ[n][o]) C[n][i], row block wave / 2, two column blocks
+    //      (a fresh accumulator per tile keeps the fp32 running sum short)
+    {
+      const int ob = wave >> 1, ib0 = (wave & 1) * 2;
+      floatx16 accT[2];
+      accT[0] = floatx16{0}; accT[1] = floatx16{0};
+#pragma unroll 1
+      for (int ks = 0; ks < TN / 16; ++ks) {
+        const int e0 = 16 * ks + 8 * hh;            // this lane half's eight rows of the step
+        Bf16Frag xh, xm, xl;
+        {
+          const float4 s0 = *reinterpret_cast<const float4*>(s_s + e0), s1 = *reinterpret_cast<const float4*>(s_s + e0 + 4);
+          const float sv[8] = {s0.x, s0.y, s0.z, s0.w, s1.x, s1.y, s1.z, s1.w};
+          float x[8];
+#pragma unroll
+          for (int i = 0; i < 8; ++i) x[i] = sv[i] * gJ_s[(e0 + i) * LD + ob * 32 + r];
+          split3x8(x, xh, xm, xl);
+        }
+        Bf16Frag cf[2];
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+          const uint2 lo = lds_column4(C_s, LDW, e0, (ib0 + j) * 32, lane), hi = lds_column4(C_s, LDW, e0 + 4, (ib0 + j) * 32, lane);
+          cf[j].u[0] = lo.x; cf[j].u[1] = lo.y; cf[j].u[2] = hi.x; cf[j].u[3] = hi.y;
+        }
+#pragma unroll
+        for (int j = 0; j < 2; ++j) accT[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xl.v, cf[j].v, accT[j], 0, 0, 0);
+#pragma unroll
+        for (int j = 0; j < 2; ++j) accT[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xm.v, cf[j].v, accT[j], 0, 0, 0);
+#pragma unroll
+        for (int j = 0; j < 2; ++j) accT[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xh.v, cf[j].v, accT[j], 0, 0, 0);
+      }
+      accW[0] += accT[0];
+      accW[1] += accT[1];
+    }
+    // ---- grad_H block (nb, ib): [n][i] = sum_o gJ[n][o] W[o][i]
+    {
+      const int nb = wave & 1, ib = wave >> 1;
+      floatx16 acc = {0};
+      const float* grow = gJ_s + (nb * 32 + r) * LD + hh * 8;
+#pragma unroll 2
+      for (int m = 0; m < DO / 16; ++m) {
+        const float4 lo4 = *reinterpret_cast<const float4*>(grow + 16 * m), hi4 = *reinterpret_cast<const float4*>(grow + 16 * m + 4);
+        const float x[8] = {lo4.x, lo4.y, lo4.z, lo4.w, hi4.x, hi4.y, hi4.z, hi4.w};
+        Bf16Frag gh, gm, gl, wh, wm, wl;
+        split3x8(x, gh, gm, gl);
+        {
+          const int j0 = 16 * m + 8 * hh;
+          const uint2 h0 = lds_column4(Wp, LDWW, j0, ib * 32, lane), h1 = lds_column4(Wp, LDWW, j0 + 4, ib * 32, lane);
+          const uint2 m0 = lds_column4(Wp + DO * LDWW, LDWW, j0, ib * 32, lane), m1 = lds_column4(Wp + DO * LDWW, LDWW, j0 + 4, ib * 32, lane);
+          const uint2 l0 = lds_column4(Wp + 2 * DO * LDWW, LDWW, j0, ib * 32, lane), l1 = lds_column4(Wp + 2 * DO * LDWW, LDWW, j0 + 4, ib * 32, lane);
+          wh.u[0] = h0.x; wh.u[1] = h0.y; wh.u[2] = h1.x; wh.u[3] = h1.y;
+          wm.u[0] = m0.x; wm.u[1] = m0.y; wm.u[2] = m1.x; wm.u[3] = m1.y;
+          wl.u[0] = l0.x; wl.u[1] = l0.y; wl.u[2] = l1.x; wl.u[3] = l1.y;
+        }
+        mfma_split(gh, gm, gl, wh, wm, wl, acc);
+        __builtin_amdgcn_sched_barrier(0);   // one k-step's fragments at a time
+      }
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int64_t n = n0 + nb * 32 + acc_row(v, lane);
+        if (n < N) {
+          gH[n * D + ib * 32 + r] = acc[v] * sc_s[nb * 32 + acc_row(v, lane)];
+          gE[n * D + ib * 32 + r] = acc[v];
+        }
+      }
+    }
+    // column sums over this thread's sixteen rows: the rank-one part of grad_W
+    {
+      float sz = 0.f;
+#pragma unroll
+      for (int k = 0; k < RP; ++k) sz = fmaf(mid_s[sn0 + k], gJ_s[(sn0 + k) * LD + so], sz);
+      zw_acc += sz;
+    }
+  }
+  // the row parts' column sums, in fixed order; the rank-one part joins the blocks
+  __syncthreads();
+  float* colsum_s = gJ_s;                          // [NQ][DO]
+  colsum_s[(tid / DO) * DO + so] = zw_acc;
+  __syncthreads();
+  float* out = part_W + (size_t)blockIdx.x * DO * D;
+  {
+    const int ob = wave >> 1, ib0 = (wave & 1) * 2;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      const int o = ob * 32 + acc_row(v, lane);
+      float zw = 0.f;
+#pragma unroll
+      for (int q = 0; q < NQ; ++q) zw += colsum_s[q * DO + o];
+#pragma unroll
+      for (int j = 0; j < 2; ++j) out[o * D + (ib0 + j) * 32 + r] = accW[j][v] + zw;
+    }
+  }
+}
+
 // ------------------------------------------------------------- host helpers ----
 size_t align256(size_t b) { return (b + 255) & ~(size_t)255; }
 
@@ -3340,12 +3547,26 @@ tinykg_status bwd_impl(const tinykg_graph* g, const tinykg_saved* sv, const floa
   const bool with_heavy = g->n_edges > 0 && n_heavy_elems > 0;
   int dense_blocks = 0;
   {
-    const size_t smem = (size_t)(DOP * LD + 64 * LD + 64 * (DOP + 4) + 64) * 4;
-    auto kern = rebuild_H ? dense_bwd_kernel<D, 32> : dense_bwd_kernel<D, BITS>;
-    if ((rc = set_smem(kern, smem)) != TINYKG_OK) return rc;
     const int grid = dense_grid(N);
     dense_blocks = grid;
-    {
+    bool code_form = false;
+    if constexpr (D == 128 && BITS != 32) {
+      // (d_in = d_out = 128, H_hat saved with one (Z, scale) pair per row: everything on the bf16 matrix cores)
+      code_form = !rebuild_H && d_out == 128 && group >= D;
+      if (code_form) {
+        const size_t smem = (size_t)dense_code_smem_bytes();
+        auto kern = dense_bwd_code_kernel<BITS>;
+        if ((rc = set_smem(kern, smem)) != TINYKG_OK) return rc;
+        ProfileScope prof("dense_bwd_kernel", st);
+        hipLaunchKernelGGL(kern, dim3(grid), dim3(kDenseCodeWaves * 64), smem, st, srcH, sv->mask_J, gEout, W,
+                           slope, N, gH, gE, pW, acc, with_heavy ? n_heavy_elems * kHeavyReplicas : 0,
+                           uniform ? g->rowptr : (const int32_t*)nullptr);
+      }
+    }
+    if (!code_form) {
+      const size_t smem = (size_t)(DOP * LD + 64 * LD + 64 * (DOP + 4) + 64) * 4;
+      auto kern = rebuild_H ? dense_bwd_kernel<D, 32> : dense_bwd_kernel<D, BITS>;
+      if ((rc = set_smem(kern, smem)) != TINYKG_OK) return rc;
       ProfileScope prof("dense_bwd_kernel", st);
       hipLaunchKernelGGL(kern, dim3(grid), dim3(dense_bwd_waves<D>() * 64), smem, st, srcH, sv->mask_J, gEout, W,
                          d_out, slope, N, gH, gE, pW, acc, with_heavy ? n_heavy_elems * kHeavyReplicas : 0,

@@ -1052,17 +1052,19 @@ __global__ __launch_bounds__(kThreads) void heavy_part3_kernel(HeavyList hl, con
 
 // ------------------------------------------------------------- dense stage ----
 // J = H W^T, E' = LeakyReLU(J), mask = [J > 0].  64 nodes per tile.
-// A wave keeps its 32 x D block of W in registers for the whole launch (wave w: output block
-// w mod NOB; the waves that share a block share the tile's two node blocks), so LDS holds only
-// the tile and several workgroups fit a compute unit: the loads, the products and the stores of
-// different workgroups overlap, which a single resident workgroup's barriers rule out.
+// A wave keeps its 32 x D block of W in registers for the whole launch, split into its three
+// bfloat16 pieces (wave w: output block w mod NOB; the waves that share a block share the tile's
+// two node blocks), so LDS holds only the tile and several workgroups fit a compute unit: the
+// loads, the products and the stores of different workgroups overlap, which a single resident
+// workgroup's barriers rule out.  The rows of H are split as they are read: six piece products
+// on the bf16 matrix cores per sixteen k-values (k-step m of lane half hh covers k = 16 m + 8 hh + 0..7).
 template <int D>
 __global__ __launch_bounds__(kThreads) void dense_fwd_kernel(const float* __restrict__ H,
                                                              const float* __restrict__ W, int d_out,
                                                              float slope, int64_t N,
                                                              float* __restrict__ E_out,
                                                              uint8_t* __restrict__ mask) {
-  constexpr int LD = D + 4, LPR = D / 4, TN = 64, KH = D / 2;
+  constexpr int LD = D + 4, LPR = D / 4, TN = 64, NM = D / 16;
   const int DOP = (d_out + 31) & ~31, LDJ = DOP + 4, NOB = DOP / 32;
   float* H_s = reinterpret_cast<float*>(smem_raw);   // [TN][LD]
   float* J_s = H_s + TN * LD;                        // [TN][LDJ]
@@ -1070,14 +1072,18 @@ __global__ __launch_bounds__(kThreads) void dense_fwd_kernel(const float* __rest
   const int r = lane & 31, hh = lane >> 5;
   const int ob = wave % NOB;                         // NOB <= 4 = waves
   const int rank = wave / NOB, sharers = (4 - ob + NOB - 1) / NOB;   // waves with this block: w = ob + NOB j
-  float wreg[KH];                                    // W[ob * 32 + r][hh * KH + s]
+  Bf16Frag wh[NM], wm[NM], wl[NM];                   // pieces of W[ob * 32 + r][16 m + 8 hh + 0..7]
   {
     const int row = ob * 32 + r;
 #pragma unroll
-    for (int s = 0; s < KH; s += 4) {
-      float4 w = make_float4(0.f, 0.f, 0.f, 0.f);
-      if (row < d_out) w = *reinterpret_cast<const float4*>(W + (size_t)row * D + hh * KH + s);
-      wreg[s] = w.x; wreg[s + 1] = w.y; wreg[s + 2] = w.z; wreg[s + 3] = w.w;
+    for (int m = 0; m < NM; ++m) {
+      float4 lo4 = make_float4(0.f, 0.f, 0.f, 0.f), hi4 = lo4;
+      if (row < d_out) {
+        lo4 = *reinterpret_cast<const float4*>(W + (size_t)row * D + 16 * m + 8 * hh);
+        hi4 = *reinterpret_cast<const float4*>(W + (size_t)row * D + 16 * m + 8 * hh + 4);
+      }
+      const float x[8] = {lo4.x, lo4.y, lo4.z, lo4.w, hi4.x, hi4.y, hi4.z, hi4.w};
+      split3x8(x, wh[m], wm[m], wl[m]);
     }
   }
   const int64_t n_tiles = (N + TN - 1) / TN;
@@ -1106,14 +1112,14 @@ __global__ __launch_bounds__(kThreads) void dense_fwd_kernel(const float* __rest
     __syncthreads();
     for (int nb = rank; nb < 2; nb += sharers) {
       floatx16 acc = {0};
-      const float* ap = H_s + (nb * 32 + r) * LD + hh * KH;
+      const float* ap = H_s + (nb * 32 + r) * LD + hh * 8;
 #pragma unroll
-      for (int s = 0; s < KH; s += 4) {
-        const float4 a = *reinterpret_cast<const float4*>(ap + s);
-        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.x, wreg[s], acc, 0, 0, 0);
-        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.y, wreg[s + 1], acc, 0, 0, 0);
-        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.z, wreg[s + 2], acc, 0, 0, 0);
-        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.w, wreg[s + 3], acc, 0, 0, 0);
+      for (int m = 0; m < NM; ++m) {
+        const float4 lo4 = *reinterpret_cast<const float4*>(ap + 16 * m), hi4 = *reinterpret_cast<const float4*>(ap + 16 * m + 4);
+        const float x[8] = {lo4.x, lo4.y, lo4.z, lo4.w, hi4.x, hi4.y, hi4.z, hi4.w};
+        Bf16Frag ah, am, al;
+        split3x8(x, ah, am, al);
+        mfma_split(ah, am, al, wh[m], wm[m], wl[m], acc);
       }
 #pragma unroll
       for (int v = 0; v < 16; ++v)

@@ -762,8 +762,10 @@ def config1_result(a, tk, torch, inp):
         "value": round(alg / (ms_per_step * 1e-3) / 1e9, 2), "unit": "GB/s",
         "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "ms_per_step": round(ms_per_step, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
-        "dtype_note": "fp32 in, fp32 out, fp32 accumulation; the attention projections are evaluated as exact "
-                      "three-way bfloat16 splits of their fp32 operands on the bf16 matrix cores (fp32 accuracy)",
+        "dtype_note": "fp32 in, fp32 out, fp32 accumulation; the contractions (attention projections, dense "
+                      "forward stage, and the backward products on saved codes) are evaluated as exact three-way "
+                      "bfloat16 splits of their fp32 operands on the bf16 matrix cores (fp32 accuracy; integer "
+                      "codes are exact bfloat16 values)",
         "data": "synthetic",
         "config": {"workload": "configs[1]: one KGAT-style attentive aggregation layer, forward+backward, "
                                "100k entities, dim 64, 16 relations, 1M triplets (Zipf 1.1 tails), "

@@ -13,12 +13,18 @@
 //                     the products run on the bf16 matrix cores with every fp32 operand split
 //                     exactly into three bfloat16 pieces (six piece products, fp32 accuracy)
 //   attend_fwd_kernel per head: softmax over its out-edges, H_h = e_h + sum pi e_t
-//   dense_fwd_kernel  J = H W^T (MFMA), E' = LeakyReLU(J), 1-bit sign mask
+//   dense_fwd_kernel  J = H W^T (six piece products), E' = LeakyReLU(J), 1-bit sign mask
 //   dense_bwd_kernel  grad_J from the mask, grad_H = grad_J W, grad_W = grad_J^T H_hat
+//                     (dense_bwd_code_kernel: the same on saved codes, d_in = d_out = 128)
 //   attend_bwd_kernel per head: pi, g_j = grad_H_h . e_hat_t, grad_s_j
-//   edge_bwd_kernel   relation-bucketed tiles: recompute a, b; grad_a, grad_b;
+//   edge kernels      relation-bucketed tiles: recompute a, b; grad_a, grad_b;
 //                     W_r^T grad_a / W_r^T grad_b rows scattered to tails / heads;
-//                     grad_W_r, grad_e_r accumulated per chunk
+//                     grad_W_r, grad_e_r accumulated per span or chunk.  Four forms:
+//                     edge_code_kernel (d <= 64) and edge_coop_code_kernel (d = 128) work on the
+//                     saved integer codes when a row has one (Z, scale) pair -- Eq. (4) is linear,
+//                     so nothing is dequantised and every product runs on the bf16 matrix cores;
+//                     edge_wave_kernel (d <= 64) and edge_bwd_kernel (d = 128) serve the other contexts
+//   uniform_tail_kernel  the transposed sparse product of the uniform layer, edges in tail order
 //   epilogue_kernel   fixed-order sums of the per-chunk / per-workgroup partial parameter
 //                     gradients, and the heavy nodes' double-precision rows, in one launch
 //

@@ -65,7 +65,8 @@ def run_uniform(tk, N, R, head, rel, tail, d, dout, bits, group, seed=9, data_se
 
 
 @pytest.mark.parametrize("d,dout,bits,group", [(64, 64, 2, 64), (32, 16, 2, 64), (128, 128, 4, 128),
-                                               (64, 32, 8, 32), (128, 48, 2, 256)])
+                                               (64, 32, 8, 32), (128, 48, 2, 256), (128, 128, 1, 128),
+                                               (128, 128, 8, 256), (128, 128, 2, 128)])
 def test_small_graphs(tk, d, dout, bits, group):
     N, R, T = 1000, 5, 9000
     head, rel, tail = gen.kg_triplets(N, R, T, seed=11, tail_zipf=1.1)
@@ -89,6 +90,16 @@ def test_hot_head_hot_tail_and_isolated_nodes(tk):
 def test_no_edges(tk):
     none = np.zeros(0, np.int32)
     run_uniform(tk, 256, 0, none, none, none, 64, 32, 2, 64)
+    run_uniform(tk, 192, 0, none, none, none, 128, 128, 4, 128)
+
+
+def test_fewer_nodes_than_a_tile_at_width_128(tk):
+    # the dense stage works on 64-node tiles: 8 nodes, 20 edges, saved codes with one pair per row
+    rng = np.random.default_rng(4)
+    head, tail = rng.integers(0, 8, 20).astype(np.int32), rng.integers(0, 8, 20).astype(np.int32)
+    rel = rng.integers(0, 2, 20).astype(np.int32)
+    run_uniform(tk, 8, 2, head, rel, tail, 128, 128, 4, 128)
+    run_uniform(tk, 65, 2, head, rel, tail, 128, 128, 2, 128)
 
 
 def test_config1_graph_full_size(tk):
